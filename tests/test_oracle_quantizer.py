@@ -1,0 +1,322 @@
+"""Pins for the oracle's quantiser, packer and keep-row logic: closed forms, invariants,
+special cases and brute force.  None of these re-types the oracle's formulas; each checks a
+consequence that a wrong sign, index, rounding or transposition would break."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import kvsink_oracle as O
+from tests.helpers import random_fp16
+
+BITS = [2, 3, 4]
+GROUPS = [32, 64, 128]
+
+
+def _all_fp16_sorted():
+    v = np.arange(0, 0x7C00, dtype=np.uint16).view(np.float16).astype(np.float64)   # +0 .. max finite
+    return v
+
+
+def test_round_up_to_fp16_matches_brute_force_search():
+    rng = np.random.default_rng(1)
+    table = _all_fp16_sorted()
+    x = np.concatenate([
+        np.exp(rng.uniform(np.log(1e-9), np.log(6e4), 20000)),
+        table[rng.integers(0, len(table), 2000)],                        # exactly representable
+        table[1:2001] * (1 + 1e-7), table[1:2001] * (1 - 1e-7),
+    ]).astype(np.float32)
+    got = O.fp32_to_fp16_round_up(x).astype(np.float64)
+    idx = np.searchsorted(table, x.astype(np.float64), side="left")   # first fp16 >= x
+    assert np.array_equal(got, table[idx])
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("kind", ["normal", "wide", "positive", "tiny"])
+def test_scale_is_tight_upper_rounding_of_range_over_qmax(bits, kind):
+    rng = np.random.default_rng(bits)
+    x = random_fp16(rng, (500, 16), kind)
+    mn, mx = x.min(1).astype(np.float32), x.max(1).astype(np.float32)
+    scale_h, zero = O.group_params(mn, mx, np.full(500, 16), bits)
+    qmax = 2 ** bits - 1
+    for i in range(500):
+        if mx[i] == mn[i]:
+            continue
+        exact = (Fraction(float(mx[i])) - Fraction(float(mn[i]))) / qmax
+        s = Fraction(float(scale_h[i]))
+        below = Fraction(float(np.nextafter(scale_h[i], np.float16(0))))
+        assert s >= exact * (1 - Fraction(1, 2 ** 23))
+        assert below < exact * (1 + Fraction(1, 2 ** 23))
+        # zero is the rounded position of the minimum, with the sign the zero equation gives it
+        assert abs(Fraction(int(zero[i])) + Fraction(float(mn[i])) / s) <= Fraction(1, 2) + Fraction(1, 256)
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("G", GROUPS)
+@pytest.mark.parametrize("kind", ["normal", "wide", "positive"])
+def test_round_trip_error_at_most_half_scale(bits, G, kind):
+    rng = np.random.default_rng(10 * bits + G)
+    n, D = 256, 128
+    qmax = 2 ** bits - 1
+    for which in ("k", "v"):
+        X = random_fp16(rng, (n, D), kind)
+        masked = np.zeros((n, D), bool)
+        masked[rng.integers(0, n, 5)] = True                      # some kept rows
+        masked |= rng.random((n, D)) < 0.01                       # some isolated entries
+        if which == "k":
+            codes, s, z = O.quantize_k_head(X, masked, bits, G)
+            S = np.repeat(s, G, axis=0)
+            Z = np.repeat(z, G, axis=0)
+        else:
+            codes, s, z = O.quantize_v_head(X, masked, bits, G)
+            S = np.repeat(s, G, axis=1)
+            Z = np.repeat(z, G, axis=1)
+        assert codes.min() >= 0 and codes.max() <= qmax
+        assert np.all(codes[masked] == 0)
+        xd = O.dequantize_entries(codes, S, Z).astype(np.float64)
+        err = np.abs(xd - X.astype(np.float64))
+        bound = S.astype(np.float64) / 2 * (1 + 2.0 ** -8)
+        assert np.all(err[~masked] <= bound[~masked])
+        # exact zeros stay exact whenever 0 lies inside the group's range (it always does
+        # for a sign-mixed group)
+        zeros = (X == 0) & ~masked
+        assert np.all(xd[zeros] == 0) or kind == "positive"
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_group_min_maps_to_code_zero_and_max_to_top_codes(bits):
+    rng = np.random.default_rng(3)
+    X = random_fp16(rng, (128, 128), "normal")
+    qmax = 2 ** bits - 1
+    codes, s, z = O.quantize_k_head(X, np.zeros_like(X, bool), bits, 64)
+    for g in range(2):
+        blk, cb = X[64 * g:64 * g + 64], codes[64 * g:64 * g + 64]
+        assert np.all(cb[blk.argmin(0), np.arange(128)] == 0)
+        top = cb[blk.argmax(0), np.arange(128)]
+        assert np.all((top == qmax) | (top == qmax - 1))
+    # monotone: a larger value in a group never gets a smaller code
+    order = np.argsort(X[:64, 7].astype(np.float32), kind="stable")
+    assert np.all(np.diff(codes[:64, 7][order].astype(int)) >= 0)
+
+
+def test_constant_group_is_reproduced_exactly():
+    for value in (3.25, -0.0123, 0.0, 60000.0, -5.96e-8):
+        X = np.full((64, 128), value, np.float16)
+        for bits in BITS:
+            for fn, G in ((O.quantize_k_head, 32), (O.quantize_v_head, 64)):
+                codes, s, z = fn(X, np.zeros_like(X, bool), bits, G)
+                rep = (G, 0) if fn is O.quantize_k_head else (G, 1)
+                xd = O.dequantize_entries(codes, np.repeat(s, rep[0], rep[1]), np.repeat(z, rep[0], rep[1]))
+                assert np.array_equal(xd.astype(np.float16).view(np.uint16) & 0x7FFF,
+                                      X.view(np.uint16) & 0x7FFF)
+                assert np.array_equal(xd, X.astype(np.float32))
+
+
+def test_fully_masked_group_has_unit_params_and_zero_codes():
+    rng = np.random.default_rng(4)
+    X = random_fp16(rng, (128, 128))
+    masked = np.zeros((128, 128), bool)
+    masked[:64] = True                                             # the whole first token group kept
+    codes, s, z = O.quantize_k_head(X, masked, 4, 64)
+    assert np.all(codes[:64] == 0) and np.all(s[0] == np.float16(1)) and np.all(z[0] == 0)
+    assert np.any(codes[64:] != 0)
+    codes, s, z = O.quantize_v_head(X, masked, 4, 128)
+    assert np.all(codes[:64] == 0) and np.all(s[:64] == np.float16(1)) and np.all(z[:64] == 0)
+
+
+def test_integer_grid_is_lossless_at_4_bits():
+    rng = np.random.default_rng(5)
+    for fn, axis in ((O.quantize_k_head, 0), (O.quantize_v_head, 1)):
+        X = rng.integers(0, 16, (128, 128)).astype(np.float16)
+        if axis == 0:                                              # both ends present in each K group
+            X[0], X[1], X[64], X[65] = 0, 15, 0, 15
+        else:                                                      # ... or in each V row
+            X[:, 0], X[:, 1] = 0, 15
+        G = 64 if axis == 0 else 128
+        codes, s, z = fn(X, np.zeros_like(X, bool), 4, G)
+        assert np.all(s == np.float16(1)) and np.all(z == 0)
+        assert np.array_equal(codes, X.astype(np.uint8))
+
+
+def test_shifted_grid_gives_nonzero_zero_point_with_the_right_sign():
+    # values {-6 .. 9}: scale 1, minimum -6 -> zero = +6 (the zero equation's leading minus)
+    X = np.tile(np.arange(-6, 10, dtype=np.float16), (32, 8))
+    codes, s, z = O.quantize_v_head(X, np.zeros_like(X, bool), 4, 128)
+    assert np.all(s == np.float16(1)) and np.all(z == 6)
+    assert np.array_equal(codes, (X + 6).astype(np.uint8))
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_chosen_code_minimises_reconstruction_error_brute_force(bits):
+    rng = np.random.default_rng(6 + bits)
+    qmax = 2 ** bits - 1
+    X = random_fp16(rng, (32, 128), "normal")
+    codes, s, z = O.quantize_v_head(X, np.zeros_like(X, bool), bits, 32)
+    for t in range(32):
+        for c in range(128):
+            sc, zc = float(s[t, c // 32]), int(z[t, c // 32])
+            errs = [abs(float(X[t, c]) - sc * (q - zc)) for q in range(qmax + 1)]
+            assert errs[codes[t, c]] <= min(errs) + sc * 2.0 ** -9
+
+
+def test_key_groups_run_along_tokens_and_value_groups_along_channels():
+    # One huge entry widens exactly the statistics of its own group and no other.
+    base = np.tile(np.linspace(-1, 1, 128, dtype=np.float16), (128, 1))
+    base = (base + base.T).astype(np.float16)
+    ref_k = O.quantize_k_head(base, np.zeros_like(base, bool), 4, 32)[1]
+    ref_v = O.quantize_v_head(base, np.zeros_like(base, bool), 4, 32)[1]
+    X = base.copy()
+    X[70, 5] = 1000
+    sk = O.quantize_k_head(X, np.zeros_like(X, bool), 4, 32)[1]       # [n/G, D]
+    sv = O.quantize_v_head(X, np.zeros_like(X, bool), 4, 32)[1]       # [n, D/G]
+    changed_k = np.argwhere(sk != ref_k)
+    changed_v = np.argwhere(sv != ref_v)
+    assert changed_k.tolist() == [[70 // 32, 5]]
+    assert changed_v.tolist() == [[70, 5 // 32]]
+    # ... and masking that entry (a kept token / an isolated outlier) restores the statistics
+    m = np.zeros_like(X, bool)
+    m[70, 5] = True
+    sk_m = O.quantize_k_head(X, m, 4, 32)[1]
+    assert sk_m[70 // 32, 5] < sk[70 // 32, 5]
+    others = np.ones_like(sk_m, bool)
+    others[70 // 32, 5] = False
+    assert np.array_equal(sk_m[others], ref_k[others])
+
+
+# ------------------------------------------------------------------------------ packing
+def test_hand_computed_words():
+    c = np.zeros(128, np.uint8)
+    c[:8] = [1, 2, 3, 4, 5, 6, 7, 8]
+    assert O._pack_last_axis(c, 4)[0] == 0x87654321
+    c = np.zeros(128, np.uint8)
+    c[:10] = [1, 2, 3, 4, 5, 6, 7, 0, 1, 2]
+    # five codes in the low half-word: 1 | 2<<3 | 3<<6 | 4<<9 | 5<<12 = 0x58D1;
+    # five in the high half-word: 6 | 7<<3 | 0<<6 | 1<<9 | 2<<12 = 0x223E
+    assert O._pack_last_axis(c, 3)[0] == 0x223E58D1
+    c = np.zeros(128, np.uint8)
+    c[:16] = [1, 2, 3, 0, 1, 2, 3, 0, 3, 3, 0, 0, 1, 1, 2, 2]
+    assert O._pack_last_axis(c, 2)[0] == int("".join(f"{v:02b}" for v in reversed(c[:16].tolist())), 2)
+    assert O.words_per_128(2) == 8 and O.words_per_128(3) == 13 and O.words_per_128(4) == 16
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_pack_unpack_identity_and_padding(bits):
+    rng = np.random.default_rng(bits)
+    codes = rng.integers(0, 2 ** bits, (256, 128)).astype(np.uint8)
+    wk, wv = O.pack_k(codes, bits), O.pack_v(codes, bits)
+    assert wk.shape == (4, O.words_per_128(bits), 64) and wv.shape == (2, O.words_per_128(bits), 128)
+    assert np.array_equal(O.unpack_k(wk, bits), codes)
+    assert np.array_equal(O.unpack_v(wv, bits), codes)
+    if bits == 3:
+        assert np.all(wk & np.uint32(0x80008000) == 0) and np.all(wv & np.uint32(0x80008000) == 0)
+        # the 13th word holds elements 120..127 only: slots 8 and 9 (bits 25..30) are empty
+        assert np.all(wk[:, 12, :] >> np.uint32(25) == 0) and np.all(wv[:, 12, :] >> np.uint32(25) == 0)
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_single_code_lands_in_the_documented_word_and_bits(bits):
+    cpw = O.codes_per_word(bits)
+    rng = np.random.default_rng(17)
+    for _ in range(20):
+        t, c = int(rng.integers(0, 256)), int(rng.integers(0, 128))
+        codes = np.zeros((256, 128), np.uint8)
+        codes[t, c] = 2 ** bits - 1
+        shift = lambda j: (3 * (j % 5) + 16 * (j // 5)) if bits == 3 else bits * j
+        wk = O.pack_k(codes, bits)
+        nz = np.argwhere(wk)
+        assert nz.tolist() == [[t // 64, c // cpw, t % 64]]           # (tile, word = channel chunk, token)
+        assert wk[tuple(nz[0])] == (2 ** bits - 1) << shift(c % cpw)
+        wv = O.pack_v(codes, bits)
+        nz = np.argwhere(wv)
+        assert nz.tolist() == [[t // 128, (t % 128) // cpw, c]]       # (tile, word = token chunk, channel)
+        assert wv[tuple(nz[0])] == (2 ** bits - 1) << shift((t % 128) % cpw)
+
+
+def test_param_word_encoding():
+    s = np.array([1.0, 0.5, 6.1e-5], np.float16)
+    z = np.array([0, -3, 30720], np.int16)
+    p = O.encode_params(s, z)
+    assert p[0] == 0x00003C00 and p[1] == (0xFFFD << 16 | 0x3800)
+    s2, z2 = O.decode_params(p)
+    assert np.array_equal(s2, s) and np.array_equal(z2, z)
+
+
+# ------------------------------------------------------------------------------ keep rows
+def test_keep_rows_are_exact_copies_in_ascending_order():
+    rng = np.random.default_rng(8)
+    B, H, n, D = 2, 3, 256, 128
+    K, V = random_fp16(rng, (B, H, n, D)), random_fp16(rng, (B, H, n, D), "wide")
+    mask = np.zeros((B, n), np.uint8)
+    mask[0, [0, 14, 200]] = 1
+    mask[1, [0, 1, 2, 3, 77]] = 1
+    cache = O.quantize_kv(K, V, mask, 4, 128, keep_cap=6)
+    assert cache.status == O.STATUS_OK
+    assert cache.keep_cnt.tolist() == [3, 5] == mask.sum(1).tolist()
+    assert cache.keep_idx[0].tolist() == [0, 14, 200, -1, -1, -1]
+    assert cache.keep_idx[1].tolist() == [0, 1, 2, 3, 77, -1]
+    for b in range(B):
+        for j in range(cache.keep_cnt[b]):
+            t = cache.keep_idx[b, j]
+            assert np.array_equal(cache.keep_k[b, :, j].view(np.uint16), K[b, :, t].view(np.uint16))
+            assert np.array_equal(cache.keep_v[b, :, j].view(np.uint16), V[b, :, t].view(np.uint16))
+        assert not cache.keep_k[b, :, cache.keep_cnt[b]:].any()
+    # kept tokens carry code 0 everywhere and do not influence their groups' statistics
+    assert not cache.k_codes_logical[0, :, [0, 14, 200]].any()
+    K2 = K.copy()
+    K2[0, :, 14] = 30000                                            # a wild kept row changes nothing else
+    cache2 = O.quantize_kv(K2, V, mask, 4, 128, keep_cap=6)
+    assert np.array_equal(cache2.k_codes, cache.k_codes) and np.array_equal(cache2.k_params, cache.k_params)
+    # capacity overflow is reported
+    assert O.quantize_kv(K, V, mask, 4, 128, keep_cap=4).status == O.STATUS_CAPACITY
+
+
+# ------------------------------------------------------------------------------ sparse
+def test_sparse_threshold_against_full_sort():
+    rng = np.random.default_rng(9)
+    B, H, n, D = 2, 2, 128, 128
+    X = random_fp16(rng, (B, H, n, D), "wide")
+    X[0, 0, 5, :64] = X[0, 0, 6, 0]                                  # plant ties
+    mask = np.zeros((B, n), np.uint8)
+    mask[:, [0, 14]] = 1
+    for frac in (0.01, 0.001, 0.05):
+        tau = O.sparse_threshold(X, mask, frac)
+        live = np.abs(X[:, :, mask[0] == 0, :].astype(np.float64)).ravel()   # same mask for both sequences
+        m = int(np.ceil(np.float64(np.float32(frac)) * live.size))
+        mth_largest = np.sort(live)[::-1][m - 1]
+        assert float(np.uint16(tau).view(np.float16)) == mth_largest
+        nnz = int((live >= mth_largest).sum())
+        ties = int((live == mth_largest).sum())
+        assert nnz >= m and nnz - ties < m
+
+
+def test_sparse_csr_structure_and_reduction_to_dense():
+    rng = np.random.default_rng(10)
+    B, H, n, D = 1, 2, 128, 128
+    K, V = random_fp16(rng, (B, H, n, D), "wide"), random_fp16(rng, (B, H, n, D))
+    mask = np.zeros((B, n), np.uint8)
+    mask[0, [0, 3]] = 1
+    cache = O.quantize_kv(K, V, mask, 3, 128, keep_cap=2, sparse_frac=0.01)
+    for X, rowptr, col, val, tau in ((K, cache.k_rowptr, cache.k_col, cache.k_val, cache.k_tau),
+                                     (V, cache.v_rowptr, cache.v_col, cache.v_val, cache.v_tau)):
+        tau_f = float(np.uint16(tau).view(np.float16))
+        assert rowptr[0] == 0 and rowptr[-1] == len(col) == len(val) and np.all(np.diff(rowptr) >= 0)
+        dense = np.zeros((B * H * n, D), bool)
+        for r in range(B * H * n):
+            cols = col[rowptr[r]:rowptr[r + 1]].astype(int)
+            assert np.all(np.diff(cols) > 0)
+            dense[r, cols] = True
+            assert np.array_equal(val[rowptr[r]:rowptr[r + 1]], X.reshape(-1, D)[r, cols])
+        dense = dense.reshape(B, H, n, D)
+        assert not dense[:, :, [0, 3]].any()                        # kept rows hold no sparse entries
+        live = np.ones(n, bool)
+        live[[0, 3]] = False
+        assert np.all(np.abs(X[dense].astype(np.float32)) >= tau_f)
+        assert np.all(np.abs(X[:, :, live][~dense[:, :, live]].astype(np.float32)) < tau_f)
+        assert dense.sum() >= np.ceil(0.01 * B * H * (n - 2) * D)
+    assert not cache.k_codes_logical[(np.abs(K.astype(np.float32)) >= float(np.uint16(cache.k_tau).view(np.float16)))].any()
+    # a vanishing fraction isolates nothing and reproduces the dense path bit for bit
+    dense_cache = O.quantize_kv(K, V, mask, 3, 128, keep_cap=2)
+    tiny = O.quantize_kv(K, V, mask, 3, 128, keep_cap=2, sparse_frac=1e-12)
+    assert len(tiny.k_col) <= 2 * 1 + 64                             # ceil(tiny * count) = 1 entry (+ ties)
+    none = O.quantize_kv(K, V, mask, 3, 128, keep_cap=2, sparse_frac=0.0)
+    assert np.array_equal(none.k_codes, dense_cache.k_codes) and none.k_rowptr is None
