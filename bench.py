@@ -1,0 +1,214 @@
+"""Benchmark of the KVSink hot path on one MI355X.
+
+A step = one pass of the whole path over one synthetic batch: kvs_predict_sinks on the hidden
+state, kvs_quantize_kv of one layer's K and V into a cache, kvs_decode_attn of one query per
+sequence and head over a cache.  The step quantises into cache slot i and decodes from slot
+i + 1 (quantised several steps earlier), and the K/V inputs rotate over distinct copies, so
+every stream comes from HBM rather than from the 256 MB last-level cache.
+
+Prints ONE JSON line.  value = effective HBM GB/s of kvs_decode_attn (algorithmic bytes of the
+call / its mean duration, both kernels), the headline metric; quantize tokens/s is reported next
+to it.  Inputs are resident in HBM before the timed region.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def decode_algorithmic_bytes(w, keep_rows_per_seq: int) -> int:
+    """Bytes one kvs_decode_attn call must move: packed codes, 4-byte parameter words, the keep
+    mask, the fp16 keep rows, q and out.  (Not the fp16 cache it avoids reading.)"""
+    W = {2: 8, 3: 13, 4: 16}[w.bits]
+    bh = w.B * w.Hkv
+    codes = 2 * bh * w.n * W * 4
+    params = bh * (w.n // w.group) * w.D * 4 + bh * w.n * (w.D // w.group) * 4
+    keep = 2 * bh * keep_rows_per_seq * w.D * 2 + w.B * w.n
+    qo = 2 * w.B * w.Hq * w.D * 2
+    return codes + params + keep + qo
+
+
+def quantize_algorithmic_bytes(w) -> int:
+    """fp16 K and V read once, codes and parameters written once."""
+    W = {2: 8, 3: 13, 4: 16}[w.bits]
+    bh = w.B * w.Hkv
+    read = 2 * bh * w.n * w.D * 2 + w.B * w.n
+    write = 2 * bh * w.n * W * 4 + bh * (w.n // w.group) * w.D * 4 + bh * w.n * (w.D // w.group) * 4
+    return read + write
+
+
+def cpu_baseline(w, budget_s: float = 12.0):
+    """The oracle as it stands, timed on this host on a bounded sample of the same workload:
+    whole (sequence 0, head h) slices, one at a time, until the budget is used."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+
+    from oracle import kvsink_oracle as O
+    from paper_2508_04257_amd import synth
+
+    small = w.scaled(B=1, Hq=w.Hq // w.Hkv, Hkv=1)            # one (b, h) slice at the full n
+    H = synth.make_hidden(small).numpy()
+    q = synth.make_query(small).numpy()
+    done, t_quant, t_dec = 0, 0.0, 0.0
+    with threadpool_limits(limits=1):
+        _, mask = O.predict_sinks(H, small.channels, small.k_sinks, small.first_n)
+        t_start = time.perf_counter()
+        while time.perf_counter() - t_start < budget_s and done < w.B * w.Hkv:
+            K, V = synth.make_kv(small.scaled(seed=small.seed + done))
+            K, V = K.numpy(), V.numpy()
+            t0 = time.perf_counter()
+            cache = O.quantize_kv(K, V, mask, small.bits, small.group, max(small.keep_cap, 1))
+            t1 = time.perf_counter()
+            O.decode_attn(q, cache, Hq=small.Hq)
+            t2 = time.perf_counter()
+            t_quant += t1 - t0
+            t_dec += t2 - t1
+            done += 1
+    slice_bytes = decode_algorithmic_bytes(small, small.keep_cap)
+    return {
+        "value": round(done * slice_bytes / t_dec / 1e9, 6),
+        "unit": "GB/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": f"{done} (sequence, KV head) slices of {w.name} at full length n={w.n} "
+                  f"(of {w.B * w.Hkv}); numpy oracle, single thread",
+        "quantize_tokens_per_s": round(done * w.n / (w.Hkv * t_quant), 3),   # whole-layer equivalent
+        "decode_ms_per_slice": round(1e3 * t_dec / done, 3),
+        "quantize_ms_per_slice": round(1e3 * t_quant / done, 3),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg1")
+    ap.add_argument("--slots", type=int, default=4, help="rotating copies of inputs and caches")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2508_04257_amd import binding as kb
+    from paper_2508_04257_amd import pipeline, synth
+
+    w = synth.WORKLOADS[args.workload]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    slots = max(2, args.slots)
+
+    hidden = synth.make_hidden(w, dev)
+    q = synth.make_query(w, dev)
+    inputs = [synth.make_kv(w, dev, layer=s) for s in range(slots)]
+    bufs = [pipeline.alloc_step(w, dev) for _ in range(slots)]
+    # Fill every cache slot once so that the first timed decode reads real data.
+    for s in range(slots):
+        pipeline.run_step(w, hidden, inputs[s][0], inputs[s][1], q, bufs[s])
+    torch.cuda.synchronize()
+
+    def step(i, ev=None):
+        cur, old = bufs[i % slots], bufs[(i + 1) % slots]
+        K, V = inputs[i % slots]
+        if ev:
+            ev[0].record()
+        pipeline.predict(w, hidden, cur)
+        if ev:
+            ev[1].record()
+        pipeline.quantize(K, V, cur)
+        if ev:
+            ev[2].record()
+        pipeline.decode(q, old)
+        if ev:
+            ev[3].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_step = 1e3 * (t1 - t0) / args.steps
+    ms_predict = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    ms_quant = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    ms_decode = sum(e[2].elapsed_time(e[3]) for e in events) / args.steps
+
+    for b in bufs:
+        assert int(b.cache.status.cpu()[0]) == 0, "capacity overflow reported by the library"
+
+    dec_bytes = decode_algorithmic_bytes(w, w.keep_cap)
+    qnt_bytes = quantize_algorithmic_bytes(w)
+    dec_gbps = dec_bytes / (ms_decode * 1e-3) / 1e9
+    qnt_gbps = qnt_bytes / (ms_quant * 1e-3) / 1e9
+
+    result = {
+        "metric": "decode-attn effective HBM GB/s",
+        "value": round(dec_gbps, 2),
+        "unit": "GB/s",
+        "pct_of_hbm_peak": round(100 * dec_gbps / HBM_PEAK_GBPS, 2),
+        "quantize_tokens_per_s": round(w.B * w.n / (ms_quant * 1e-3), 1),
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "ms_predict": round(ms_predict, 4),
+        "ms_quantize": round(ms_quant, 4),
+        "ms_decode": round(ms_decode, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: B={w.B} n={w.n} Hq={w.Hq} Hkv={w.Hkv} D={w.D} INT{w.bits} G={w.group} "
+                        f"keep=first{w.first_n}+top{w.k_sinks} sparse={w.sparse_frac}",
+            "cache_slots": slots,
+            "decode_splits": kb.kvs_decode_splits(bufs[0].desc),
+        },
+        "roofline": {
+            "kernel": "kvs_decode_attn (decode_partial_kernel + decode_combine_kernel)",
+            "bound": "hbm",
+            "achieved": round(dec_gbps, 2),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(dec_gbps / HBM_PEAK_GBPS, 4),
+            "traffic": None,
+            "algorithmic_bytes": dec_bytes,
+        },
+        "roofline_quantize": {
+            "kernel": "kvs_quantize_kv (quantize_k_kernel + quantize_v_kernel + keep rows)",
+            "bound": "hbm",
+            "achieved": round(qnt_gbps, 2),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(qnt_gbps / HBM_PEAK_GBPS, 4),
+            "traffic": None,
+            "algorithmic_bytes": qnt_bytes,
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

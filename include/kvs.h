@@ -1,0 +1,176 @@
+/*
+ * kvs.h - C ABI of the KVSink hot path on AMD Instinct MI355X (gfx950).
+ *
+ * KVSink (arXiv 2508.04257) keeps the Key/Value rows of attention-sink tokens in 16 bit while
+ * the rest of the KV cache is quantised to 2-4 bits, and finds those tokens from the extreme
+ * activation outliers of one hidden-state channel.  The three calls below are the data-parallel
+ * part of that method:
+ *
+ *   kvs_predict_sinks  - top-k over tokens of |H[i, c]| (Algorithm 1, the l = l_E branch;
+ *                        Section 4.3), united with the first-N tokens of the PFN baseline.
+ *   kvs_quantize_kv    - asymmetric uniform b-bit quantisation (Appendix C equations) of K per
+ *                        channel and V per token, group size G, skipping the kept tokens, whose
+ *                        rows are copied unchanged (Algorithm 1, the two quantise steps);
+ *                        optional dense-and-sparse fp16 outliers (Section 5.1).
+ *   kvs_decode_attn    - softmax(q K'^T / sqrt(d_k)) V' for one query per sequence and head over
+ *                        the packed cache, kept rows merged in 16 bit (Section 2 attention
+ *                        equation; the sink / non-sink split of Section 4.2).
+ *
+ * Conventions common to every call
+ *   - Every pointer is a DEVICE pointer owned by the caller unless marked HOST.  The library
+ *     allocates and frees nothing and keeps no state between calls.
+ *   - Calls enqueue kernels on `stream` (a hipStream_t passed as void*, NULL = default stream)
+ *     and return without synchronising.
+ *   - Argument errors are found on the host before anything is launched; outputs are then
+ *     untouched and the return value says why.  Data-dependent overflow (more kept tokens than
+ *     keep_cap, more sparse entries than sparse_cap) cannot be known on the host: it is written
+ *     to cache->status on the device (0 = fine, KVS_ERR_CAPACITY otherwise) and the call still
+ *     returns KVS_OK.  The caller zeroes *status before the first call and reads it after
+ *     synchronising.
+ *   - fp16 is IEEE binary16; inputs must be finite.  All tensors are dense, row-major.
+ *
+ * Packed cache layout (D = 128 only)
+ *   cpw = codes per 32-bit word: 16 (2 bit), 10 (3 bit), 8 (4 bit);  W = ceil(128 / cpw) = 8, 13, 16.
+ *   Slot j of a word sits at bit 2j (2 bit) / 4j (4 bit); for 3 bit, slots 0-4 sit at bits
+ *   3j and slots 5-9 at bits 16 + 3(j - 5), bits 15 and 31 are zero.  Unused slots are zero.
+ *   k_codes  uint32 [B, Hkv, n/64, W, 64]   word (T, w, t): channels cpw*w .. of token 64T + t.
+ *   v_codes  uint32 [B, Hkv, n/128, W, 128] word (T, u, c): tokens 128T + cpw*u .. of channel c.
+ *   k_params uint32 [B, Hkv, n/G, 128]      one per (token group, channel).
+ *   v_params uint32 [B, Hkv, n, 128/G]      one per (token, channel group).
+ *            parameter word = fp16 scale in bits 0-15 | int16 zero in bits 16-31;
+ *            dequantised value = scale * (code - zero).
+ *   keep_k / keep_v  fp16 [B, Hkv, keep_cap, 128]  rows of the kept tokens, ascending token order,
+ *            zero padded;  keep_idx int32 [B, keep_cap] (-1 padded);  keep_cnt int32 [B];
+ *            keep_mask uint8 [B, n] (copy of the mask the cache was built with).
+ *   CSR of isolated outliers (only when sparse_frac > 0), rows = (b, h, token) in that order:
+ *            rowptr int32 [B*Hkv*n + 1], col uint16 [sparse_cap] ascending per row, val fp16.
+ */
+#ifndef KVS_H
+#define KVS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KVS_HEAD_DIM 128
+#define KVS_K_TILE 64
+#define KVS_V_TILE 128
+#define KVS_CACHE_FIELDS 16
+#define KVS_MAX_TOPK 1024
+#define KVS_MAX_PREDICT_TOKENS 65536
+
+typedef enum {
+  KVS_OK = 0,
+  KVS_ERR_INVALID = 1,     /* null pointer, non-positive size, shape rule broken           */
+  KVS_ERR_UNSUPPORTED = 2, /* valid request outside what this version implements           */
+  KVS_ERR_CAPACITY = 3,    /* only ever written to cache->status, see above                */
+  KVS_ERR_DEVICE = 4       /* a HIP launch failed                                          */
+} kvs_status;
+
+/* Shape and quantiser setting of one layer's cache.  Plain data, filled by the caller. */
+typedef struct kvs_desc {
+  int32_t B, n, Hq, Hkv, D; /* batch, cached tokens, query heads, KV heads, head dim (128)    */
+                            /* Hq / Hkv in {1, 2, 4, 8};  n % 128 == 0                        */
+  int32_t bits;             /* 2, 3 or 4                                                      */
+  int32_t group;            /* G: 32, 64 or 128.  K groups run along tokens, V along channels */
+  int32_t keep_cap;         /* rows of the fp16 side buffer per sequence (>= 0)               */
+  float sparse_frac;        /* fraction of entries isolated in fp16; 0 = off                  */
+  int64_t sparse_cap;       /* CSR capacity in entries per tensor when sparse_frac > 0        */
+} kvs_desc;
+
+/* The quantised cache of one layer: device pointers to caller-owned buffers whose byte sizes
+ * kvs_cache_bytes() returns in this field order.  The CSR fields may be NULL when
+ * sparse_frac == 0. */
+typedef struct kvs_cache {
+  uint32_t* k_codes;
+  uint32_t* v_codes;
+  uint32_t* k_params;
+  uint32_t* v_params;
+  void* keep_k;
+  void* keep_v;
+  int32_t* keep_idx;
+  int32_t* keep_cnt;
+  uint8_t* keep_mask;
+  int32_t* k_rowptr;
+  uint16_t* k_col;
+  void* k_val;
+  int32_t* v_rowptr;
+  uint16_t* v_col;
+  void* v_val;
+  int32_t* status;
+} kvs_cache;
+
+/* Library version (major * 100 + minor). */
+int32_t kvs_version(void);
+
+/* Static text for a status code. */
+const char* kvs_status_string(kvs_status s);
+
+/* Byte size of every kvs_cache buffer for `desc`, in field order (sizes is a HOST array of
+ * KVS_CACHE_FIELDS entries; CSR entries are 0 when sparse_frac == 0; every size is rounded up
+ * to a multiple of 16 and is at least 16).  Returns KVS_ERR_INVALID / KVS_ERR_UNSUPPORTED for a
+ * descriptor the other calls would reject. */
+kvs_status kvs_cache_bytes(const kvs_desc* desc, size_t* sizes);
+
+/* Bytes of scratch `workspace` that kvs_quantize_kv and kvs_decode_attn need for `desc`
+ * (the larger of the two; 0 for an invalid descriptor).  Contents need not be preserved
+ * between calls; calls that share a workspace must be ordered on one stream. */
+size_t kvs_workspace_bytes(const kvs_desc* desc);
+
+/* Number of token splits kvs_decode_attn uses for `desc` (each split is one workgroup per
+ * (sequence, KV head); informational, 0 for an invalid descriptor). */
+int32_t kvs_decode_splits(const kvs_desc* desc);
+
+/*
+ * Sink prediction.  For each sequence b: score[i] = max over the listed channels of
+ * |hidden[b, i, c]|; the k tokens with the largest score (ties: lower index first) are written
+ * ascending to sink_idx[b, 0..k), and keep_mask[b, i] = 1 iff i is one of them or i < first_n
+ * (else 0).  With n_channels == 1 this is exactly the paper's single-channel rule.
+ *   hidden    fp16 [B, n, d]
+ *   channels  HOST int32 [n_channels], each in [0, d), 1 <= n_channels <= 8
+ *   k in [0, min(n, KVS_MAX_TOPK)], first_n in [0, n], n <= KVS_MAX_PREDICT_TOKENS
+ *   sink_idx  int32 [B, k] (may be NULL when k == 0);  keep_mask uint8 [B, n]
+ */
+kvs_status kvs_predict_sinks(const void* hidden, int32_t B, int32_t n, int32_t d,
+                             const int32_t* channels, int32_t n_channels, int32_t k,
+                             int32_t first_n, int32_t* sink_idx, uint8_t* keep_mask,
+                             void* stream);
+
+/*
+ * Quantise one layer's K and V (fp16 [B, Hkv, n, 128]) into `out`.
+ * Per group (K: G consecutive tokens of one channel; V: G consecutive channels of one token),
+ * over the entries that are neither on a kept token nor an isolated outlier:
+ *   scale = fp16_round_up((max - min) / (2^bits - 1)),  zero = -round(min / scale),
+ *   code  = clamp(round(x / scale) + zero, 0, 2^bits - 1)
+ * in fp32 with round-half-to-even and x / scale evaluated as x * (1 / scale); kept and isolated
+ * entries get code 0.  A group with no such entry gets (scale 1, zero 0); a constant group gets
+ * scale |min| (1 if min == 0).  Rows of kept tokens are copied bit for bit to keep_k / keep_v.
+ * With sparse_frac > 0 the entries with |x| >= tau go to the CSR arrays with their fp16 value,
+ * tau being the magnitude at which the descending cumulative count over all non-kept entries
+ * of the tensor first reaches ceil(sparse_frac * count).
+ *   keep_mask uint8 [B, n] (nonzero = keep); copied to out->keep_mask.
+ *   workspace: kvs_workspace_bytes(desc) bytes (may be NULL when that is 0).
+ */
+kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const void* V,
+                           const uint8_t* keep_mask, const kvs_cache* out, void* workspace,
+                           void* stream);
+
+/*
+ * Decode attention of one query per (sequence, query head) over the whole cache:
+ *   K'[t], V'[t] = the fp16 keep row if token t is kept, else the dequantised row with isolated
+ *   outliers replaced by their fp16 value;  s_t = q . K'[t] / sqrt(128);  p = softmax(s);
+ *   out = sum_t p_t V'[t]  (fp32 accumulation, stored fp16);  lse = log sum_t exp(s_t).
+ * Query head hq reads KV head hq / (Hq / Hkv).
+ *   q fp16 [B, Hq, 128];  out fp16 [B, Hq, 128];  lse float [B, Hq] or NULL.
+ *   workspace: kvs_workspace_bytes(desc) bytes.
+ */
+kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const kvs_cache* cache,
+                           void* out, float* lse, void* workspace, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVS_H */

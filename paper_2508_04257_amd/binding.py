@@ -1,0 +1,201 @@
+"""ctypes binding of libkvs.so: same names as the C ABI (include/kvs.h), argument marshalling only.
+
+PyTorch provides device memory and the stream handle; every step of the path runs in the HIP
+kernels.  There is no CPU fallback: if the library is not built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Dict, Optional, Sequence
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvs.so")
+_lib = None
+
+KVS_OK, KVS_ERR_INVALID, KVS_ERR_UNSUPPORTED, KVS_ERR_CAPACITY, KVS_ERR_DEVICE = range(5)
+KVS_CACHE_FIELDS = 16
+CACHE_FIELD_NAMES = (
+    "k_codes", "v_codes", "k_params", "v_params", "keep_k", "keep_v", "keep_idx", "keep_cnt",
+    "keep_mask", "k_rowptr", "k_col", "k_val", "v_rowptr", "v_col", "v_val", "status",
+)
+_FIELD_DTYPES = dict(
+    k_codes=torch.int32, v_codes=torch.int32, k_params=torch.int32, v_params=torch.int32,
+    keep_k=torch.float16, keep_v=torch.float16, keep_idx=torch.int32, keep_cnt=torch.int32,
+    keep_mask=torch.uint8, k_rowptr=torch.int32, k_col=torch.int16, k_val=torch.float16,
+    v_rowptr=torch.int32, v_col=torch.int16, v_val=torch.float16, status=torch.int32,
+)
+
+
+class KvsDesc(C.Structure):
+    _fields_ = [("B", C.c_int32), ("n", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32),
+                ("D", C.c_int32), ("bits", C.c_int32), ("group", C.c_int32),
+                ("keep_cap", C.c_int32), ("sparse_frac", C.c_float), ("sparse_cap", C.c_int64)]
+
+
+class KvsCache(C.Structure):
+    _fields_ = [(name, C.c_void_p) for name in CACHE_FIELD_NAMES]
+
+
+class KvsError(RuntimeError):
+    def __init__(self, call: str, status: int):
+        self.status = status
+        super().__init__(f"{call} failed: {status_string(status)} ({status})")
+
+
+def lib() -> C.CDLL:
+    """Loads libkvs.so once.  Raises if it has not been built (python -m paper_2508_04257_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2508_04257_amd.build`")
+        L = C.CDLL(_LIB_PATH)
+        L.kvs_version.restype = C.c_int32
+        L.kvs_status_string.restype = C.c_char_p
+        L.kvs_status_string.argtypes = [C.c_int]
+        L.kvs_cache_bytes.restype = C.c_int
+        L.kvs_cache_bytes.argtypes = [C.POINTER(KvsDesc), C.POINTER(C.c_size_t)]
+        L.kvs_workspace_bytes.restype = C.c_size_t
+        L.kvs_workspace_bytes.argtypes = [C.POINTER(KvsDesc)]
+        L.kvs_decode_splits.restype = C.c_int32
+        L.kvs_decode_splits.argtypes = [C.POINTER(KvsDesc)]
+        L.kvs_predict_sinks.restype = C.c_int
+        L.kvs_predict_sinks.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32),
+                                        C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.kvs_quantize_kv.restype = C.c_int
+        L.kvs_quantize_kv.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.POINTER(KvsCache), C.c_void_p, C.c_void_p]
+        L.kvs_decode_attn.restype = C.c_int
+        L.kvs_decode_attn.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.POINTER(KvsCache), C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().kvs_status_string(int(status)).decode()
+
+
+def make_desc(B, n, Hq, Hkv, bits, group, keep_cap, D=128, sparse_frac=0.0, sparse_cap=0) -> KvsDesc:
+    return KvsDesc(B, n, Hq, Hkv, D, bits, group, keep_cap, sparse_frac, sparse_cap)
+
+
+def kvs_cache_bytes(desc: KvsDesc) -> Dict[str, int]:
+    sizes = (C.c_size_t * KVS_CACHE_FIELDS)()
+    st = lib().kvs_cache_bytes(C.byref(desc), sizes)
+    if st != KVS_OK:
+        raise KvsError("kvs_cache_bytes", st)
+    return dict(zip(CACHE_FIELD_NAMES, [int(s) for s in sizes]))
+
+
+def kvs_workspace_bytes(desc: KvsDesc) -> int:
+    return int(lib().kvs_workspace_bytes(C.byref(desc)))
+
+
+def kvs_decode_splits(desc: KvsDesc) -> int:
+    return int(lib().kvs_decode_splits(C.byref(desc)))
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_handle() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+@dataclass
+class CacheBuffers:
+    """Device buffers of one layer's quantised cache plus the struct of pointers handed to C."""
+
+    desc: KvsDesc
+    tensors: Dict[str, Optional[torch.Tensor]]
+    struct: KvsCache
+
+    def __getattr__(self, name):
+        tensors = object.__getattribute__(self, "tensors")
+        if name in tensors:
+            return tensors[name]
+        raise AttributeError(name)
+
+
+def alloc_cache(desc: KvsDesc, device="cuda") -> CacheBuffers:
+    """Allocates every buffer kvs_cache_bytes asks for (torch is the allocator) and zeroes status."""
+    sizes = kvs_cache_bytes(desc)
+    tensors: Dict[str, Optional[torch.Tensor]] = {}
+    for name in CACHE_FIELD_NAMES:
+        nbytes = sizes[name]
+        if nbytes == 0:
+            tensors[name] = None
+            continue
+        dt = _FIELD_DTYPES[name]
+        tensors[name] = torch.empty(nbytes // dt.itemsize, dtype=dt, device=device)
+    tensors["status"].zero_()
+    struct = KvsCache(**{name: _ptr(t) for name, t in tensors.items()})
+    return CacheBuffers(desc, tensors, struct)
+
+
+def alloc_workspace(desc: KvsDesc, device="cuda") -> torch.Tensor:
+    return torch.empty(max(16, kvs_workspace_bytes(desc)), dtype=torch.uint8, device=device)
+
+
+def _check_tensor(name: str, t: torch.Tensor, shape, dtype) -> None:
+    """The C side only sees pointers: shapes, dtypes and placement are verified here so that a
+    kernel never indexes past a buffer."""
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype and tuple(t.shape) == tuple(shape)):
+        raise ValueError(f"{name}: expected contiguous {dtype} {tuple(shape)} on the GPU, got "
+                         f"{t.dtype} {tuple(t.shape)} on {t.device}")
+
+
+def _check_cache(desc: KvsDesc, cache: CacheBuffers) -> None:
+    a, b = desc, cache.desc
+    same = all(getattr(a, f) == getattr(b, f) for f, _ in KvsDesc._fields_)
+    if not same:
+        raise ValueError("cache buffers were allocated for a different descriptor")
+
+
+def kvs_predict_sinks(hidden: torch.Tensor, channels: Sequence[int], k: int, first_n: int,
+                      sink_idx: Optional[torch.Tensor], keep_mask: torch.Tensor) -> None:
+    B, n, d = hidden.shape
+    _check_tensor("hidden", hidden, (B, n, d), torch.float16)
+    _check_tensor("keep_mask", keep_mask, (B, n), torch.uint8)
+    if k > 0:
+        _check_tensor("sink_idx", sink_idx, (B, k), torch.int32)
+    ch = (C.c_int32 * len(channels))(*channels)
+    st = lib().kvs_predict_sinks(hidden.data_ptr(), B, n, d, ch, len(channels), k, first_n,
+                                 _ptr(sink_idx), keep_mask.data_ptr(), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_predict_sinks", st)
+
+
+def kvs_quantize_kv(desc: KvsDesc, K: torch.Tensor, V: torch.Tensor, keep_mask: torch.Tensor,
+                    cache: CacheBuffers, workspace: Optional[torch.Tensor]) -> None:
+    shape = (desc.B, desc.Hkv, desc.n, desc.D)
+    _check_tensor("K", K, shape, torch.float16)
+    _check_tensor("V", V, shape, torch.float16)
+    _check_tensor("keep_mask", keep_mask, (desc.B, desc.n), torch.uint8)
+    _check_cache(desc, cache)
+    need = kvs_workspace_bytes(desc)
+    if desc.sparse_frac > 0 and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        raise ValueError("workspace too small")
+    st = lib().kvs_quantize_kv(C.byref(desc), K.data_ptr(), V.data_ptr(), keep_mask.data_ptr(),
+                               C.byref(cache.struct), _ptr(workspace), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_quantize_kv", st)
+
+
+def kvs_decode_attn(desc: KvsDesc, q: torch.Tensor, cache: CacheBuffers, out: torch.Tensor,
+                    lse: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    _check_tensor("q", q, (desc.B, desc.Hq, desc.D), torch.float16)
+    _check_tensor("out", out, (desc.B, desc.Hq, desc.D), torch.float16)
+    if lse is not None:
+        _check_tensor("lse", lse, (desc.B, desc.Hq), torch.float32)
+    _check_cache(desc, cache)
+    if not workspace.is_cuda or workspace.numel() * workspace.element_size() < kvs_workspace_bytes(desc):
+        raise ValueError("workspace too small")
+    st = lib().kvs_decode_attn(C.byref(desc), q.data_ptr(), C.byref(cache.struct), out.data_ptr(),
+                               _ptr(lse), workspace.data_ptr(), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_decode_attn", st)

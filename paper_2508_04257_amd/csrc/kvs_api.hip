@@ -1,0 +1,106 @@
+// Host-only part of the C ABI: descriptor validation, buffer sizing, launch geometry.
+#include "kvs_device.h"
+
+namespace kvs {
+
+kvs_status validate_desc(const kvs_desc* d) {
+  if (!d) return KVS_ERR_INVALID;
+  if (d->B < 1 || d->n < 1 || d->Hq < 1 || d->Hkv < 1 || d->D < 1) return KVS_ERR_INVALID;
+  if (d->keep_cap < 0 || !(d->sparse_frac >= 0.0f) || d->sparse_frac >= 1.0f) return KVS_ERR_INVALID;
+  if (d->Hq % d->Hkv != 0) return KVS_ERR_INVALID;
+  if (d->sparse_frac > 0.0f && d->sparse_cap < 1) return KVS_ERR_INVALID;
+  if (d->D != KVS_HEAD_DIM) return KVS_ERR_UNSUPPORTED;
+  if (d->bits != 2 && d->bits != 3 && d->bits != 4) return KVS_ERR_UNSUPPORTED;
+  if (d->group != 32 && d->group != 64 && d->group != 128) return KVS_ERR_UNSUPPORTED;
+  if (d->n % KVS_V_TILE != 0) return KVS_ERR_UNSUPPORTED;      // also a multiple of 64 and of G
+  const int rep = d->Hq / d->Hkv;
+  if (rep != 1 && rep != 2 && rep != 4 && rep != 8) return KVS_ERR_UNSUPPORTED;
+  // CSR rows and word offsets are 32-bit quantities in places; keep a wide margin.
+  const int64_t rows = static_cast<int64_t>(d->B) * d->Hkv * d->n;
+  if (rows >= (int64_t{1} << 30)) return KVS_ERR_UNSUPPORTED;
+  if (d->sparse_cap > (int64_t{1} << 31) - 1) return KVS_ERR_UNSUPPORTED;
+  return KVS_OK;
+}
+
+// Enough workgroups to cover 256 compute units several times over, each split a whole number
+// of 128-token Value tiles.
+DecodeGeometry decode_geometry(const kvs_desc* d) {
+  const int tiles = d->n / KVS_V_TILE;
+  const int pairs = d->B * d->Hkv;
+  const int target = 2048;
+  int splits = (target + pairs - 1) / pairs;
+  if (splits < 1) splits = 1;
+  if (splits > tiles) splits = tiles;
+  const int tiles_per_split = (tiles + splits - 1) / splits;
+  DecodeGeometry g;
+  g.split_tokens = tiles_per_split * KVS_V_TILE;
+  g.splits = (tiles + tiles_per_split - 1) / tiles_per_split;
+  return g;
+}
+
+}  // namespace kvs
+
+namespace {
+size_t round16(size_t v) { return v < 16 ? 16 : (v + 15) & ~static_cast<size_t>(15); }
+}  // namespace
+
+extern "C" int32_t kvs_version(void) { return 100; }
+
+extern "C" const char* kvs_status_string(kvs_status s) {
+  switch (s) {
+    case KVS_OK: return "ok";
+    case KVS_ERR_INVALID: return "invalid argument";
+    case KVS_ERR_UNSUPPORTED: return "unsupported configuration";
+    case KVS_ERR_CAPACITY: return "capacity exceeded";
+    case KVS_ERR_DEVICE: return "device launch failed";
+  }
+  return "unknown status";
+}
+
+extern "C" kvs_status kvs_cache_bytes(const kvs_desc* d, size_t* sizes) {
+  const kvs_status st = kvs::validate_desc(d);
+  if (st != KVS_OK) return st;
+  if (!sizes) return KVS_ERR_INVALID;
+  const size_t bh = static_cast<size_t>(d->B) * d->Hkv;
+  const size_t n = d->n;
+  const size_t W = kvs::words_per_128(d->bits);
+  const size_t code_bytes = bh * n * W * 4;                 // W words per 128 codes, K and V alike
+  const size_t keep_rows = bh * d->keep_cap * KVS_HEAD_DIM * 2;
+  const bool sparse = d->sparse_frac > 0.0f;
+  const size_t cap = sparse ? static_cast<size_t>(d->sparse_cap) : 0;
+  const size_t v[KVS_CACHE_FIELDS] = {
+      code_bytes,                                   // k_codes
+      code_bytes,                                   // v_codes
+      bh * (n / d->group) * KVS_HEAD_DIM * 4,       // k_params
+      bh * n * (KVS_HEAD_DIM / d->group) * 4,       // v_params
+      keep_rows,                                    // keep_k
+      keep_rows,                                    // keep_v
+      static_cast<size_t>(d->B) * d->keep_cap * 4,  // keep_idx
+      static_cast<size_t>(d->B) * 4,                // keep_cnt
+      static_cast<size_t>(d->B) * n,                // keep_mask
+      sparse ? (bh * n + 1) * 4 : 0,                // k_rowptr
+      cap * 2,                                      // k_col
+      cap * 2,                                      // k_val
+      sparse ? (bh * n + 1) * 4 : 0,                // v_rowptr
+      cap * 2,                                      // v_col
+      cap * 2,                                      // v_val
+      4,                                            // status
+  };
+  for (int i = 0; i < KVS_CACHE_FIELDS; ++i) sizes[i] = (v[i] == 0 && !sparse && i >= 9 && i <= 14) ? 0 : round16(v[i]);
+  return KVS_OK;
+}
+
+extern "C" int32_t kvs_decode_splits(const kvs_desc* d) {
+  if (kvs::validate_desc(d) != KVS_OK) return 0;
+  return kvs::decode_geometry(d).splits;
+}
+
+extern "C" size_t kvs_workspace_bytes(const kvs_desc* d) {
+  if (kvs::validate_desc(d) != KVS_OK) return 0;
+  const kvs::DecodeGeometry g = kvs::decode_geometry(d);
+  // decode: per (b, hq, split) the unnormalised fp32 output row plus running max and sum
+  const size_t decode = static_cast<size_t>(d->B) * d->Hq * g.splits * (KVS_HEAD_DIM + 2) * 4;
+  // quantise (dense-and-sparse only): two 32768-bin histograms, thresholds and counters
+  const size_t quant = d->sparse_frac > 0.0f ? (2 * 32768 + 64) * 4 : 0;
+  return round16(decode > quant ? decode : quant);
+}

@@ -1,0 +1,75 @@
+// Internal helpers shared by the gfx950 kernels: packed-word format, wave64 reductions,
+// fp16 bit handling.  Not part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvs.h"
+
+#define KVS_WAVE 64
+
+namespace kvs {
+
+// Packed-word format of one bit width (the layout comment of kvs.h).
+template <int BITS>
+struct Fmt;
+template <>
+struct Fmt<2> {
+  static constexpr int cpw = 16, W = 8, qmax = 3;
+  __host__ __device__ static constexpr int shift(int j) { return 2 * j; }
+};
+template <>
+struct Fmt<3> {
+  static constexpr int cpw = 10, W = 13, qmax = 7;
+  __host__ __device__ static constexpr int shift(int j) { return 3 * (j % 5) + 16 * (j / 5); }
+};
+template <>
+struct Fmt<4> {
+  static constexpr int cpw = 8, W = 16, qmax = 15;
+  __host__ __device__ static constexpr int shift(int j) { return 4 * j; }
+};
+
+// Host-side checks and launch geometry shared by the entry points (kvs_api.hip).
+kvs_status validate_desc(const kvs_desc* d);
+struct DecodeGeometry {
+  int splits;        // workgroups per (sequence, KV head)
+  int split_tokens;  // tokens per split, a multiple of 128
+};
+DecodeGeometry decode_geometry(const kvs_desc* d);
+
+__host__ __device__ inline int words_per_128(int bits) { return bits == 2 ? 8 : (bits == 3 ? 13 : 16); }
+
+__device__ inline float half_bits_to_float(uint16_t h) {
+  return static_cast<float>(__builtin_bit_cast(_Float16, h));
+}
+__device__ inline uint16_t float_to_half_bits_rn(float f) {
+  return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f));
+}
+
+// Parameter word: fp16 scale in the low half, int16 zero in the high half.
+__device__ inline void unpack_param(uint32_t p, float& scale, int& zero) {
+  scale = half_bits_to_float(static_cast<uint16_t>(p & 0xFFFFu));
+  zero = static_cast<int>(static_cast<int16_t>(p >> 16));
+}
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, KVS_WAVE));
+  return v;
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, KVS_WAVE);
+  return v;
+}
+__device__ inline uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    uint32_t other = static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), o, KVS_WAVE));
+    v = other > v ? other : v;
+  }
+  return v;
+}
+
+}  // namespace kvs

@@ -1,0 +1,105 @@
+// kvs_predict_sinks: sink-token prediction from the extreme activation outliers of the
+// emergence layer's hidden state (paper, Algorithm 1 - the "l = l_E" branch - and Section 4.3).
+//
+// One workgroup per sequence.  Each lane keeps the ordering keys of its tokens (token i lives in
+// lane i % 1024) in registers, so the strided column of H is read exactly once; k rounds of a
+// workgroup-wide arg-max then pick the top-k.  Key = (15-bit fp16 magnitude pattern, lower index
+// first): monotone in |x| for finite inputs and independent of how tokens map to lanes.
+#include "kvs_device.h"
+
+namespace {
+
+constexpr int kPredictThreads = 1024;
+constexpr int kMaxChannels = 8;
+constexpr int kKeysPerLane = KVS_MAX_PREDICT_TOKENS / kPredictThreads;   // 64
+
+struct ChannelList {
+  int32_t c[kMaxChannels];
+  int32_t count;
+};
+
+__global__ __launch_bounds__(kPredictThreads) void predict_sinks_kernel(
+    const uint16_t* __restrict__ hidden, int n, int d, ChannelList channels, int k, int first_n,
+    int32_t* __restrict__ sink_idx, uint8_t* __restrict__ keep_mask) {
+  __shared__ uint32_t wave_best[kPredictThreads / KVS_WAVE];
+  __shared__ int32_t chosen[KVS_MAX_TOPK];
+  __shared__ uint32_t round_best;
+
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x;
+  const uint16_t* Hb = hidden + static_cast<size_t>(b) * n * d;
+  uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * n;
+
+  // key = (magnitude + 1) << 16 | (65535 - index); 0 = no token / already taken.
+  uint32_t key[kKeysPerLane];
+#pragma unroll
+  for (int j = 0; j < kKeysPerLane; ++j) {
+    const int i = tid + j * kPredictThreads;
+    key[j] = 0;
+    if (i < n) {
+      uint32_t m = 0;
+      for (int c = 0; c < channels.count; ++c) {
+        uint32_t v = Hb[static_cast<size_t>(i) * d + channels.c[c]] & 0x7FFFu;
+        m = v > m ? v : m;
+      }
+      key[j] = ((m + 1) << 16) | static_cast<uint32_t>(65535 - i);
+      mask_b[i] = i < first_n ? 1 : 0;
+    }
+  }
+
+  for (int r = 0; r < k; ++r) {
+    uint32_t best = 0;
+#pragma unroll
+    for (int j = 0; j < kKeysPerLane; ++j) best = key[j] > best ? key[j] : best;
+    best = kvs::wave_max_u32(best);
+    if ((tid & (KVS_WAVE - 1)) == 0) wave_best[tid / KVS_WAVE] = best;
+    __syncthreads();
+    if (tid < KVS_WAVE) {
+      uint32_t v = tid < kPredictThreads / KVS_WAVE ? wave_best[tid] : 0u;
+      v = kvs::wave_max_u32(v);
+      if (tid == 0) {
+        round_best = v;
+        chosen[r] = 65535 - static_cast<int>(v & 0xFFFFu);
+      }
+    }
+    __syncthreads();
+    const uint32_t win = round_best;
+#pragma unroll
+    for (int j = 0; j < kKeysPerLane; ++j) key[j] = key[j] == win ? 0u : key[j];   // keys are unique
+  }
+  __syncthreads();
+
+  // Ascending output by rank (k is small), and the mask bits of the chosen tokens.
+  for (int j = tid; j < k; j += kPredictThreads) {
+    const int mine = chosen[j];
+    int rank = 0;
+    for (int i = 0; i < k; ++i) rank += chosen[i] < mine ? 1 : 0;
+    sink_idx[static_cast<size_t>(b) * k + rank] = mine;
+    mask_b[mine] = 1;
+  }
+}
+
+}  // namespace
+
+extern "C" kvs_status kvs_predict_sinks(const void* hidden, int32_t B, int32_t n, int32_t d,
+                                         const int32_t* channels, int32_t n_channels, int32_t k,
+                                         int32_t first_n, int32_t* sink_idx, uint8_t* keep_mask,
+                                         void* stream) {
+  if (!hidden || !channels || !keep_mask) return KVS_ERR_INVALID;
+  if (B < 1 || n < 1 || d < 1 || n_channels < 1 || k < 0 || first_n < 0) return KVS_ERR_INVALID;
+  if (k > n || first_n > n) return KVS_ERR_INVALID;
+  if (k > 0 && !sink_idx) return KVS_ERR_INVALID;
+  for (int j = 0; j < n_channels && j < kMaxChannels; ++j)
+    if (channels[j] < 0 || channels[j] >= d) return KVS_ERR_INVALID;
+  if (n_channels > kMaxChannels || k > KVS_MAX_TOPK || n > KVS_MAX_PREDICT_TOKENS)
+    return KVS_ERR_UNSUPPORTED;
+
+  ChannelList list{};
+  list.count = n_channels;
+  for (int j = 0; j < n_channels; ++j) list.c[j] = channels[j];
+
+  hipLaunchKernelGGL(predict_sinks_kernel, dim3(B), dim3(kPredictThreads), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(hidden), n, d,
+                     list, k, first_n, sink_idx, keep_mask);
+  return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
+}

@@ -1,0 +1,376 @@
+// kvs_quantize_kv: sink-preserving low-bit KV-cache quantisation (paper, Appendix C equations
+// for Q(X), scale and zero; Algorithm 1's two quantise steps; Section 4.1 for the per-channel
+// Key / per-token Value grouping).
+//
+// Every kernel here is bound by the fp16 read of K and V (2 bytes per element in, bits/8 out).
+// A workgroup of 256 lanes owns one token block of one (sequence, KV head): each lane loads
+// 8 consecutive channels (one 128-bit load) of 8 or 4 rows, statistics are reduced along the
+// group axis (LDS for the Key's token axis, cross-lane for the Value's channel axis), codes are
+// staged as bytes in LDS and packed into words whose global order is contiguous per workgroup.
+//
+// The quantiser arithmetic is the exact fp32 sequence the ABI header documents; this file is
+// compiled with floating-point contraction off so that no multiply-add fuses across it.
+#include "kvs_device.h"
+
+namespace {
+
+using kvs::Fmt;
+
+constexpr int kThreads = 256;
+constexpr int kRowStride = 132;   // bytes per staged code row: 128 + 4 keeps LDS banks spread
+
+struct GroupParam {
+  float inv;    // 1 / scale, fp32
+  int zero;
+  uint32_t word;
+};
+
+// scale / zero of one group from its unmasked minimum and maximum (count == 0: empty group).
+template <int BITS>
+__device__ inline GroupParam make_param(float mn, float mx, bool any) {
+  constexpr float qmax = static_cast<float>(Fmt<BITS>::qmax);
+  if (!any) { mn = 0.0f; mx = 0.0f; }
+  uint16_t hbits;
+  if (mx == mn) {
+    const float a = mn != 0.0f ? fabsf(mn) : 1.0f;    // exactly representable in fp16
+    hbits = kvs::float_to_half_bits_rn(a);
+  } else {
+    const float s32 = (mx - mn) / qmax;
+    hbits = kvs::float_to_half_bits_rn(s32);
+    if (kvs::half_bits_to_float(hbits) < s32) hbits += 1;   // next fp16 up (positive values)
+  }
+  const float s = kvs::half_bits_to_float(hbits);
+  GroupParam p;
+  p.inv = 1.0f / s;
+  p.zero = -static_cast<int>(rintf(mn * p.inv));
+  p.word = static_cast<uint32_t>(hbits) | (static_cast<uint32_t>(p.zero & 0xFFFF) << 16);
+  return p;
+}
+
+template <int BITS>
+__device__ inline uint32_t quantize_one(float x, float inv, int zero, bool masked) {
+  int c = static_cast<int>(rintf(x * inv)) + zero;
+  c = c < 0 ? 0 : (c > Fmt<BITS>::qmax ? Fmt<BITS>::qmax : c);
+  return masked ? 0u : static_cast<uint32_t>(c);
+}
+
+__device__ inline void unpack8(const uint4& raw, uint16_t h[8]) {
+  h[0] = raw.x & 0xFFFF; h[1] = raw.x >> 16; h[2] = raw.y & 0xFFFF; h[3] = raw.y >> 16;
+  h[4] = raw.z & 0xFFFF; h[5] = raw.z >> 16; h[6] = raw.w & 0xFFFF; h[7] = raw.w >> 16;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Keys: per channel, groups of G consecutive tokens.  Block = TB = max(G, 64) tokens.
+// ---------------------------------------------------------------------------------------------
+template <int BITS, int G>
+__global__ __launch_bounds__(kThreads) void quantize_k_kernel(
+    const uint4* __restrict__ K, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
+    uint32_t tau, uint32_t* __restrict__ k_codes, uint32_t* __restrict__ k_params) {
+  constexpr int TB = G > 64 ? G : 64;
+  constexpr int NG = TB / G;             // groups per block: 1 or 2
+  constexpr int ROWS = TB / 16;          // rows per lane
+  constexpr int W = Fmt<BITS>::W, cpw = Fmt<BITS>::cpw;
+
+  __shared__ float red_min[NG][16][128];
+  __shared__ float red_max[NG][16][128];
+  __shared__ float inv_s[NG][128];
+  __shared__ int zero_s[NG][128];
+  __shared__ __align__(16) uint8_t code_s[TB * kRowStride];
+
+  const int tid = threadIdx.x;
+  const int chunk = tid & 15;            // channels 8*chunk .. 8*chunk+7
+  const int rslot = tid >> 4;            // rows rslot, rslot+16, ...
+  const int blocks_per_head = n / TB;
+  const int blk = blockIdx.x % blocks_per_head;
+  const size_t bh = blockIdx.x / blocks_per_head;       // b * Hkv + h
+  const int b = static_cast<int>(bh / Hkv);
+  const int t0 = blk * TB;
+
+  const uint4* src = K + (bh * n + t0) * 16;            // 16 uint4 per 128-channel row
+  const uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * n + t0;
+
+  uint4 raw[ROWS];
+  bool kept[ROWS];
+#pragma unroll
+  for (int i = 0; i < ROWS; ++i) {
+    const int r = rslot + 16 * i;
+    raw[i] = src[r * 16 + chunk];
+    kept[i] = mask_b[r] != 0;
+  }
+
+  // Lane-local min / max per channel and per group, over the unmasked entries.
+  float mn[NG][8], mx[NG][8];
+#pragma unroll
+  for (int g = 0; g < NG; ++g)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { mn[g][j] = INFINITY; mx[g][j] = -INFINITY; }
+#pragma unroll
+  for (int i = 0; i < ROWS; ++i) {
+    constexpr int rows_per_group = G / 16;
+    const int g = i / rows_per_group;     // compile-time after unrolling
+    uint16_t h[8];
+    unpack8(raw[i], h);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bool masked = kept[i] || (h[j] & 0x7FFFu) >= tau;
+      const float x = kvs::half_bits_to_float(h[j]);
+      mn[g][j] = masked ? mn[g][j] : fminf(mn[g][j], x);
+      mx[g][j] = masked ? mx[g][j] : fmaxf(mx[g][j], x);
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < NG; ++g)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      red_min[g][rslot][8 * chunk + j] = mn[g][j];
+      red_max[g][rslot][8 * chunk + j] = mx[g][j];
+    }
+  __syncthreads();
+
+  // One lane per (group, channel): finish the reduction, derive scale / zero, publish.
+  if (tid < NG * 128) {
+    const int g = tid >> 7, c = tid & 127;
+    float a = INFINITY, z = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      a = fminf(a, red_min[g][s][c]);
+      z = fmaxf(z, red_max[g][s][c]);
+    }
+    const GroupParam p = make_param<BITS>(a, z, a <= z);
+    inv_s[g][c] = p.inv;
+    zero_s[g][c] = p.zero;
+    k_params[(bh * (n / G) + static_cast<size_t>(t0 / G + g)) * 128 + c] = p.word;
+  }
+  __syncthreads();
+
+  // Codes of the lane's entries -> bytes in LDS.
+#pragma unroll
+  for (int i = 0; i < ROWS; ++i) {
+    constexpr int rows_per_group = G / 16;
+    const int g = i / rows_per_group;
+    const int r = rslot + 16 * i;
+    uint16_t h[8];
+    unpack8(raw[i], h);
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bool masked = kept[i] || (h[j] & 0x7FFFu) >= tau;
+      const uint32_t c = quantize_one<BITS>(kvs::half_bits_to_float(h[j]), inv_s[g][8 * chunk + j],
+                                            zero_s[g][8 * chunk + j], masked);
+      if (j < 4) lo |= c << (8 * j); else hi |= c << (8 * (j - 4));
+    }
+    uint32_t* dst = reinterpret_cast<uint32_t*>(code_s + r * kRowStride + 8 * chunk);
+    dst[0] = lo;
+    dst[1] = hi;
+  }
+  __syncthreads();
+
+  // Pack: the block's words are contiguous in global memory in (tile, w, t) order.
+  uint32_t* out = k_codes + (bh * (n / KVS_K_TILE) + static_cast<size_t>(t0 / KVS_K_TILE)) * (W * KVS_K_TILE);
+  constexpr int words = (TB / KVS_K_TILE) * W * KVS_K_TILE;
+  for (int widx = tid; widx < words; widx += kThreads) {
+    const int t = widx % KVS_K_TILE;
+    const int w = (widx / KVS_K_TILE) % W;
+    const int tile = widx / (KVS_K_TILE * W);
+    const uint8_t* row = code_s + (tile * KVS_K_TILE + t) * kRowStride + cpw * w;
+    uint32_t word = 0;
+#pragma unroll
+    for (int j = 0; j < cpw; ++j)
+      if (cpw * w + j < 128) word |= static_cast<uint32_t>(row[j]) << Fmt<BITS>::shift(j);
+    out[widx] = word;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Values: per token, groups of G consecutive channels.  Block = one 128-token code tile.
+// ---------------------------------------------------------------------------------------------
+template <int BITS, int G>
+__global__ __launch_bounds__(kThreads) void quantize_v_kernel(
+    const uint4* __restrict__ V, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
+    uint32_t tau, uint32_t* __restrict__ v_codes, uint32_t* __restrict__ v_params) {
+  constexpr int ROWS = KVS_V_TILE / 16;  // 8 rows per lane
+  constexpr int W = Fmt<BITS>::W, cpw = Fmt<BITS>::cpw;
+  constexpr int LANES_PER_GROUP = G / 8;
+  constexpr int NGC = 128 / G;
+
+  __shared__ __align__(16) uint8_t code_s[KVS_V_TILE * kRowStride];
+
+  const int tid = threadIdx.x;
+  const int chunk = tid & 15;
+  const int rslot = tid >> 4;
+  const int tiles_per_head = n / KVS_V_TILE;
+  const int tile = blockIdx.x % tiles_per_head;
+  const size_t bh = blockIdx.x / tiles_per_head;
+  const int b = static_cast<int>(bh / Hkv);
+  const int t0 = tile * KVS_V_TILE;
+
+  const uint4* src = V + (bh * n + t0) * 16;
+  const uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * n + t0;
+
+#pragma unroll
+  for (int i = 0; i < ROWS; ++i) {
+    const int r = rslot + 16 * i;
+    const uint4 raw = src[r * 16 + chunk];
+    const bool kept = mask_b[r] != 0;
+    uint16_t h[8];
+    unpack8(raw, h);
+    float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bool masked = kept || (h[j] & 0x7FFFu) >= tau;
+      const float x = kvs::half_bits_to_float(h[j]);
+      mn = masked ? mn : fminf(mn, x);
+      mx = masked ? mx : fmaxf(mx, x);
+    }
+    // The lanes of one channel group are LANES_PER_GROUP consecutive lanes of the same row.
+#pragma unroll
+    for (int o = 1; o < LANES_PER_GROUP; o <<= 1) {
+      mn = fminf(mn, __shfl_xor(mn, o, KVS_WAVE));
+      mx = fmaxf(mx, __shfl_xor(mx, o, KVS_WAVE));
+    }
+    const GroupParam p = make_param<BITS>(mn, mx, mn <= mx);
+    if ((chunk % LANES_PER_GROUP) == 0)
+      v_params[(bh * n + static_cast<size_t>(t0 + r)) * NGC + chunk / LANES_PER_GROUP] = p.word;
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bool masked = kept || (h[j] & 0x7FFFu) >= tau;
+      const uint32_t c = quantize_one<BITS>(kvs::half_bits_to_float(h[j]), p.inv, p.zero, masked);
+      if (j < 4) lo |= c << (8 * j); else hi |= c << (8 * (j - 4));
+    }
+    uint32_t* dst = reinterpret_cast<uint32_t*>(code_s + r * kRowStride + 8 * chunk);
+    dst[0] = lo;
+    dst[1] = hi;
+  }
+  __syncthreads();
+
+  // Pack along tokens: word (u, c) holds tokens cpw*u .. of channel c; contiguous per block.
+  uint32_t* out = v_codes + (bh * tiles_per_head + static_cast<size_t>(tile)) * (W * 128);
+  for (int widx = tid; widx < W * 128; widx += kThreads) {
+    const int c = widx & 127;
+    const int u = widx >> 7;
+    uint32_t word = 0;
+#pragma unroll
+    for (int j = 0; j < cpw; ++j)
+      if (cpw * u + j < 128)
+        word |= static_cast<uint32_t>(code_s[(cpw * u + j) * kRowStride + c]) << Fmt<BITS>::shift(j);
+    out[widx] = word;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Keep rows: index list of the kept tokens (ascending) and bit-exact copies of their rows.
+// ---------------------------------------------------------------------------------------------
+constexpr int kIndexThreads = 1024;
+
+__global__ __launch_bounds__(kIndexThreads) void keep_index_kernel(
+    const uint8_t* __restrict__ keep_mask, int n, int cap, int32_t* __restrict__ keep_idx,
+    int32_t* __restrict__ keep_cnt, uint8_t* __restrict__ mask_copy, int32_t* __restrict__ status) {
+  __shared__ int wave_count[kIndexThreads / KVS_WAVE];
+  __shared__ int base_s;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int lane = tid & (KVS_WAVE - 1), wave = tid / KVS_WAVE;
+  const uint8_t* m = keep_mask + static_cast<size_t>(b) * n;
+  if (tid == 0) base_s = 0;
+  __syncthreads();
+  for (int i0 = 0; i0 < n; i0 += kIndexThreads) {
+    const int i = i0 + tid;
+    const bool flag = i < n && m[i] != 0;
+    if (i < n) mask_copy[static_cast<size_t>(b) * n + i] = flag ? 1 : 0;
+    const unsigned long long ballot = __ballot(flag);
+    const int before = __popcll(ballot & ((1ull << lane) - 1ull));
+    if (lane == 0) wave_count[wave] = __popcll(ballot);
+    __syncthreads();
+    int offset = base_s;
+    for (int w = 0; w < wave; ++w) offset += wave_count[w];
+    const int pos = offset + before;
+    if (flag && pos < cap) keep_idx[static_cast<size_t>(b) * cap + pos] = i;
+    __syncthreads();
+    if (tid == 0) {
+      int total = 0;
+      for (int w = 0; w < kIndexThreads / KVS_WAVE; ++w) total += wave_count[w];
+      base_s += total;
+    }
+    __syncthreads();
+  }
+  const int total = base_s;
+  for (int j = total + tid; j < cap; j += kIndexThreads) keep_idx[static_cast<size_t>(b) * cap + j] = -1;
+  if (tid == 0) {
+    keep_cnt[b] = total;
+    if (total > cap) atomicCAS(status, 0, static_cast<int>(KVS_ERR_CAPACITY));
+  }
+}
+
+// One wave per (b, h, j): copies the 256-byte K row and V row of kept token j (zeros past the count).
+__global__ __launch_bounds__(KVS_WAVE) void keep_gather_kernel(
+    const uint32_t* __restrict__ K, const uint32_t* __restrict__ V, int n, int Hkv, int cap,
+    const int32_t* __restrict__ keep_idx, uint32_t* __restrict__ keep_k, uint32_t* __restrict__ keep_v) {
+  const int j = blockIdx.x % cap;
+  const size_t bh = blockIdx.x / cap;
+  const int b = static_cast<int>(bh / Hkv);
+  const int t = keep_idx[static_cast<size_t>(b) * cap + j];
+  const int lane = threadIdx.x;
+  const size_t dst = (bh * cap + j) * 64 + lane;       // 64 uint32 per row
+  if (t >= 0) {
+    const size_t srcw = (bh * n + t) * 64 + lane;
+    keep_k[dst] = K[srcw];
+    keep_v[dst] = V[srcw];
+  } else {
+    keep_k[dst] = 0;
+    keep_v[dst] = 0;
+  }
+}
+
+template <int BITS, int G>
+void launch_dense(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask,
+                  const kvs_cache* out, uint32_t tau_k, uint32_t tau_v, hipStream_t stream) {
+  constexpr int TB = G > 64 ? G : 64;
+  const int bh = d->B * d->Hkv;
+  hipLaunchKernelGGL((quantize_k_kernel<BITS, G>), dim3(bh * (d->n / TB)), dim3(kThreads), 0, stream,
+                     static_cast<const uint4*>(K), mask, d->n, d->Hkv, tau_k, out->k_codes, out->k_params);
+  hipLaunchKernelGGL((quantize_v_kernel<BITS, G>), dim3(bh * (d->n / KVS_V_TILE)), dim3(kThreads), 0,
+                     stream, static_cast<const uint4*>(V), mask, d->n, d->Hkv, tau_v, out->v_codes,
+                     out->v_params);
+}
+
+template <int BITS>
+void launch_dense_g(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask,
+                    const kvs_cache* out, uint32_t tk, uint32_t tv, hipStream_t s) {
+  switch (d->group) {
+    case 32: launch_dense<BITS, 32>(d, K, V, mask, out, tk, tv, s); break;
+    case 64: launch_dense<BITS, 64>(d, K, V, mask, out, tk, tv, s); break;
+    default: launch_dense<BITS, 128>(d, K, V, mask, out, tk, tv, s); break;
+  }
+}
+
+}  // namespace
+
+extern "C" kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const void* V,
+                                       const uint8_t* keep_mask, const kvs_cache* out,
+                                       void* workspace, void* stream) {
+  const kvs_status st = kvs::validate_desc(desc);
+  if (st != KVS_OK) return st;
+  if (!K || !V || !keep_mask || !out) return KVS_ERR_INVALID;
+  if (!out->k_codes || !out->v_codes || !out->k_params || !out->v_params || !out->keep_idx ||
+      !out->keep_cnt || !out->keep_mask || !out->status)
+    return KVS_ERR_INVALID;
+  if (desc->keep_cap > 0 && (!out->keep_k || !out->keep_v)) return KVS_ERR_INVALID;
+  if (desc->sparse_frac > 0.0f) return KVS_ERR_UNSUPPORTED;
+  (void)workspace;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  const uint32_t no_tau = 0x8000u;   // no fp16 magnitude pattern reaches it: nothing is isolated
+  switch (desc->bits) {
+    case 2: launch_dense_g<2>(desc, K, V, keep_mask, out, no_tau, no_tau, s); break;
+    case 3: launch_dense_g<3>(desc, K, V, keep_mask, out, no_tau, no_tau, s); break;
+    default: launch_dense_g<4>(desc, K, V, keep_mask, out, no_tau, no_tau, s); break;
+  }
+  hipLaunchKernelGGL(keep_index_kernel, dim3(desc->B), dim3(kIndexThreads), 0, s, keep_mask, desc->n,
+                     desc->keep_cap, out->keep_idx, out->keep_cnt, out->keep_mask, out->status);
+  if (desc->keep_cap > 0)
+    hipLaunchKernelGGL(keep_gather_kernel, dim3(desc->B * desc->Hkv * desc->keep_cap), dim3(KVS_WAVE), 0, s,
+                       static_cast<const uint32_t*>(K), static_cast<const uint32_t*>(V), desc->n, desc->Hkv,
+                       desc->keep_cap, out->keep_idx, static_cast<uint32_t*>(out->keep_k),
+                       static_cast<uint32_t*>(out->keep_v));
+  return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
+}

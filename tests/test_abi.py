@@ -1,0 +1,87 @@
+"""Host-side checks of the C-ABI library: it loads, exports every declared symbol, sizes buffers
+as documented and rejects bad arguments before anything is launched (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2508_04257_amd import binding as kb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "kvs.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvs_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert {"kvs_predict_sinks", "kvs_quantize_kv", "kvs_decode_attn", "kvs_cache_bytes",
+            "kvs_workspace_bytes"} <= set(names)
+    L = kb.lib()
+    for name in names:
+        assert hasattr(L, name), name
+    assert L.kvs_version() >= 100
+    assert kb.status_string(kb.KVS_ERR_CAPACITY) == "capacity exceeded"
+
+
+def test_struct_layouts_match_the_header():
+    assert C.sizeof(kb.KvsDesc) == 48                  # 9 x 4 bytes, padding, one int64
+    assert kb.KvsDesc.sparse_cap.offset == 40
+    assert C.sizeof(kb.KvsCache) == 16 * 8
+    text = open(os.path.join(ROOT, "include", "kvs.h")).read()
+    body = text[text.index("typedef struct kvs_cache {"):text.index("} kvs_cache;")]
+    fields = re.findall(r"\b(\w+);", body)
+    assert tuple(fields) == kb.CACHE_FIELD_NAMES
+
+
+def test_cache_bytes_for_the_headline_workload():
+    d = kb.make_desc(B=8, n=4096, Hq=32, Hkv=32, bits=4, group=128, keep_cap=5)
+    s = kb.kvs_cache_bytes(d)
+    assert s["k_codes"] == s["v_codes"] == 8 * 32 * 4096 * 64          # half a byte per element
+    assert s["k_params"] == 8 * 32 * 32 * 128 * 4 and s["v_params"] == 8 * 32 * 4096 * 4
+    assert s["keep_k"] == 8 * 32 * 5 * 256 and s["keep_idx"] == 8 * 5 * 4
+    assert s["keep_mask"] == 8 * 4096 and s["k_col"] == 0 and s["status"] == 16
+    d3 = kb.make_desc(B=16, n=8192, Hq=32, Hkv=8, bits=3, group=64, keep_cap=4)
+    assert kb.kvs_cache_bytes(d3)["k_codes"] == 16 * 8 * 8192 * 13 * 4   # 13 words per 128 codes
+    d2 = kb.make_desc(B=4, n=32768, Hq=32, Hkv=32, bits=2, group=32, keep_cap=24)
+    assert kb.kvs_cache_bytes(d2)["v_params"] == 4 * 32 * 32768 * 4 * 4
+    assert kb.kvs_workspace_bytes(d) >= 8 * 32 * kb.kvs_decode_splits(d) * 130 * 4
+    assert kb.kvs_decode_splits(d) == 8
+
+
+@pytest.mark.parametrize("field,value,expected", [
+    ("D", 64, kb.KVS_ERR_UNSUPPORTED), ("bits", 5, kb.KVS_ERR_UNSUPPORTED),
+    ("group", 16, kb.KVS_ERR_UNSUPPORTED), ("n", 1000, kb.KVS_ERR_UNSUPPORTED),
+    ("n", 0, kb.KVS_ERR_INVALID), ("Hkv", 5, kb.KVS_ERR_INVALID), ("keep_cap", -1, kb.KVS_ERR_INVALID),
+    ("Hq", 512, kb.KVS_ERR_UNSUPPORTED), ("sparse_frac", 1.5, kb.KVS_ERR_INVALID),
+])
+def test_bad_descriptors_are_rejected_on_the_host(field, value, expected):
+    d = kb.make_desc(B=2, n=1024, Hq=32, Hkv=32, bits=4, group=128, keep_cap=2)
+    setattr(d, field, value)
+    sizes = (C.c_size_t * kb.KVS_CACHE_FIELDS)()
+    assert kb.lib().kvs_cache_bytes(C.byref(d), sizes) == expected
+    assert kb.kvs_workspace_bytes(d) == 0
+    # the compute entry points refuse the same descriptor before touching any pointer
+    cache = kb.KvsCache()
+    assert kb.lib().kvs_quantize_kv(C.byref(d), 16, 16, 16, C.byref(cache), None, None) == expected
+    assert kb.lib().kvs_decode_attn(C.byref(d), 16, C.byref(cache), 16, None, 16, None) == expected
+
+
+def test_null_pointers_are_rejected_on_the_host():
+    d = kb.make_desc(B=2, n=1024, Hq=32, Hkv=32, bits=4, group=128, keep_cap=2)
+    cache = kb.KvsCache()                              # all NULL
+    L = kb.lib()
+    assert L.kvs_quantize_kv(C.byref(d), None, None, None, C.byref(cache), None, None) == kb.KVS_ERR_INVALID
+    assert L.kvs_quantize_kv(C.byref(d), 16, 16, 16, C.byref(cache), None, None) == kb.KVS_ERR_INVALID
+    assert L.kvs_decode_attn(C.byref(d), 16, C.byref(cache), 16, None, 16, None) == kb.KVS_ERR_INVALID
+    assert L.kvs_quantize_kv(None, 16, 16, 16, C.byref(cache), None, None) == kb.KVS_ERR_INVALID
+    ch = (C.c_int32 * 1)(5000)
+    assert L.kvs_predict_sinks(16, 1, 128, 4096, ch, 1, 2, 0, 16, 16, None) == kb.KVS_ERR_INVALID   # channel >= d
+    ch = (C.c_int32 * 1)(7)
+    assert L.kvs_predict_sinks(None, 1, 128, 4096, ch, 1, 2, 0, 16, 16, None) == kb.KVS_ERR_INVALID
+    assert L.kvs_predict_sinks(16, 1, 128, 4096, ch, 1, 200, 0, 16, 16, None) == kb.KVS_ERR_INVALID  # k > n
+    assert L.kvs_predict_sinks(16, 1, 1 << 20, 4096, ch, 1, 2, 0, 16, 16, None) == kb.KVS_ERR_UNSUPPORTED

@@ -1,0 +1,285 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the same seeded inputs.
+
+Bars: sink indices, keep masks, packed codes, parameter words and keep rows bit-exact; attention
+outputs within 2e-3 max relative error per row (max_c |o - o_ref| / max_c |o_ref|).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvsink_oracle as O
+from paper_2508_04257_amd import binding as kb
+from paper_2508_04257_amd import pipeline, synth
+from tests.helpers import random_fp16
+
+pytestmark = pytest.mark.gpu
+
+OUT_TOL = 2e-3
+DEV = "cuda"
+
+
+def u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def row_rel_err(got, ref64):
+    got = got.astype(np.float64)
+    return float((np.abs(got - ref64).max(axis=-1) / np.abs(ref64).max(axis=-1)).max())
+
+
+def hip_quantize(K, V, mask, bits, G, keep_cap, Hq=None):
+    """numpy in -> (desc, cache buffers) after kvs_quantize_kv."""
+    B, H, n, D = K.shape
+    desc = kb.make_desc(B, n, Hq or H, H, bits, G, keep_cap)
+    cache = kb.alloc_cache(desc, DEV)
+    ws = kb.alloc_workspace(desc, DEV)
+    kb.kvs_quantize_kv(desc, torch.from_numpy(K).to(DEV), torch.from_numpy(V).to(DEV),
+                       torch.from_numpy(mask).to(DEV), cache, ws)
+    torch.cuda.synchronize()
+    return desc, cache, ws
+
+
+def assert_cache_equal(cache, ref: O.Cache, check_status=True):
+    W = O.words_per_128(ref.bits)
+    B, H, n, D, G, cap = ref.B, ref.Hkv, ref.n, ref.D, ref.group, ref.keep_cap
+    assert np.array_equal(u32(cache.k_codes)[:ref.k_codes.size].reshape(ref.k_codes.shape), ref.k_codes)
+    assert np.array_equal(u32(cache.v_codes)[:ref.v_codes.size].reshape(ref.v_codes.shape), ref.v_codes)
+    assert np.array_equal(u32(cache.k_params)[:ref.k_params.size].reshape(ref.k_params.shape), ref.k_params)
+    assert np.array_equal(u32(cache.v_params)[:ref.v_params.size].reshape(ref.v_params.shape), ref.v_params)
+    assert np.array_equal(cache.keep_cnt.cpu().numpy()[:B], ref.keep_cnt)
+    assert np.array_equal(cache.keep_mask.cpu().numpy()[:B * n].reshape(B, n), ref.keep_mask)
+    if check_status:
+        assert int(cache.status.cpu()[0]) == ref.status
+    if cap and ref.status == O.STATUS_OK:
+        assert np.array_equal(cache.keep_idx.cpu().numpy()[:B * cap].reshape(B, cap), ref.keep_idx)
+        kk = cache.keep_k.cpu().numpy().view(np.uint16)[:ref.keep_k.size].reshape(ref.keep_k.shape)
+        kv = cache.keep_v.cpu().numpy().view(np.uint16)[:ref.keep_v.size].reshape(ref.keep_v.shape)
+        assert np.array_equal(kk, ref.keep_k.view(np.uint16))
+        assert np.array_equal(kv, ref.keep_v.view(np.uint16))
+
+
+def hip_decode(desc, cache, ws, q):
+    out = torch.empty((desc.B, desc.Hq, 128), dtype=torch.float16, device=DEV)
+    lse = torch.empty((desc.B, desc.Hq), dtype=torch.float32, device=DEV)
+    kb.kvs_decode_attn(desc, torch.from_numpy(q).to(DEV), cache, out, lse, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), lse.cpu().numpy()
+
+
+# ------------------------------------------------------------------------------ prediction
+@pytest.mark.parametrize("name", ["cfg0_kvsink", "cfg0_pfn"])
+def test_predict_worked_example(name):
+    w = synth.WORKLOADS[name]
+    H = synth.make_hidden(w, DEV)
+    buf = pipeline.alloc_step(w, DEV)
+    pipeline.predict(w, H, buf)
+    torch.cuda.synchronize()
+    ref_idx, ref_mask = O.predict_sinks(H.cpu().numpy(), w.channels, w.k_sinks, w.first_n)
+    assert np.array_equal(buf.keep_mask.cpu().numpy(), ref_mask)
+    if w.k_sinks:
+        assert np.array_equal(buf.sink_idx.cpu().numpy(), ref_idx)
+        assert buf.sink_idx.cpu().numpy().tolist() == [[0, 14]]
+
+
+@pytest.mark.parametrize("B,n,d,channels,k,first_n", [
+    (3, 97, 16, [5], 5, 0),          # ragged length, ties
+    (2, 1000, 64, [3, 60], 20, 7),   # two channels, union with first-N
+    (1, 1, 8, [0], 1, 1),            # single token
+    (2, 4096, 32, [31], 0, 16),      # PFN only
+    (1, 65536, 4, [2], 8, 0),        # longest supported sequence
+    (1, 3000, 8, [1], 1024, 0),      # largest supported k
+])
+def test_predict_edge_cases(B, n, d, channels, k, first_n):
+    rng = np.random.default_rng(n + k)
+    H = random_fp16(rng, (B, n, d))
+    H[:, :, channels[0]] = (np.round(H[:, :, channels[0]].astype(np.float32) * 4) / 4).astype(np.float16)  # many ties
+    if n > 50:
+        H[0, 40, channels[0]], H[0, 41, channels[0]] = 9.0, -9.0
+    ref_idx, ref_mask = O.predict_sinks(H, channels, k, first_n)
+    Hd = torch.from_numpy(H).to(DEV)
+    mask = torch.full((B, n), 7, dtype=torch.uint8, device=DEV)
+    idx = torch.full((B, k), -5, dtype=torch.int32, device=DEV) if k else None
+    kb.kvs_predict_sinks(Hd, channels, k, first_n, idx, mask)
+    torch.cuda.synchronize()
+    assert np.array_equal(mask.cpu().numpy(), ref_mask)
+    if k:
+        assert np.array_equal(idx.cpu().numpy(), ref_idx)
+
+
+# ------------------------------------------------------------------------------ quantise + decode, small
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("G", [32, 64, 128])
+@pytest.mark.parametrize("rep", [1, 4])
+def test_quantize_and_decode_small(bits, G, rep):
+    rng = np.random.default_rng(100 * bits + G + rep)
+    B, H, n = 2, 2, 1152                                  # 9 Value tiles: uneven splits
+    K, V = random_fp16(rng, (B, H, n, 128)), random_fp16(rng, (B, H, n, 128), "wide")
+    K[:, :, :, [3, 77]] *= np.float16(10)
+    mask = np.zeros((B, n), np.uint8)
+    mask[0, [0, 14, 500]] = 1
+    mask[1, [0, 1, 2, 3, 1151]] = 1
+    q = random_fp16(rng, (B, H * rep, 128))
+    desc, cache, ws = hip_quantize(K, V, mask, bits, G, keep_cap=6, Hq=H * rep)
+    ref = O.quantize_kv(K, V, mask, bits, G, keep_cap=6)
+    assert_cache_equal(cache, ref)
+    out, lse = hip_decode(desc, cache, ws, q)
+    _, ref_lse, ref64 = O.decode_attn(q, ref, Hq=H * rep)
+    assert row_rel_err(out, ref64) <= OUT_TOL
+    assert np.abs(lse - ref_lse).max() <= 1e-3
+    # same call again: identical bytes (no order-dependent arithmetic)
+    out2, _ = hip_decode(desc, cache, ws, q)
+    assert np.array_equal(out.view(np.uint16), out2.view(np.uint16))
+
+
+@pytest.mark.parametrize("rep", [2, 8])
+def test_other_gqa_ratios(rep):
+    rng = np.random.default_rng(rep)
+    B, H, n = 1, 2, 512
+    K, V = random_fp16(rng, (B, H, n, 128)), random_fp16(rng, (B, H, n, 128))
+    mask = np.zeros((B, n), np.uint8)
+    mask[0, [0, 14]] = 1
+    q = random_fp16(rng, (B, H * rep, 128))
+    desc, cache, ws = hip_quantize(K, V, mask, 4, 128, keep_cap=2, Hq=H * rep)
+    ref = O.quantize_kv(K, V, mask, 4, 128, keep_cap=2)
+    assert_cache_equal(cache, ref)
+    out, _ = hip_decode(desc, cache, ws, q)
+    assert row_rel_err(out, O.decode_attn(q, ref, Hq=H * rep)[2]) <= OUT_TOL
+
+
+@pytest.mark.parametrize("case", ["group_all_kept", "all_kept", "none_kept", "constant", "zeros",
+                                  "huge", "tiny", "overflow"])
+def test_degenerate_inputs(case):
+    rng = np.random.default_rng(7)
+    B, H, n, bits, G, cap = 1, 2, 256, 4, 128, 4
+    K, V = random_fp16(rng, (B, H, n, 128)), random_fp16(rng, (B, H, n, 128))
+    mask = np.zeros((B, n), np.uint8)
+    mask[0, [0, 14]] = 1
+    if case == "group_all_kept":                       # first Key group has no unmasked token
+        mask[0, :128] = 1
+        cap = 128
+    elif case == "all_kept":                           # nothing is quantised: exact attention
+        mask[:] = 1
+        cap = 256
+    elif case == "none_kept":
+        mask[:] = 0
+        cap = 0
+    elif case == "constant":
+        K[:] = np.float16(0.37)
+        V[:, :, :, :64] = np.float16(-2.5)
+    elif case == "zeros":
+        K[:] = 0
+        V[:] = 0
+    elif case == "huge":
+        K = random_fp16(rng, (B, H, n, 128), "positive")
+        V = np.clip(rng.standard_normal((B, H, n, 128)) * 20000, -60000, 60000).astype(np.float16)
+    elif case == "tiny":
+        K = random_fp16(rng, (B, H, n, 128), "tiny")
+        V = random_fp16(rng, (B, H, n, 128), "tiny")
+    elif case == "overflow":
+        mask[0, 100:110] = 1                            # 12 kept tokens, capacity 4
+    q = (random_fp16(rng, (B, H, 128)) * np.float16(0.01 if case == "huge" else 1)).astype(np.float16)
+    desc, cache, ws = hip_quantize(K, V, mask, bits, G, keep_cap=cap)
+    ref = O.quantize_kv(K, V, mask, bits, G, keep_cap=cap)
+    if case == "overflow":
+        assert ref.status == O.STATUS_CAPACITY and int(cache.status.cpu()[0]) == kb.KVS_ERR_CAPACITY
+        assert np.array_equal(cache.keep_cnt.cpu().numpy()[:B], ref.keep_cnt)
+        return
+    assert_cache_equal(cache, ref)
+    out, lse = hip_decode(desc, cache, ws, q)
+    _, ref_lse, ref64 = O.decode_attn(q, ref, Hq=H)
+    assert np.all(np.isfinite(out))
+    if case == "zeros":
+        assert not out.any()
+    elif case == "tiny":
+        assert np.abs(out.astype(np.float64) - ref64).max() <= 2e-7    # below fp16 resolution of the outputs
+    else:
+        assert row_rel_err(out, ref64) <= OUT_TOL
+    assert np.abs(lse - ref_lse).max() <= 2e-3 * max(1.0, np.abs(ref_lse).max())
+
+
+def test_whole_path_on_the_worked_example_workload():
+    for name in ("cfg0_kvsink", "cfg0_pfn"):
+        w = synth.WORKLOADS[name]
+        H, (K, V), q = synth.make_hidden(w, DEV), synth.make_kv(w, DEV), synth.make_query(w, DEV)
+        buf = pipeline.alloc_step(w, DEV)
+        pipeline.run_step(w, H, K, V, q, buf)
+        torch.cuda.synchronize()
+        _, ref_mask = O.predict_sinks(H.cpu().numpy(), w.channels, w.k_sinks, w.first_n)
+        ref = O.quantize_kv(K.cpu().numpy(), V.cpu().numpy(), ref_mask, w.bits, w.group, buf.desc.keep_cap)
+        assert_cache_equal(buf.cache, ref)
+        ref64 = O.decode_attn(q.cpu().numpy(), ref, Hq=w.Hq)[2]
+        assert row_rel_err(buf.out.cpu().numpy(), ref64) <= OUT_TOL
+
+
+# ------------------------------------------------------------------------------ full-size workloads, sampled
+def _sampled_full_size(name, n_pairs=3):
+    """Runs the whole path at the benchmark's launch configuration and checks sampled (b, h)
+    slices against the oracle, plus properties that hold at any size."""
+    w = synth.WORKLOADS[name]
+    H, (K, V), q = synth.make_hidden(w, DEV), synth.make_kv(w, DEV), synth.make_query(w, DEV)
+    buf = pipeline.alloc_step(w, DEV)
+    pipeline.run_step(w, H, K, V, q, buf)
+    torch.cuda.synchronize()
+    assert int(buf.cache.status.cpu()[0]) == 0
+
+    # prediction: full comparison (the oracle only needs the listed channels)
+    Hc = H[:, :, list(w.channels)].cpu().numpy()
+    ref_idx, ref_mask = O.predict_sinks(Hc, range(len(w.channels)), w.k_sinks, w.first_n)
+    assert np.array_equal(buf.keep_mask.cpu().numpy(), ref_mask)
+    assert np.array_equal(buf.sink_idx.cpu().numpy(), ref_idx)
+    assert np.array_equal(np.sort(ref_idx, axis=1), synth.sink_positions(w))   # the planted tokens
+
+    W = O.words_per_128(w.bits)
+    cap = buf.desc.keep_cap
+    def shaped(t, *shape):
+        return t[:int(np.prod(shape))].view(*shape)
+
+    kc = shaped(buf.cache.k_codes, w.B, w.Hkv, w.n // 64, W, 64)
+    vc = shaped(buf.cache.v_codes, w.B, w.Hkv, w.n // 128, W, 128)
+    kp = shaped(buf.cache.k_params, w.B, w.Hkv, w.n // w.group, 128)
+    vp = shaped(buf.cache.v_params, w.B, w.Hkv, w.n, 128 // w.group)
+    keep_k = shaped(buf.cache.keep_k, w.B, w.Hkv, cap, 128)
+    keep_v = shaped(buf.cache.keep_v, w.B, w.Hkv, cap, 128)
+    out = buf.out.cpu().numpy()
+    rng = np.random.default_rng(5)
+    rep = w.Hq // w.Hkv
+    worst = 0.0
+    for _ in range(n_pairs):
+        b, h = int(rng.integers(0, w.B)), int(rng.integers(0, w.Hkv))
+        Ks, Vs = K[b:b + 1, h:h + 1].cpu().numpy(), V[b:b + 1, h:h + 1].cpu().numpy()
+        ref = O.quantize_kv(Ks, Vs, ref_mask[b:b + 1], w.bits, w.group, cap)
+        assert np.array_equal(u32(kc[b, h]), ref.k_codes[0, 0])
+        assert np.array_equal(u32(vc[b, h]), ref.v_codes[0, 0])
+        assert np.array_equal(u32(kp[b, h]), ref.k_params[0, 0])
+        assert np.array_equal(u32(vp[b, h]), ref.v_params[0, 0])
+        assert np.array_equal(keep_k[b, h].cpu().numpy().view(np.uint16), ref.keep_k[0, 0].view(np.uint16))
+        assert np.array_equal(keep_v[b, h].cpu().numpy().view(np.uint16), ref.keep_v[0, 0].view(np.uint16))
+        qs = q[b:b + 1, h * rep:(h + 1) * rep].cpu().numpy()
+        ref64 = O.decode_attn(qs, ref, Hq=rep)[2]
+        worst = max(worst, row_rel_err(out[b:b + 1, h * rep:(h + 1) * rep], ref64))
+    assert worst <= OUT_TOL
+
+    # properties at full size
+    idx = shaped(buf.cache.keep_idx, w.B, cap).cpu().numpy()
+    cnt = buf.cache.keep_cnt.cpu().numpy()[:w.B]
+    assert np.array_equal(cnt, ref_mask.sum(1))
+    for b in range(w.B):
+        assert np.array_equal(idx[b, :cnt[b]], np.nonzero(ref_mask[b])[0]) and np.all(idx[b, cnt[b]:] == -1)
+        rows = torch.as_tensor(idx[b, :cnt[b]], device=DEV, dtype=torch.long)
+        assert torch.equal(keep_k[b, :, :cnt[b]], K[b][:, rows]) and torch.equal(keep_v[b, :, :cnt[b]], V[b][:, rows])
+    assert bool(torch.isfinite(buf.out).all()) and bool(torch.isfinite(buf.lse).all())
+    # a convex combination of value rows stays inside their range
+    assert float(buf.out.float().abs().max()) <= float(V.float().abs().max()) * 1.01
+    return worst
+
+
+def test_full_size_headline_workload():
+    _sampled_full_size("cfg1")
+
+
+def test_full_size_gqa_int3_workload():
+    _sampled_full_size("cfg2", n_pairs=2)
+
+
+def test_full_size_long_context_int2_workload():
+    _sampled_full_size("cfg3", n_pairs=1)
