@@ -253,9 +253,12 @@ def unpack_v(words: np.ndarray, bits: int) -> np.ndarray:
 def sparse_threshold(X: np.ndarray, keep_mask: np.ndarray, frac: float) -> int:
     """X fp16 [B, H, n, D], keep_mask [B, n].  Returns tau as a 15-bit fp16 magnitude pattern
     (0x7FFF + 1 = 32768 when nothing is isolated)."""
-    mag = (np.asarray(X).view(np.uint16) & np.uint16(0x7FFF))
-    live = np.broadcast_to((np.asarray(keep_mask) == 0)[:, None, :, None], mag.shape)
-    hist = np.bincount(mag[live].astype(np.int64), minlength=32768)
+    X = np.asarray(X)
+    hist = np.zeros(32768, np.int64)
+    for b in range(X.shape[0]):                                   # one sequence at a time (memory)
+        mag = X[b].view(np.uint16) & np.uint16(0x7FFF)            # [H, n, D]
+        live = np.asarray(keep_mask[b]) == 0
+        hist += np.bincount(mag[:, live, :].ravel(), minlength=32768)
     count = int(hist.sum())
     m = int(math.ceil(float(np.float32(frac)) * count))
     if m <= 0:
@@ -290,7 +293,9 @@ class Cache:
     keep_cnt: np.ndarray           # int32 [B]
     keep_mask: np.ndarray          # uint8 [B, n]
     status: int = STATUS_OK
-    # dense-and-sparse part (None when off): CSR over rows (b, h, t), ascending columns
+    # dense-and-sparse part (None when off).  Keys: CSR over rows (b, h, token), column =
+    # channel.  Values: CSR over rows (b, h, 128-token tile, channel), column = token inside
+    # the tile - the same transposition as the Value code tiles.  Columns ascend in a row.
     k_rowptr: Optional[np.ndarray] = None
     k_col: Optional[np.ndarray] = None
     k_val: Optional[np.ndarray] = None
@@ -304,9 +309,14 @@ class Cache:
     v_codes_logical: Optional[np.ndarray] = None
 
 
-def _csr_from_mask(X: np.ndarray, outlier: np.ndarray):
-    """Rows (b, h, t) in that order, ascending column; col uint16, val = the original fp16."""
+def _csr_from_mask(X: np.ndarray, outlier: np.ndarray, by_channel: bool):
+    """CSR of the flagged entries, col uint16, val = the original fp16.
+    by_channel False: rows (b, h, t), column = channel.
+    by_channel True:  rows (b, h, T, c) with T the 128-token tile, column = t - 128 T."""
     B, H, n, D = X.shape
+    if by_channel:
+        X = X.reshape(B, H, n // V_TILE, V_TILE, D).transpose(0, 1, 2, 4, 3)
+        outlier = outlier.reshape(B, H, n // V_TILE, V_TILE, D).transpose(0, 1, 2, 4, 3)
     flat = outlier.reshape(B * H * n, D)
     counts = flat.sum(axis=1)
     rowptr = np.zeros(B * H * n + 1, np.int64)
@@ -317,9 +327,12 @@ def _csr_from_mask(X: np.ndarray, outlier: np.ndarray):
 
 
 def quantize_kv(K: np.ndarray, V: np.ndarray, keep_mask: np.ndarray, bits: int, group: int,
-                keep_cap: int, sparse_frac: float = 0.0, sparse_cap: Optional[int] = None) -> Cache:
+                keep_cap: int, sparse_frac: float = 0.0, sparse_cap: Optional[int] = None,
+                taus: Optional[tuple] = None) -> Cache:
     """Algorithm 1's two quantise steps for one layer: K and V rows of tokens outside the
-    keep set are quantised, rows inside it are copied unchanged into the fp16 side buffer."""
+    keep set are quantised, rows inside it are copied unchanged into the fp16 side buffer.
+    ``taus`` = (k_tau, v_tau) supplies thresholds that ``sparse_threshold`` found on a larger
+    tensor of which K, V are a slice (the threshold is a property of the whole layer)."""
     K = np.asarray(K)
     V = np.asarray(V)
     assert K.dtype == np.float16 and V.dtype == np.float16 and K.shape == V.shape
@@ -331,7 +344,9 @@ def quantize_kv(K: np.ndarray, V: np.ndarray, keep_mask: np.ndarray, bits: int, 
     status = STATUS_OK
 
     tau_k = tau_v = 32768
-    if sparse_frac > 0:
+    if sparse_frac > 0 and taus is not None:
+        tau_k, tau_v = taus
+    elif sparse_frac > 0:
         tau_k = sparse_threshold(K, keep_mask, sparse_frac)
         tau_v = sparse_threshold(V, keep_mask, sparse_frac)
     not_kept = (~kept)[:, None, :, None]
@@ -371,8 +386,8 @@ def quantize_kv(K: np.ndarray, V: np.ndarray, keep_mask: np.ndarray, bits: int, 
                   keep_k, keep_v, keep_idx, keep_cnt, keep_mask, status,
                   k_tau=tau_k, v_tau=tau_v, k_codes_logical=k_log, v_codes_logical=v_log)
     if sparse_frac > 0:
-        cache.k_rowptr, cache.k_col, cache.k_val = _csr_from_mask(K, out_k)
-        cache.v_rowptr, cache.v_col, cache.v_val = _csr_from_mask(V, out_v)
+        cache.k_rowptr, cache.k_col, cache.k_val = _csr_from_mask(K, out_k, by_channel=False)
+        cache.v_rowptr, cache.v_col, cache.v_val = _csr_from_mask(V, out_v, by_channel=True)
         if sparse_cap is not None and max(len(cache.k_col), len(cache.v_col)) > sparse_cap:
             cache.status = STATUS_CAPACITY
     return cache
@@ -395,12 +410,14 @@ def effective_kv(cache: Cache, b: int, h: int):
     Kd = Kd.astype(np.float64)
     Vd = Vd.astype(np.float64)
     if cache.k_rowptr is not None:
-        base = (b * cache.Hkv + h) * n
-        for X, rowptr, col, val in ((Kd, cache.k_rowptr, cache.k_col, cache.k_val),
-                                    (Vd, cache.v_rowptr, cache.v_col, cache.v_val)):
-            lo, hi = int(rowptr[base]), int(rowptr[base + n])
-            rows = np.repeat(np.arange(n), np.diff(rowptr[base:base + n + 1].astype(np.int64)))
-            X[rows, col[lo:hi].astype(np.int64)] = val[lo:hi].astype(np.float64)
+        base = (b * cache.Hkv + h) * n                      # both CSRs have n rows per (b, h)
+        lo, hi = int(cache.k_rowptr[base]), int(cache.k_rowptr[base + n])
+        rows = np.repeat(np.arange(n), np.diff(cache.k_rowptr[base:base + n + 1].astype(np.int64)))
+        Kd[rows, cache.k_col[lo:hi].astype(np.int64)] = cache.k_val[lo:hi].astype(np.float64)
+        lo, hi = int(cache.v_rowptr[base]), int(cache.v_rowptr[base + n])
+        rows = np.repeat(np.arange(n), np.diff(cache.v_rowptr[base:base + n + 1].astype(np.int64)))
+        tile, chan = rows // D, rows % D                    # row = tile * 128 + channel
+        Vd[tile * V_TILE + cache.v_col[lo:hi].astype(np.int64), chan] = cache.v_val[lo:hi].astype(np.float64)
     for j in range(min(int(cache.keep_cnt[b]), cache.keep_cap)):
         t = int(cache.keep_idx[b, j])
         Kd[t] = cache.keep_k[b, h, j].astype(np.float64)

@@ -31,12 +31,19 @@ __device__ inline float code_at(uint32_t word, int j) {
   return static_cast<float>((word >> Fmt<BITS>::shift(j)) & static_cast<uint32_t>(Fmt<BITS>::qmax));
 }
 
-template <int BITS, int G, int R>
+// CSR arrays of the isolated fp16 outliers (dense-and-sparse caches only).
+struct SparseView {
+  const int32_t* k_rowptr; const uint16_t* k_col; const uint16_t* k_val;   // rows (b, h, token), col = channel
+  const int32_t* v_rowptr; const uint16_t* v_col; const uint16_t* v_val;   // rows (b, h, tile, channel), col = token in tile
+  int cap;   // entries the col / val arrays hold; row pointers past it (reported overflow) are not followed
+};
+
+template <int BITS, int G, int R, bool SPARSE>
 __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
     const uint16_t* __restrict__ q, const uint32_t* __restrict__ k_codes,
     const uint32_t* __restrict__ v_codes, const uint32_t* __restrict__ k_params,
     const uint32_t* __restrict__ v_params, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
-    int rep, int splits, int split_tokens, float* __restrict__ ws) {
+    int rep, int splits, int split_tokens, float* __restrict__ ws, SparseView sp) {
   constexpr int W = Fmt<BITS>::W, cpw = Fmt<BITS>::cpw;
   constexpr int NGK = 128 / G;   // Key token groups per 128-token chunk
   constexpr int NGC = 128 / G;   // Value channel groups per row
@@ -46,6 +53,12 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
   __shared__ float qs[kWaves][NGK][R][128];          // query x Key scale, per wave and group
   __shared__ float wl[kWaves][R][NGC][128];          // softmax weight x Value scale, per token
   __shared__ float red_m[kWaves][R], red_l[kWaves][R];
+  // Dense-and-sparse only: an isolated slot holds code 0, i.e. it dequantises to -scale * zero.
+  // Replacing it by its fp16 value adds  q (val + scale zero)  to a score and
+  // p (val + scale zero)  to an output channel.
+  __shared__ float kz[SPARSE ? kWaves : 1][NGK][SPARSE ? 128 : 1];      // Key zero points
+  __shared__ float pl[SPARSE ? kWaves : 1][R][SPARSE ? 128 : 1];        // softmax weights
+  __shared__ float wz[SPARSE ? kWaves : 1][R][NGC][SPARSE ? 128 : 1];   // weight x Value scale x zero
 
   const int tid = threadIdx.x, lane = tid & (KVS_WAVE - 1), wave = tid / KVS_WAVE;
   const int head_groups = rep / R;
@@ -102,6 +115,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
             qs[wave][gl][r][c] = v;
             part[r] += v * static_cast<float>(z);
           }
+          if constexpr (SPARSE) kz[wave][gl][c] = static_cast<float>(z);
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) kbias[gl][r] = kvs::wave_sum(part[r]);
@@ -131,6 +145,16 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
 #pragma unroll
               for (int r = 0; r < R; ++r) dot[r] += qs[wave][gl][r][c] * f;
             }
+          }
+        }
+        if constexpr (SPARSE) {
+          const size_t row = bh * n + static_cast<size_t>(t0 + tl);
+          const int e1 = min(sp.k_rowptr[row + 1], sp.cap);
+          for (int e = sp.k_rowptr[row]; e < e1; ++e) {
+            const int c = sp.k_col[e];
+            const float v = kvs::half_bits_to_float(sp.k_val[e]);
+#pragma unroll
+            for (int r = 0; r < R; ++r) dot[r] += qf[r][c] * v + qs[wave][gl][r][c] * kz[wave][gl][c];
           }
         }
         const bool kept = mask_b[t0 + tl] != 0;
@@ -169,7 +193,12 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
           wl[wave][r][g][lane] = w0;
           wl[wave][r][g][64 + lane] = w1;
           zacc[r][g] = zacc[r][g] * alpha + w0 * static_cast<float>(z0) + w1 * static_cast<float>(z1);
+          if constexpr (SPARSE) {
+            wz[wave][r][g][lane] = w0 * static_cast<float>(z0);
+            wz[wave][r][g][64 + lane] = w1 * static_cast<float>(z1);
+          }
         }
+        if constexpr (SPARSE) { pl[wave][r][lane] = p0; pl[wave][r][64 + lane] = p1; }
       }
     }
     __syncthreads();
@@ -192,6 +221,20 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
               acc[r][0] += wl[wave][r][g0][tl] * f0;
               acc[r][1] += wl[wave][r][g1][tl] * f1;
             }
+          }
+        }
+      }
+      if constexpr (SPARSE) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const int g = half ? g1 : g0;
+          const size_t row = (bh * (n / KVS_V_TILE) + static_cast<size_t>(t0 / KVS_V_TILE)) * 128 + lane + 64 * half;
+          const int e1 = min(sp.v_rowptr[row + 1], sp.cap);
+          for (int e = sp.v_rowptr[row]; e < e1; ++e) {
+            const int tl = sp.v_col[e];
+            const float v = kvs::half_bits_to_float(sp.v_val[e]);
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc[r][half] += pl[wave][r][tl] * v + wz[wave][r][g][tl];
           }
         }
       }
@@ -282,9 +325,17 @@ void launch_partial(const kvs_desc* d, const kvs::DecodeGeometry& geo, const voi
                     float* ws, hipStream_t s) {
   const int rep = d->Hq / d->Hkv;
   const int grid = d->B * d->Hkv * (rep / R) * geo.splits;
-  hipLaunchKernelGGL((decode_partial_kernel<BITS, G, R>), dim3(grid), dim3(kThreads), 0, s,
-                     static_cast<const uint16_t*>(q), c->k_codes, c->v_codes, c->k_params, c->v_params,
-                     c->keep_mask, d->n, d->Hkv, rep, geo.splits, geo.split_tokens, ws);
+  SparseView sp{c->k_rowptr, c->k_col, static_cast<const uint16_t*>(c->k_val),
+                c->v_rowptr, c->v_col, static_cast<const uint16_t*>(c->v_val),
+                static_cast<int>(d->sparse_cap)};
+  if (d->sparse_frac > 0.0f)
+    hipLaunchKernelGGL((decode_partial_kernel<BITS, G, R, true>), dim3(grid), dim3(kThreads), 0, s,
+                       static_cast<const uint16_t*>(q), c->k_codes, c->v_codes, c->k_params, c->v_params,
+                       c->keep_mask, d->n, d->Hkv, rep, geo.splits, geo.split_tokens, ws, sp);
+  else
+    hipLaunchKernelGGL((decode_partial_kernel<BITS, G, R, false>), dim3(grid), dim3(kThreads), 0, s,
+                       static_cast<const uint16_t*>(q), c->k_codes, c->v_codes, c->k_params, c->v_params,
+                       c->keep_mask, d->n, d->Hkv, rep, geo.splits, geo.split_tokens, ws, sp);
 }
 
 template <int BITS, int G>
@@ -318,7 +369,9 @@ extern "C" kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const
       !cache->keep_cnt || !cache->keep_mask)
     return KVS_ERR_INVALID;
   if (desc->keep_cap > 0 && (!cache->keep_k || !cache->keep_v)) return KVS_ERR_INVALID;
-  if (desc->sparse_frac > 0.0f) return KVS_ERR_UNSUPPORTED;
+  if (desc->sparse_frac > 0.0f && (!cache->k_rowptr || !cache->k_col || !cache->k_val ||
+                                   !cache->v_rowptr || !cache->v_col || !cache->v_val))
+    return KVS_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const kvs::DecodeGeometry geo = kvs::decode_geometry(desc);
   float* ws = static_cast<float*>(workspace);

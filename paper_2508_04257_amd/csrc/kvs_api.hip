@@ -18,7 +18,10 @@ kvs_status validate_desc(const kvs_desc* d) {
   // CSR rows and word offsets are 32-bit quantities in places; keep a wide margin.
   const int64_t rows = static_cast<int64_t>(d->B) * d->Hkv * d->n;
   if (rows >= (int64_t{1} << 30)) return KVS_ERR_UNSUPPORTED;
-  if (d->sparse_cap > (int64_t{1} << 31) - 1) return KVS_ERR_UNSUPPORTED;
+  if (d->sparse_frac > 0.0f) {
+    // CSR positions are int32: the whole tensor must be countable even if every entry ties.
+    if (d->sparse_cap > (int64_t{1} << 31) - 1 || rows * KVS_HEAD_DIM >= (int64_t{1} << 31)) return KVS_ERR_UNSUPPORTED;
+  }
   return KVS_OK;
 }
 
@@ -86,7 +89,10 @@ extern "C" kvs_status kvs_cache_bytes(const kvs_desc* d, size_t* sizes) {
       cap * 2,                                      // v_val
       4,                                            // status
   };
-  for (int i = 0; i < KVS_CACHE_FIELDS; ++i) sizes[i] = (v[i] == 0 && !sparse && i >= 9 && i <= 14) ? 0 : round16(v[i]);
+  for (int i = 0; i < KVS_CACHE_FIELDS; ++i) {
+    const bool csr_field = i >= 9 && i <= 14;
+    sizes[i] = (csr_field && !sparse) ? 0 : round16(v[i]);
+  }
   return KVS_OK;
 }
 
@@ -100,7 +106,7 @@ extern "C" size_t kvs_workspace_bytes(const kvs_desc* d) {
   const kvs::DecodeGeometry g = kvs::decode_geometry(d);
   // decode: per (b, hq, split) the unnormalised fp32 output row plus running max and sum
   const size_t decode = static_cast<size_t>(d->B) * d->Hq * g.splits * (KVS_HEAD_DIM + 2) * 4;
-  // quantise (dense-and-sparse only): two 32768-bin histograms, thresholds and counters
-  const size_t quant = d->sparse_frac > 0.0f ? (2 * 32768 + 64) * 4 : 0;
+  // quantise (dense-and-sparse only): two 32768-bin histograms, thresholds, scan scratch
+  const size_t quant = d->sparse_frac > 0.0f ? kvs::sparse_workspace_words(d) * 4 : 0;
   return round16(decode > quant ? decode : quant);
 }

@@ -38,6 +38,22 @@ struct DecodeGeometry {
 };
 DecodeGeometry decode_geometry(const kvs_desc* d);
 
+// Dense-and-sparse helpers (sparse.hip): where the scratch lives and the launch sequences.
+struct SparsePlan {
+  size_t rows;      // B * Hkv * n, the row count of both CSR structures
+  int nblk;         // scan workgroups
+  uint32_t* hist;   // [2][32768] magnitude histograms of K and V
+  uint32_t* tau;    // [2] thresholds as fp16 magnitude patterns (0x8000 = isolate nothing)
+  int* sums_k;      // [nblk + 1] scan scratch
+  int* sums_v;
+};
+size_t sparse_workspace_words(const kvs_desc* d);
+SparsePlan sparse_plan(const kvs_desc* d, void* workspace);
+void sparse_thresholds(const kvs_desc* d, const SparsePlan& p, const void* K, const void* V,
+                       const uint8_t* mask, const kvs_cache* out, hipStream_t s);
+void sparse_build_csr(const kvs_desc* d, const SparsePlan& p, const void* K, const void* V,
+                      const uint8_t* mask, const kvs_cache* out, hipStream_t s);
+
 __host__ __device__ inline int words_per_128(int bits) { return bits == 2 ? 8 : (bits == 3 ? 13 : 16); }
 
 __device__ inline float half_bits_to_float(uint16_t h) {

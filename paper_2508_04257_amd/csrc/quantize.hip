@@ -65,7 +65,8 @@ __device__ inline void unpack8(const uint4& raw, uint16_t h[8]) {
 template <int BITS, int G>
 __global__ __launch_bounds__(kThreads) void quantize_k_kernel(
     const uint4* __restrict__ K, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
-    uint32_t tau, uint32_t* __restrict__ k_codes, uint32_t* __restrict__ k_params) {
+    const uint32_t* __restrict__ tau_ptr, uint32_t* __restrict__ k_codes, uint32_t* __restrict__ k_params,
+    int32_t* __restrict__ row_count) {
   constexpr int TB = G > 64 ? G : 64;
   constexpr int NG = TB / G;             // groups per block: 1 or 2
   constexpr int ROWS = TB / 16;          // rows per lane
@@ -80,6 +81,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_kernel(
   const int tid = threadIdx.x;
   const int chunk = tid & 15;            // channels 8*chunk .. 8*chunk+7
   const int rslot = tid >> 4;            // rows rslot, rslot+16, ...
+  const uint32_t tau = tau_ptr ? *tau_ptr : 0x8000u;   // 0x8000: no magnitude pattern reaches it
   const int blocks_per_head = n / TB;
   const int blk = blockIdx.x % blocks_per_head;
   const size_t bh = blockIdx.x / blocks_per_head;       // b * Hkv + h
@@ -162,6 +164,14 @@ __global__ __launch_bounds__(kThreads) void quantize_k_kernel(
     uint32_t* dst = reinterpret_cast<uint32_t*>(code_s + r * kRowStride + 8 * chunk);
     dst[0] = lo;
     dst[1] = hi;
+    if (row_count) {                     // isolated entries of this row (CSR row = token)
+      int cnt = 0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) cnt += (!kept[i] && (h[j] & 0x7FFFu) >= tau) ? 1 : 0;
+#pragma unroll
+      for (int o = 1; o < 16; o <<= 1) cnt += __shfl_xor(cnt, o, KVS_WAVE);
+      if (chunk == 0) row_count[bh * n + t0 + r] = cnt;
+    }
   }
   __syncthreads();
 
@@ -187,17 +197,24 @@ __global__ __launch_bounds__(kThreads) void quantize_k_kernel(
 template <int BITS, int G>
 __global__ __launch_bounds__(kThreads) void quantize_v_kernel(
     const uint4* __restrict__ V, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
-    uint32_t tau, uint32_t* __restrict__ v_codes, uint32_t* __restrict__ v_params) {
+    const uint32_t* __restrict__ tau_ptr, uint32_t* __restrict__ v_codes, uint32_t* __restrict__ v_params,
+    int32_t* __restrict__ row_count) {
   constexpr int ROWS = KVS_V_TILE / 16;  // 8 rows per lane
   constexpr int W = Fmt<BITS>::W, cpw = Fmt<BITS>::cpw;
   constexpr int LANES_PER_GROUP = G / 8;
   constexpr int NGC = 128 / G;
 
   __shared__ __align__(16) uint8_t code_s[KVS_V_TILE * kRowStride];
+  __shared__ int col_count[128];
 
   const int tid = threadIdx.x;
   const int chunk = tid & 15;
   const int rslot = tid >> 4;
+  const uint32_t tau = tau_ptr ? *tau_ptr : 0x8000u;
+  if (row_count) {
+    if (tid < 128) col_count[tid] = 0;
+    __syncthreads();
+  }
   const int tiles_per_head = n / KVS_V_TILE;
   const int tile = blockIdx.x % tiles_per_head;
   const size_t bh = blockIdx.x / tiles_per_head;
@@ -237,12 +254,16 @@ __global__ __launch_bounds__(kThreads) void quantize_v_kernel(
       const bool masked = kept || (h[j] & 0x7FFFu) >= tau;
       const uint32_t c = quantize_one<BITS>(kvs::half_bits_to_float(h[j]), p.inv, p.zero, masked);
       if (j < 4) lo |= c << (8 * j); else hi |= c << (8 * (j - 4));
+      if (row_count && masked && !kept) atomicAdd(&col_count[8 * chunk + j], 1);   // integer: order-free
     }
     uint32_t* dst = reinterpret_cast<uint32_t*>(code_s + r * kRowStride + 8 * chunk);
     dst[0] = lo;
     dst[1] = hi;
   }
   __syncthreads();
+
+  if (row_count && tid < 128)            // CSR row = (tile, channel)
+    row_count[(bh * tiles_per_head + static_cast<size_t>(tile)) * 128 + tid] = col_count[tid];
 
   // Pack along tokens: word (u, c) holds tokens cpw*u .. of channel c; contiguous per block.
   uint32_t* out = v_codes + (bh * tiles_per_head + static_cast<size_t>(tile)) * (W * 128);
@@ -323,23 +344,24 @@ __global__ __launch_bounds__(KVS_WAVE) void keep_gather_kernel(
 
 template <int BITS, int G>
 void launch_dense(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask,
-                  const kvs_cache* out, uint32_t tau_k, uint32_t tau_v, hipStream_t stream) {
+                  const kvs_cache* out, const uint32_t* tau, hipStream_t stream) {
   constexpr int TB = G > 64 ? G : 64;
   const int bh = d->B * d->Hkv;
   hipLaunchKernelGGL((quantize_k_kernel<BITS, G>), dim3(bh * (d->n / TB)), dim3(kThreads), 0, stream,
-                     static_cast<const uint4*>(K), mask, d->n, d->Hkv, tau_k, out->k_codes, out->k_params);
+                     static_cast<const uint4*>(K), mask, d->n, d->Hkv, tau, out->k_codes, out->k_params,
+                     tau ? out->k_rowptr + 1 : nullptr);
   hipLaunchKernelGGL((quantize_v_kernel<BITS, G>), dim3(bh * (d->n / KVS_V_TILE)), dim3(kThreads), 0,
-                     stream, static_cast<const uint4*>(V), mask, d->n, d->Hkv, tau_v, out->v_codes,
-                     out->v_params);
+                     stream, static_cast<const uint4*>(V), mask, d->n, d->Hkv, tau ? tau + 1 : nullptr,
+                     out->v_codes, out->v_params, tau ? out->v_rowptr + 1 : nullptr);
 }
 
 template <int BITS>
 void launch_dense_g(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask,
-                    const kvs_cache* out, uint32_t tk, uint32_t tv, hipStream_t s) {
+                    const kvs_cache* out, const uint32_t* tau, hipStream_t s) {
   switch (d->group) {
-    case 32: launch_dense<BITS, 32>(d, K, V, mask, out, tk, tv, s); break;
-    case 64: launch_dense<BITS, 64>(d, K, V, mask, out, tk, tv, s); break;
-    default: launch_dense<BITS, 128>(d, K, V, mask, out, tk, tv, s); break;
+    case 32: launch_dense<BITS, 32>(d, K, V, mask, out, tau, s); break;
+    case 64: launch_dense<BITS, 64>(d, K, V, mask, out, tau, s); break;
+    default: launch_dense<BITS, 128>(d, K, V, mask, out, tau, s); break;
   }
 }
 
@@ -355,16 +377,25 @@ extern "C" kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const
       !out->keep_cnt || !out->keep_mask || !out->status)
     return KVS_ERR_INVALID;
   if (desc->keep_cap > 0 && (!out->keep_k || !out->keep_v)) return KVS_ERR_INVALID;
-  if (desc->sparse_frac > 0.0f) return KVS_ERR_UNSUPPORTED;
-  (void)workspace;
+  const bool sparse = desc->sparse_frac > 0.0f;
+  if (sparse && (!workspace || !out->k_rowptr || !out->k_col || !out->k_val || !out->v_rowptr ||
+                 !out->v_col || !out->v_val))
+    return KVS_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(stream);
 
-  const uint32_t no_tau = 0x8000u;   // no fp16 magnitude pattern reaches it: nothing is isolated
-  switch (desc->bits) {
-    case 2: launch_dense_g<2>(desc, K, V, keep_mask, out, no_tau, no_tau, s); break;
-    case 3: launch_dense_g<3>(desc, K, V, keep_mask, out, no_tau, no_tau, s); break;
-    default: launch_dense_g<4>(desc, K, V, keep_mask, out, no_tau, no_tau, s); break;
+  kvs::SparsePlan plan{};
+  const uint32_t* tau = nullptr;       // device [2]: thresholds of K and V
+  if (sparse) {
+    plan = kvs::sparse_plan(desc, workspace);
+    kvs::sparse_thresholds(desc, plan, K, V, keep_mask, out, s);
+    tau = plan.tau;
   }
+  switch (desc->bits) {
+    case 2: launch_dense_g<2>(desc, K, V, keep_mask, out, tau, s); break;
+    case 3: launch_dense_g<3>(desc, K, V, keep_mask, out, tau, s); break;
+    default: launch_dense_g<4>(desc, K, V, keep_mask, out, tau, s); break;
+  }
+  if (sparse) kvs::sparse_build_csr(desc, plan, K, V, keep_mask, out, s);
   hipLaunchKernelGGL(keep_index_kernel, dim3(desc->B), dim3(kIndexThreads), 0, s, keep_mask, desc->n,
                      desc->keep_cap, out->keep_idx, out->keep_cnt, out->keep_mask, out->status);
   if (desc->keep_cap > 0)

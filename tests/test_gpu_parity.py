@@ -27,10 +27,10 @@ def row_rel_err(got, ref64):
     return float((np.abs(got - ref64).max(axis=-1) / np.abs(ref64).max(axis=-1)).max())
 
 
-def hip_quantize(K, V, mask, bits, G, keep_cap, Hq=None):
+def hip_quantize(K, V, mask, bits, G, keep_cap, Hq=None, sparse_frac=0.0, sparse_cap=0):
     """numpy in -> (desc, cache buffers) after kvs_quantize_kv."""
     B, H, n, D = K.shape
-    desc = kb.make_desc(B, n, Hq or H, H, bits, G, keep_cap)
+    desc = kb.make_desc(B, n, Hq or H, H, bits, G, keep_cap, sparse_frac=sparse_frac, sparse_cap=sparse_cap)
     cache = kb.alloc_cache(desc, DEV)
     ws = kb.alloc_workspace(desc, DEV)
     kb.kvs_quantize_kv(desc, torch.from_numpy(K).to(DEV), torch.from_numpy(V).to(DEV),
@@ -56,6 +56,18 @@ def assert_cache_equal(cache, ref: O.Cache, check_status=True):
         kv = cache.keep_v.cpu().numpy().view(np.uint16)[:ref.keep_v.size].reshape(ref.keep_v.shape)
         assert np.array_equal(kk, ref.keep_k.view(np.uint16))
         assert np.array_equal(kv, ref.keep_v.view(np.uint16))
+
+
+def assert_csr_equal(cache, ref: O.Cache):
+    rows = ref.B * ref.Hkv * ref.n
+    for name in ("k", "v"):
+        rp = getattr(cache, name + "_rowptr").cpu().numpy()[:rows + 1]
+        ref_rp = getattr(ref, name + "_rowptr")
+        assert np.array_equal(rp, ref_rp)
+        nnz = int(ref_rp[-1])
+        assert np.array_equal(getattr(cache, name + "_col").cpu().numpy().view(np.uint16)[:nnz], getattr(ref, name + "_col"))
+        assert np.array_equal(getattr(cache, name + "_val").cpu().numpy().view(np.uint16)[:nnz],
+                              getattr(ref, name + "_val").view(np.uint16))
 
 
 def hip_decode(desc, cache, ws, q):
@@ -197,6 +209,44 @@ def test_degenerate_inputs(case):
     assert np.abs(lse - ref_lse).max() <= 2e-3 * max(1.0, np.abs(ref_lse).max())
 
 
+@pytest.mark.parametrize("bits,G,rep,frac,kind", [
+    (3, 128, 1, 0.01, "student"), (2, 32, 4, 0.005, "student"), (4, 64, 1, 0.05, "normal"),
+    (3, 128, 1, 0.01, "ties"),
+])
+def test_dense_and_sparse_small(bits, G, rep, frac, kind):
+    rng = np.random.default_rng(int(frac * 1000) + bits)
+    B, H, n = 2, 2, 640
+    def draw():
+        if kind == "student":
+            x = rng.standard_t(4, (B, H, n, 128))
+        elif kind == "ties":                                      # few distinct magnitudes: tau sits in a large tie class
+            x = rng.integers(-6, 7, (B, H, n, 128)).astype(np.float64)
+        else:
+            x = rng.standard_normal((B, H, n, 128))
+        return np.clip(x, -60000, 60000).astype(np.float16)
+    K, V = draw(), draw()
+    K[:, :, :, [5, 99]] *= np.float16(10)
+    mask = np.zeros((B, n), np.uint8)
+    mask[0, [0, 14, 300]] = 1
+    mask[1, [0, 639]] = 1
+    q = random_fp16(rng, (B, H * rep, 128))
+    ref = O.quantize_kv(K, V, mask, bits, G, keep_cap=4, sparse_frac=frac)
+    cap = max(len(ref.k_col), len(ref.v_col)) + 16
+    desc, cache, ws = hip_quantize(K, V, mask, bits, G, keep_cap=4, Hq=H * rep, sparse_frac=frac, sparse_cap=cap)
+    assert_cache_equal(cache, ref)
+    assert_csr_equal(cache, ref)
+    out, lse = hip_decode(desc, cache, ws, q)
+    _, ref_lse, ref64 = O.decode_attn(q, ref, Hq=H * rep)
+    assert row_rel_err(out, ref64) <= OUT_TOL
+    assert np.abs(lse - ref_lse).max() <= 2e-3 * max(1.0, np.abs(ref_lse).max())
+    # too small a capacity is reported, never overrun
+    small = max(len(ref.k_col), len(ref.v_col)) // 2
+    desc2, cache2, ws2 = hip_quantize(K, V, mask, bits, G, keep_cap=4, Hq=H * rep, sparse_frac=frac, sparse_cap=small)
+    assert int(cache2.status.cpu()[0]) == kb.KVS_ERR_CAPACITY
+    out2, _ = hip_decode(desc2, cache2, ws2, q)                   # still runs inside its buffers
+    assert np.all(np.isfinite(out2))
+
+
 def test_whole_path_on_the_worked_example_workload():
     for name in ("cfg0_kvsink", "cfg0_pfn"):
         w = synth.WORKLOADS[name]
@@ -229,6 +279,19 @@ def _sampled_full_size(name, n_pairs=3):
     assert np.array_equal(buf.sink_idx.cpu().numpy(), ref_idx)
     assert np.array_equal(np.sort(ref_idx, axis=1), synth.sink_positions(w))   # the planted tokens
 
+    taus = None
+    if w.sparse_frac > 0:                                   # thresholds are a property of the whole layer
+        Kh, Vh = K.cpu().numpy(), V.cpu().numpy()
+        taus = (O.sparse_threshold(Kh, ref_mask, w.sparse_frac), O.sparse_threshold(Vh, ref_mask, w.sparse_frac))
+        del Kh, Vh
+        rows = w.B * w.Hkv * w.n
+        k_rp = buf.cache.k_rowptr.cpu().numpy()[:rows + 1]
+        v_rp = buf.cache.v_rowptr.cpu().numpy()[:rows + 1]
+        assert k_rp[0] == 0 and v_rp[0] == 0 and np.all(np.diff(k_rp) >= 0) and np.all(np.diff(v_rp) >= 0)
+        total = w.Hkv * w.D * int((w.n - ref_mask.sum(1).astype(np.int64)).sum())
+        need = int(np.ceil(float(np.float32(w.sparse_frac)) * total))
+        assert need <= k_rp[-1] <= buf.desc.sparse_cap and need <= v_rp[-1] <= buf.desc.sparse_cap
+
     W = O.words_per_128(w.bits)
     cap = buf.desc.keep_cap
     def shaped(t, *shape):
@@ -247,7 +310,16 @@ def _sampled_full_size(name, n_pairs=3):
     for _ in range(n_pairs):
         b, h = int(rng.integers(0, w.B)), int(rng.integers(0, w.Hkv))
         Ks, Vs = K[b:b + 1, h:h + 1].cpu().numpy(), V[b:b + 1, h:h + 1].cpu().numpy()
-        ref = O.quantize_kv(Ks, Vs, ref_mask[b:b + 1], w.bits, w.group, cap)
+        ref = O.quantize_kv(Ks, Vs, ref_mask[b:b + 1], w.bits, w.group, cap, sparse_frac=w.sparse_frac, taus=taus)
+        if taus is not None:                                # this slice's rows of the two CSR structures
+            base = (b * w.Hkv + h) * w.n
+            for rp, col, val, rref, cref, vref in (
+                    (k_rp, buf.cache.k_col, buf.cache.k_val, ref.k_rowptr, ref.k_col, ref.k_val),
+                    (v_rp, buf.cache.v_col, buf.cache.v_val, ref.v_rowptr, ref.v_col, ref.v_val)):
+                lo, hi = int(rp[base]), int(rp[base + w.n])
+                assert np.array_equal(rp[base:base + w.n + 1] - lo, rref)
+                assert np.array_equal(col[lo:hi].cpu().numpy().view(np.uint16), cref)
+                assert np.array_equal(val[lo:hi].cpu().numpy().view(np.uint16), vref.view(np.uint16))
         assert np.array_equal(u32(kc[b, h]), ref.k_codes[0, 0])
         assert np.array_equal(u32(vc[b, h]), ref.v_codes[0, 0])
         assert np.array_equal(u32(kp[b, h]), ref.k_params[0, 0])
@@ -283,3 +355,7 @@ def test_full_size_gqa_int3_workload():
 
 def test_full_size_long_context_int2_workload():
     _sampled_full_size("cfg3", n_pairs=1)
+
+
+def test_full_size_dense_and_sparse_workload_one_layer():
+    _sampled_full_size("cfg4", n_pairs=2)

@@ -296,8 +296,9 @@ def test_sparse_csr_structure_and_reduction_to_dense():
     mask = np.zeros((B, n), np.uint8)
     mask[0, [0, 3]] = 1
     cache = O.quantize_kv(K, V, mask, 3, 128, keep_cap=2, sparse_frac=0.01)
-    for X, rowptr, col, val, tau in ((K, cache.k_rowptr, cache.k_col, cache.k_val, cache.k_tau),
-                                     (V, cache.v_rowptr, cache.v_col, cache.v_val, cache.v_tau)):
+    Vt = V.reshape(B, H, n // 128, 128, D).transpose(0, 1, 2, 4, 3)          # rows (b, h, tile, channel)
+    for X, rowptr, col, val, tau, transposed in ((K, cache.k_rowptr, cache.k_col, cache.k_val, cache.k_tau, False),
+                                                 (Vt, cache.v_rowptr, cache.v_col, cache.v_val, cache.v_tau, True)):
         tau_f = float(np.uint16(tau).view(np.float16))
         assert rowptr[0] == 0 and rowptr[-1] == len(col) == len(val) and np.all(np.diff(rowptr) >= 0)
         dense = np.zeros((B * H * n, D), bool)
@@ -306,7 +307,10 @@ def test_sparse_csr_structure_and_reduction_to_dense():
             assert np.all(np.diff(cols) > 0)
             dense[r, cols] = True
             assert np.array_equal(val[rowptr[r]:rowptr[r + 1]], X.reshape(-1, D)[r, cols])
-        dense = dense.reshape(B, H, n, D)
+        dense = dense.reshape(X.shape)
+        if transposed:                                              # back to (b, h, token, channel)
+            dense = dense.transpose(0, 1, 2, 4, 3).reshape(B, H, n, D)
+            X = V
         assert not dense[:, :, [0, 3]].any()                        # kept rows hold no sparse entries
         live = np.ones(n, bool)
         live[[0, 3]] = False
