@@ -23,6 +23,7 @@ SOURCES = {
     "quantize.hip": ["-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt"],
     "sparse.hip": [],
     "decode.hip": [],
+    "decode_mfma.hip": [],
 }
 
 COMMON = [

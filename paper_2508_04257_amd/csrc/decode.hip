@@ -276,48 +276,68 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
   }
 }
 
-// One workgroup (128 lanes, lane = channel) per (b, hq).
-__global__ __launch_bounds__(128) void decode_combine_kernel(
+// One wave per (b, hq), lane = channels 2 lane and 2 lane + 1: log-sum-exp merge of the splits,
+// then the kept tokens' fp16 rows join the same running softmax.
+__global__ __launch_bounds__(KVS_WAVE) void decode_combine_kernel(
     const uint16_t* __restrict__ q, const float* __restrict__ ws, int splits, int Hq, int Hkv,
     int cap, const uint16_t* __restrict__ keep_k, const uint16_t* __restrict__ keep_v,
     const int32_t* __restrict__ keep_cnt, uint16_t* __restrict__ out, float* __restrict__ lse) {
-  __shared__ float xchg[2];
-  const int c = threadIdx.x;
+  const int lane = threadIdx.x;
   const size_t bq = blockIdx.x;                       // b * Hq + hq
   const int b = static_cast<int>(bq / Hq), hq = static_cast<int>(bq % Hq);
   const int h = hq / (Hq / Hkv);
   const float* row = ws + bq * splits * kWsRow;
+  const int cnt = min(keep_cnt[b], cap);
+  const uint32_t q2 = reinterpret_cast<const uint32_t*>(q + bq * 128)[lane];
+  const float q0 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 & 0xFFFFu));
+  const float q1 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 >> 16));
 
   float M = -INFINITY;
-  for (int s = 0; s < splits; ++s) M = fmaxf(M, row[s * kWsRow + 128]);
-  float L = 0.0f, O = 0.0f;
+  for (int s = lane; s < splits; s += KVS_WAVE) M = fmaxf(M, row[s * kWsRow + 128]);
+  M = kvs::wave_max(M);
+  float L = 0.0f, O0 = 0.0f, O1 = 0.0f;
+#pragma unroll 4
   for (int s = 0; s < splits; ++s) {
     const float ms = row[s * kWsRow + 128];
     const float f = ms == -INFINITY ? 0.0f : __expf(ms - M);
+    const float2 o = reinterpret_cast<const float2*>(row + s * kWsRow)[lane];
     L += row[s * kWsRow + 129] * f;
-    O += row[s * kWsRow + c] * f;
+    O0 += o.x * f;
+    O1 += o.y * f;
   }
 
-  // Kept tokens: exact fp16 rows, folded into the same running softmax.
-  const int cnt = min(keep_cnt[b], cap);
-  const float qc = kvs::half_bits_to_float(q[bq * 128 + c]);
-  for (int j = 0; j < cnt; ++j) {
-    const size_t rowoff = ((static_cast<size_t>(b) * Hkv + h) * cap + j) * 128 + c;
-    float part = kvs::wave_sum(qc * kvs::half_bits_to_float(keep_k[rowoff]));
-    __syncthreads();
-    if ((c & 63) == 0) xchg[c >> 6] = part;
-    __syncthreads();
-    const float s = (xchg[0] + xchg[1]) * kRsqrtD;
-    const float m_new = fmaxf(M, s);
-    const float alpha = M == -INFINITY ? 0.0f : __expf(M - m_new);
-    const float p = __expf(s - m_new);
-    L = L * alpha + p;
-    O = O * alpha + p * kvs::half_bits_to_float(keep_v[rowoff]);
-    M = m_new;
+  // Kept tokens: exact fp16 rows.  Four rows per step so that their loads overlap.
+  const uint32_t* kk = reinterpret_cast<const uint32_t*>(keep_k) + (static_cast<size_t>(b) * Hkv + h) * cap * 64 + lane;
+  const uint32_t* kv = reinterpret_cast<const uint32_t*>(keep_v) + (static_cast<size_t>(b) * Hkv + h) * cap * 64 + lane;
+  for (int j0 = 0; j0 < cnt; j0 += 4) {
+    uint32_t kw[4], vw[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = min(j0 + u, cnt - 1);
+      kw[u] = kk[j * 64];
+      vw[u] = kv[j * 64];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (j0 + u < cnt) {
+        const float part = q0 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] & 0xFFFFu)) +
+                           q1 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] >> 16));
+        const float s = kvs::wave_sum(part) * kRsqrtD;
+        const float m_new = fmaxf(M, s);
+        const float alpha = M == -INFINITY ? 0.0f : __expf(M - m_new);
+        const float p = __expf(s - m_new);
+        L = L * alpha + p;
+        O0 = O0 * alpha + p * kvs::half_bits_to_float(static_cast<uint16_t>(vw[u] & 0xFFFFu));
+        O1 = O1 * alpha + p * kvs::half_bits_to_float(static_cast<uint16_t>(vw[u] >> 16));
+        M = m_new;
+      }
+    }
   }
-  const float o = L > 0.0f ? O / L : 0.0f;
-  out[bq * 128 + c] = kvs::float_to_half_bits_rn(o);
-  if (lse && c == 0) lse[bq] = L > 0.0f ? M + __logf(L) : -INFINITY;
+  const float inv = L > 0.0f ? 1.0f / L : 0.0f;
+  const uint32_t packed = static_cast<uint32_t>(kvs::float_to_half_bits_rn(O0 * inv)) |
+                          (static_cast<uint32_t>(kvs::float_to_half_bits_rn(O1 * inv)) << 16);
+  reinterpret_cast<uint32_t*>(out + bq * 128)[lane] = packed;
+  if (lse && lane == 0) lse[bq] = L > 0.0f ? M + __logf(L) : -INFINITY;
 }
 
 template <int BITS, int G, int R>
@@ -376,12 +396,16 @@ extern "C" kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const
   const kvs::DecodeGeometry geo = kvs::decode_geometry(desc);
   float* ws = static_cast<float*>(workspace);
 
-  switch (desc->bits) {
-    case 2: launch_partial_g<2>(desc, geo, q, cache, ws, s); break;
-    case 3: launch_partial_g<3>(desc, geo, q, cache, ws, s); break;
-    default: launch_partial_g<4>(desc, geo, q, cache, ws, s); break;
+  if (geo.mfma) {
+    kvs::launch_decode_mfma(desc, geo, q, cache, ws, s);
+  } else {
+    switch (desc->bits) {
+      case 2: launch_partial_g<2>(desc, geo, q, cache, ws, s); break;
+      case 3: launch_partial_g<3>(desc, geo, q, cache, ws, s); break;
+      default: launch_partial_g<4>(desc, geo, q, cache, ws, s); break;
+    }
   }
-  hipLaunchKernelGGL(decode_combine_kernel, dim3(desc->B * desc->Hq), dim3(128), 0, s,
+  hipLaunchKernelGGL(decode_combine_kernel, dim3(desc->B * desc->Hq), dim3(KVS_WAVE), 0, s,
                      static_cast<const uint16_t*>(q), ws, geo.splits, desc->Hq, desc->Hkv, desc->keep_cap,
                      static_cast<const uint16_t*>(cache->keep_k), static_cast<const uint16_t*>(cache->keep_v),
                      cache->keep_cnt, static_cast<uint16_t*>(out), lse);

@@ -25,17 +25,30 @@ kvs_status validate_desc(const kvs_desc* d) {
   return KVS_OK;
 }
 
-// Enough workgroups to cover 256 compute units several times over, each split a whole number
-// of 128-token Value tiles.
+#ifndef KVS_MFMA_TARGET_WAVES
+#define KVS_MFMA_TARGET_WAVES 4096
+#endif
+
+// Splits are whole numbers of 128-token Value tiles.  Generic kernel: one workgroup (4 waves) per
+// split, enough workgroups to cover 256 compute units several times over.  Matrix-core kernel:
+// one wave per split, a few thousand waves in all.
 DecodeGeometry decode_geometry(const kvs_desc* d) {
   const int tiles = d->n / KVS_V_TILE;
   const int pairs = d->B * d->Hkv;
-  const int target = 2048;
-  int splits = (target + pairs - 1) / pairs;
-  if (splits < 1) splits = 1;
-  if (splits > tiles) splits = tiles;
-  const int tiles_per_split = (tiles + splits - 1) / splits;
   DecodeGeometry g;
+  g.mfma = decode_mfma_supported(d);
+  int tiles_per_split;
+  if (g.mfma) {
+    const long long total = static_cast<long long>(pairs) * tiles;
+    tiles_per_split = static_cast<int>((total + KVS_MFMA_TARGET_WAVES - 1) / KVS_MFMA_TARGET_WAVES);
+    if (tiles_per_split > tiles) tiles_per_split = tiles;
+  } else {
+    const int target = 2048;
+    int splits = (target + pairs - 1) / pairs;
+    if (splits > tiles) splits = tiles;
+    tiles_per_split = (tiles + splits - 1) / splits;
+  }
+  if (tiles_per_split < 1) tiles_per_split = 1;
   g.split_tokens = tiles_per_split * KVS_V_TILE;
   g.splits = (tiles + tiles_per_split - 1) / tiles_per_split;
   return g;
