@@ -397,7 +397,8 @@ extern "C" kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const
   float* ws = static_cast<float*>(workspace);
 
   if (geo.mfma) {
-    kvs::launch_decode_mfma(desc, geo, q, cache, ws, s);
+    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, s);
+    if (geo.splits == 1) return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;   // finished in one kernel
   } else {
     switch (desc->bits) {
       case 2: launch_partial_g<2>(desc, geo, q, cache, ws, s); break;

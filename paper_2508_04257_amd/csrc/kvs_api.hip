@@ -25,32 +25,35 @@ kvs_status validate_desc(const kvs_desc* d) {
   return KVS_OK;
 }
 
-#ifndef KVS_MFMA_TARGET_WAVES
-#define KVS_MFMA_TARGET_WAVES 4096
+#ifndef KVS_MFMA_TARGET_GROUPS
+#define KVS_MFMA_TARGET_GROUPS 256   // one 8-wave workgroup per compute unit
 #endif
 
 // Splits are whole numbers of 128-token Value tiles.  Generic kernel: one workgroup (4 waves) per
 // split, enough workgroups to cover 256 compute units several times over.  Matrix-core kernel:
-// one wave per split, a few thousand waves in all.
+// one 8-wave workgroup per split, about one per compute unit, and a single split per (b, h)
+// whenever there are enough (b, h) pairs - then no second kernel is needed.
 DecodeGeometry decode_geometry(const kvs_desc* d) {
   const int tiles = d->n / KVS_V_TILE;
   const int pairs = d->B * d->Hkv;
   DecodeGeometry g;
   g.mfma = decode_mfma_supported(d);
-  int tiles_per_split;
+  g.wave_tokens = 0;
+  int splits;
   if (g.mfma) {
-    const long long total = static_cast<long long>(pairs) * tiles;
-    tiles_per_split = static_cast<int>((total + KVS_MFMA_TARGET_WAVES - 1) / KVS_MFMA_TARGET_WAVES);
-    if (tiles_per_split > tiles) tiles_per_split = tiles;
+    splits = pairs >= KVS_MFMA_TARGET_GROUPS ? 1 : (KVS_MFMA_TARGET_GROUPS + pairs / 2) / pairs;
   } else {
-    const int target = 2048;
-    int splits = (target + pairs - 1) / pairs;
-    if (splits > tiles) splits = tiles;
-    tiles_per_split = (tiles + splits - 1) / splits;
+    splits = (2048 + pairs - 1) / pairs;
   }
-  if (tiles_per_split < 1) tiles_per_split = 1;
+  if (splits > tiles) splits = tiles;
+  if (splits < 1) splits = 1;
+  const int tiles_per_split = (tiles + splits - 1) / splits;
   g.split_tokens = tiles_per_split * KVS_V_TILE;
   g.splits = (tiles + tiles_per_split - 1) / tiles_per_split;
+  if (g.mfma) {
+    const int waves = decode_mfma_waves();
+    g.wave_tokens = ((tiles_per_split + waves - 1) / waves) * KVS_V_TILE;
+  }
   return g;
 }
 

@@ -33,15 +33,17 @@ struct Fmt<4> {
 // Host-side checks and launch geometry shared by the entry points (kvs_api.hip).
 kvs_status validate_desc(const kvs_desc* d);
 struct DecodeGeometry {
-  int splits;        // independent token ranges per (sequence, KV head)
+  int splits;        // workgroups (token ranges) per (sequence, KV head)
   int split_tokens;  // tokens per split, a multiple of 128
-  bool mfma;         // matrix-core kernel (one wave per split) instead of the generic one
+  int wave_tokens;   // matrix-core kernel: tokens per wave inside a split, a multiple of 128
+  bool mfma;         // matrix-core kernel instead of the generic one
 };
 DecodeGeometry decode_geometry(const kvs_desc* d);
 // Matrix-core decode kernel (decode_mfma.hip).
 bool decode_mfma_supported(const kvs_desc* d);
+int decode_mfma_waves();
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                        float* ws, hipStream_t s);
+                        void* out, float* lse, float* ws, hipStream_t s);
 
 // Dense-and-sparse helpers (sparse.hip): where the scratch lives and the launch sequences.
 struct SparsePlan {
