@@ -28,7 +28,10 @@ namespace {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 
-constexpr int kWaves = 8;
+#ifndef KVS_MFMA_WAVES
+#define KVS_MFMA_WAVES 8
+#endif
+constexpr int kWaves = KVS_MFMA_WAVES;
 constexpr int kThreads = kWaves * KVS_WAVE;
 constexpr float kLog2eRsqrtD = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
 constexpr float kRsqrtD = 0.08838834764831845f;
@@ -125,6 +128,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_int4_kernel(MfmaArgs a) 
   const int b = static_cast<int>(bh / a.Hkv), h = static_cast<int>(bh % a.Hkv);
   const int Hq = a.Hkv * R;
   const int hq0 = h * R;
+  const int keep_cnt_b = a.keep_cnt[b];            // uniform: a scalar load, issued first
 
   // Query of the lane's two channels (2 lane, 2 lane + 1), all R heads, scaled to log2 units.
   float qf[R][2];
@@ -315,6 +319,26 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_int4_kernel(MfmaArgs a) 
     }
   }
 
+  // ---- kept (sink) rows: start their loads now so that they overlap the merge below -----------
+  // Wave r finishes head r; lane = channels 2 lane, 2 lane + 1.  The first 8 rows are fetched in
+  // one batch (the usual keep set is a handful of tokens).
+  constexpr int kBatch = 8;
+  const bool finisher = wave < R && a.parts == 1;
+  const int cnt = min(keep_cnt_b, a.cap);
+  const uint32_t* kk = reinterpret_cast<const uint32_t*>(a.keep_k) + bh * a.cap * 64 + lane;
+  const uint32_t* kv = reinterpret_cast<const uint32_t*>(a.keep_v) + bh * a.cap * 64 + lane;
+  uint32_t kw[kBatch], vw[kBatch];
+#pragma unroll
+  for (int u = 0; u < kBatch; ++u) { kw[u] = 0; vw[u] = 0; }
+  if (finisher && cnt > 0) {
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int j = min(u, cnt - 1);
+      kw[u] = kk[j * 64];
+      vw[u] = kv[j * 64];
+    }
+  }
+
   // ---- each wave's state to LDS: unnormalised row, max (natural-log units), sum ----------------
   {
     float zsum[R], lsum[R];
@@ -339,7 +363,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_int4_kernel(MfmaArgs a) 
   }
   __syncthreads();
 
-  // ---- merge: wave r finishes head r; lane = channels 2 lane, 2 lane + 1 ------------------------
+  // ---- merge the waves' states ----------------------------------------------------------------
   if (wave < R) {
     const int r = wave;
     const size_t bq_row = static_cast<size_t>(b) * Hq + hq0 + r;
@@ -363,29 +387,34 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_int4_kernel(MfmaArgs a) 
       return;
     }
     // Kept tokens: exact fp16 rows join the same running softmax.
-    const int cnt = min(a.keep_cnt[b], a.cap);
     const uint32_t q2 = reinterpret_cast<const uint32_t*>(a.q + bq_row * 128)[lane];
     const float q0 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 & 0xFFFFu));
     const float q1 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 >> 16));
-    const uint32_t* kk = reinterpret_cast<const uint32_t*>(a.keep_k) + bh * a.cap * 64 + lane;
-    const uint32_t* kv = reinterpret_cast<const uint32_t*>(a.keep_v) + bh * a.cap * 64 + lane;
-    for (int j0 = 0; j0 < cnt; j0 += 4) {
-      uint32_t kw[4], vw[4];
+    for (int j0 = 0; j0 < cnt; j0 += kBatch) {
+      if (j0 > 0) {                                    // rare: more kept tokens than one batch
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int j = min(j0 + u, cnt - 1);
-        kw[u] = kk[j * 64];
-        vw[u] = kv[j * 64];
+        for (int u = 0; u < kBatch; ++u) {
+          const int j = min(j0 + u, cnt - 1);
+          kw[u] = kk[j * 64];
+          vw[u] = kv[j * 64];
+        }
       }
+      float sj[kBatch];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < kBatch; ++u)
+        sj[u] = q0 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] & 0xFFFFu)) +
+                q1 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] >> 16));
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1)                 // eight reductions in step
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) sj[u] += __shfl_xor(sj[u], o, KVS_WAVE);
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
         if (j0 + u < cnt) {
-          const float dotp = q0 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] & 0xFFFFu)) +
-                             q1 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] >> 16));
-          const float s = kvs::wave_sum(dotp) * kRsqrtD;
-          const float m_new = fmaxf(M, s);
+          const float sc_u = sj[u] * kRsqrtD;
+          const float m_new = fmaxf(M, sc_u);
           const float alpha = M == -INFINITY ? 0.0f : __expf(M - m_new);
-          const float p = __expf(s - m_new);
+          const float p = __expf(sc_u - m_new);
           L = L * alpha + p;
           O0 = O0 * alpha + p * kvs::half_bits_to_float(static_cast<uint16_t>(vw[u] & 0xFFFFu));
           O1 = O1 * alpha + p * kvs::half_bits_to_float(static_cast<uint16_t>(vw[u] >> 16));
