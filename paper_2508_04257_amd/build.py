@@ -21,6 +21,7 @@ SOURCES = {
     "kvs_api.hip": [],
     "predict.hip": [],
     "quantize.hip": ["-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt"],
+    "quantize_fast.hip": ["-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt"],
     "sparse.hip": [],
     "decode.hip": [],
     "decode_mfma.hip": [],

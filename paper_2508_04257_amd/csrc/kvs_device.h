@@ -45,6 +45,11 @@ int decode_mfma_waves();
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
                         void* out, float* lse, float* ws, hipStream_t s);
 
+// Lean 2 / 4 bit dense quantisation kernels (quantize_fast.hip).
+bool quantize_fast_supported(const kvs_desc* d);
+void launch_quantize_fast(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask,
+                          const kvs_cache* out, hipStream_t s);
+
 // Dense-and-sparse helpers (sparse.hip): where the scratch lives and the launch sequences.
 struct SparsePlan {
   size_t rows;      // B * Hkv * n, the row count of both CSR structures

@@ -383,6 +383,11 @@ extern "C" kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const
     return KVS_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(stream);
 
+  if (kvs::quantize_fast_supported(desc)) {            // 2 / 4 bit without isolated outliers
+    kvs::launch_quantize_fast(desc, K, V, keep_mask, out, s);
+    return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
+  }
+
   kvs::SparsePlan plan{};
   const uint32_t* tau = nullptr;       // device [2]: thresholds of K and V
   if (sparse) {

@@ -1,0 +1,405 @@
+// Lean 2-bit / 4-bit quantisation kernels for the dense (no isolated outliers) case of
+// kvs_quantize_kv (paper, Appendix C equations; Algorithm 1's two quantise steps).  Same results
+// bit for bit as the general kernels of quantize.hip, which also cover 3 bit and the
+// dense-and-sparse variant; these exist because the general ones spend ~17 vector instructions
+// per element and are bound by the ALU, not by the 2-byte-per-element fp16 read.
+//
+// What is different here:
+//   * group minima / maxima are taken on the raw fp16 pairs (v_pk_min_f16 / v_pk_max_f16): the
+//     minimum of the fp16 values converted to fp32 is the converted fp16 minimum;
+//   * one lane per group derives scale / zero (two IEEE divisions) and the others receive them;
+//   * codes are clamped in fp32 and inserted into the word with one shift-or each;
+//   * Values: a lane owns 8 consecutive tokens x 8 channels, which is exactly eight 4-bit words of
+//     the token-packed layout, so nothing is staged in LDS; Keys: one word per (token, lane), moved
+//     through a padded LDS tile so that the global stores are contiguous.
+//   * rows of kept tokens go straight from registers to the fp16 side buffer.
+// Compiled with floating-point contraction off and correctly rounded division, like quantize.hip.
+#include "kvs_device.h"
+
+namespace {
+
+using kvs::Fmt;
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+constexpr uint32_t kPosMax2 = 0x7BFF7BFFu;   // (+65504, +65504)
+constexpr uint32_t kNegMax2 = 0xFBFFFBFFu;   // (-65504, -65504)
+
+__device__ inline uint32_t pk_min(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b)));
+}
+__device__ inline uint32_t pk_max(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b)));
+}
+__device__ inline float lo_half(uint32_t v) { return kvs::half_bits_to_float(static_cast<uint16_t>(v & 0xFFFFu)); }
+__device__ inline float hi_half(uint32_t v) { return kvs::half_bits_to_float(static_cast<uint16_t>(v >> 16)); }
+
+struct Param {
+  float inv;     // 1 / scale
+  float zero;    // zero point as an exact float
+  uint32_t word; // fp16 scale | int16 zero << 16
+};
+
+// scale / zero of one group from its minimum and maximum (any == false: no unmasked entry).
+template <int BITS>
+__device__ inline Param make_param(float mn, float mx, bool any) {
+  constexpr float qmax = static_cast<float>(Fmt<BITS>::qmax);
+  if (!any) { mn = 0.0f; mx = 0.0f; }
+  uint16_t hbits;
+  if (mx == mn) {
+    hbits = kvs::float_to_half_bits_rn(mn != 0.0f ? fabsf(mn) : 1.0f);
+  } else {
+    const float s32 = (mx - mn) / qmax;
+    hbits = kvs::float_to_half_bits_rn(s32);
+    if (kvs::half_bits_to_float(hbits) < s32) hbits += 1;   // next fp16 up (positive values)
+  }
+  Param p;
+  p.inv = 1.0f / kvs::half_bits_to_float(hbits);
+  const int z = -static_cast<int>(rintf(mn * p.inv));
+  p.zero = static_cast<float>(z);
+  p.word = static_cast<uint32_t>(hbits) | (static_cast<uint32_t>(z & 0xFFFF) << 16);
+  return p;
+}
+
+// clamp(rne(x / scale) + zero, 0, qmax) as an unsigned integer; every intermediate is an exact
+// integer in fp32, so clamping before the conversion gives the same code as clamping after it.
+template <int BITS>
+__device__ inline uint32_t code_of(float x, float inv, float zero) {
+  const float v = rintf(x * inv) + zero;
+  return static_cast<uint32_t>(__builtin_amdgcn_fmed3f(v, 0.0f, static_cast<float>(Fmt<BITS>::qmax)));
+}
+
+// The eight codes of one uint4 of fp16 values (channels 8 chunk .. + 7), code j at bits BITS * j.
+template <int BITS>
+__device__ inline uint32_t codes8(const uint4& raw, const float inv[8], const float zero[8]) {
+  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+  uint32_t out = 0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    out |= code_of<BITS>(lo_half(w[k]), inv[2 * k], zero[2 * k]) << (BITS * 2 * k);
+    out |= code_of<BITS>(hi_half(w[k]), inv[2 * k + 1], zero[2 * k + 1]) << (BITS * (2 * k + 1));
+  }
+  return out;
+}
+
+// Slot of token t in the ascending keep list of its sequence, or -1.
+__device__ inline int keep_slot(const int32_t* __restrict__ keep_idx, int cnt, int t) {
+  for (int j = 0; j < cnt; ++j)
+    if (keep_idx[j] == t) return j;
+  return -1;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Keys: per channel, groups of G consecutive tokens.  Block = TB = max(G, 64) tokens.
+// ---------------------------------------------------------------------------------------------
+template <int BITS, int G>
+__global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
+    const uint4* __restrict__ K, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
+    uint32_t* __restrict__ k_codes, uint32_t* __restrict__ k_params, const int32_t* __restrict__ keep_idx,
+    const int32_t* __restrict__ keep_cnt, int cap, uint4* __restrict__ keep_k) {
+  constexpr int TB = G > 64 ? G : 64;
+  constexpr int NG = TB / G;
+  constexpr int ROWS = TB / 16;
+  constexpr int RPG = G / 16;                   // rows of one lane that fall into one group
+  constexpr int W = Fmt<BITS>::W;
+  constexpr int TILE_STRIDE = 68;               // padded token stride of the staged word tile
+  constexpr int LANES_PER_WORD = Fmt<BITS>::cpw / 8;   // 1 (4 bit) or 2 (2 bit)
+
+  __shared__ uint32_t red_mn[NG][16][64];       // [group][row slot][channel pair] packed fp16 minima
+  __shared__ uint32_t red_mx[NG][16][64];
+  __shared__ float inv_s[NG][128];
+  __shared__ float zero_s[NG][128];
+  __shared__ __align__(16) uint32_t tile_s[(TB / KVS_K_TILE) * W * TILE_STRIDE];
+
+  const int tid = threadIdx.x;
+  const int chunk = tid & 15;
+  const int rslot = tid >> 4;
+  const int blocks_per_head = n / TB;
+  const int blk = blockIdx.x % blocks_per_head;
+  const size_t bh = blockIdx.x / blocks_per_head;
+  const int b = static_cast<int>(bh / Hkv);
+  const int t0 = blk * TB;
+  const uint4* src = K + (bh * n + t0) * 16;
+  const uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * n + t0;
+
+  uint4 raw[ROWS];
+  bool kept[ROWS];
+#pragma unroll
+  for (int i = 0; i < ROWS; ++i) {
+    const int r = rslot + 16 * i;
+    raw[i] = src[r * 16 + chunk];
+    kept[i] = mask_b[r] != 0;
+  }
+
+  // Lane-local packed minima / maxima per group over the rows that are not kept.
+  bool any_g[NG];                               // does any token of the group survive?
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    uint32_t mn[4] = {kPosMax2, kPosMax2, kPosMax2, kPosMax2};
+    uint32_t mx[4] = {kNegMax2, kNegMax2, kNegMax2, kNegMax2};
+    bool any = false;
+#pragma unroll
+    for (int i = g * RPG; i < (g + 1) * RPG; ++i) {
+      if (!kept[i]) {
+        mn[0] = pk_min(mn[0], raw[i].x); mn[1] = pk_min(mn[1], raw[i].y);
+        mn[2] = pk_min(mn[2], raw[i].z); mn[3] = pk_min(mn[3], raw[i].w);
+        mx[0] = pk_max(mx[0], raw[i].x); mx[1] = pk_max(mx[1], raw[i].y);
+        mx[2] = pk_max(mx[2], raw[i].z); mx[3] = pk_max(mx[3], raw[i].w);
+        any = true;
+      }
+    }
+    *reinterpret_cast<uint4*>(&red_mn[g][rslot][4 * chunk]) = uint4{mn[0], mn[1], mn[2], mn[3]};
+    *reinterpret_cast<uint4*>(&red_mx[g][rslot][4 * chunk]) = uint4{mx[0], mx[1], mx[2], mx[3]};
+    any_g[g] = __syncthreads_or(any ? 1 : 0) != 0;     // also orders the LDS writes before the reads
+  }
+
+  // One lane per (group, channel pair): finish the reduction, derive both parameters.
+  if (tid < NG * 64) {
+    const int g = tid >> 6, cp = tid & 63;
+    uint32_t a = kPosMax2, z = kNegMax2;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) { a = pk_min(a, red_mn[g][s][cp]); z = pk_max(z, red_mx[g][s][cp]); }
+    const bool any = any_g[g];
+    const Param p0 = make_param<BITS>(lo_half(a), lo_half(z), any);
+    const Param p1 = make_param<BITS>(hi_half(a), hi_half(z), any);
+    inv_s[g][2 * cp] = p0.inv;  inv_s[g][2 * cp + 1] = p1.inv;
+    zero_s[g][2 * cp] = p0.zero;  zero_s[g][2 * cp + 1] = p1.zero;
+    reinterpret_cast<uint2*>(k_params + (bh * (n / G) + static_cast<size_t>(t0 / G + g)) * 128)[cp] = uint2{p0.word, p1.word};
+  }
+  __syncthreads();
+
+  // Codes: one word (4 bit) or half a word (2 bit) per row and lane, staged as [tile][w][token].
+  const int cnt = min(keep_cnt[b], cap);
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    float inv[8], zero[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { inv[j] = inv_s[g][8 * chunk + j]; zero[j] = zero_s[g][8 * chunk + j]; }
+#pragma unroll
+    for (int i = g * RPG; i < (g + 1) * RPG; ++i) {
+      const int r = rslot + 16 * i;
+      uint32_t word = kept[i] ? 0u : codes8<BITS>(raw[i], inv, zero);
+      if (LANES_PER_WORD == 2) {                  // 2 bit: lanes (even, odd) share a word
+        const uint32_t other = static_cast<uint32_t>(__shfl_xor(static_cast<int>(word), 1, KVS_WAVE));
+        word = word | (other << 16);
+      }
+      if (LANES_PER_WORD == 1 || (chunk & 1) == 0)
+        tile_s[((r / KVS_K_TILE) * W + chunk / LANES_PER_WORD) * TILE_STRIDE + (r % KVS_K_TILE)] = word;
+      if (kept[i]) {                              // exact copy of the row into the fp16 side buffer
+        const int j = keep_slot(keep_idx + static_cast<size_t>(b) * cap, cnt, t0 + r);
+        if (j >= 0) keep_k[(bh * cap + j) * 16 + chunk] = raw[i];
+      }
+    }
+  }
+  __syncthreads();
+
+  // The block's words are contiguous in global memory in (tile, w, t) order: 128-bit stores.
+  uint4* out = reinterpret_cast<uint4*>(k_codes + (bh * (n / KVS_K_TILE) + static_cast<size_t>(t0 / KVS_K_TILE)) * (W * KVS_K_TILE));
+  constexpr int quads = (TB / KVS_K_TILE) * W * (KVS_K_TILE / 4);
+  for (int qi = tid; qi < quads; qi += kThreads) {
+    const int row = qi / (KVS_K_TILE / 4), t4 = qi % (KVS_K_TILE / 4);
+    out[qi] = *reinterpret_cast<const uint4*>(&tile_s[row * TILE_STRIDE + 4 * t4]);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Values: per token, groups of G consecutive channels.  Block = one 128-token tile; a lane owns
+// tokens 8 rs .. 8 rs + 7 and channels 8 chunk .. 8 chunk + 7.
+// ---------------------------------------------------------------------------------------------
+template <int BITS, int G>
+__global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
+    const uint4* __restrict__ V, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
+    uint32_t* __restrict__ v_codes, uint32_t* __restrict__ v_params, const int32_t* __restrict__ keep_idx,
+    const int32_t* __restrict__ keep_cnt, int cap, uint4* __restrict__ keep_v) {
+  constexpr int W = Fmt<BITS>::W;
+  constexpr int LPG = G / 8;                    // lanes per channel group: 4, 8, 16
+  constexpr int NGC = 128 / G;
+  constexpr int ROWS_PER_LANE = LPG >= 8 ? 1 : 8 / LPG;   // rows whose parameters one lane derives
+
+  const int tid = threadIdx.x;
+  const int lane = tid & (KVS_WAVE - 1);
+  const int chunk = tid & 15;
+  const int rs = tid >> 4;                      // token word: tokens 8 rs .. 8 rs + 7
+  const int tiles_per_head = n / KVS_V_TILE;
+  const int tile = blockIdx.x % tiles_per_head;
+  const size_t bh = blockIdx.x / tiles_per_head;
+  const int b = static_cast<int>(bh / Hkv);
+  const int t0 = tile * KVS_V_TILE;
+  const uint4* src = V + (bh * n + t0 + 8 * rs) * 16 + chunk;
+  const uint2 mask8 = *reinterpret_cast<const uint2*>(keep_mask + static_cast<size_t>(b) * n + t0 + 8 * rs);
+
+  uint4 raw[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) raw[i] = src[i * 16];
+
+  // (min, -max) of the lane's 8 values of each row as one packed pair, then across the group's
+  // lanes: one packed minimum per step does both.
+  uint32_t stat[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const uint32_t mn2 = pk_min(pk_min(raw[i].x, raw[i].y), pk_min(raw[i].z, raw[i].w));
+    const uint32_t mx2 = pk_max(pk_max(raw[i].x, raw[i].y), pk_max(raw[i].z, raw[i].w));
+    const uint32_t mn1 = pk_min(mn2, mn2 >> 16) & 0xFFFFu;
+    const uint32_t mx1 = pk_max(mx2, mx2 >> 16) & 0xFFFFu;
+    uint32_t s = mn1 | ((mx1 ^ 0x8000u) << 16);
+#pragma unroll
+    for (int o = 1; o < LPG; o <<= 1) s = pk_min(s, static_cast<uint32_t>(__shfl_xor(static_cast<int>(s), o, KVS_WAVE)));
+    stat[i] = s;
+  }
+
+  // Lane p of a group derives the parameters of rows p, p + LPG, ...; the others fetch them.
+  const int p = chunk % LPG;
+  const int group_base = lane - p;
+  float inv_mine[ROWS_PER_LANE], zero_mine[ROWS_PER_LANE];
+#pragma unroll
+  for (int k = 0; k < ROWS_PER_LANE; ++k) {
+    const int row = p + k * LPG;                // may exceed 7 for idle lanes of wide groups
+    uint32_t s = stat[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) s = row == i ? stat[i] : s;
+    const bool kept = row < 8 && ((row < 4 ? mask8.x >> (8 * row) : mask8.y >> (8 * (row - 4))) & 0xFFu) != 0;
+    const Param prm = make_param<BITS>(lo_half(s), -hi_half(s), !kept);
+    inv_mine[k] = prm.inv;
+    zero_mine[k] = prm.zero;
+    if (row < 8) v_params[(bh * n + static_cast<size_t>(t0 + 8 * rs + row)) * NGC + chunk / LPG] = prm.word;
+  }
+
+  const int cnt = min(keep_cnt[b], cap);
+  uint32_t words[8];                            // word j: channel 8 chunk + j, tokens 8 rs .. + 7
+#pragma unroll
+  for (int j = 0; j < 8; ++j) words[j] = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int owner = group_base + (i % LPG);
+    const int k = i / LPG;                      // compile-time after unrolling
+    const float inv = __shfl(inv_mine[k < ROWS_PER_LANE ? k : 0], owner, KVS_WAVE);
+    const float zero = __shfl(zero_mine[k < ROWS_PER_LANE ? k : 0], owner, KVS_WAVE);
+    const bool kept = ((i < 4 ? mask8.x >> (8 * i) : mask8.y >> (8 * (i - 4))) & 0xFFu) != 0;
+    if (!kept) {
+      const uint32_t w4[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        words[2 * c] |= code_of<BITS>(lo_half(w4[c]), inv, zero) << (BITS * i);
+        words[2 * c + 1] |= code_of<BITS>(hi_half(w4[c]), inv, zero) << (BITS * i);
+      }
+    } else {
+      const int j = keep_slot(keep_idx + static_cast<size_t>(b) * cap, cnt, t0 + 8 * rs + i);
+      if (j >= 0) keep_v[(bh * cap + j) * 16 + chunk] = raw[i];
+    }
+  }
+  if (BITS == 2) {                              // 16 tokens per word: row slots (even, odd) share it
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t other = static_cast<uint32_t>(__shfl_xor(static_cast<int>(words[j]), 16, KVS_WAVE));
+      words[j] |= other << 16;
+    }
+  }
+  if (BITS == 4 || (rs & 1) == 0) {
+    const int u = BITS == 4 ? rs : rs / 2;
+    uint4* out = reinterpret_cast<uint4*>(v_codes + (bh * tiles_per_head + static_cast<size_t>(tile)) * (W * 128) + u * 128 + 8 * chunk);
+    out[0] = uint4{words[0], words[1], words[2], words[3]};
+    out[1] = uint4{words[4], words[5], words[6], words[7]};
+  }
+}
+
+// Index list of the kept tokens (ascending), count, mask copy, overflow status, and zero padding
+// of the unused rows of the fp16 side buffers.  One wave per sequence, 16 mask bytes per lane
+// and step.
+__global__ __launch_bounds__(KVS_WAVE) void keep_index_fast_kernel(
+    const uint8_t* __restrict__ keep_mask, int n, int Hkv, int cap, int32_t* __restrict__ keep_idx,
+    int32_t* __restrict__ keep_cnt, uint8_t* __restrict__ mask_copy, int32_t* __restrict__ status,
+    uint4* __restrict__ keep_k, uint4* __restrict__ keep_v) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const uint8_t* m = keep_mask + static_cast<size_t>(b) * n;
+  uint8_t* mc = mask_copy + static_cast<size_t>(b) * n;
+  int base = 0;
+  for (int i0 = 0; i0 < n; i0 += KVS_WAVE * 16) {        // n is a multiple of 128, not of 1024
+    const int i = i0 + lane * 16;
+    uint4 v = {0, 0, 0, 0};
+    if (i < n) v = *reinterpret_cast<const uint4*>(m + i);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t norm[4];
+    int mine = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      uint32_t nz = w[k] | (w[k] >> 4);
+      nz |= nz >> 2;  nz |= nz >> 1;                     // bit 0 of each byte = byte != 0
+      norm[k] = nz & 0x01010101u;
+      mine += __popc(norm[k]);
+    }
+    if (i < n) *reinterpret_cast<uint4*>(mc + i) = uint4{norm[0], norm[1], norm[2], norm[3]};
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < KVS_WAVE; o <<= 1) {
+      const int up = __shfl_up(incl, o, KVS_WAVE);
+      if (lane >= o) incl += up;
+    }
+    int pos = base + incl - mine;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if ((norm[k] >> (8 * j)) & 1u) {
+          if (pos < cap) keep_idx[static_cast<size_t>(b) * cap + pos] = i + 4 * k + j;
+          ++pos;
+        }
+    base += __shfl(incl, KVS_WAVE - 1, KVS_WAVE);
+  }
+  for (int j = base + lane; j < cap; j += KVS_WAVE) keep_idx[static_cast<size_t>(b) * cap + j] = -1;
+  if (lane == 0) {
+    keep_cnt[b] = base;
+    if (base > cap) atomicCAS(status, 0, static_cast<int>(KVS_ERR_CAPACITY));
+  }
+  // zero the rows past the count, for every head of this sequence (16 uint4 per row)
+  const int first = min(base, cap);
+  const int per_head = (cap - first) * 16;
+  for (int h = 0; h < Hkv; ++h) {
+    const size_t row0 = ((static_cast<size_t>(b) * Hkv + h) * cap + first) * 16;
+    for (int e = lane; e < per_head; e += KVS_WAVE) {
+      keep_k[row0 + e] = uint4{0, 0, 0, 0};
+      keep_v[row0 + e] = uint4{0, 0, 0, 0};
+    }
+  }
+}
+
+template <int BITS, int G>
+void launch_fast(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask, const kvs_cache* out,
+                 hipStream_t s) {
+  constexpr int TB = G > 64 ? G : 64;
+  const int bh = d->B * d->Hkv;
+  hipLaunchKernelGGL(keep_index_fast_kernel, dim3(d->B), dim3(KVS_WAVE), 0, s, mask, d->n, d->Hkv, d->keep_cap,
+                     out->keep_idx, out->keep_cnt, out->keep_mask, out->status, static_cast<uint4*>(out->keep_k),
+                     static_cast<uint4*>(out->keep_v));
+  hipLaunchKernelGGL((quantize_k_fast_kernel<BITS, G>), dim3(bh * (d->n / TB)), dim3(kThreads), 0, s,
+                     static_cast<const uint4*>(K), mask, d->n, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
+                     out->keep_cnt, d->keep_cap, static_cast<uint4*>(out->keep_k));
+  hipLaunchKernelGGL((quantize_v_fast_kernel<BITS, G>), dim3(bh * (d->n / KVS_V_TILE)), dim3(kThreads), 0, s,
+                     static_cast<const uint4*>(V), mask, d->n, d->Hkv, out->v_codes, out->v_params, out->keep_idx,
+                     out->keep_cnt, d->keep_cap, static_cast<uint4*>(out->keep_v));
+}
+
+template <int BITS>
+void launch_fast_g(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask, const kvs_cache* out,
+                   hipStream_t s) {
+  switch (d->group) {
+    case 32: launch_fast<BITS, 32>(d, K, V, mask, out, s); break;
+    case 64: launch_fast<BITS, 64>(d, K, V, mask, out, s); break;
+    default: launch_fast<BITS, 128>(d, K, V, mask, out, s); break;
+  }
+}
+
+}  // namespace
+
+namespace kvs {
+
+bool quantize_fast_supported(const kvs_desc* d) {
+  return (d->bits == 2 || d->bits == 4) && d->sparse_frac == 0.0f;
+}
+
+void launch_quantize_fast(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask,
+                          const kvs_cache* out, hipStream_t s) {
+  if (d->bits == 2) launch_fast_g<2>(d, K, V, mask, out, s);
+  else launch_fast_g<4>(d, K, V, mask, out, s);
+}
+
+}  // namespace kvs
