@@ -128,6 +128,9 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg1")
     ap.add_argument("--slots", type=int, default=4, help="rotating copies of inputs and caches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain copy of known size (256 MiB read + 256 MiB written) a few times "
+                         "before the steps: the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -142,6 +145,14 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     slots = max(2, args.slots)
+
+    if args.calibrate:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)      # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)              # one elementwise kernel: reads src once, writes dst once
+        torch.cuda.synchronize()
+        del src, dst
 
     hidden = synth.make_hidden(w, dev)
     q = synth.make_query(w, dev)
