@@ -25,6 +25,9 @@ SOURCES = {
     "sparse.hip": [],
     "decode.hip": [],
     "decode_mfma.hip": [],
+    "decode_mfma_b2.hip": [],
+    "decode_mfma_b3.hip": [],
+    "decode_mfma_b4.hip": [],
 }
 
 COMMON = [

@@ -1,0 +1,625 @@
+// Matrix-core decode-attention kernel over the packed low-bit KV cache, all bit widths and group
+// sizes (paper, Section 2 attention equation over the quantised cache; the sink / non-sink split
+// of Section 4.2).  Same result as the generic kernel in decode.hip, which documents the folding
+// of scales and zero points.  Included by decode_mfma_b{2,3,4}.hip, one bit width each.
+//
+// Why matrix cores even for a one-row query: at ~0.5 byte per cached element the HBM stream
+// delivers ~1e13 codes/s, and unpack + convert + multiply-add on the vector ALU costs 3+
+// instructions per code, which is what bounds the generic kernel.  Here a code becomes an fp16
+// operand with ~0.6 instruction: a b-bit field sitting in mantissa bits [p, p+b) of a half whose
+// exponent field is set to 25 - p reads as 2^(10-p) + code, so (w & mask) | magic yields two
+// operands at once and most fields need no shift.  The additive offsets leave with the zero
+// points.  The products run on v_mfma_f32_16x16x32_f16; spare columns of the 16-wide tile carry
+// the low half of an fp16 hi/lo split of the other operand (query x scale, weight x scale), so
+// the fp16 rounding of that operand does not reach the result, and - for group size 32 - the
+// second quantisation group that a 64-row tile spans.
+//
+// A workgroup of 8 waves owns one part of the token range of one (sequence, KV head); each wave
+// walks its own run of 128-token chunks with the next chunk's codes already in flight, and the
+// waves meet once, at the end, to merge their running softmax states in LDS.  When a single
+// workgroup covers the whole sequence the kept (sink) tokens' fp16 rows are folded in and the
+// output row is written right there; otherwise the part's state goes to the workspace and the
+// combine kernel of decode.hip finishes.  Per 128-token chunk:
+//   scores  S^T[token, col] = sum_c code[token, c] * B[c, col]     tokens are the M rows
+//   softmax with lane = token (scores pass through LDS once)
+//   output  O^T[chan, col] = sum_t code[t, chan] * W[t, col]       channels are the M rows
+// Operand layouts follow the instruction: lane l holds row (l % 16) and the 8 contraction
+// indices of chunk (l / 16); the result holds rows 4 (l / 16) + i of column (l % 16).
+#pragma once
+
+#include "kvs_device.h"
+
+namespace kvs_mfma {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+#ifndef KVS_MFMA_WAVES
+#define KVS_MFMA_WAVES 8
+#endif
+constexpr int kWaves = KVS_MFMA_WAVES;
+constexpr int kThreads = kWaves * KVS_WAVE;
+constexpr float kLog2eRsqrtD = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
+constexpr float kRsqrtD = 0.08838834764831845f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kWsRow = KVS_HEAD_DIM + 2;
+
+// Exponent patterns (both halves) under which a field at mantissa bit p reads 2^(10-p) + code.
+// They live in vector registers so that (x & mask) | magic is one v_and_or_b32; the empty asm
+// emits nothing and only hides the constants from the compiler, which would otherwise split
+// the operation in two.
+struct Magic {
+  uint32_t m0, m2, m3, m4, m6, m8;   // fields at mantissa bit 0, 2, 3, 4, 6, 8
+};
+__device__ inline Magic make_magic() {
+  Magic m{0x64006400u, 0x5C005C00u, 0x58005800u, 0x54005400u, 0x4C004C00u, 0x44004400u};
+  asm volatile("" : "+v"(m.m0), "+v"(m.m2), "+v"(m.m3), "+v"(m.m4), "+v"(m.m6), "+v"(m.m8));
+  return m;
+}
+
+// Register-level format of one packed word: it unpacks into RPW registers, register rho holding
+// slots (rho, rho + RPW) of the word as two halves; offset(rho) is the additive constant.
+template <int BITS>
+struct Pack;
+template <>
+struct Pack<4> {
+  static constexpr int CPW = 8, RPW = 4, W = 16;
+  __device__ static constexpr float offset(int rho) { return (rho & 1) ? 64.0f : 1024.0f; }
+  __device__ static inline void unpack(uint32_t w, uint32_t* r, const Magic& m) {
+    const uint32_t t = w >> 8;
+    r[0] = (w & 0x000F000Fu) | m.m0;
+    r[1] = (w & 0x00F000F0u) | m.m4;
+    r[2] = (t & 0x000F000Fu) | m.m0;
+    r[3] = (t & 0x00F000F0u) | m.m4;
+  }
+};
+template <>
+struct Pack<3> {   // five codes in bits 0-14, five in bits 16-30
+  static constexpr int CPW = 10, RPW = 5, W = 13;
+  __device__ static constexpr float offset(int rho) { return (rho == 0 || rho == 3) ? 1024.0f : ((rho == 2) ? 16.0f : 128.0f); }
+  __device__ static inline void unpack(uint32_t w, uint32_t* r, const Magic& m) {
+    const uint32_t t = w >> 9;
+    r[0] = (w & 0x00070007u) | m.m0;
+    r[1] = (w & 0x00380038u) | m.m3;
+    r[2] = (w & 0x01C001C0u) | m.m6;
+    r[3] = (t & 0x00070007u) | m.m0;
+    r[4] = (t & 0x00380038u) | m.m3;
+  }
+};
+template <>
+struct Pack<2> {
+  static constexpr int CPW = 16, RPW = 8, W = 8;
+  __device__ static constexpr float offset(int rho) {
+    return (rho == 0 || rho == 5) ? 1024.0f : ((rho == 1 || rho == 6) ? 256.0f : ((rho == 2 || rho == 7) ? 64.0f : (rho == 3 ? 16.0f : 4.0f)));
+  }
+  __device__ static inline void unpack(uint32_t w, uint32_t* r, const Magic& m) {
+    const uint32_t t = w >> 10;
+    r[0] = (w & 0x00030003u) | m.m0;
+    r[1] = (w & 0x000C000Cu) | m.m2;
+    r[2] = (w & 0x00300030u) | m.m4;
+    r[3] = (w & 0x00C000C0u) | m.m6;
+    r[4] = (w & 0x03000300u) | m.m8;
+    r[5] = (t & 0x00030003u) | m.m0;
+    r[6] = (t & 0x000C000Cu) | m.m2;
+    r[7] = (t & 0x00300030u) | m.m4;
+  }
+};
+
+// Lane group g (= lane / 16) streams word rows g, 4 + g, 8 + g, ... of a tile; its unpacked
+// registers, in that order, are cut into operands of 4 registers (8 contraction slots).
+template <int BITS>
+struct Shape {
+  static constexpr int CPW = Pack<BITS>::CPW, RPW = Pack<BITS>::RPW, W = Pack<BITS>::W;
+  static constexpr int KW = (W + 3) / 4;            // word rows per lane group (the last may be missing)
+  static constexpr int NREG = KW * RPW;             // registers per lane and row: 16, 20, 16
+  static constexpr int NOPS = NREG / 4;             // matrix instructions per 16 rows: 4, 5, 4
+  static constexpr int TBL = NOPS * 32;             // halves of one operand-table column
+  static_assert(NREG % 4 == 0, "operands must be whole");
+  // Position in a table column of element e (a channel for Keys, a token of the tile for Values).
+  __device__ static inline int table_pos(int e) {
+    const int w = e / CPW, j = e % CPW;
+    const int lin = (w >> 2) * RPW + (j % RPW);
+    return ((lin >> 2) * 4 + (w & 3)) * 8 + 2 * (lin & 3) + j / RPW;
+  }
+  __device__ static inline float elem_offset(int e) {
+    const int rho = (e % CPW) % RPW;
+    float f = Pack<BITS>::offset(0);
+#pragma unroll
+    for (int i = 1; i < RPW; ++i) f = rho == i ? Pack<BITS>::offset(i) : f;
+    return f;
+  }
+};
+
+__device__ inline uint32_t word_of(const uint4& v, int r) { return r == 0 ? v.x : (r == 1 ? v.y : (r == 2 ? v.z : v.w)); }
+
+// lane n of each 16-lane row receives the value of lane n + S of the same row (0 past the row end).
+template <int S>
+__device__ inline float row_shift_down(float v) {
+  static_assert(S >= 1 && S <= 15, "row shift");
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x100 + S, 0xF, 0xF, true));
+}
+
+__device__ inline void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+struct MfmaArgs {
+  const uint16_t* q;
+  const uint32_t* k_codes; const uint32_t* v_codes; const uint32_t* k_params; const uint32_t* v_params;
+  const uint8_t* keep_mask;
+  const uint16_t* keep_k; const uint16_t* keep_v; const int32_t* keep_cnt;
+  uint16_t* out; float* lse; float* ws;
+  int n, Hkv, cap;
+  int parts;         // workgroups per (b, h)
+  int part_tokens;   // tokens per workgroup
+  int wave_tokens;   // tokens per wave, a multiple of 128
+};
+
+template <int BITS, int G, int R>
+__global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
+  using S = Shape<BITS>;
+  constexpr int W = S::W, KW = S::KW, RPW = S::RPW, NOPS = S::NOPS, TBL = S::TBL;
+  constexpr int NGK = 128 / G;                     // Key token groups per chunk
+  constexpr int NGT = G < 64 ? 2 : 1;              // Key token groups per 64-token tile
+  constexpr int NGC = 128 / G;                     // Value channel groups
+  constexpr int NTAB = G == 128 ? 1 : 2;           // Value operand tables (one per channel half)
+  constexpr int KCOLS = 2 * R * NGT;               // [hi | lo] per group of the tile
+  constexpr int VCOLS = G == 32 ? 4 * R : 2 * R;   // [hi | lo] per channel group of the half
+  static_assert(KCOLS <= 16 && VCOLS <= 16, "tile columns");
+  constexpr int LOG2G = G == 32 ? 5 : (G == 64 ? 6 : 7);
+
+  // Per-wave LDS: operand tables in the instruction's slot order (column *COLS stays zero: the
+  // lanes of the unused tile columns read it, and so do padded slots), and the score exchange.
+  __shared__ __align__(16) _Float16 bq[kWaves][KCOLS + 1][TBL];          // query x Key scale
+  __shared__ __align__(16) float sc[kWaves][R][128];                     // scores, token order
+  __shared__ __align__(16) _Float16 wh[kWaves][NTAB][VCOLS + 1][TBL];    // weight x Value scale
+  __shared__ __align__(16) float part_o[kWaves][R][128];                 // end: each wave's row
+  __shared__ float part_m[kWaves][R], part_l[kWaves][R];
+
+  const int lane = threadIdx.x & (KVS_WAVE - 1), wave = threadIdx.x / KVS_WAVE;
+  const int col = lane & 15, grp = lane >> 4;
+  const Magic magic = make_magic();
+  const int kcol = col < KCOLS ? col : KCOLS;      // table columns this lane's tile column reads
+  const int vcol = col < VCOLS ? col : VCOLS;
+  {
+    uint32_t* zq = reinterpret_cast<uint32_t*>(&bq[wave][0][0]);
+    for (int i = lane; i < (KCOLS + 1) * TBL / 2; i += KVS_WAVE) zq[i] = 0;
+    uint32_t* zw = reinterpret_cast<uint32_t*>(&wh[wave][0][0][0]);
+    for (int i = lane; i < NTAB * (VCOLS + 1) * TBL / 2; i += KVS_WAVE) zw[i] = 0;
+  }
+  const int n = a.n;
+  const size_t bh = blockIdx.x / a.parts;
+  const int part = blockIdx.x % a.parts;
+  const int b = static_cast<int>(bh / a.Hkv), h = static_cast<int>(bh % a.Hkv);
+  const int Hq = a.Hkv * R;
+  const int hq0 = h * R;
+  const int keep_cnt_b = a.keep_cnt[b];            // uniform: a scalar load, issued first
+
+  // Query of the lane's two channels (2 lane, 2 lane + 1), all R heads, scaled to log2 units;
+  // where those channels and the lane's two tokens (lane, lane + 64) sit in a table column.
+  float qf[R][2];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const uint32_t two = reinterpret_cast<const uint32_t*>(a.q + (static_cast<size_t>(b) * Hq + hq0 + r) * 128)[lane];
+    qf[r][0] = kvs::half_bits_to_float(static_cast<uint16_t>(two & 0xFFFFu)) * kLog2eRsqrtD;
+    qf[r][1] = kvs::half_bits_to_float(static_cast<uint16_t>(two >> 16)) * kLog2eRsqrtD;
+  }
+  const int cpos0 = S::table_pos(2 * lane), cpos1 = S::table_pos(2 * lane + 1);
+  const float coff0 = S::elem_offset(2 * lane), coff1 = S::elem_offset(2 * lane + 1);
+  const int tpos0 = S::table_pos(lane), tpos1 = S::table_pos(lane + 64);
+  const float toff0 = S::elem_offset(lane), toff1 = S::elem_offset(lane + 64);
+
+  const int part_end = min(n, (part + 1) * a.part_tokens);
+  const int tok_begin = min(part_end, part * a.part_tokens + wave * a.wave_tokens);
+  const int tok_end = min(part_end, tok_begin + a.wave_tokens);
+  const uint8_t* mask_b = a.keep_mask + static_cast<size_t>(b) * n;
+  const uint32_t* kcodes = a.k_codes + bh * (n / 64) * (W * 64);
+  const uint32_t* vcodes = a.v_codes + bh * (n / 128) * (W * 128);
+  const uint32_t* kparams = a.k_params + bh * (n / G) * 128;
+  const uint32_t* vparams = a.v_params + bh * n * NGC;
+
+  float m_run[R], l_run[R], z_run[R][NGC];         // running max (log2 units), lane-partial sums
+  float4v acc[2][4];                               // [channel half][r]: rows = channels 64 half + 16 grp + 4 i + r
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    m_run[r] = -INFINITY; l_run[r] = 0.0f;
+#pragma unroll
+    for (int g = 0; g < NGC; ++g) z_run[r][g] = 0.0f;
+  }
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc[hf][r] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
+
+  // Streamed data is double buffered in registers, Keys and Values on their own schedule: the
+  // next chunk's Key loads are issued before the current chunk's score product and its Value
+  // loads right after it (when the current Key registers have just died), so a chunk's stream is
+  // in flight for about one whole chunk of math.  Addresses past the wave's last chunk are
+  // clamped to it: every path issues the same number of loads, which keeps the waits exact.
+  struct KeyRegs {
+    uint4 kx[2][KW];       // [64-token tile][word row 4 k + grp], tokens 4 col .. 4 col + 3
+    uint2 kp[NGK];         // parameters of channels 2 lane, 2 lane + 1, per token group
+  };
+  struct ValueRegs {
+    uint4 vx[KW][2];       // [token word row 4 k + grp][channel half], channels 4 col .. + 3
+    uint32_t vp0[NGC], vp1[NGC];   // parameters of tokens lane, lane + 64
+    uint8_t mask0, mask1;  // keep-mask bytes of the same tokens
+  };
+  const int nchunks = (tok_end - tok_begin) / 128;
+  KeyRegs key_a, key_b;
+  ValueRegs val_a, val_b;
+  auto load_keys = [&](KeyRegs& s, int ci) {
+    const int t0 = tok_begin + min(ci, nchunks - 1) * 128;
+    const uint32_t* ktile = kcodes + static_cast<size_t>(t0 / 64) * (W * 64);
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int k = 0; k < KW; ++k) {
+        s.kx[kt][k] = uint4{0, 0, 0, 0};
+        if (4 * k + 3 < W || 4 * k + grp < W)      // only the last word row of a 13-row tile can be missing
+          s.kx[kt][k] = *reinterpret_cast<const uint4*>(ktile + kt * (W * 64) + (4 * k + grp) * 64 + 4 * col);
+      }
+#pragma unroll
+    for (int g = 0; g < NGK; ++g)
+      s.kp[g] = reinterpret_cast<const uint2*>(kparams + static_cast<size_t>(t0 / G + g) * 128)[lane];
+  };
+  auto load_values = [&](ValueRegs& s, int ci) {
+    const int t0 = tok_begin + min(ci, nchunks - 1) * 128;
+    const uint32_t* vtile = vcodes + static_cast<size_t>(t0 / 128) * (W * 128);
+#pragma unroll
+    for (int g = 0; g < NGC; ++g) {
+      s.vp0[g] = vparams[static_cast<size_t>(t0 + lane) * NGC + g];
+      s.vp1[g] = vparams[static_cast<size_t>(t0 + 64 + lane) * NGC + g];
+    }
+    s.mask0 = mask_b[t0 + lane];
+    s.mask1 = mask_b[t0 + 64 + lane];
+#pragma unroll
+    for (int k = 0; k < KW; ++k)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        s.vx[k][hf] = uint4{0, 0, 0, 0};
+        if (4 * k + 3 < W || 4 * k + grp < W)
+          s.vx[k][hf] = *reinterpret_cast<const uint4*>(vtile + (4 * k + grp) * 128 + 64 * hf + 4 * col);
+      }
+  };
+
+  float bias[NGK][R];                              // what the score product holds for offsets and zero points
+
+  auto score_chunk = [&](const KeyRegs& s) {
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      // ---- (1) B operand of the score product: q x scale as hi + lo halves, per token group ----
+      if (G < 128 || kt == 0) {
+#pragma unroll
+        for (int ga = 0; ga < NGT; ++ga) {
+          const int gi = G == 128 ? 0 : kt * NGT + ga;       // group inside the chunk
+          float s0, s1; int z0, z1;
+          kvs::unpack_param(s.kp[gi].x, s0, z0);
+          kvs::unpack_param(s.kp[gi].y, s1, z1);
+          const float zf0 = static_cast<float>(z0) + coff0, zf1 = static_cast<float>(z1) + coff1;
+#pragma unroll
+          for (int r = 0; r < R; ++r) {
+            const float a0 = qf[r][0] * s0, a1 = qf[r][1] * s1;
+            const _Float16 h0 = static_cast<_Float16>(a0), h1 = static_cast<_Float16>(a1);
+            const _Float16 e0 = static_cast<_Float16>(a0 - static_cast<float>(h0));
+            const _Float16 e1 = static_cast<_Float16>(a1 - static_cast<float>(h1));
+            bq[wave][ga * 2 * R + r][cpos0] = h0;  bq[wave][ga * 2 * R + r][cpos1] = h1;
+            bq[wave][ga * 2 * R + R + r][cpos0] = e0;  bq[wave][ga * 2 * R + R + r][cpos1] = e1;
+            // offsets and zero points exactly as the rounded operands will multiply them
+            bias[gi][r] = kvs::wave_sum((static_cast<float>(h0) + static_cast<float>(e0)) * zf0 +
+                                        (static_cast<float>(h1) + static_cast<float>(e1)) * zf1);
+          }
+        }
+        wave_lds_sync();
+      }
+      half8 bqr[NOPS];
+#pragma unroll
+      for (int m = 0; m < NOPS; ++m) bqr[m] = *reinterpret_cast<const half8*>(&bq[wave][kcol][(4 * m + grp) * 8]);
+
+      // ---- (2) scores on the matrix cores; hi + lo columns merged; to LDS in token order -------
+      float4v d[4];                                    // [r]: rows = tokens 64 kt + 4 m + r, m = 0..15
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        d[r] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
+        uint32_t regs[S::NREG];
+#pragma unroll
+        for (int k = 0; k < KW; ++k) Pack<BITS>::unpack(word_of(s.kx[kt][k], r), regs + k * RPW, magic);
+#pragma unroll
+        for (int m = 0; m < NOPS; ++m) {
+          const uint32_t op[4] = {regs[4 * m], regs[4 * m + 1], regs[4 * m + 2], regs[4 * m + 3]};
+          d[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, op), bqr[m], d[r], 0, 0, 0);
+        }
+      }
+      float4v out[4];                                  // [i]: tokens 64 kt + 16 grp + 4 i + (0..3)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float v = d[r][i] + row_shift_down<R>(d[r][i]);            // hi + lo
+          if (NGT == 2) {                                            // rows of lane groups 2, 3 belong to the
+            const float w2 = row_shift_down<(2 * R) % 16 == 0 ? 1 : (2 * R) % 16>(v);   // tile's second token group
+            v = grp >= 2 ? w2 : v;
+          }
+          out[i][r] = v;
+        }
+      if (col < R) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          *reinterpret_cast<float4v*>(&sc[wave][col][64 * kt + 16 * grp + 4 * i]) = out[i];
+      }
+      if (G < 128 && kt == 0) wave_lds_sync();         // the table is rebuilt for the second tile
+    }
+    wave_lds_sync();
+  };
+
+  auto value_chunk = [&](const ValueRegs& s) {
+    // ---- (3) online softmax, lane = tokens (lane, lane + 64); weights x Value scale to LDS -----
+    float alpha[R];
+    {
+      float sv0[NGC], sv1[NGC], zf0[NGC], zf1[NGC];
+#pragma unroll
+      for (int g = 0; g < NGC; ++g) {
+        int z0, z1;
+        kvs::unpack_param(s.vp0[g], sv0[g], z0);
+        kvs::unpack_param(s.vp1[g], sv1[g], z1);
+        zf0[g] = static_cast<float>(z0) + toff0;
+        zf1[g] = static_cast<float>(z1) + toff1;
+      }
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        // token lane is in Key group lane / G of the chunk, token lane + 64 in group (lane + 64) / G
+        float b0 = bias[0][r], b1 = bias[NGK - 1][r];
+        if (NGK == 2) { b0 = bias[0][r]; b1 = bias[1][r]; }
+        if (NGK == 4) { b0 = lane >= 32 ? bias[1][r] : bias[0][r]; b1 = lane >= 32 ? bias[3][r] : bias[2][r]; }
+        const float s0 = s.mask0 ? -INFINITY : sc[wave][r][lane] - b0;
+        const float s1 = s.mask1 ? -INFINITY : sc[wave][r][64 + lane] - b1;
+        const float mx = kvs::wave_max(fmaxf(s0, s1));
+        const float m_new = fmaxf(m_run[r], mx);
+        const float m_use = m_new == -INFINITY ? 0.0f : m_new;
+        alpha[r] = __builtin_amdgcn_exp2f(m_run[r] - m_use);
+        const float e0 = __builtin_amdgcn_exp2f(s0 - m_use), e1 = __builtin_amdgcn_exp2f(s1 - m_use);
+        m_run[r] = m_new;
+        l_run[r] = l_run[r] * alpha[r] + (e0 + e1);
+#pragma unroll
+        for (int g = 0; g < NGC; ++g) {
+          const float w0 = e0 * sv0[g], w1 = e1 * sv1[g];
+          const _Float16 h0 = static_cast<_Float16>(w0), h1 = static_cast<_Float16>(w1);
+          const _Float16 g0 = static_cast<_Float16>(w0 - static_cast<float>(h0));
+          const _Float16 g1 = static_cast<_Float16>(w1 - static_cast<float>(h1));
+          const int tab = G == 128 ? 0 : (G == 64 ? g : g >> 1);
+          const int cb = G == 32 ? (g & 1) * 2 * R : 0;
+          wh[wave][tab][cb + r][tpos0] = h0;  wh[wave][tab][cb + r][tpos1] = h1;
+          wh[wave][tab][cb + R + r][tpos0] = g0;  wh[wave][tab][cb + R + r][tpos1] = g1;
+          z_run[r][g] = z_run[r][g] * alpha[r] + (static_cast<float>(h0) + static_cast<float>(g0)) * zf0[g] +
+                        (static_cast<float>(h1) + static_cast<float>(g1)) * zf1[g];
+        }
+      }
+    }
+    wave_lds_sync();
+
+    // ---- (4) rescale the accumulators if a running max moved, then the Value product -----------
+    {
+      bool moved = false;
+#pragma unroll
+      for (int r = 0; r < R; ++r) moved = moved || alpha[r] != 1.0f;     // wave-uniform
+      if (moved) {
+        float f = 1.0f;
+#pragma unroll
+        for (int r = 0; r < R; ++r) f = (col % R) == r ? alpha[r] : f;
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[hf][r] *= f;
+      }
+    }
+    half8 bwr[NOPS];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      if (NTAB == 2 || hf == 0) {
+#pragma unroll
+        for (int m = 0; m < NOPS; ++m)
+          bwr[m] = *reinterpret_cast<const half8*>(&wh[wave][NTAB == 2 ? hf : 0][vcol][(4 * m + grp) * 8]);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        uint32_t regs[S::NREG];
+#pragma unroll
+        for (int k = 0; k < KW; ++k) Pack<BITS>::unpack(word_of(s.vx[k][hf], r), regs + k * RPW, magic);
+#pragma unroll
+        for (int m = 0; m < NOPS; ++m) {
+          const uint32_t op[4] = {regs[4 * m], regs[4 * m + 1], regs[4 * m + 2], regs[4 * m + 3]};
+          acc[hf][r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, op), bwr[m], acc[hf][r], 0, 0, 0);
+        }
+      }
+    }
+    wave_lds_sync();                                   // tables are rewritten by the next chunk
+  };
+
+  wave_lds_sync();                                     // tables zeroed
+  if (nchunks > 0) {
+    load_keys(key_a, 0);
+    load_values(val_a, 0);
+    for (int ci = 0; ci < nchunks; ci += 2) {
+      load_keys(key_b, ci + 1);
+      score_chunk(key_a);
+      load_values(val_b, ci + 1);
+      value_chunk(val_a);
+      if (ci + 1 >= nchunks) break;
+      load_keys(key_a, ci + 2);
+      score_chunk(key_b);
+      load_values(val_a, ci + 2);
+      value_chunk(val_b);
+    }
+  }
+
+  // ---- kept (sink) rows: start their loads now so that they overlap the merge below -----------
+  // Wave r finishes head r; lane = channels 2 lane, 2 lane + 1.  The first 8 rows are fetched in
+  // one batch (the usual keep set is a handful of tokens).
+  constexpr int kBatch = 8;
+  const bool finisher = wave < R && a.parts == 1;
+  const int cnt = min(keep_cnt_b, a.cap);
+  const uint32_t* kk = reinterpret_cast<const uint32_t*>(a.keep_k) + bh * a.cap * 64 + lane;
+  const uint32_t* kv = reinterpret_cast<const uint32_t*>(a.keep_v) + bh * a.cap * 64 + lane;
+  uint32_t kw[kBatch], vw[kBatch];
+#pragma unroll
+  for (int u = 0; u < kBatch; ++u) { kw[u] = 0; vw[u] = 0; }
+  if (finisher && cnt > 0) {
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int j = min(u, cnt - 1);
+      kw[u] = kk[j * 64];
+      vw[u] = kv[j * 64];
+    }
+  }
+
+  // ---- each wave's state to LDS: unnormalised row, max (natural-log units), sum ----------------
+  {
+    float lsum[R], zsum[R][NGC];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      lsum[r] = kvs::wave_sum(l_run[r]);
+#pragma unroll
+      for (int g = 0; g < NGC; ++g) zsum[r][g] = kvs::wave_sum(z_run[r][g]);
+    }
+    float mmine = m_run[0], lmine = lsum[0];
+#pragma unroll
+    for (int r = 1; r < R; ++r) { mmine = col == r ? m_run[r] : mmine; lmine = col == r ? lsum[r] : lmine; }
+    const int head = col < R ? col : 0;
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      // zero-point term of this lane's rows: channels 64 hf + 16 grp + ..., group (64 hf + 16 grp) / G
+      const int gc = G == 128 ? 0 : (G == 64 ? hf : 2 * hf + (grp >> 1));
+      float zmine = zsum[0][0];
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int g = 0; g < NGC; ++g) zmine = (head == r && gc == g) ? zsum[r][g] : zmine;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float4v o;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float v = acc[hf][r][i] + row_shift_down<R>(acc[hf][r][i]);
+          if (G == 32) {
+            const float w2 = row_shift_down<(2 * R) % 16 == 0 ? 1 : (2 * R) % 16>(v);
+            v = grp >= 2 ? w2 : v;
+          }
+          o[r] = v - zmine;
+        }
+        if (col < R) *reinterpret_cast<float4v*>(&part_o[wave][head][64 * hf + 16 * grp + 4 * i]) = o;
+      }
+    }
+    if (col < R && grp == 0) { part_m[wave][head] = mmine * kLn2; part_l[wave][head] = lmine; }
+  }
+  __syncthreads();
+
+  // ---- merge the waves' states ----------------------------------------------------------------
+  if (wave < R) {
+    const int r = wave;
+    const size_t bq_row = static_cast<size_t>(b) * Hq + hq0 + r;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) M = fmaxf(M, part_m[w][r]);
+    float L = 0.0f, O0 = 0.0f, O1 = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float ms = part_m[w][r];
+      const float f = ms == -INFINITY ? 0.0f : __expf(ms - M);
+      const float2 o = reinterpret_cast<const float2*>(&part_o[w][r][0])[lane];
+      L += part_l[w][r] * f;
+      O0 += o.x * f;
+      O1 += o.y * f;
+    }
+    if (a.parts > 1) {                                 // another kernel merges the parts
+      float* dst = a.ws + (bq_row * a.parts + part) * kWsRow;
+      reinterpret_cast<float2*>(dst)[lane] = float2{O0, O1};
+      if (lane == 0) { dst[128] = M; dst[129] = L; }
+      return;
+    }
+    // Kept tokens: exact fp16 rows join the same running softmax.
+    const uint32_t q2 = reinterpret_cast<const uint32_t*>(a.q + bq_row * 128)[lane];
+    const float q0 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 & 0xFFFFu));
+    const float q1 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 >> 16));
+    for (int j0 = 0; j0 < cnt; j0 += kBatch) {
+      if (j0 > 0) {                                    // rare: more kept tokens than one batch
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+          const int j = min(j0 + u, cnt - 1);
+          kw[u] = kk[j * 64];
+          vw[u] = kv[j * 64];
+        }
+      }
+      float sj[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u)
+        sj[u] = q0 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] & 0xFFFFu)) +
+                q1 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] >> 16));
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1)                 // eight reductions in step
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) sj[u] += __shfl_xor(sj[u], o, KVS_WAVE);
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        if (j0 + u < cnt) {
+          const float sc_u = sj[u] * kRsqrtD;
+          const float m_new = fmaxf(M, sc_u);
+          const float alpha = M == -INFINITY ? 0.0f : __expf(M - m_new);
+          const float p = __expf(sc_u - m_new);
+          L = L * alpha + p;
+          O0 = O0 * alpha + p * kvs::half_bits_to_float(static_cast<uint16_t>(vw[u] & 0xFFFFu));
+          O1 = O1 * alpha + p * kvs::half_bits_to_float(static_cast<uint16_t>(vw[u] >> 16));
+          M = m_new;
+        }
+      }
+    }
+    const float inv = L > 0.0f ? 1.0f / L : 0.0f;
+    const uint32_t packed = static_cast<uint32_t>(kvs::float_to_half_bits_rn(O0 * inv)) |
+                            (static_cast<uint32_t>(kvs::float_to_half_bits_rn(O1 * inv)) << 16);
+    reinterpret_cast<uint32_t*>(a.out + bq_row * 128)[lane] = packed;
+    if (a.lse && lane == 0) a.lse[bq_row] = L > 0.0f ? M + __logf(L) : -INFINITY;
+  }
+}
+
+inline MfmaArgs make_args(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c,
+                          void* out, float* lse, float* ws) {
+  MfmaArgs a;
+  a.q = static_cast<const uint16_t*>(q);
+  a.k_codes = c->k_codes; a.v_codes = c->v_codes; a.k_params = c->k_params; a.v_params = c->v_params;
+  a.keep_mask = c->keep_mask;
+  a.keep_k = static_cast<const uint16_t*>(c->keep_k); a.keep_v = static_cast<const uint16_t*>(c->keep_v);
+  a.keep_cnt = c->keep_cnt;
+  a.out = static_cast<uint16_t*>(out); a.lse = lse; a.ws = ws;
+  a.n = d->n; a.Hkv = d->Hkv; a.cap = d->keep_cap;
+  a.parts = geo.splits; a.part_tokens = geo.split_tokens; a.wave_tokens = geo.wave_tokens;
+  return a;
+}
+
+template <int BITS, int G, int R>
+void launch_one(const kvs_desc* d, const kvs::DecodeGeometry& geo, const MfmaArgs& args, hipStream_t s) {
+  hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R>), dim3(d->B * d->Hkv * geo.splits), dim3(kThreads), 0, s, args);
+}
+
+// Instantiated shapes: every group size with 1 or 4 query heads per KV head; 2 and 8 heads for
+// group size 128 (8 heads x 2 groups x hi/lo would need 32 tile columns at group size 32).
+template <int BITS>
+void launch_bits(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c, void* out,
+                 float* lse, float* ws, hipStream_t s) {
+  const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws);
+  const int rep = d->Hq / d->Hkv;
+  if (d->group == 128) {
+    if (rep == 1) launch_one<BITS, 128, 1>(d, geo, a, s);
+    else if (rep == 2) launch_one<BITS, 128, 2>(d, geo, a, s);
+    else if (rep == 4) launch_one<BITS, 128, 4>(d, geo, a, s);
+    else launch_one<BITS, 128, 8>(d, geo, a, s);
+  } else if (d->group == 64) {
+    if (rep == 1) launch_one<BITS, 64, 1>(d, geo, a, s);
+    else launch_one<BITS, 64, 4>(d, geo, a, s);
+  } else {
+    if (rep == 1) launch_one<BITS, 32, 1>(d, geo, a, s);
+    else launch_one<BITS, 32, 4>(d, geo, a, s);
+  }
+}
+
+}  // namespace kvs_mfma
