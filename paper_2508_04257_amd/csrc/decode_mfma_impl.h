@@ -130,6 +130,17 @@ struct Shape {
   }
 };
 
+// Streaming (read-once) 16-byte load: the code stream should not displace anything in the caches.
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+__device__ inline uint4 load_stream(const uint32_t* src) {
+#ifdef KVS_DECODE_PLAIN_LOADS
+  return *reinterpret_cast<const uint4*>(src);
+#else
+  const uint4v v = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(src));
+  return uint4{v.x, v.y, v.z, v.w};
+#endif
+}
+
 __device__ inline uint32_t word_of(const uint4& v, int r) { return r == 0 ? v.x : (r == 1 ? v.y : (r == 2 ? v.z : v.w)); }
 
 // lane n of each 16-lane row receives the value of lane n + S of the same row (0 past the row end).
@@ -259,7 +270,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
       for (int k = 0; k < KW; ++k) {
         s.kx[kt][k] = uint4{0, 0, 0, 0};
         if (4 * k + 3 < W || 4 * k + grp < W)      // only the last word row of a 13-row tile can be missing
-          s.kx[kt][k] = *reinterpret_cast<const uint4*>(ktile + kt * (W * 64) + (4 * k + grp) * 64 + 4 * col);
+          s.kx[kt][k] = load_stream(ktile + kt * (W * 64) + (4 * k + grp) * 64 + 4 * col);
       }
 #pragma unroll
     for (int g = 0; g < NGK; ++g)
@@ -281,7 +292,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
       for (int hf = 0; hf < 2; ++hf) {
         s.vx[k][hf] = uint4{0, 0, 0, 0};
         if (4 * k + 3 < W || 4 * k + grp < W)
-          s.vx[k][hf] = *reinterpret_cast<const uint4*>(vtile + (4 * k + grp) * 128 + 64 * hf + 4 * col);
+          s.vx[k][hf] = load_stream(vtile + (4 * k + grp) * 128 + 64 * hf + 4 * col);
       }
   };
 

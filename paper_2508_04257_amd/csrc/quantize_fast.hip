@@ -31,6 +31,18 @@ __device__ inline uint32_t pk_min(uint32_t a, uint32_t b) {
 __device__ inline uint32_t pk_max(uint32_t a, uint32_t b) {
   return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b)));
 }
+// Streaming store of 16 bytes: the packed cache is written once and read much later, so it
+// should not linger as dirty lines in the last-level cache (whoever streams next would pay for
+// its write-back).
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+__device__ inline void store_stream(uint4* dst, const uint4& v) {
+  __builtin_nontemporal_store(uint4v{v.x, v.y, v.z, v.w}, reinterpret_cast<uint4v*>(dst));
+}
+__device__ inline uint4 load_stream(const uint4* src) {
+  const uint4v v = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(src));
+  return uint4{v.x, v.y, v.z, v.w};
+}
+
 __device__ inline float lo_half(uint32_t v) { return kvs::half_bits_to_float(static_cast<uint16_t>(v & 0xFFFFu)); }
 __device__ inline float hi_half(uint32_t v) { return kvs::half_bits_to_float(static_cast<uint16_t>(v >> 16)); }
 
@@ -127,7 +139,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
 #pragma unroll
   for (int i = 0; i < ROWS; ++i) {
     const int r = rslot + 16 * i;
-    raw[i] = src[r * 16 + chunk];
+    raw[i] = load_stream(src + r * 16 + chunk);
     kept[i] = mask_b[r] != 0;
   }
 
@@ -198,7 +210,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
   constexpr int quads = (TB / KVS_K_TILE) * W * (KVS_K_TILE / 4);
   for (int qi = tid; qi < quads; qi += kThreads) {
     const int row = qi / (KVS_K_TILE / 4), t4 = qi % (KVS_K_TILE / 4);
-    out[qi] = *reinterpret_cast<const uint4*>(&tile_s[row * TILE_STRIDE + 4 * t4]);
+    store_stream(out + qi, *reinterpret_cast<const uint4*>(&tile_s[row * TILE_STRIDE + 4 * t4]));
   }
 }
 
@@ -230,7 +242,7 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
 
   uint4 raw[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) raw[i] = src[i * 16];
+  for (int i = 0; i < 8; ++i) raw[i] = load_stream(src + i * 16);
 
   // (min, -max) of the lane's 8 values of each row as one packed pair, then across the group's
   // lanes: one packed minimum per step does both.
@@ -297,8 +309,8 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
   if (BITS == 4 || (rs & 1) == 0) {
     const int u = BITS == 4 ? rs : rs / 2;
     uint4* out = reinterpret_cast<uint4*>(v_codes + (bh * tiles_per_head + static_cast<size_t>(tile)) * (W * 128) + u * 128 + 8 * chunk);
-    out[0] = uint4{words[0], words[1], words[2], words[3]};
-    out[1] = uint4{words[4], words[5], words[6], words[7]};
+    store_stream(out, uint4{words[0], words[1], words[2], words[3]});
+    store_stream(out + 1, uint4{words[4], words[5], words[6], words[7]});
   }
 }
 
