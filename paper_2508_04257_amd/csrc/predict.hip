@@ -1,45 +1,51 @@
 // kvs_predict_sinks: sink-token prediction from the extreme activation outliers of the
 // emergence layer's hidden state (paper, Algorithm 1 - the "l = l_E" branch - and Section 4.3).
 //
-// One workgroup per sequence.  Each lane keeps the ordering keys of its tokens (token i lives in
-// lane i % 1024) in registers, so the strided column of H is read exactly once; k rounds of a
-// workgroup-wide arg-max then pick the top-k.  Key = (15-bit fp16 magnitude pattern, lower index
-// first): monotone in |x| for finite inputs and independent of how tokens map to lanes.
+// One workgroup of 16 waves per sequence.  Token i lives in lane i % 1024; each lane keeps the
+// ordering keys of its tokens in registers, so the strided column of H is read exactly once.
+// Key = (15-bit fp16 magnitude pattern, lower index first): monotone in |x| for finite inputs
+// and independent of how tokens map to lanes, so the result is unique.
+// Selection, k <= 64: every wave extracts the top k of its own tokens with wave-level arg-max
+// rounds (no workgroup barrier), then wave 0 extracts the top k of the 16 k candidates.
+// Larger k: k rounds of a workgroup-wide arg-max.
 #include "kvs_device.h"
 
 namespace {
 
 constexpr int kPredictThreads = 1024;
+constexpr int kPredictWaves = kPredictThreads / KVS_WAVE;
 constexpr int kMaxChannels = 8;
-constexpr int kKeysPerLane = KVS_MAX_PREDICT_TOKENS / kPredictThreads;   // 64
+constexpr int kFastK = 64;
 
 struct ChannelList {
   int32_t c[kMaxChannels];
   int32_t count;
 };
 
+// KPL = keys per lane: the kernel is instantiated for n <= 1024 * KPL.
+template <int KPL>
 __global__ __launch_bounds__(kPredictThreads) void predict_sinks_kernel(
     const uint16_t* __restrict__ hidden, int n, int d, ChannelList channels, int k, int first_n,
     int32_t* __restrict__ sink_idx, uint8_t* __restrict__ keep_mask) {
-  __shared__ uint32_t wave_best[kPredictThreads / KVS_WAVE];
+  __shared__ uint32_t cand[kPredictWaves * kFastK];   // per-wave winners (fast path) / wave maxima
   __shared__ int32_t chosen[KVS_MAX_TOPK];
   __shared__ uint32_t round_best;
 
   const int b = blockIdx.x;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & (KVS_WAVE - 1), wave = tid / KVS_WAVE;
   const uint16_t* Hb = hidden + static_cast<size_t>(b) * n * d;
   uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * n;
 
   // key = (magnitude + 1) << 16 | (65535 - index); 0 = no token / already taken.
-  uint32_t key[kKeysPerLane];
+  uint32_t key[KPL];
 #pragma unroll
-  for (int j = 0; j < kKeysPerLane; ++j) {
+  for (int j = 0; j < KPL; ++j) {
     const int i = tid + j * kPredictThreads;
     key[j] = 0;
     if (i < n) {
       uint32_t m = 0;
       for (int c = 0; c < channels.count; ++c) {
-        uint32_t v = Hb[static_cast<size_t>(i) * d + channels.c[c]] & 0x7FFFu;
+        const uint32_t v = Hb[static_cast<size_t>(i) * d + channels.c[c]] & 0x7FFFu;
         m = v > m ? v : m;
       }
       key[j] = ((m + 1) << 16) | static_cast<uint32_t>(65535 - i);
@@ -47,27 +53,59 @@ __global__ __launch_bounds__(kPredictThreads) void predict_sinks_kernel(
     }
   }
 
-  for (int r = 0; r < k; ++r) {
-    uint32_t best = 0;
+  if (k <= kFastK) {
+    for (int r = 0; r < k; ++r) {                       // top k of this wave's tokens
+      uint32_t best = 0;
 #pragma unroll
-    for (int j = 0; j < kKeysPerLane; ++j) best = key[j] > best ? key[j] : best;
-    best = kvs::wave_max_u32(best);
-    if ((tid & (KVS_WAVE - 1)) == 0) wave_best[tid / KVS_WAVE] = best;
+      for (int j = 0; j < KPL; ++j) best = key[j] > best ? key[j] : best;
+      best = kvs::wave_max_u32(best);
+#pragma unroll
+      for (int j = 0; j < KPL; ++j) key[j] = key[j] == best ? 0u : key[j];   // keys are unique
+      if (lane == 0) cand[wave * k + r] = best;         // 0 once the wave has run out of tokens
+    }
     __syncthreads();
-    if (tid < KVS_WAVE) {
-      uint32_t v = tid < kPredictThreads / KVS_WAVE ? wave_best[tid] : 0u;
-      v = kvs::wave_max_u32(v);
-      if (tid == 0) {
-        round_best = v;
-        chosen[r] = 65535 - static_cast<int>(v & 0xFFFFu);
+    if (wave == 0) {                                    // top k of the 16 k candidates
+      constexpr int CPL = kPredictWaves * kFastK / KVS_WAVE;   // 16 candidates per lane at most
+      uint32_t c[CPL];
+#pragma unroll
+      for (int j = 0; j < CPL; ++j) {
+        const int idx = lane + j * KVS_WAVE;
+        c[j] = idx < kPredictWaves * k ? cand[idx] : 0u;
+      }
+      for (int r = 0; r < k; ++r) {
+        uint32_t best = 0;
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) best = c[j] > best ? c[j] : best;
+        best = kvs::wave_max_u32(best);
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) c[j] = c[j] == best ? 0u : c[j];
+        if (lane == 0) chosen[r] = 65535 - static_cast<int>(best & 0xFFFFu);
       }
     }
     __syncthreads();
-    const uint32_t win = round_best;
+  } else {
+    for (int r = 0; r < k; ++r) {
+      uint32_t best = 0;
 #pragma unroll
-    for (int j = 0; j < kKeysPerLane; ++j) key[j] = key[j] == win ? 0u : key[j];   // keys are unique
+      for (int j = 0; j < KPL; ++j) best = key[j] > best ? key[j] : best;
+      best = kvs::wave_max_u32(best);
+      if (lane == 0) cand[wave] = best;
+      __syncthreads();
+      if (tid < KVS_WAVE) {
+        uint32_t v = tid < kPredictWaves ? cand[tid] : 0u;
+        v = kvs::wave_max_u32(v);
+        if (tid == 0) {
+          round_best = v;
+          chosen[r] = 65535 - static_cast<int>(v & 0xFFFFu);
+        }
+      }
+      __syncthreads();
+      const uint32_t win = round_best;
+#pragma unroll
+      for (int j = 0; j < KPL; ++j) key[j] = key[j] == win ? 0u : key[j];
+    }
+    __syncthreads();
   }
-  __syncthreads();
 
   // Ascending output by rank (k is small), and the mask bits of the chosen tokens.
   for (int j = tid; j < k; j += kPredictThreads) {
@@ -77,6 +115,13 @@ __global__ __launch_bounds__(kPredictThreads) void predict_sinks_kernel(
     sink_idx[static_cast<size_t>(b) * k + rank] = mine;
     mask_b[mine] = 1;
   }
+}
+
+template <int KPL>
+void launch_predict(int B, hipStream_t s, const uint16_t* hidden, int n, int d, const ChannelList& list, int k,
+                    int first_n, int32_t* sink_idx, uint8_t* keep_mask) {
+  hipLaunchKernelGGL(predict_sinks_kernel<KPL>, dim3(B), dim3(kPredictThreads), 0, s, hidden, n, d, list, k,
+                     first_n, sink_idx, keep_mask);
 }
 
 }  // namespace
@@ -98,8 +143,10 @@ extern "C" kvs_status kvs_predict_sinks(const void* hidden, int32_t B, int32_t n
   list.count = n_channels;
   for (int j = 0; j < n_channels; ++j) list.c[j] = channels[j];
 
-  hipLaunchKernelGGL(predict_sinks_kernel, dim3(B), dim3(kPredictThreads), 0,
-                     static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(hidden), n, d,
-                     list, k, first_n, sink_idx, keep_mask);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const uint16_t* Hp = static_cast<const uint16_t*>(hidden);
+  if (n <= 4 * kPredictThreads) launch_predict<4>(B, s, Hp, n, d, list, k, first_n, sink_idx, keep_mask);
+  else if (n <= 16 * kPredictThreads) launch_predict<16>(B, s, Hp, n, d, list, k, first_n, sink_idx, keep_mask);
+  else launch_predict<64>(B, s, Hp, n, d, list, k, first_n, sink_idx, keep_mask);
   return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
 }
