@@ -239,8 +239,9 @@ def main() -> int:
             "decode_splits": kb.kvs_decode_splits(bufs[0].desc),
         },
         "roofline": {
-            "kernel": "kvs_decode_attn = decode_mfma_int4_kernel (one launch per call when B*Hkv >= 256)"
-                      if (w.bits == 4 and w.group == 128 and w.sparse_frac == 0) else
+            "kernel": ("kvs_decode_attn = decode_mfma_kernel<%d,%d,%d>" % (w.bits, w.group, w.Hq // w.Hkv)
+                       + ("" if kb.kvs_decode_splits(bufs[0].desc) == 1 else " + decode_combine_kernel"))
+                      if w.sparse_frac == 0 else
                       "kvs_decode_attn = decode_partial_kernel + decode_combine_kernel",
             "bound": "hbm",
             "achieved": round(dec_gbps, 2),
@@ -255,7 +256,9 @@ def main() -> int:
                              "note": "same call repeated over the rotating cold caches, no events between launches"},
         },
         "roofline_quantize": {
-            "kernel": "kvs_quantize_kv (quantize_k_kernel + quantize_v_kernel + keep rows)",
+            "kernel": "kvs_quantize_kv = keep_index_fast_kernel + quantize_k_fast_kernel + quantize_v_fast_kernel"
+                      if (w.bits != 3 and w.sparse_frac == 0) else
+                      "kvs_quantize_kv = quantize_k_kernel + quantize_v_kernel + keep rows (+ histogram, scan, CSR fill)",
             "bound": "hbm",
             "achieved": round(qnt_gbps, 2),
             "peak": HBM_PEAK_GBPS,

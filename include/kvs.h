@@ -42,8 +42,10 @@
  *   keep_k / keep_v  fp16 [B, Hkv, keep_cap, 128]  rows of the kept tokens, ascending token order,
  *            zero padded;  keep_idx int32 [B, keep_cap] (-1 padded);  keep_cnt int32 [B];
  *            keep_mask uint8 [B, n] (copy of the mask the cache was built with).
- *   CSR of isolated outliers (only when sparse_frac > 0), rows = (b, h, token) in that order:
+ *   CSR of isolated outliers (only when sparse_frac > 0), B*Hkv*n rows per tensor:
  *            rowptr int32 [B*Hkv*n + 1], col uint16 [sparse_cap] ascending per row, val fp16.
+ *            Keys: row = (b, h, token), col = channel.  Values: row = (b, h, 128-token tile,
+ *            channel), col = token inside the tile (the transposition of the Value code tiles).
  */
 #ifndef KVS_H
 #define KVS_H
@@ -133,11 +135,15 @@ int32_t kvs_decode_splits(const kvs_desc* desc);
  *   channels  HOST int32 [n_channels], each in [0, d), 1 <= n_channels <= 8
  *   k in [0, min(n, KVS_MAX_TOPK)], first_n in [0, n], n <= KVS_MAX_PREDICT_TOKENS
  *   sink_idx  int32 [B, k] (may be NULL when k == 0);  keep_mask uint8 [B, n]
+ *   workspace kvs_predict_workspace_bytes(B, n, k) bytes of scratch, or NULL.  With it, sequences
+ *             longer than 4096 tokens are scanned by one workgroup per 4096-token slice; without
+ *             it (or when that size is 0) one workgroup scans a whole sequence.  Same result.
  */
+size_t kvs_predict_workspace_bytes(int32_t B, int32_t n, int32_t k);
 kvs_status kvs_predict_sinks(const void* hidden, int32_t B, int32_t n, int32_t d,
                              const int32_t* channels, int32_t n_channels, int32_t k,
                              int32_t first_n, int32_t* sink_idx, uint8_t* keep_mask,
-                             void* stream);
+                             void* workspace, void* stream);
 
 /*
  * Quantise one layer's K and V (fp16 [B, Hkv, n, 128]) into `out`.

@@ -62,8 +62,11 @@ def lib() -> C.CDLL:
         L.kvs_decode_splits.restype = C.c_int32
         L.kvs_decode_splits.argtypes = [C.POINTER(KvsDesc)]
         L.kvs_predict_sinks.restype = C.c_int
+        L.kvs_predict_workspace_bytes.restype = C.c_size_t
+        L.kvs_predict_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
         L.kvs_predict_sinks.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32),
-                                        C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+                                        C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p]
         L.kvs_quantize_kv.restype = C.c_int
         L.kvs_quantize_kv.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.POINTER(KvsCache), C.c_void_p, C.c_void_p]
@@ -156,16 +159,24 @@ def _check_cache(desc: KvsDesc, cache: CacheBuffers) -> None:
         raise ValueError("cache buffers were allocated for a different descriptor")
 
 
+def kvs_predict_workspace_bytes(B: int, n: int, k: int) -> int:
+    return int(lib().kvs_predict_workspace_bytes(B, n, k))
+
+
 def kvs_predict_sinks(hidden: torch.Tensor, channels: Sequence[int], k: int, first_n: int,
-                      sink_idx: Optional[torch.Tensor], keep_mask: torch.Tensor) -> None:
+                      sink_idx: Optional[torch.Tensor], keep_mask: torch.Tensor,
+                      workspace: Optional[torch.Tensor] = None) -> None:
     B, n, d = hidden.shape
     _check_tensor("hidden", hidden, (B, n, d), torch.float16)
     _check_tensor("keep_mask", keep_mask, (B, n), torch.uint8)
     if k > 0:
         _check_tensor("sink_idx", sink_idx, (B, k), torch.int32)
+    if workspace is not None and (not workspace.is_cuda or
+                                  workspace.numel() * workspace.element_size() < kvs_predict_workspace_bytes(B, n, k)):
+        raise ValueError("predict workspace too small")
     ch = (C.c_int32 * len(channels))(*channels)
     st = lib().kvs_predict_sinks(hidden.data_ptr(), B, n, d, ch, len(channels), k, first_n,
-                                 _ptr(sink_idx), keep_mask.data_ptr(), _stream_handle())
+                                 _ptr(sink_idx), keep_mask.data_ptr(), _ptr(workspace), _stream_handle())
     if st != KVS_OK:
         raise KvsError("kvs_predict_sinks", st)
 

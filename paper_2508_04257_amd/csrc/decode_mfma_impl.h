@@ -150,6 +150,12 @@ __device__ inline float row_shift_down(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x100 + S, 0xF, 0xF, true));
 }
 
+// A value that is the same in every lane (the result of a wave reduction), moved to a scalar
+// register: the per-head running state then costs no vector registers.
+__device__ inline float uniform(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, v)));
+}
+
 __device__ inline void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
@@ -319,8 +325,8 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
             bq[wave][ga * 2 * R + r][cpos0] = h0;  bq[wave][ga * 2 * R + r][cpos1] = h1;
             bq[wave][ga * 2 * R + R + r][cpos0] = e0;  bq[wave][ga * 2 * R + R + r][cpos1] = e1;
             // offsets and zero points exactly as the rounded operands will multiply them
-            bias[gi][r] = kvs::wave_sum((static_cast<float>(h0) + static_cast<float>(e0)) * zf0 +
-                                        (static_cast<float>(h1) + static_cast<float>(e1)) * zf1);
+            bias[gi][r] = uniform(kvs::wave_sum((static_cast<float>(h0) + static_cast<float>(e0)) * zf0 +
+                                                (static_cast<float>(h1) + static_cast<float>(e1)) * zf1));
           }
         }
         wave_lds_sync();
@@ -342,6 +348,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
           const uint32_t op[4] = {regs[4 * m], regs[4 * m + 1], regs[4 * m + 2], regs[4 * m + 3]};
           d[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, op), bqr[m], d[r], 0, 0, 0);
         }
+        if (R > 1) __builtin_amdgcn_sched_barrier(0);   // keep one row set's operands live at a time
       }
       float4v out[4];                                  // [i]: tokens 64 kt + 16 grp + 4 i + (0..3)
 #pragma unroll
@@ -386,7 +393,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
         if (NGK == 4) { b0 = lane >= 32 ? bias[1][r] : bias[0][r]; b1 = lane >= 32 ? bias[3][r] : bias[2][r]; }
         const float s0 = s.mask0 ? -INFINITY : sc[wave][r][lane] - b0;
         const float s1 = s.mask1 ? -INFINITY : sc[wave][r][64 + lane] - b1;
-        const float mx = kvs::wave_max(fmaxf(s0, s1));
+        const float mx = uniform(kvs::wave_max(fmaxf(s0, s1)));
         const float m_new = fmaxf(m_run[r], mx);
         const float m_use = m_new == -INFINITY ? 0.0f : m_new;
         alpha[r] = __builtin_amdgcn_exp2f(m_run[r] - m_use);
@@ -443,6 +450,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
           const uint32_t op[4] = {regs[4 * m], regs[4 * m + 1], regs[4 * m + 2], regs[4 * m + 3]};
           acc[hf][r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, op), bwr[m], acc[hf][r], 0, 0, 0);
         }
+        if (R > 1) __builtin_amdgcn_sched_barrier(0);
       }
     }
     wave_lds_sync();                                   // tables are rewritten by the next chunk
@@ -450,18 +458,35 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
 
   wave_lds_sync();                                     // tables zeroed
   if (nchunks > 0) {
-    load_keys(key_a, 0);
-    load_values(val_a, 0);
-    for (int ci = 0; ci < nchunks; ci += 2) {
-      load_keys(key_b, ci + 1);
-      score_chunk(key_a);
-      load_values(val_b, ci + 1);
-      value_chunk(val_a);
-      if (ci + 1 >= nchunks) break;
-      load_keys(key_a, ci + 2);
-      score_chunk(key_b);
-      load_values(val_a, ci + 2);
-      value_chunk(val_b);
+    if (R == 1) {
+      load_keys(key_a, 0);
+      load_values(val_a, 0);
+      for (int ci = 0; ci < nchunks; ci += 2) {
+        load_keys(key_b, ci + 1);
+        score_chunk(key_a);
+        load_values(val_b, ci + 1);
+        value_chunk(val_a);
+        if (ci + 1 >= nchunks) break;
+        load_keys(key_a, ci + 2);
+        score_chunk(key_b);
+        load_values(val_a, ci + 2);
+        value_chunk(val_b);
+      }
+    } else {
+      // Several query heads per KV head keep more state in registers: only the Keys are fetched
+      // a chunk ahead, the Values at the start of their own chunk (they are needed last).
+      load_keys(key_a, 0);
+      for (int ci = 0; ci < nchunks; ci += 2) {
+        load_values(val_a, ci);
+        load_keys(key_b, ci + 1);
+        score_chunk(key_a);
+        value_chunk(val_a);
+        if (ci + 1 >= nchunks) break;
+        load_values(val_a, ci + 1);
+        load_keys(key_a, ci + 2);
+        score_chunk(key_b);
+        value_chunk(val_a);
+      }
     }
   }
 

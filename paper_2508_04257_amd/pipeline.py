@@ -25,6 +25,7 @@ class StepBuffers:
     cache: kb.CacheBuffers
     workspace: torch.Tensor
     sink_idx: Optional[torch.Tensor]
+    predict_ws: Optional[torch.Tensor]
     keep_mask: torch.Tensor
     out: torch.Tensor
     lse: torch.Tensor
@@ -37,6 +38,8 @@ def alloc_step(w: Workload, device="cuda") -> StepBuffers:
         cache=kb.alloc_cache(desc, device),
         workspace=kb.alloc_workspace(desc, device),
         sink_idx=torch.empty((w.B, w.k_sinks), dtype=torch.int32, device=device) if w.k_sinks else None,
+        predict_ws=(torch.empty(kb.kvs_predict_workspace_bytes(w.B, w.n, w.k_sinks), dtype=torch.uint8, device=device)
+                    if kb.kvs_predict_workspace_bytes(w.B, w.n, w.k_sinks) else None),
         keep_mask=torch.empty((w.B, w.n), dtype=torch.uint8, device=device),
         out=torch.empty((w.B, w.Hq, w.D), dtype=torch.float16, device=device),
         lse=torch.empty((w.B, w.Hq), dtype=torch.float32, device=device),
@@ -44,7 +47,8 @@ def alloc_step(w: Workload, device="cuda") -> StepBuffers:
 
 
 def predict(w: Workload, hidden: torch.Tensor, buf: StepBuffers) -> None:
-    kb.kvs_predict_sinks(hidden, list(w.channels), w.k_sinks, w.first_n, buf.sink_idx, buf.keep_mask)
+    kb.kvs_predict_sinks(hidden, list(w.channels), w.k_sinks, w.first_n, buf.sink_idx, buf.keep_mask,
+                         buf.predict_ws)
 
 
 def quantize(K: torch.Tensor, V: torch.Tensor, buf: StepBuffers) -> None:

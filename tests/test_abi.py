@@ -80,8 +80,9 @@ def test_null_pointers_are_rejected_on_the_host():
     assert L.kvs_decode_attn(C.byref(d), 16, C.byref(cache), 16, None, 16, None) == kb.KVS_ERR_INVALID
     assert L.kvs_quantize_kv(None, 16, 16, 16, C.byref(cache), None, None) == kb.KVS_ERR_INVALID
     ch = (C.c_int32 * 1)(5000)
-    assert L.kvs_predict_sinks(16, 1, 128, 4096, ch, 1, 2, 0, 16, 16, None) == kb.KVS_ERR_INVALID   # channel >= d
+    assert L.kvs_predict_sinks(16, 1, 128, 4096, ch, 1, 2, 0, 16, 16, None, None) == kb.KVS_ERR_INVALID   # channel >= d
     ch = (C.c_int32 * 1)(7)
-    assert L.kvs_predict_sinks(None, 1, 128, 4096, ch, 1, 2, 0, 16, 16, None) == kb.KVS_ERR_INVALID
-    assert L.kvs_predict_sinks(16, 1, 128, 4096, ch, 1, 200, 0, 16, 16, None) == kb.KVS_ERR_INVALID  # k > n
-    assert L.kvs_predict_sinks(16, 1, 1 << 20, 4096, ch, 1, 2, 0, 16, 16, None) == kb.KVS_ERR_UNSUPPORTED
+    assert L.kvs_predict_sinks(None, 1, 128, 4096, ch, 1, 2, 0, 16, 16, None, None) == kb.KVS_ERR_INVALID
+    assert L.kvs_predict_sinks(16, 1, 128, 4096, ch, 1, 200, 0, 16, 16, None, None) == kb.KVS_ERR_INVALID  # k > n
+    assert L.kvs_predict_sinks(16, 1, 1 << 20, 4096, ch, 1, 2, 0, 16, 16, None, None) == kb.KVS_ERR_UNSUPPORTED
+    assert kb.kvs_predict_workspace_bytes(4, 32768, 8) == 4 * 8 * 8 * 4 and kb.kvs_predict_workspace_bytes(8, 4096, 5) == 0

@@ -100,8 +100,11 @@ def test_predict_worked_example(name):
     (2, 4096, 32, [31], 0, 16),      # PFN only
     (1, 65536, 4, [2], 8, 0),        # longest supported sequence
     (1, 3000, 8, [1], 1024, 0),      # largest supported k
+    (3, 9000, 8, [1, 6], 64, 20),    # sliced scan, ragged last slice, largest k of the fast path
+    (2, 20000, 8, [3], 65, 0),       # long sequence, k beyond the fast path
 ])
-def test_predict_edge_cases(B, n, d, channels, k, first_n):
+@pytest.mark.parametrize("with_workspace", [False, True])
+def test_predict_edge_cases(B, n, d, channels, k, first_n, with_workspace):
     rng = np.random.default_rng(n + k)
     H = random_fp16(rng, (B, n, d))
     H[:, :, channels[0]] = (np.round(H[:, :, channels[0]].astype(np.float32) * 4) / 4).astype(np.float16)  # many ties
@@ -111,7 +114,10 @@ def test_predict_edge_cases(B, n, d, channels, k, first_n):
     Hd = torch.from_numpy(H).to(DEV)
     mask = torch.full((B, n), 7, dtype=torch.uint8, device=DEV)
     idx = torch.full((B, k), -5, dtype=torch.int32, device=DEV) if k else None
-    kb.kvs_predict_sinks(Hd, channels, k, first_n, idx, mask)
+    ws = None
+    if with_workspace and kb.kvs_predict_workspace_bytes(B, n, k):
+        ws = torch.empty(kb.kvs_predict_workspace_bytes(B, n, k), dtype=torch.uint8, device=DEV)
+    kb.kvs_predict_sinks(Hd, channels, k, first_n, idx, mask, ws)
     torch.cuda.synchronize()
     assert np.array_equal(mask.cpu().numpy(), ref_mask)
     if k:
