@@ -14,12 +14,15 @@
 // the fp16 rounding of that operand does not reach the result, and - for group size 32 - the
 // second quantisation group that a 64-row tile spans.
 //
-// A workgroup of 8 waves owns one part of the token range of one (sequence, KV head); each wave
-// walks its own run of 128-token chunks with the next chunk's codes already in flight, and the
-// waves meet once, at the end, to merge their running softmax states in LDS.  When a single
-// workgroup covers the whole sequence the kept (sink) tokens' fp16 rows are folded in and the
-// output row is written right there; otherwise the part's state goes to the workspace and the
-// combine kernel of decode.hip finishes.  Per 128-token chunk:
+// A workgroup of 8 waves owns one part of the token range of one (sequence, KV head); its
+// 128-token chunks are handed to the waves on demand (a counter in LDS), each wave keeping the
+// next chunk's codes in flight, and the waves meet once, at the end, to merge their running
+// softmax states in LDS.  (Which wave gets which chunk depends on timing, so the fp32 summation
+// order - not the result beyond rounding - can differ between two runs.)  When a single
+// workgroup covers the whole sequence the kept (sink) tokens' fp16 rows are folded in - wave w
+// takes rows w, w + 8, ... as one more softmax state - and the output row is written right
+// there; otherwise the part's state goes to the workspace and the combine kernel of decode.hip
+// finishes.  Per 128-token chunk:
 //   scores  S^T[token, col] = sum_c code[token, c] * B[c, col]     tokens are the M rows
 //   softmax with lane = token (scores pass through LDS once)
 //   output  O^T[chan, col] = sum_t code[t, chan] * W[t, col]       channels are the M rows
@@ -37,10 +40,12 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 #ifndef KVS_MFMA_WAVES
 #define KVS_MFMA_WAVES 8
 #endif
-constexpr int kWaves = KVS_MFMA_WAVES;
-constexpr int kThreads = kWaves * KVS_WAVE;
+#ifndef KVS_MFMA_WAVES_MHA
+#define KVS_MFMA_WAVES_MHA 8
+#endif
+// Waves per workgroup: with one query head per KV head a wave needs fewer registers.
+__host__ __device__ constexpr int waves_for(int R) { return R == 1 ? KVS_MFMA_WAVES_MHA : KVS_MFMA_WAVES; }
 constexpr float kLog2eRsqrtD = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
-constexpr float kRsqrtD = 0.08838834764831845f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kWsRow = KVS_HEAD_DIM + 2;
 
@@ -171,11 +176,11 @@ struct MfmaArgs {
   int n, Hkv, cap;
   int parts;         // workgroups per (b, h)
   int part_tokens;   // tokens per workgroup
-  int wave_tokens;   // tokens per wave, a multiple of 128
 };
 
 template <int BITS, int G, int R>
-__global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
+__global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(MfmaArgs a) {
+  constexpr int kWaves = waves_for(R);
   using S = Shape<BITS>;
   constexpr int W = S::W, KW = S::KW, RPW = S::RPW, NOPS = S::NOPS, TBL = S::TBL;
   constexpr int NGK = 128 / G;                     // Key token groups per chunk
@@ -192,8 +197,11 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
   __shared__ __align__(16) _Float16 bq[kWaves][KCOLS + 1][TBL];          // query x Key scale
   __shared__ __align__(16) float sc[kWaves][R][128];                     // scores, token order
   __shared__ __align__(16) _Float16 wh[kWaves][NTAB][VCOLS + 1][TBL];    // weight x Value scale
-  __shared__ __align__(16) float part_o[kWaves][R][128];                 // end: each wave's row
-  __shared__ float part_m[kWaves][R], part_l[kWaves][R];
+  // At the end each wave leaves its unnormalised output rows (R x 128 floats) in its own table.
+  static_assert(sizeof(wh[0]) >= R * 128 * sizeof(float), "output rows must fit the weight table");
+  auto part_o = [&](int w, int r) -> float* { return reinterpret_cast<float*>(&wh[w][0][0][0]) + r * 128; };
+  __shared__ float part_m[2 * kWaves][R], part_l[2 * kWaves][R];         // [kWaves + w]: wave w's kept rows
+  __shared__ int next_chunk;                                             // chunk hand-out counter
 
   const int lane = threadIdx.x & (KVS_WAVE - 1), wave = threadIdx.x / KVS_WAVE;
   const int col = lane & 15, grp = lane >> 4;
@@ -213,6 +221,15 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
   const int Hq = a.Hkv * R;
   const int hq0 = h * R;
   const int keep_cnt_b = a.keep_cnt[b];            // uniform: a scalar load, issued first
+  // The wave's first kept row (rows past the count are zero padding), requested before the
+  // stream starts so that it has long arrived when it is needed.
+  const uint32_t* keep_rows_k = reinterpret_cast<const uint32_t*>(a.keep_k) + bh * a.cap * 64 + lane;
+  const uint32_t* keep_rows_v = reinterpret_cast<const uint32_t*>(a.keep_v) + bh * a.cap * 64 + lane;
+  uint32_t keep_first_k = 0, keep_first_v = 0;
+  if (a.parts == 1 && wave < a.cap) {
+    keep_first_k = keep_rows_k[wave * 64];
+    keep_first_v = keep_rows_v[wave * 64];
+  }
 
   // Query of the lane's two channels (2 lane, 2 lane + 1), all R heads, scaled to log2 units;
   // where those channels and the lane's two tokens (lane, lane + 64) sit in a table column.
@@ -228,9 +245,11 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
   const int tpos0 = S::table_pos(lane), tpos1 = S::table_pos(lane + 64);
   const float toff0 = S::elem_offset(lane), toff1 = S::elem_offset(lane + 64);
 
-  const int part_end = min(n, (part + 1) * a.part_tokens);
-  const int tok_begin = min(part_end, part * a.part_tokens + wave * a.wave_tokens);
-  const int tok_end = min(part_end, tok_begin + a.wave_tokens);
+  const int part_begin = min(n, part * a.part_tokens);
+  const int part_end = min(n, part_begin + a.part_tokens);
+  const int nchunks = (part_end - part_begin) / 128;       // chunks of this workgroup
+  if (threadIdx.x == 0) next_chunk = kWaves;               // chunks 0 .. kWaves - 1 are the waves' first
+  __syncthreads();
   const uint8_t* mask_b = a.keep_mask + static_cast<size_t>(b) * n;
   const uint32_t* kcodes = a.k_codes + bh * (n / 64) * (W * 64);
   const uint32_t* vcodes = a.v_codes + bh * (n / 128) * (W * 128);
@@ -250,11 +269,11 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) acc[hf][r] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
 
-  // Streamed data is double buffered in registers, Keys and Values on their own schedule: the
-  // next chunk's Key loads are issued before the current chunk's score product and its Value
-  // loads right after it (when the current Key registers have just died), so a chunk's stream is
-  // in flight for about one whole chunk of math.  Addresses past the wave's last chunk are
-  // clamped to it: every path issues the same number of loads, which keeps the waits exact.
+  // Streamed data is double buffered in registers.  A wave takes its next chunk from the
+  // workgroup's counter when it starts one, so waves that the memory system serves late end up
+  // with fewer chunks and all of them stream until the workgroup's range is used up.  Past the
+  // last chunk the same loads are still issued (every path issues the same number of loads, which
+  // keeps the waits exact) but every lane then reads the head of the range: a few cache lines.
   struct KeyRegs {
     uint4 kx[2][KW];       // [64-token tile][word row 4 k + grp], tokens 4 col .. 4 col + 3
     uint2 kp[NGK];         // parameters of channels 2 lane, 2 lane + 1, per token group
@@ -264,47 +283,78 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
     uint32_t vp0[NGC], vp1[NGC];   // parameters of tokens lane, lane + 64
     uint8_t mask0, mask1;  // keep-mask bytes of the same tokens
   };
-  const int nchunks = (tok_end - tok_begin) / 128;
   KeyRegs key_a, key_b;
   ValueRegs val_a, val_b;
-  auto load_keys = [&](KeyRegs& s, int ci) {
-    const int t0 = tok_begin + min(ci, nchunks - 1) * 128;
-    const uint32_t* ktile = kcodes + static_cast<size_t>(t0 / 64) * (W * 64);
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int k = 0; k < KW; ++k) {
-        s.kx[kt][k] = uint4{0, 0, 0, 0};
-        if (4 * k + 3 < W || 4 * k + grp < W)      // only the last word row of a 13-row tile can be missing
-          s.kx[kt][k] = load_stream(ktile + kt * (W * 64) + (4 * k + grp) * 64 + 4 * col);
-      }
-#pragma unroll
-    for (int g = 0; g < NGK; ++g)
-      s.kp[g] = reinterpret_cast<const uint2*>(kparams + static_cast<size_t>(t0 / G + g) * 128)[lane];
+  auto take_chunk = [&]() -> int {
+    int c = 0;
+    if (lane == 0) c = atomicAdd(&next_chunk, 1);
+    return __builtin_amdgcn_readfirstlane(c);
   };
-  auto load_values = [&](ValueRegs& s, int ci) {
-    const int t0 = tok_begin + min(ci, nchunks - 1) * 128;
-    const uint32_t* vtile = vcodes + static_cast<size_t>(t0 / 128) * (W * 128);
+  // Loaders, one piece at a time so that a piece can be requested again the moment it has been
+  // consumed.  A chunk index past the end (wave-uniform) turns the piece into a few cache lines.
+  auto load_key_tile = [&](KeyRegs& s, int ci, int kt) {        // 64 tokens x W words
+    const bool real = ci < nchunks;
+    const int t0 = real ? part_begin + ci * 128 : 0;
+    const int lane_words = real ? grp * 64 + 4 * col : 0;
+    const uint32_t* ktile = kcodes + static_cast<size_t>(t0 / 64 + kt) * (W * 64) + lane_words;
+#pragma unroll
+    for (int k = 0; k < KW; ++k) {
+      s.kx[kt][k] = uint4{0, 0, 0, 0};
+      if (4 * k + 3 < W || 4 * k + grp < W)        // only the last word row of a 13-row tile can be missing
+        s.kx[kt][k] = load_stream(ktile + 4 * k * 64);
+    }
+  };
+  auto load_key_params = [&](KeyRegs& s, int ci, int kt) {      // the token groups that tile kt uses first
+    const bool real = ci < nchunks;
+    const int t0 = real ? part_begin + ci * 128 : 0;
+    const int lane_pair = real ? lane : 0;
+    if (G == 128 && kt == 1) return;
+#pragma unroll
+    for (int ga = 0; ga < NGT; ++ga) {
+      const int g = G == 128 ? 0 : kt * NGT + ga;
+      s.kp[g] = reinterpret_cast<const uint2*>(kparams + static_cast<size_t>(t0 / G + g) * 128)[lane_pair];
+    }
+  };
+  auto load_value_params = [&](ValueRegs& s, int ci) {
+    const bool real = ci < nchunks;
+    const int t0 = real ? part_begin + ci * 128 : 0;
+    const int lane_tok = real ? lane : 0;
 #pragma unroll
     for (int g = 0; g < NGC; ++g) {
-      s.vp0[g] = vparams[static_cast<size_t>(t0 + lane) * NGC + g];
-      s.vp1[g] = vparams[static_cast<size_t>(t0 + 64 + lane) * NGC + g];
+      s.vp0[g] = vparams[static_cast<size_t>(t0 + lane_tok) * NGC + g];
+      s.vp1[g] = vparams[static_cast<size_t>(t0 + 64 + lane_tok) * NGC + g];
     }
-    s.mask0 = mask_b[t0 + lane];
-    s.mask1 = mask_b[t0 + 64 + lane];
-#pragma unroll
-    for (int k = 0; k < KW; ++k)
-#pragma unroll
-      for (int hf = 0; hf < 2; ++hf) {
-        s.vx[k][hf] = uint4{0, 0, 0, 0};
-        if (4 * k + 3 < W || 4 * k + grp < W)
-          s.vx[k][hf] = load_stream(vtile + (4 * k + grp) * 128 + 64 * hf + 4 * col);
-      }
+    s.mask0 = mask_b[t0 + lane_tok];
+    s.mask1 = mask_b[t0 + 64 + lane_tok];
   };
+  auto load_value_half = [&](ValueRegs& s, int ci, int hf) {    // 128 tokens x 64 channels
+    const bool real = ci < nchunks;
+    const int t0 = real ? part_begin + ci * 128 : 0;
+    const int lane_words = real ? grp * 128 + 4 * col : 0;
+    const uint32_t* vtile = vcodes + static_cast<size_t>(t0 / 128) * (W * 128) + lane_words + 64 * hf;
+#pragma unroll
+    for (int k = 0; k < KW; ++k) {
+      s.vx[k][hf] = uint4{0, 0, 0, 0};
+      if (4 * k + 3 < W || 4 * k + grp < W)
+        s.vx[k][hf] = load_stream(vtile + 4 * k * 128);
+    }
+  };
+  auto load_keys = [&](KeyRegs& s, int ci) {
+    load_key_tile(s, ci, 0);  load_key_params(s, ci, 0);     // the order in which they are requested again
+    load_key_tile(s, ci, 1);  load_key_params(s, ci, 1);
+  };
+  auto load_values = [&](ValueRegs& s, int ci) {
+    load_value_params(s, ci);
+    load_value_half(s, ci, 0);  load_value_half(s, ci, 1);
+  };
+  // With one query head per KV head the registers allow two whole chunks of stream per wave:
+  // every piece of the chunk being consumed is requested again, for the chunk after next, as
+  // soon as its last use is over.
+  constexpr bool kRefill = R == 1;
 
   float bias[NGK][R];                              // what the score product holds for offsets and zero points
 
-  auto score_chunk = [&](const KeyRegs& s) {
+  auto score_chunk = [&](KeyRegs& s, int refill) {
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
       // ---- (1) B operand of the score product: q x scale as hi + lo halves, per token group ----
@@ -362,6 +412,12 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
           }
           out[i][r] = v;
         }
+      if (kRefill) {                                   // the barrier keeps the loads below the last use
+        __builtin_amdgcn_sched_barrier(0);
+        load_key_tile(s, refill, kt);
+        load_key_params(s, refill, kt);
+        __builtin_amdgcn_sched_barrier(0);
+      }
       if (col < R) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -372,7 +428,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
     wave_lds_sync();
   };
 
-  auto value_chunk = [&](const ValueRegs& s) {
+  auto value_chunk = [&](ValueRegs& s, int refill) {
     // ---- (3) online softmax, lane = tokens (lane, lane + 64); weights x Value scale to LDS -----
     float alpha[R];
     {
@@ -384,6 +440,9 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
         kvs::unpack_param(s.vp1[g], sv1[g], z1);
         zf0[g] = static_cast<float>(z0) + toff0;
         zf1[g] = static_cast<float>(z1) + toff1;
+        // Convert here and now: the parameter registers are about to be loaded again, and a
+        // conversion postponed past that load would keep them alive in a second set.
+        if (kRefill) asm volatile("" : "+v"(sv0[g]), "+v"(sv1[g]), "+v"(zf0[g]), "+v"(zf1[g]));
       }
 #pragma unroll
       for (int r = 0; r < R; ++r) {
@@ -414,6 +473,11 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
                         (static_cast<float>(h1) + static_cast<float>(g1)) * zf1[g];
         }
       }
+    }
+    if (kRefill) {
+      __builtin_amdgcn_sched_barrier(0);
+      load_value_params(s, refill);
+      __builtin_amdgcn_sched_barrier(0);
     }
     wave_lds_sync();
 
@@ -452,61 +516,81 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
         }
         if (R > 1) __builtin_amdgcn_sched_barrier(0);
       }
+      if (kRefill) {
+        __builtin_amdgcn_sched_barrier(0);
+        load_value_half(s, refill, hf);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     wave_lds_sync();                                   // tables are rewritten by the next chunk
   };
 
   wave_lds_sync();                                     // tables zeroed
-  if (nchunks > 0) {
-    if (R == 1) {
-      load_keys(key_a, 0);
-      load_values(val_a, 0);
-      for (int ci = 0; ci < nchunks; ci += 2) {
-        load_keys(key_b, ci + 1);
-        score_chunk(key_a);
-        load_values(val_b, ci + 1);
-        value_chunk(val_a);
-        if (ci + 1 >= nchunks) break;
-        load_keys(key_a, ci + 2);
-        score_chunk(key_b);
-        load_values(val_a, ci + 2);
-        value_chunk(val_b);
+  if (wave < nchunks) {
+    int cur = wave, nxt = take_chunk();
+    if (kRefill) {
+      load_keys(key_a, cur);
+      load_values(val_a, cur);
+      while (true) {                                   // each piece is requested again for chunk nxt
+        score_chunk(key_a, nxt);                       // as soon as it has been consumed
+        value_chunk(val_a, nxt);
+        if (nxt >= nchunks) break;
+        nxt = take_chunk();
       }
     } else {
       // Several query heads per KV head keep more state in registers: only the Keys are fetched
       // a chunk ahead, the Values at the start of their own chunk (they are needed last).
-      load_keys(key_a, 0);
-      for (int ci = 0; ci < nchunks; ci += 2) {
-        load_values(val_a, ci);
-        load_keys(key_b, ci + 1);
-        score_chunk(key_a);
-        value_chunk(val_a);
-        if (ci + 1 >= nchunks) break;
-        load_values(val_a, ci + 1);
-        load_keys(key_a, ci + 2);
-        score_chunk(key_b);
-        value_chunk(val_a);
+      load_keys(key_a, cur);
+      while (true) {
+        load_values(val_a, cur);
+        load_keys(key_b, nxt);
+        score_chunk(key_a, 0);
+        cur = nxt;  nxt = take_chunk();
+        value_chunk(val_a, 0);
+        if (cur >= nchunks) break;
+        load_values(val_a, cur);
+        load_keys(key_a, nxt);
+        score_chunk(key_b, 0);
+        cur = nxt;  nxt = take_chunk();
+        value_chunk(val_a, 0);
+        if (cur >= nchunks) break;
       }
     }
   }
 
-  // ---- kept (sink) rows: start their loads now so that they overlap the merge below -----------
-  // Wave r finishes head r; lane = channels 2 lane, 2 lane + 1.  The first 8 rows are fetched in
-  // one batch (the usual keep set is a handful of tokens).
-  constexpr int kBatch = 8;
-  const bool finisher = wave < R && a.parts == 1;
-  const int cnt = min(keep_cnt_b, a.cap);
-  const uint32_t* kk = reinterpret_cast<const uint32_t*>(a.keep_k) + bh * a.cap * 64 + lane;
-  const uint32_t* kv = reinterpret_cast<const uint32_t*>(a.keep_v) + bh * a.cap * 64 + lane;
-  uint32_t kw[kBatch], vw[kBatch];
+  // ---- kept (sink) rows: wave w folds rows w, w + kWaves, ... into a softmax state of its own ----
+  // (only when this workgroup covers the whole sequence; otherwise the combine kernel does it).
+  // Lane = channels 2 lane, 2 lane + 1; the wave's score exchange area is free by now and takes
+  // the unnormalised row.  The first row was requested at kernel start.
+  const bool fold_keep = a.parts == 1;
+  if (fold_keep) {
+    const int cnt = min(keep_cnt_b, a.cap);
+    float ms[R], ls[R], o0[R], o1[R];
 #pragma unroll
-  for (int u = 0; u < kBatch; ++u) { kw[u] = 0; vw[u] = 0; }
-  if (finisher && cnt > 0) {
+    for (int r = 0; r < R; ++r) { ms[r] = -INFINITY; ls[r] = 0.0f; o0[r] = 0.0f; o1[r] = 0.0f; }
+    for (int j = wave; j < cnt; j += kWaves) {
+      uint32_t kw = keep_first_k, vw = keep_first_v;
+      if (j != wave) { kw = keep_rows_k[j * 64]; vw = keep_rows_v[j * 64]; }
+      const float k0 = kvs::half_bits_to_float(static_cast<uint16_t>(kw & 0xFFFFu));
+      const float k1 = kvs::half_bits_to_float(static_cast<uint16_t>(kw >> 16));
+      const float v0 = kvs::half_bits_to_float(static_cast<uint16_t>(vw & 0xFFFFu));
+      const float v1 = kvs::half_bits_to_float(static_cast<uint16_t>(vw >> 16));
 #pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      const int j = min(u, cnt - 1);
-      kw[u] = kk[j * 64];
-      vw[u] = kv[j * 64];
+      for (int r = 0; r < R; ++r) {
+        const float s2 = uniform(kvs::wave_sum(qf[r][0] * k0 + qf[r][1] * k1));   // log2 units
+        const float m_new = fmaxf(ms[r], s2);
+        const float alpha = __builtin_amdgcn_exp2f(ms[r] - m_new);
+        const float pj = __builtin_amdgcn_exp2f(s2 - m_new);
+        ls[r] = ls[r] * alpha + pj;
+        o0[r] = o0[r] * alpha + pj * v0;
+        o1[r] = o1[r] * alpha + pj * v1;
+        ms[r] = m_new;
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      reinterpret_cast<float2*>(&sc[wave][r][0])[lane] = float2{o0[r], o1[r]};
+      if (lane == 0) { part_m[kWaves + wave][r] = ms[r] * kLn2; part_l[kWaves + wave][r] = ls[r]; }
     }
   }
 
@@ -544,26 +628,30 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
           }
           o[r] = v - zmine;
         }
-        if (col < R) *reinterpret_cast<float4v*>(&part_o[wave][head][64 * hf + 16 * grp + 4 * i]) = o;
+        if (col < R) *reinterpret_cast<float4v*>(part_o(wave, head) + 64 * hf + 16 * grp + 4 * i) = o;
       }
     }
     if (col < R && grp == 0) { part_m[wave][head] = mmine * kLn2; part_l[wave][head] = lmine; }
   }
   __syncthreads();
 
-  // ---- merge the waves' states ----------------------------------------------------------------
+  // ---- merge the waves' states (and the kept rows' states) -----------------------------------
   if (wave < R) {
     const int r = wave;
     const size_t bq_row = static_cast<size_t>(b) * Hq + hq0 + r;
     float M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) M = fmaxf(M, part_m[w][r]);
+    if (fold_keep) {
+#pragma unroll
+      for (int w = kWaves; w < 2 * kWaves; ++w) M = fmaxf(M, part_m[w][r]);
+    }
     float L = 0.0f, O0 = 0.0f, O1 = 0.0f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
       const float ms = part_m[w][r];
       const float f = ms == -INFINITY ? 0.0f : __expf(ms - M);
-      const float2 o = reinterpret_cast<const float2*>(&part_o[w][r][0])[lane];
+      const float2 o = reinterpret_cast<const float2*>(part_o(w, r))[lane];
       L += part_l[w][r] * f;
       O0 += o.x * f;
       O1 += o.y * f;
@@ -574,41 +662,14 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(MfmaArgs a) {
       if (lane == 0) { dst[128] = M; dst[129] = L; }
       return;
     }
-    // Kept tokens: exact fp16 rows join the same running softmax.
-    const uint32_t q2 = reinterpret_cast<const uint32_t*>(a.q + bq_row * 128)[lane];
-    const float q0 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 & 0xFFFFu));
-    const float q1 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 >> 16));
-    for (int j0 = 0; j0 < cnt; j0 += kBatch) {
-      if (j0 > 0) {                                    // rare: more kept tokens than one batch
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-          const int j = min(j0 + u, cnt - 1);
-          kw[u] = kk[j * 64];
-          vw[u] = kv[j * 64];
-        }
-      }
-      float sj[kBatch];
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u)
-        sj[u] = q0 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] & 0xFFFFu)) +
-                q1 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] >> 16));
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1)                 // eight reductions in step
-#pragma unroll
-        for (int u = 0; u < kBatch; ++u) sj[u] += __shfl_xor(sj[u], o, KVS_WAVE);
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        if (j0 + u < cnt) {
-          const float sc_u = sj[u] * kRsqrtD;
-          const float m_new = fmaxf(M, sc_u);
-          const float alpha = M == -INFINITY ? 0.0f : __expf(M - m_new);
-          const float p = __expf(sc_u - m_new);
-          L = L * alpha + p;
-          O0 = O0 * alpha + p * kvs::half_bits_to_float(static_cast<uint16_t>(vw[u] & 0xFFFFu));
-          O1 = O1 * alpha + p * kvs::half_bits_to_float(static_cast<uint16_t>(vw[u] >> 16));
-          M = m_new;
-        }
-      }
+    for (int w = 0; w < kWaves; ++w) {
+      const float ms = part_m[kWaves + w][r];
+      const float f = ms == -INFINITY ? 0.0f : __expf(ms - M);
+      const float2 o = reinterpret_cast<const float2*>(&sc[w][r][0])[lane];
+      L += part_l[kWaves + w][r] * f;
+      O0 += o.x * f;
+      O1 += o.y * f;
     }
     const float inv = L > 0.0f ? 1.0f / L : 0.0f;
     const uint32_t packed = static_cast<uint32_t>(kvs::float_to_half_bits_rn(O0 * inv)) |
@@ -628,13 +689,13 @@ inline MfmaArgs make_args(const kvs_desc* d, const kvs::DecodeGeometry& geo, con
   a.keep_cnt = c->keep_cnt;
   a.out = static_cast<uint16_t*>(out); a.lse = lse; a.ws = ws;
   a.n = d->n; a.Hkv = d->Hkv; a.cap = d->keep_cap;
-  a.parts = geo.splits; a.part_tokens = geo.split_tokens; a.wave_tokens = geo.wave_tokens;
+  a.parts = geo.splits; a.part_tokens = geo.split_tokens;
   return a;
 }
 
 template <int BITS, int G, int R>
 void launch_one(const kvs_desc* d, const kvs::DecodeGeometry& geo, const MfmaArgs& args, hipStream_t s) {
-  hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R>), dim3(d->B * d->Hkv * geo.splits), dim3(kThreads), 0, s, args);
+  hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R>), dim3(d->B * d->Hkv * geo.splits), dim3(waves_for(R) * KVS_WAVE), 0, s, args);
 }
 
 // Instantiated shapes: every group size with 1 or 4 query heads per KV head; 2 and 8 heads for

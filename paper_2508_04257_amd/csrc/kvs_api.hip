@@ -38,7 +38,6 @@ DecodeGeometry decode_geometry(const kvs_desc* d) {
   const int pairs = d->B * d->Hkv;
   DecodeGeometry g;
   g.mfma = decode_mfma_supported(d);
-  g.wave_tokens = 0;
   int splits;
   if (g.mfma) {
     splits = pairs >= KVS_MFMA_TARGET_GROUPS ? 1 : (KVS_MFMA_TARGET_GROUPS + pairs / 2) / pairs;
@@ -50,10 +49,6 @@ DecodeGeometry decode_geometry(const kvs_desc* d) {
   const int tiles_per_split = (tiles + splits - 1) / splits;
   g.split_tokens = tiles_per_split * KVS_V_TILE;
   g.splits = (tiles + tiles_per_split - 1) / tiles_per_split;
-  if (g.mfma) {
-    const int waves = decode_mfma_waves();
-    g.wave_tokens = ((tiles_per_split + waves - 1) / waves) * KVS_V_TILE;
-  }
   return g;
 }
 

@@ -35,7 +35,6 @@ kvs_status validate_desc(const kvs_desc* d);
 struct DecodeGeometry {
   int splits;        // workgroups (token ranges) per (sequence, KV head)
   int split_tokens;  // tokens per split, a multiple of 128
-  int wave_tokens;   // matrix-core kernel: tokens per wave inside a split, a multiple of 128
   bool mfma;         // matrix-core kernel instead of the generic one
 };
 DecodeGeometry decode_geometry(const kvs_desc* d);
