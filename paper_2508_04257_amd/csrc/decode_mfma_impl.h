@@ -269,11 +269,14 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
 #pragma unroll
     for (int r = 0; r < 4; ++r) acc[hf][r] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
 
-  // Streamed data is double buffered in registers.  A wave takes its next chunk from the
-  // workgroup's counter when it starts one, so waves that the memory system serves late end up
-  // with fewer chunks and all of them stream until the workgroup's range is used up.  Past the
-  // last chunk the same loads are still issued (every path issues the same number of loads, which
-  // keeps the waits exact) but every lane then reads the head of the range: a few cache lines.
+  // The stream of one chunk lives in registers, and every piece of it (a 64-token Key tile, the
+  // parameters, a 64-channel half of the Value tile) is requested again - for the wave's next
+  // chunk - as soon as its last use is over, so that about one chunk per wave is always in
+  // flight.  A wave takes its next chunk from the workgroup's counter when it starts one: waves
+  // that the memory system serves late end up with fewer chunks, and all of them stream until
+  // the workgroup's range is used up.  Past the last chunk the same loads are still issued
+  // (every path issues the same number of loads, which keeps the waits exact) but every lane
+  // then reads the head of the range: a few cache lines.
   struct KeyRegs {
     uint4 kx[2][KW];       // [64-token tile][word row 4 k + grp], tokens 4 col .. 4 col + 3
     uint2 kp[NGK];         // parameters of channels 2 lane, 2 lane + 1, per token group
@@ -283,8 +286,8 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
     uint32_t vp0[NGC], vp1[NGC];   // parameters of tokens lane, lane + 64
     uint8_t mask0, mask1;  // keep-mask bytes of the same tokens
   };
-  KeyRegs key_a, key_b;
-  ValueRegs val_a, val_b;
+  KeyRegs keys;
+  ValueRegs vals;
   auto take_chunk = [&]() -> int {
     int c = 0;
     if (lane == 0) c = atomicAdd(&next_chunk, 1);
@@ -347,11 +350,6 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
     load_value_params(s, ci);
     load_value_half(s, ci, 0);  load_value_half(s, ci, 1);
   };
-  // With one query head per KV head the registers allow two whole chunks of stream per wave:
-  // every piece of the chunk being consumed is requested again, for the chunk after next, as
-  // soon as its last use is over.
-  constexpr bool kRefill = R == 1;
-
   float bias[NGK][R];                              // what the score product holds for offsets and zero points
 
   auto score_chunk = [&](KeyRegs& s, int refill) {
@@ -412,12 +410,10 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
           }
           out[i][r] = v;
         }
-      if (kRefill) {                                   // the barrier keeps the loads below the last use
-        __builtin_amdgcn_sched_barrier(0);
-        load_key_tile(s, refill, kt);
-        load_key_params(s, refill, kt);
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      __builtin_amdgcn_sched_barrier(0);               // keeps the loads below the tile's last use
+      load_key_tile(s, refill, kt);
+      load_key_params(s, refill, kt);
+      __builtin_amdgcn_sched_barrier(0);
       if (col < R) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -442,7 +438,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
         zf1[g] = static_cast<float>(z1) + toff1;
         // Convert here and now: the parameter registers are about to be loaded again, and a
         // conversion postponed past that load would keep them alive in a second set.
-        if (kRefill) asm volatile("" : "+v"(sv0[g]), "+v"(sv1[g]), "+v"(zf0[g]), "+v"(zf1[g]));
+        asm volatile("" : "+v"(sv0[g]), "+v"(sv1[g]), "+v"(zf0[g]), "+v"(zf1[g]));
       }
 #pragma unroll
       for (int r = 0; r < R; ++r) {
@@ -474,11 +470,9 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
         }
       }
     }
-    if (kRefill) {
-      __builtin_amdgcn_sched_barrier(0);
-      load_value_params(s, refill);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+    __builtin_amdgcn_sched_barrier(0);
+    load_value_params(s, refill);
+    __builtin_amdgcn_sched_barrier(0);
     wave_lds_sync();
 
     // ---- (4) rescale the accumulators if a running max moved, then the Value product -----------
@@ -516,45 +510,23 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
         }
         if (R > 1) __builtin_amdgcn_sched_barrier(0);
       }
-      if (kRefill) {
-        __builtin_amdgcn_sched_barrier(0);
-        load_value_half(s, refill, hf);
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      __builtin_amdgcn_sched_barrier(0);
+      load_value_half(s, refill, hf);
+      __builtin_amdgcn_sched_barrier(0);
     }
     wave_lds_sync();                                   // tables are rewritten by the next chunk
   };
 
   wave_lds_sync();                                     // tables zeroed
   if (wave < nchunks) {
-    int cur = wave, nxt = take_chunk();
-    if (kRefill) {
-      load_keys(key_a, cur);
-      load_values(val_a, cur);
-      while (true) {                                   // each piece is requested again for chunk nxt
-        score_chunk(key_a, nxt);                       // as soon as it has been consumed
-        value_chunk(val_a, nxt);
-        if (nxt >= nchunks) break;
-        nxt = take_chunk();
-      }
-    } else {
-      // Several query heads per KV head keep more state in registers: only the Keys are fetched
-      // a chunk ahead, the Values at the start of their own chunk (they are needed last).
-      load_keys(key_a, cur);
-      while (true) {
-        load_values(val_a, cur);
-        load_keys(key_b, nxt);
-        score_chunk(key_a, 0);
-        cur = nxt;  nxt = take_chunk();
-        value_chunk(val_a, 0);
-        if (cur >= nchunks) break;
-        load_values(val_a, cur);
-        load_keys(key_a, nxt);
-        score_chunk(key_b, 0);
-        cur = nxt;  nxt = take_chunk();
-        value_chunk(val_a, 0);
-        if (cur >= nchunks) break;
-      }
+    int nxt = take_chunk();
+    load_keys(keys, wave);
+    load_values(vals, wave);
+    while (true) {                                     // the registers hold the chunk to process and
+      score_chunk(keys, nxt);                          // are filled again, piece by piece, for chunk nxt
+      value_chunk(vals, nxt);
+      if (nxt >= nchunks) break;
+      nxt = take_chunk();
     }
   }
 
