@@ -24,6 +24,7 @@ SOURCES = {
     "quantize_fast.hip": ["-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt"],
     "sparse.hip": [],
     "decode.hip": [],
+    "decode_sparse.hip": [],
     "decode_mfma.hip": [],
     "decode_mfma_b2.hip": [],
     "decode_mfma_b3.hip": [],

@@ -396,8 +396,15 @@ extern "C" kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const
   const kvs::DecodeGeometry geo = kvs::decode_geometry(desc);
   float* ws = static_cast<float*>(workspace);
 
+  if (geo.mfma && desc->sparse_frac > 0.0f) {        // Key corrections, matrix-core kernel, finish
+    float* cs = ws + kvs::decode_parts_floats(desc, geo);
+    kvs::launch_sparse_key_corr(desc, q, cache, cs, s);
+    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, cs, s);
+    kvs::launch_decode_finish_sparse(desc, geo, q, cache, ws, cs, out, lse, s);
+    return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
+  }
   if (geo.mfma) {
-    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, s);
+    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, nullptr, s);
     if (geo.splits == 1) return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;   // finished in one kernel
   } else {
     switch (desc->bits) {

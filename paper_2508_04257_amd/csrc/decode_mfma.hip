@@ -8,13 +8,13 @@
 
 namespace kvs {
 
-void launch_decode_mfma_b2(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, hipStream_t);
-void launch_decode_mfma_b3(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, hipStream_t);
-void launch_decode_mfma_b4(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, hipStream_t);
+void launch_decode_mfma_b2(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, hipStream_t);
+void launch_decode_mfma_b3(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, hipStream_t);
+void launch_decode_mfma_b4(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, hipStream_t);
 
 bool decode_mfma_supported(const kvs_desc* d) {
-  if (d->sparse_frac != 0.0f) return false;          // isolated outliers: generic kernel
   const int rep = d->Hq / d->Hkv;
+  if (d->sparse_frac != 0.0f) return rep == 1;       // isolated outliers: one query head per KV head
   if (rep == 1 || rep == 4) return true;
   return d->group == 128;                            // 2 or 8 query heads per KV head
 }
@@ -22,10 +22,10 @@ bool decode_mfma_supported(const kvs_desc* d) {
 int decode_mfma_waves() { return KVS_MFMA_WAVES; }
 
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                        void* out, float* lse, float* ws, hipStream_t s) {
-  if (d->bits == 2) launch_decode_mfma_b2(d, geo, q, c, out, lse, ws, s);
-  else if (d->bits == 3) launch_decode_mfma_b3(d, geo, q, c, out, lse, ws, s);
-  else launch_decode_mfma_b4(d, geo, q, c, out, lse, ws, s);
+                        void* out, float* lse, float* ws, float* cs, hipStream_t s) {
+  if (d->bits == 2) launch_decode_mfma_b2(d, geo, q, c, out, lse, ws, cs, s);
+  else if (d->bits == 3) launch_decode_mfma_b3(d, geo, q, c, out, lse, ws, cs, s);
+  else launch_decode_mfma_b4(d, geo, q, c, out, lse, ws, cs, s);
 }
 
 }  // namespace kvs

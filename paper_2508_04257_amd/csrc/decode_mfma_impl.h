@@ -173,12 +173,18 @@ struct MfmaArgs {
   const uint8_t* keep_mask;
   const uint16_t* keep_k; const uint16_t* keep_v; const int32_t* keep_cnt;
   uint16_t* out; float* lse; float* ws;
+  float* cs;         // dense-and-sparse only: per (b, hq, token) score correction in, final score out
   int n, Hkv, cap;
   int parts;         // workgroups per (b, h)
   int part_tokens;   // tokens per workgroup
 };
 
-template <int BITS, int G, int R>
+// SPARSE (caches with isolated fp16 outliers): an isolated slot holds code 0.  A kernel that ran
+// before this one left, per token, what replacing those Key slots by their fp16 values adds to the
+// score (a.cs, log2 units); it is added before the softmax, the corrected score is written back in
+// its place, and the workgroup's state always goes to the workspace: the finishing kernel applies
+// the Value-side corrections, which need the final softmax weights.
+template <int BITS, int G, int R, bool SPARSE>
 __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(MfmaArgs a) {
   constexpr int kWaves = waves_for(R);
   using S = Shape<BITS>;
@@ -226,7 +232,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
   const uint32_t* keep_rows_k = reinterpret_cast<const uint32_t*>(a.keep_k) + bh * a.cap * 64 + lane;
   const uint32_t* keep_rows_v = reinterpret_cast<const uint32_t*>(a.keep_v) + bh * a.cap * 64 + lane;
   uint32_t keep_first_k = 0, keep_first_v = 0;
-  if (a.parts == 1 && wave < a.cap) {
+  if (a.parts == 1 && !SPARSE && wave < a.cap) {
     keep_first_k = keep_rows_k[wave * 64];
     keep_first_v = keep_rows_v[wave * 64];
   }
@@ -284,6 +290,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
   struct ValueRegs {
     uint4 vx[KW][2];       // [token word row 4 k + grp][channel half], channels 4 col .. + 3
     uint32_t vp0[NGC], vp1[NGC];   // parameters of tokens lane, lane + 64
+    float c0[SPARSE ? R : 1], c1[SPARSE ? R : 1];   // score corrections of the same tokens
     uint8_t mask0, mask1;  // keep-mask bytes of the same tokens
   };
   KeyRegs keys;
@@ -329,6 +336,14 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
     }
     s.mask0 = mask_b[t0 + lane_tok];
     s.mask1 = mask_b[t0 + 64 + lane_tok];
+    if (SPARSE) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const float* row = a.cs + (static_cast<size_t>(b) * Hq + hq0 + r) * n + t0 + lane_tok;
+        s.c0[r] = row[0];
+        s.c1[r] = row[64];
+      }
+    }
   };
   auto load_value_half = [&](ValueRegs& s, int ci, int hf) {    // 128 tokens x 64 channels
     const bool real = ci < nchunks;
@@ -424,7 +439,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
     wave_lds_sync();
   };
 
-  auto value_chunk = [&](ValueRegs& s, int refill) {
+  auto value_chunk = [&](ValueRegs& s, int refill, int cur) {
     // ---- (3) online softmax, lane = tokens (lane, lane + 64); weights x Value scale to LDS -----
     float alpha[R];
     {
@@ -446,8 +461,13 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
         float b0 = bias[0][r], b1 = bias[NGK - 1][r];
         if (NGK == 2) { b0 = bias[0][r]; b1 = bias[1][r]; }
         if (NGK == 4) { b0 = lane >= 32 ? bias[1][r] : bias[0][r]; b1 = lane >= 32 ? bias[3][r] : bias[2][r]; }
-        const float s0 = s.mask0 ? -INFINITY : sc[wave][r][lane] - b0;
-        const float s1 = s.mask1 ? -INFINITY : sc[wave][r][64 + lane] - b1;
+        float s0 = s.mask0 ? -INFINITY : sc[wave][r][lane] - b0;
+        float s1 = s.mask1 ? -INFINITY : sc[wave][r][64 + lane] - b1;
+        if (SPARSE) {
+          s0 += s.c0[r];  s1 += s.c1[r];
+          float* row = a.cs + (static_cast<size_t>(b) * Hq + hq0 + r) * n + part_begin + cur * 128 + lane;
+          row[0] = s0;  row[64] = s1;
+        }
         const float mx = uniform(kvs::wave_max(fmaxf(s0, s1)));
         const float m_new = fmaxf(m_run[r], mx);
         const float m_use = m_new == -INFINITY ? 0.0f : m_new;
@@ -522,10 +542,12 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
     int nxt = take_chunk();
     load_keys(keys, wave);
     load_values(vals, wave);
-    while (true) {                                     // the registers hold the chunk to process and
-      score_chunk(keys, nxt);                          // are filled again, piece by piece, for chunk nxt
-      value_chunk(vals, nxt);
+    int cur = wave;
+    while (true) {                                     // the registers hold chunk cur and are filled
+      score_chunk(keys, nxt);                          // again, piece by piece, for chunk nxt
+      value_chunk(vals, nxt, cur);
       if (nxt >= nchunks) break;
+      cur = nxt;
       nxt = take_chunk();
     }
   }
@@ -534,7 +556,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
   // (only when this workgroup covers the whole sequence; otherwise the combine kernel does it).
   // Lane = channels 2 lane, 2 lane + 1; the wave's score exchange area is free by now and takes
   // the unnormalised row.  The first row was requested at kernel start.
-  const bool fold_keep = a.parts == 1;
+  const bool fold_keep = a.parts == 1 && !SPARSE;
   if (fold_keep) {
     const int cnt = min(keep_cnt_b, a.cap);
     float ms[R], ls[R], o0[R], o1[R];
@@ -628,7 +650,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
       O0 += o.x * f;
       O1 += o.y * f;
     }
-    if (a.parts > 1) {                                 // another kernel merges the parts
+    if (a.parts > 1 || SPARSE) {                       // another kernel finishes
       float* dst = a.ws + (bq_row * a.parts + part) * kWsRow;
       reinterpret_cast<float2*>(dst)[lane] = float2{O0, O1};
       if (lane == 0) { dst[128] = M; dst[129] = L; }
@@ -652,14 +674,14 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
 }
 
 inline MfmaArgs make_args(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                          void* out, float* lse, float* ws) {
+                          void* out, float* lse, float* ws, float* cs) {
   MfmaArgs a;
   a.q = static_cast<const uint16_t*>(q);
   a.k_codes = c->k_codes; a.v_codes = c->v_codes; a.k_params = c->k_params; a.v_params = c->v_params;
   a.keep_mask = c->keep_mask;
   a.keep_k = static_cast<const uint16_t*>(c->keep_k); a.keep_v = static_cast<const uint16_t*>(c->keep_v);
   a.keep_cnt = c->keep_cnt;
-  a.out = static_cast<uint16_t*>(out); a.lse = lse; a.ws = ws;
+  a.out = static_cast<uint16_t*>(out); a.lse = lse; a.ws = ws; a.cs = cs;
   a.n = d->n; a.Hkv = d->Hkv; a.cap = d->keep_cap;
   a.parts = geo.splits; a.part_tokens = geo.split_tokens;
   return a;
@@ -667,15 +689,23 @@ inline MfmaArgs make_args(const kvs_desc* d, const kvs::DecodeGeometry& geo, con
 
 template <int BITS, int G, int R>
 void launch_one(const kvs_desc* d, const kvs::DecodeGeometry& geo, const MfmaArgs& args, hipStream_t s) {
-  hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R>), dim3(d->B * d->Hkv * geo.splits), dim3(waves_for(R) * KVS_WAVE), 0, s, args);
+  const dim3 grid(d->B * d->Hkv * geo.splits), block(waves_for(R) * KVS_WAVE);
+  if constexpr (R == 1) {
+    if (d->sparse_frac > 0.0f) {
+      hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, true>), grid, block, 0, s, args);
+      return;
+    }
+  }
+  hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, false>), grid, block, 0, s, args);
 }
 
 // Instantiated shapes: every group size with 1 or 4 query heads per KV head; 2 and 8 heads for
 // group size 128 (8 heads x 2 groups x hi/lo would need 32 tile columns at group size 32).
+// The dense-and-sparse variant exists for one query head per KV head.
 template <int BITS>
 void launch_bits(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c, void* out,
-                 float* lse, float* ws, hipStream_t s) {
-  const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws);
+                 float* lse, float* ws, float* cs, hipStream_t s) {
+  const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws, cs);
   const int rep = d->Hq / d->Hkv;
   if (d->group == 128) {
     if (rep == 1) launch_one<BITS, 128, 1>(d, geo, a, s);

@@ -116,7 +116,9 @@ extern "C" size_t kvs_workspace_bytes(const kvs_desc* d) {
   if (kvs::validate_desc(d) != KVS_OK) return 0;
   const kvs::DecodeGeometry g = kvs::decode_geometry(d);
   // decode: per (b, hq, split) the unnormalised fp32 output row plus running max and sum
-  const size_t decode = static_cast<size_t>(d->B) * d->Hq * g.splits * (KVS_HEAD_DIM + 2) * 4;
+  size_t decode = static_cast<size_t>(d->B) * d->Hq * g.splits * (KVS_HEAD_DIM + 2) * 4;
+  if (g.mfma && d->sparse_frac > 0.0f)               // plus one score per (b, hq, token)
+    decode = (kvs::decode_parts_floats(d, g) + kvs::decode_sparse_score_floats(d)) * 4;
   // quantise (dense-and-sparse only): two 32768-bin histograms, thresholds, scan scratch
   const size_t quant = d->sparse_frac > 0.0f ? kvs::sparse_workspace_words(d) * 4 : 0;
   return round16(decode > quant ? decode : quant);

@@ -42,7 +42,18 @@ DecodeGeometry decode_geometry(const kvs_desc* d);
 bool decode_mfma_supported(const kvs_desc* d);
 int decode_mfma_waves();
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                        void* out, float* lse, float* ws, hipStream_t s);
+                        void* out, float* lse, float* ws, float* cs, hipStream_t s);
+// Dense-and-sparse companions of the matrix-core kernel (decode_sparse.hip).  The workspace then
+// holds the parts (B * Hq * splits rows of 130 floats, rounded up to 64 floats) followed by one
+// float per (b, hq, token).
+size_t decode_sparse_score_floats(const kvs_desc* d);
+inline size_t decode_parts_floats(const kvs_desc* d, const DecodeGeometry& g) {
+  const size_t f = static_cast<size_t>(d->B) * d->Hq * g.splits * (KVS_HEAD_DIM + 2);
+  return (f + 63) & ~static_cast<size_t>(63);
+}
+void launch_sparse_key_corr(const kvs_desc* d, const void* q, const kvs_cache* c, float* cs, hipStream_t s);
+void launch_decode_finish_sparse(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
+                                 const float* ws, const float* cs, void* out, float* lse, hipStream_t s);
 
 // Lean 2 / 4 bit dense quantisation kernels (quantize_fast.hip).
 bool quantize_fast_supported(const kvs_desc* d);

@@ -253,6 +253,27 @@ def test_dense_and_sparse_small(bits, G, rep, frac, kind):
     assert np.all(np.isfinite(out2))
 
 
+def test_dense_and_sparse_long_sequence():
+    """More than 4096 tokens: the finishing kernel stages the sequence in two segments, the second one
+    ragged (5 tiles), and the stream is cut into several parts per head."""
+    rng = np.random.default_rng(77)
+    B, H, n, bits, G, frac = 1, 2, 4096 + 640, 4, 128, 0.01
+    K = np.clip(rng.standard_t(4, (B, H, n, 128)), -60000, 60000).astype(np.float16)
+    V = np.clip(rng.standard_t(4, (B, H, n, 128)), -60000, 60000).astype(np.float16)
+    mask = np.zeros((B, n), np.uint8)
+    mask[0, [0, 14, 4095, 4096, n - 1]] = 1
+    q = random_fp16(rng, (B, H, 128))
+    ref = O.quantize_kv(K, V, mask, bits, G, keep_cap=8, sparse_frac=frac)
+    cap = max(len(ref.k_col), len(ref.v_col)) + 16
+    desc, cache, ws = hip_quantize(K, V, mask, bits, G, keep_cap=8, sparse_frac=frac, sparse_cap=cap)
+    assert_cache_equal(cache, ref)
+    assert_csr_equal(cache, ref)
+    out, lse = hip_decode(desc, cache, ws, q)
+    _, ref_lse, ref64 = O.decode_attn(q, ref, Hq=H)
+    assert row_rel_err(out, ref64) <= OUT_TOL
+    assert np.abs(lse - ref_lse).max() <= 2e-3 * max(1.0, np.abs(ref_lse).max())
+
+
 def test_whole_path_on_the_worked_example_workload():
     for name in ("cfg0_kvsink", "cfg0_pfn"):
         w = synth.WORKLOADS[name]
