@@ -61,6 +61,15 @@ void launch_quantize_fast(const kvs_desc* d, const void* K, const void* V, const
                           const kvs_cache* out, hipStream_t s);
 
 // Dense-and-sparse helpers (sparse.hip): where the scratch lives and the launch sequences.
+// Where a quantise kernel leaves the isolated entries of one tensor: every workgroup claims one
+// run of the staging list (counter), notes where it starts (block_base, one per workgroup) and
+// writes its entries there in their final relative order as  index | fp16 value << 16.
+struct SparseEmit {
+  uint32_t* list;     // [cap]
+  int* counter;       // entries claimed so far
+  int* block_base;    // [workgroups of the quantise kernel]
+  long long cap;
+};
 struct SparsePlan {
   size_t rows;      // B * Hkv * n, the row count of both CSR structures
   int nblk;         // scan workgroups
@@ -68,13 +77,14 @@ struct SparsePlan {
   uint32_t* tau;    // [2] thresholds as fp16 magnitude patterns (0x8000 = isolate nothing)
   int* sums_k;      // [nblk + 1] scan scratch
   int* sums_v;
+  SparseEmit emit_k, emit_v;
+  int rows_per_block_k;   // CSR rows per quantise workgroup: max(G, 64) for Keys, 128 for Values
 };
 size_t sparse_workspace_words(const kvs_desc* d);
 SparsePlan sparse_plan(const kvs_desc* d, void* workspace);
 void sparse_thresholds(const kvs_desc* d, const SparsePlan& p, const void* K, const void* V,
                        const uint8_t* mask, const kvs_cache* out, hipStream_t s);
-void sparse_build_csr(const kvs_desc* d, const SparsePlan& p, const void* K, const void* V,
-                      const uint8_t* mask, const kvs_cache* out, hipStream_t s);
+void sparse_build_csr(const kvs_desc* d, const SparsePlan& p, const kvs_cache* out, hipStream_t s);
 
 __host__ __device__ inline int words_per_128(int bits) { return bits == 2 ? 8 : (bits == 3 ? 13 : 16); }
 

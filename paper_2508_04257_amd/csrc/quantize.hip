@@ -66,7 +66,7 @@ template <int BITS, int G>
 __global__ __launch_bounds__(kThreads) void quantize_k_kernel(
     const uint4* __restrict__ K, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
     const uint32_t* __restrict__ tau_ptr, uint32_t* __restrict__ k_codes, uint32_t* __restrict__ k_params,
-    int32_t* __restrict__ row_count) {
+    int32_t* __restrict__ row_count, kvs::SparseEmit emit) {
   constexpr int TB = G > 64 ? G : 64;
   constexpr int NG = TB / G;             // groups per block: 1 or 2
   constexpr int ROWS = TB / 16;          // rows per lane
@@ -77,11 +77,20 @@ __global__ __launch_bounds__(kThreads) void quantize_k_kernel(
   __shared__ float inv_s[NG][128];
   __shared__ int zero_s[NG][128];
   __shared__ __align__(16) uint8_t code_s[TB * kRowStride];
+  // Dense-and-sparse only: which entries of each row are isolated (128 bits per row), where the
+  // row's entries start inside the block's run, and where that run starts in the staging list.
+  __shared__ uint32_t iso_s[TB][4];
+  __shared__ int row_off_s[TB];
+  __shared__ int run_base_s;
 
   const int tid = threadIdx.x;
   const int chunk = tid & 15;            // channels 8*chunk .. 8*chunk+7
   const int rslot = tid >> 4;            // rows rslot, rslot+16, ...
   const uint32_t tau = tau_ptr ? *tau_ptr : 0x8000u;   // 0x8000: no magnitude pattern reaches it
+  if (row_count) {
+    for (int i = tid; i < TB * 4; i += kThreads) (&iso_s[0][0])[i] = 0;
+    __syncthreads();
+  }
   const int blocks_per_head = n / TB;
   const int blk = blockIdx.x % blocks_per_head;
   const size_t bh = blockIdx.x / blocks_per_head;       // b * Hkv + h
@@ -112,13 +121,17 @@ __global__ __launch_bounds__(kThreads) void quantize_k_kernel(
     const int g = i / rows_per_group;     // compile-time after unrolling
     uint16_t h[8];
     unpack8(raw[i], h);
+    uint32_t bits = 0;                    // isolated entries of this row piece
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const bool masked = kept[i] || (h[j] & 0x7FFFu) >= tau;
+      const bool iso = !kept[i] && (h[j] & 0x7FFFu) >= tau;
+      const bool masked = kept[i] || iso;
       const float x = kvs::half_bits_to_float(h[j]);
       mn[g][j] = masked ? mn[g][j] : fminf(mn[g][j], x);
       mx[g][j] = masked ? mx[g][j] : fmaxf(mx[g][j], x);
+      bits |= iso ? 1u << j : 0u;
     }
+    if (row_count && bits) atomicOr(&iso_s[rslot + 16 * i][chunk >> 2], bits << (8 * (chunk & 3)));
   }
 #pragma unroll
   for (int g = 0; g < NG; ++g)
@@ -143,6 +156,33 @@ __global__ __launch_bounds__(kThreads) void quantize_k_kernel(
     zero_s[g][c] = p.zero;
     k_params[(bh * (n / G) + static_cast<size_t>(t0 / G + g)) * 128 + c] = p.word;
   }
+  if (row_count && tid >= kThreads - KVS_WAVE) {
+    // Meanwhile the last wave: row counts (CSR row = token), their exclusive scan over the block,
+    // and one claim in the staging list for the block's whole run.
+    const int lane = tid - (kThreads - KVS_WAVE);
+    int cnt[TB / KVS_WAVE], mine = 0;
+#pragma unroll
+    for (int k = 0; k < TB / KVS_WAVE; ++k) {
+      const int r = lane * (TB / KVS_WAVE) + k;
+      cnt[k] = __popc(iso_s[r][0]) + __popc(iso_s[r][1]) + __popc(iso_s[r][2]) + __popc(iso_s[r][3]);
+      row_count[bh * n + t0 + r] = cnt[k];
+      mine += cnt[k];
+    }
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < KVS_WAVE; o <<= 1) {
+      const int up = __shfl_up(incl, o, KVS_WAVE);
+      if (lane >= o) incl += up;
+    }
+    int run = incl - mine;
+#pragma unroll
+    for (int k = 0; k < TB / KVS_WAVE; ++k) { row_off_s[lane * (TB / KVS_WAVE) + k] = run; run += cnt[k]; }
+    if (lane == KVS_WAVE - 1) {
+      const int base = incl > 0 ? atomicAdd(emit.counter, incl) : 0;
+      emit.block_base[blockIdx.x] = base;
+      run_base_s = base;
+    }
+  }
   __syncthreads();
 
   // Codes of the lane's entries -> bytes in LDS.
@@ -164,16 +204,29 @@ __global__ __launch_bounds__(kThreads) void quantize_k_kernel(
     uint32_t* dst = reinterpret_cast<uint32_t*>(code_s + r * kRowStride + 8 * chunk);
     dst[0] = lo;
     dst[1] = hi;
-    if (row_count) {                     // isolated entries of this row (CSR row = token)
-      int cnt = 0;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) cnt += (!kept[i] && (h[j] & 0x7FFFu) >= tau) ? 1 : 0;
-#pragma unroll
-      for (int o = 1; o < 16; o <<= 1) cnt += __shfl_xor(cnt, o, KVS_WAVE);
-      if (chunk == 0) row_count[bh * n + t0 + r] = cnt;
-    }
   }
   __syncthreads();
+
+  if (row_count) {
+    // Isolated entries to the block's run of the staging list, in final order (rows ascending,
+    // channels ascending inside a row).  Driven by the mask words, one or two per lane, so the
+    // work is proportional to the number of entries; their fp16 values are read again from
+    // memory (two bytes each, just read by this workgroup).
+    const uint16_t* src16 = reinterpret_cast<const uint16_t*>(src);
+    for (int wi = tid; wi < TB * 4; wi += kThreads) {
+      uint32_t m = (&iso_s[0][0])[wi];
+      if (m == 0) continue;
+      const int r = wi >> 2, q4 = wi & 3;
+      long long pos = static_cast<long long>(run_base_s) + row_off_s[r];
+      for (int k = 0; k < q4; ++k) pos += __popc(iso_s[r][k]);
+      while (m) {
+        const int c = 32 * q4 + __builtin_ctz(m);
+        m &= m - 1;
+        if (pos < emit.cap) emit.list[pos] = static_cast<uint32_t>(c) | (static_cast<uint32_t>(src16[r * 128 + c]) << 16);
+        ++pos;
+      }
+    }
+  }
 
   // Pack: the block's words are contiguous in global memory in (tile, w, t) order.
   uint32_t* out = k_codes + (bh * (n / KVS_K_TILE) + static_cast<size_t>(t0 / KVS_K_TILE)) * (W * KVS_K_TILE);
@@ -198,21 +251,25 @@ template <int BITS, int G>
 __global__ __launch_bounds__(kThreads) void quantize_v_kernel(
     const uint4* __restrict__ V, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
     const uint32_t* __restrict__ tau_ptr, uint32_t* __restrict__ v_codes, uint32_t* __restrict__ v_params,
-    int32_t* __restrict__ row_count) {
+    int32_t* __restrict__ row_count, kvs::SparseEmit emit) {
   constexpr int ROWS = KVS_V_TILE / 16;  // 8 rows per lane
   constexpr int W = Fmt<BITS>::W, cpw = Fmt<BITS>::cpw;
   constexpr int LANES_PER_GROUP = G / 8;
   constexpr int NGC = 128 / G;
 
   __shared__ __align__(16) uint8_t code_s[KVS_V_TILE * kRowStride];
-  __shared__ int col_count[128];
+  // Dense-and-sparse only: which tokens of each channel are isolated (128 bits per channel = one
+  // CSR row), where the channel's entries start inside the tile's run, where the run starts.
+  __shared__ uint32_t iso_s[128][4];
+  __shared__ int chan_off_s[128];
+  __shared__ int run_base_s;
 
   const int tid = threadIdx.x;
   const int chunk = tid & 15;
   const int rslot = tid >> 4;
   const uint32_t tau = tau_ptr ? *tau_ptr : 0x8000u;
   if (row_count) {
-    if (tid < 128) col_count[tid] = 0;
+    for (int i = tid; i < 128 * 4; i += kThreads) (&iso_s[0][0])[i] = 0;
     __syncthreads();
   }
   const int tiles_per_head = n / KVS_V_TILE;
@@ -224,17 +281,70 @@ __global__ __launch_bounds__(kThreads) void quantize_v_kernel(
   const uint4* src = V + (bh * n + t0) * 16;
   const uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * n + t0;
 
+  // Load; with isolated outliers, first mark them (per channel: which tokens), so that the counts
+  // and the tile's place in the staging list are known while the codes are being computed.
+  uint4 raw[ROWS];
+  bool kept[ROWS];
+  uint32_t iso_bits[ROWS];               // bit j of row i = channel 8 chunk + j is isolated
 #pragma unroll
   for (int i = 0; i < ROWS; ++i) {
     const int r = rslot + 16 * i;
-    const uint4 raw = src[r * 16 + chunk];
-    const bool kept = mask_b[r] != 0;
+    raw[i] = src[r * 16 + chunk];
+    kept[i] = mask_b[r] != 0;
+    iso_bits[i] = 0;
+  }
+  if (row_count) {
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) {
+      const int r = rslot + 16 * i;
+      uint16_t h[8];
+      unpack8(raw[i], h);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (!kept[i] && (h[j] & 0x7FFFu) >= tau) {
+          iso_bits[i] |= 1u << j;
+          atomicOr(&iso_s[8 * chunk + j][r >> 5], 1u << (r & 31));
+        }
+      }
+    }
+    __syncthreads();
+    if (tid >= kThreads - KVS_WAVE) {
+      // The last wave: channel counts (CSR row = (tile, channel)), their exclusive scan over the
+      // tile, one claim in the staging list for the tile's whole run.
+      const int lane = tid - (kThreads - KVS_WAVE);
+      int cnt[2], mine = 0;
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int c = 2 * lane + k;
+        cnt[k] = __popc(iso_s[c][0]) + __popc(iso_s[c][1]) + __popc(iso_s[c][2]) + __popc(iso_s[c][3]);
+        row_count[(bh * tiles_per_head + static_cast<size_t>(tile)) * 128 + c] = cnt[k];
+        mine += cnt[k];
+      }
+      int incl = mine;
+#pragma unroll
+      for (int o = 1; o < KVS_WAVE; o <<= 1) {
+        const int up = __shfl_up(incl, o, KVS_WAVE);
+        if (lane >= o) incl += up;
+      }
+      chan_off_s[2 * lane] = incl - mine;
+      chan_off_s[2 * lane + 1] = incl - mine + cnt[0];
+      if (lane == KVS_WAVE - 1) {
+        const int base = incl > 0 ? atomicAdd(emit.counter, incl) : 0;
+        emit.block_base[blockIdx.x] = base;
+        run_base_s = base;
+      }
+    }
+  }
+
+#pragma unroll
+  for (int i = 0; i < ROWS; ++i) {
+    const int r = rslot + 16 * i;
     uint16_t h[8];
-    unpack8(raw, h);
+    unpack8(raw[i], h);
     float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const bool masked = kept || (h[j] & 0x7FFFu) >= tau;
+      const bool masked = kept[i] || ((iso_bits[i] >> j) & 1u);
       const float x = kvs::half_bits_to_float(h[j]);
       mn = masked ? mn : fminf(mn, x);
       mx = masked ? mx : fmaxf(mx, x);
@@ -251,10 +361,9 @@ __global__ __launch_bounds__(kThreads) void quantize_v_kernel(
     uint32_t lo = 0, hi = 0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const bool masked = kept || (h[j] & 0x7FFFu) >= tau;
+      const bool masked = kept[i] || ((iso_bits[i] >> j) & 1u);
       const uint32_t c = quantize_one<BITS>(kvs::half_bits_to_float(h[j]), p.inv, p.zero, masked);
       if (j < 4) lo |= c << (8 * j); else hi |= c << (8 * (j - 4));
-      if (row_count && masked && !kept) atomicAdd(&col_count[8 * chunk + j], 1);   // integer: order-free
     }
     uint32_t* dst = reinterpret_cast<uint32_t*>(code_s + r * kRowStride + 8 * chunk);
     dst[0] = lo;
@@ -262,8 +371,24 @@ __global__ __launch_bounds__(kThreads) void quantize_v_kernel(
   }
   __syncthreads();
 
-  if (row_count && tid < 128)            // CSR row = (tile, channel)
-    row_count[(bh * tiles_per_head + static_cast<size_t>(tile)) * 128 + tid] = col_count[tid];
+  if (row_count) {
+    // Isolated entries to the tile's run of the staging list in final order (channels ascending,
+    // tokens ascending inside a channel), driven by the mask words; values read again from memory.
+    const uint16_t* src16 = reinterpret_cast<const uint16_t*>(src);
+    for (int wi = tid; wi < 128 * 4; wi += kThreads) {
+      uint32_t m = (&iso_s[0][0])[wi];
+      if (m == 0) continue;
+      const int c = wi >> 2, q4 = wi & 3;
+      long long pos = static_cast<long long>(run_base_s) + chan_off_s[c];
+      for (int k = 0; k < q4; ++k) pos += __popc(iso_s[c][k]);
+      while (m) {
+        const int t = 32 * q4 + __builtin_ctz(m);
+        m &= m - 1;
+        if (pos < emit.cap) emit.list[pos] = static_cast<uint32_t>(t) | (static_cast<uint32_t>(src16[t * 128 + c]) << 16);
+        ++pos;
+      }
+    }
+  }
 
   // Pack along tokens: word (u, c) holds tokens cpw*u .. of channel c; contiguous per block.
   uint32_t* out = v_codes + (bh * tiles_per_head + static_cast<size_t>(tile)) * (W * 128);
@@ -344,24 +469,24 @@ __global__ __launch_bounds__(KVS_WAVE) void keep_gather_kernel(
 
 template <int BITS, int G>
 void launch_dense(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask,
-                  const kvs_cache* out, const uint32_t* tau, hipStream_t stream) {
+                  const kvs_cache* out, const uint32_t* tau, const kvs::SparsePlan& plan, hipStream_t stream) {
   constexpr int TB = G > 64 ? G : 64;
   const int bh = d->B * d->Hkv;
   hipLaunchKernelGGL((quantize_k_kernel<BITS, G>), dim3(bh * (d->n / TB)), dim3(kThreads), 0, stream,
                      static_cast<const uint4*>(K), mask, d->n, d->Hkv, tau, out->k_codes, out->k_params,
-                     tau ? out->k_rowptr + 1 : nullptr);
+                     tau ? out->k_rowptr + 1 : nullptr, plan.emit_k);
   hipLaunchKernelGGL((quantize_v_kernel<BITS, G>), dim3(bh * (d->n / KVS_V_TILE)), dim3(kThreads), 0,
                      stream, static_cast<const uint4*>(V), mask, d->n, d->Hkv, tau ? tau + 1 : nullptr,
-                     out->v_codes, out->v_params, tau ? out->v_rowptr + 1 : nullptr);
+                     out->v_codes, out->v_params, tau ? out->v_rowptr + 1 : nullptr, plan.emit_v);
 }
 
 template <int BITS>
 void launch_dense_g(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask,
-                    const kvs_cache* out, const uint32_t* tau, hipStream_t s) {
+                    const kvs_cache* out, const uint32_t* tau, const kvs::SparsePlan& plan, hipStream_t s) {
   switch (d->group) {
-    case 32: launch_dense<BITS, 32>(d, K, V, mask, out, tau, s); break;
-    case 64: launch_dense<BITS, 64>(d, K, V, mask, out, tau, s); break;
-    default: launch_dense<BITS, 128>(d, K, V, mask, out, tau, s); break;
+    case 32: launch_dense<BITS, 32>(d, K, V, mask, out, tau, plan, s); break;
+    case 64: launch_dense<BITS, 64>(d, K, V, mask, out, tau, plan, s); break;
+    default: launch_dense<BITS, 128>(d, K, V, mask, out, tau, plan, s); break;
   }
 }
 
@@ -396,11 +521,11 @@ extern "C" kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const
     tau = plan.tau;
   }
   switch (desc->bits) {
-    case 2: launch_dense_g<2>(desc, K, V, keep_mask, out, tau, s); break;
-    case 3: launch_dense_g<3>(desc, K, V, keep_mask, out, tau, s); break;
-    default: launch_dense_g<4>(desc, K, V, keep_mask, out, tau, s); break;
+    case 2: launch_dense_g<2>(desc, K, V, keep_mask, out, tau, plan, s); break;
+    case 3: launch_dense_g<3>(desc, K, V, keep_mask, out, tau, plan, s); break;
+    default: launch_dense_g<4>(desc, K, V, keep_mask, out, tau, plan, s); break;
   }
-  if (sparse) kvs::sparse_build_csr(desc, plan, K, V, keep_mask, out, s);
+  if (sparse) kvs::sparse_build_csr(desc, plan, out, s);
   hipLaunchKernelGGL(keep_index_kernel, dim3(desc->B), dim3(kIndexThreads), 0, s, keep_mask, desc->n,
                      desc->keep_cap, out->keep_idx, out->keep_cnt, out->keep_mask, out->status);
   if (desc->keep_cap > 0)

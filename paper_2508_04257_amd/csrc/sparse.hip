@@ -6,8 +6,10 @@
 // non-kept tokens (one workgroup per compute unit, the whole 32768-bin histogram in 128 KB of
 // LDS), then a suffix scan picks the magnitude tau at which the descending cumulative count
 // first reaches ceil(f * count).  Integer counting only, so the result is order-free.
-// CSR: per-row counts come out of the quantise kernels, an in-place scan turns them into row
-// pointers, and a fill pass writes (index, fp16 value) pairs in ascending order.
+// CSR: the quantise kernels count the isolated entries per row and park them, block by block and
+// already in their final relative order, in a staging list; an in-place scan turns the counts
+// into row pointers and one small kernel moves every block's run to its place.  K and V are
+// read twice in all (histogram, quantise).
 #include "kvs_device.h"
 
 namespace {
@@ -152,66 +154,22 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(int* __restric
   }
 }
 
-// ---- fill ----------------------------------------------------------------------------------
-// Keys: rows = (b, h, token), column = channel.  16 lanes per row, 8 channels per lane.
-__global__ __launch_bounds__(256) void csr_fill_k_kernel(
-    const uint4* __restrict__ K, const uint8_t* __restrict__ keep_mask, size_t rows, int n, int Hkv,
-    const uint32_t* __restrict__ tau_ptr, const int32_t* __restrict__ rowptr, long long cap,
-    uint16_t* __restrict__ col, uint16_t* __restrict__ val) {
-  const size_t row = blockIdx.x * static_cast<size_t>(16) + (threadIdx.x >> 4);
-  const int chunk = threadIdx.x & 15;
-  if (row >= rows) return;                                // rows is a multiple of 16: never taken
-  const uint32_t tau = *tau_ptr;
-  const size_t b = row / (static_cast<size_t>(Hkv) * n);
-  const int t = static_cast<int>(row % n);
-  const bool kept = keep_mask[b * n + t] != 0;
-  const uint4 raw = K[row * 16 + chunk];
-  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-  uint16_t hv[8];
-  int cnt = 0;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    hv[j] = static_cast<uint16_t>(j & 1 ? w[j >> 1] >> 16 : w[j >> 1] & 0xFFFFu);
-    cnt += (!kept && (hv[j] & 0x7FFFu) >= tau) ? 1 : 0;
-  }
-  int incl = cnt;
-#pragma unroll
-  for (int o = 1; o < 16; o <<= 1) {
-    const int up = __shfl_up(incl, o, 16);
-    if (chunk >= o) incl += up;
-  }
-  long long pos = static_cast<long long>(rowptr[row]) + incl - cnt;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    if (!kept && (hv[j] & 0x7FFFu) >= tau) {
-      if (pos < cap) { col[pos] = static_cast<uint16_t>(8 * chunk + j); val[pos] = hv[j]; }
-      ++pos;
-    }
-  }
-}
-
-// Values: rows = (b, h, 128-token tile, channel), column = token inside the tile.  One lane per
-// channel walks the tile's tokens in order.
-__global__ __launch_bounds__(128) void csr_fill_v_kernel(
-    const uint16_t* __restrict__ V, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
-    const uint32_t* __restrict__ tau_ptr, const int32_t* __restrict__ rowptr, long long cap,
-    uint16_t* __restrict__ col, uint16_t* __restrict__ val) {
-  const int c = threadIdx.x;
-  const int tiles = n / KVS_V_TILE;
-  const int tile = blockIdx.x % tiles;
-  const size_t bh = blockIdx.x / tiles;
-  const size_t b = bh / Hkv;
-  const int t0 = tile * KVS_V_TILE;
-  const uint32_t tau = *tau_ptr;
-  const uint16_t* src = V + (bh * n + t0) * 128 + c;
-  const uint8_t* mask_b = keep_mask + b * n + t0;
-  long long pos = rowptr[(bh * tiles + tile) * 128 + c];
-#pragma unroll 8
-  for (int t = 0; t < KVS_V_TILE; ++t) {
-    const uint16_t x = src[static_cast<size_t>(t) * 128];
-    if (!mask_b[t] && (x & 0x7FFFu) >= tau) {
-      if (pos < cap) { col[pos] = static_cast<uint16_t>(t); val[pos] = x; }
-      ++pos;
+// ---- staging list -> CSR ---------------------------------------------------------------------
+// One wave per workgroup of the quantise kernel: its run of the staging list, already in final
+// order, moves to where the scanned row pointers put the block's first row.  A run that did not
+// fit the list (a reported overflow) is replaced by harmless entries.
+__global__ __launch_bounds__(KVS_WAVE) void csr_move_kernel(
+    const uint32_t* __restrict__ list, const int* __restrict__ block_base, int rows_per_block,
+    const int32_t* __restrict__ rowptr, long long cap, uint16_t* __restrict__ col, uint16_t* __restrict__ val) {
+  const size_t first_row = blockIdx.x * static_cast<size_t>(rows_per_block);
+  const long long dst0 = rowptr[first_row];
+  const int cnt = static_cast<int>(rowptr[first_row + rows_per_block] - dst0);
+  const long long src0 = block_base[blockIdx.x];
+  for (int e = threadIdx.x; e < cnt; e += KVS_WAVE) {
+    if (dst0 + e < cap) {
+      const uint32_t w = src0 + e < cap ? list[src0 + e] : 0u;
+      col[dst0 + e] = static_cast<uint16_t>(w & 0xFFFFu);
+      val[dst0 + e] = static_cast<uint16_t>(w >> 16);
     }
   }
 }
@@ -220,11 +178,15 @@ __global__ __launch_bounds__(128) void csr_fill_v_kernel(
 
 namespace kvs {
 
-// Workspace layout in uint32 words.
+// Workspace layout in uint32 words: histograms, thresholds and the two staging counters (zeroed
+// together), scan scratch, the per-workgroup run starts, the two staging lists.
+static int key_block_rows(const kvs_desc* d) { return d->group > 64 ? d->group : 64; }
+
 size_t sparse_workspace_words(const kvs_desc* d) {
   const size_t rows = static_cast<size_t>(d->B) * d->Hkv * d->n;
   const size_t nblk = (rows + kScanBlock - 1) / kScanBlock;
-  return 2 * kBins + 64 + 2 * (nblk + 1);
+  const size_t bases = rows / key_block_rows(d) + rows / KVS_V_TILE;
+  return 2 * kBins + 64 + 2 * (nblk + 1) + bases + 2 * static_cast<size_t>(d->sparse_cap);
 }
 
 SparsePlan sparse_plan(const kvs_desc* d, void* workspace) {
@@ -234,9 +196,15 @@ SparsePlan sparse_plan(const kvs_desc* d, void* workspace) {
   p.rows = rows;
   p.nblk = static_cast<int>((rows + kScanBlock - 1) / kScanBlock);
   p.hist = w;
-  p.tau = w + 2 * kBins;
+  p.tau = w + 2 * kBins;                                   // words 0, 1 of a 64-word block
   p.sums_k = reinterpret_cast<int*>(w + 2 * kBins + 64);
   p.sums_v = p.sums_k + p.nblk + 1;
+  p.rows_per_block_k = key_block_rows(d);
+  int* bases = p.sums_v + p.nblk + 1;
+  uint32_t* lists = reinterpret_cast<uint32_t*>(bases + rows / p.rows_per_block_k + rows / KVS_V_TILE);
+  p.emit_k = SparseEmit{lists, reinterpret_cast<int*>(w + 2 * kBins + 2), bases, d->sparse_cap};
+  p.emit_v = SparseEmit{lists + d->sparse_cap, reinterpret_cast<int*>(w + 2 * kBins + 3),
+                        bases + rows / p.rows_per_block_k, d->sparse_cap};
   return p;
 }
 
@@ -253,8 +221,7 @@ void sparse_thresholds(const kvs_desc* d, const SparsePlan& p, const void* K, co
   hipLaunchKernelGGL(sparse_threshold_kernel, dim3(2), dim3(1024), 0, s, p.hist, d->sparse_frac, p.tau);
 }
 
-void sparse_build_csr(const kvs_desc* d, const SparsePlan& p, const void* K, const void* V,
-                      const uint8_t* mask, const kvs_cache* out, hipStream_t s) {
+void sparse_build_csr(const kvs_desc* d, const SparsePlan& p, const kvs_cache* out, hipStream_t s) {
   const long long cap = d->sparse_cap;
   int* xs[2] = {out->k_rowptr + 1, out->v_rowptr + 1};
   int* sums[2] = {p.sums_k, p.sums_v};
@@ -263,12 +230,12 @@ void sparse_build_csr(const kvs_desc* d, const SparsePlan& p, const void* K, con
     hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(kScanThreads), 0, s, sums[i], p.nblk, cap, out->status);
     hipLaunchKernelGGL(scan_apply_kernel, dim3(p.nblk), dim3(kScanThreads), 0, s, xs[i], p.rows, sums[i]);
   }
-  hipLaunchKernelGGL(csr_fill_k_kernel, dim3(static_cast<unsigned>(p.rows / 16)), dim3(256), 0, s,
-                     static_cast<const uint4*>(K), mask, p.rows, d->n, d->Hkv, p.tau, out->k_rowptr, cap,
-                     out->k_col, static_cast<uint16_t*>(out->k_val));
-  hipLaunchKernelGGL(csr_fill_v_kernel, dim3(static_cast<unsigned>(p.rows / KVS_V_TILE)), dim3(128), 0, s,
-                     static_cast<const uint16_t*>(V), mask, d->n, d->Hkv, p.tau + 1, out->v_rowptr, cap,
-                     out->v_col, static_cast<uint16_t*>(out->v_val));
+  hipLaunchKernelGGL(csr_move_kernel, dim3(static_cast<unsigned>(p.rows / p.rows_per_block_k)), dim3(KVS_WAVE), 0, s,
+                     p.emit_k.list, p.emit_k.block_base, p.rows_per_block_k, out->k_rowptr, cap, out->k_col,
+                     static_cast<uint16_t*>(out->k_val));
+  hipLaunchKernelGGL(csr_move_kernel, dim3(static_cast<unsigned>(p.rows / KVS_V_TILE)), dim3(KVS_WAVE), 0, s,
+                     p.emit_v.list, p.emit_v.block_base, KVS_V_TILE, out->v_rowptr, cap, out->v_col,
+                     static_cast<uint16_t*>(out->v_val));
 }
 
 }  // namespace kvs
