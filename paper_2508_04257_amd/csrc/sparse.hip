@@ -24,35 +24,112 @@ __global__ void fill_u32_kernel(uint32_t* __restrict__ p, size_t count, uint32_t
 }
 
 // X: fp16 [B*Hkv*n, 128] viewed as uint4 (8 values); entries on kept tokens are skipped.
+//
+// Only the top of the histogram decides tau, and one LDS atomic per element is what this pass
+// costs, so the bulk of the elements is not counted at all: a workgroup counts everything in its
+// first kSampleSteps grid-stride steps (a sample spread over the whole tensor), takes from that
+// sample the magnitude l0 above which about kSampleMargin * frac of the entries lie, and from
+// then on counts only magnitudes >= l0.  Bins >= the largest l0 of any workgroup are exact in
+// the merged histogram; the number of entries is counted separately.  If the threshold turns out
+// to lie below that (a sample that misjudged the tail), ctrl[kNeedFull] is raised and the full
+// histogram - the same kernel with full != 0 - is taken after all; it returns at once otherwise.
+constexpr int kSampleSteps = 8;
+constexpr float kSampleMargin = 3.0f;
+enum { kCtrlCount = 0, kCtrlL0 = 1, kNeedFull = 2, kCtrlWords = 4 };   // per tensor, in the control block
+
 __global__ __launch_bounds__(kHistThreads) void sparse_hist_kernel(
     const uint4* __restrict__ X, const uint8_t* __restrict__ keep_mask, size_t rows, int n, int Hkv,
-    uint32_t* __restrict__ hist) {
+    float frac, int full, uint32_t* __restrict__ hist, uint32_t* __restrict__ ctrl) {
   __shared__ uint32_t h[kBins];
+  __shared__ unsigned long long part[kHistThreads];
+  __shared__ uint32_t l0_s, seen_s;
+  if (full && ctrl[kNeedFull] == 0) return;             // the bounded histogram was enough
   for (int i = threadIdx.x; i < kBins; i += kHistThreads) h[i] = 0;
+  if (threadIdx.x == 0) { l0_s = 0; seen_s = 0; }
   __syncthreads();
+  const int tid = threadIdx.x;
   const size_t units = rows * 16;                       // 16-byte units
-  for (size_t u = blockIdx.x * static_cast<size_t>(kHistThreads) + threadIdx.x; u < units;
-       u += static_cast<size_t>(gridDim.x) * kHistThreads) {
-    const size_t row = u >> 4;
-    const size_t b = row / (static_cast<size_t>(Hkv) * n);
-    const int t = static_cast<int>(row % n);
-    if (keep_mask[b * n + t]) continue;
-    const uint4 v = X[u];
-    atomicAdd(&h[v.x & 0x7FFFu], 1u); atomicAdd(&h[(v.x >> 16) & 0x7FFFu], 1u);
-    atomicAdd(&h[v.y & 0x7FFFu], 1u); atomicAdd(&h[(v.y >> 16) & 0x7FFFu], 1u);
-    atomicAdd(&h[v.z & 0x7FFFu], 1u); atomicAdd(&h[(v.z >> 16) & 0x7FFFu], 1u);
-    atomicAdd(&h[v.w & 0x7FFFu], 1u); atomicAdd(&h[(v.w >> 16) & 0x7FFFu], 1u);
+  const size_t stride = static_cast<size_t>(gridDim.x) * kHistThreads;
+  uint32_t seen = 0;                                    // units of non-kept tokens this lane met
+  uint32_t l0 = 0;
+  constexpr int U = 4;                                  // 16-byte loads in flight per lane
+  const int steps = static_cast<int>((units + stride * U - 1) / (stride * U));   // the same for every lane
+  for (int step = 0; step < steps; ++step) {
+    if (!full && step == kSampleSteps / U) {
+      // ---- lower bound from the sample: suffix sums over 1024 runs of 32 bins -----------------
+      __syncthreads();
+      unsigned long long own = 0;
+      for (int j = 0; j < 32; ++j) own += h[32 * tid + j];
+      part[tid] = own;
+      __syncthreads();
+      for (int o = 1; o < kHistThreads; o <<= 1) {
+        const unsigned long long add = tid + o < kHistThreads ? part[tid + o] : 0ull;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+      }
+      const unsigned long long total = part[0], above = part[tid] - own;
+      const unsigned long long want = static_cast<unsigned long long>(
+          fminf(kSampleMargin * frac, 1.0f) * static_cast<float>(total)) + 1;
+      if (want > total) { if (tid == 0) l0_s = 0; }
+      else if (above < want && above + own >= want) {
+        unsigned long long cum = above;
+        for (int j = 31; j >= 0; --j) {
+          cum += h[32 * tid + j];
+          if (cum >= want) { l0_s = static_cast<uint32_t>(32 * tid + j); break; }
+        }
+      }
+      __syncthreads();
+      l0 = l0_s;
+    }
+    uint4 v[U];
+    bool use[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      const size_t u = blockIdx.x * static_cast<size_t>(kHistThreads) + tid + (static_cast<size_t>(step) * U + k) * stride;
+      use[k] = u < units;
+      const size_t uc = use[k] ? u : 0;
+      const size_t row = uc >> 4;
+      const size_t b = row / (static_cast<size_t>(Hkv) * n);
+      const int t = static_cast<int>(row % n);
+      use[k] = use[k] && keep_mask[b * n + t] == 0;
+      v[k] = X[uc];
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      if (!use[k]) continue;
+      ++seen;
+      const uint32_t m[8] = {v[k].x & 0x7FFFu, (v[k].x >> 16) & 0x7FFFu, v[k].y & 0x7FFFu, (v[k].y >> 16) & 0x7FFFu,
+                             v[k].z & 0x7FFFu, (v[k].z >> 16) & 0x7FFFu, v[k].w & 0x7FFFu, (v[k].w >> 16) & 0x7FFFu};
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (m[j] >= l0) atomicAdd(&h[m[j]], 1u);
+    }
   }
+  atomicAdd(&seen_s, seen);
   __syncthreads();
-  for (int i = threadIdx.x; i < kBins; i += kHistThreads)
+  for (int i = tid; i < kBins; i += kHistThreads)
     if (h[i]) atomicAdd(&hist[i], h[i]);
+  if (tid == 0) {
+    if (!full) {
+      atomicAdd(&ctrl[kCtrlCount], seen_s * 8u);
+      atomicMax(&ctrl[kCtrlL0], l0_s);
+    }
+  }
 }
 
-// One workgroup per tensor: tau = largest bin t with sum_{bin >= t} hist >= ceil(f * count).
+// One workgroup per tensor: tau = largest bin t with sum_{bin >= t} hist >= ceil(f * count), where
+// count is the number of entries on non-kept tokens.  pass 0 reads the bounded histogram, whose
+// bins below ctrl[kCtrlL0] are incomplete: if the walk would have to go below it, nothing is
+// written but ctrl[kNeedFull].  pass 1 does the same on the full histogram, if that was raised.
 __global__ __launch_bounds__(1024) void sparse_threshold_kernel(const uint32_t* __restrict__ hist_base,
-                                                                 float frac, uint32_t* __restrict__ tau_out) {
+                                                                 uint32_t* __restrict__ ctrl_base, float frac, int pass,
+                                                                 uint32_t* __restrict__ tau_out) {
   __shared__ unsigned long long part[1024];
   const uint32_t* hist = hist_base + static_cast<size_t>(blockIdx.x) * kBins;
+  uint32_t* ctrl = ctrl_base + blockIdx.x * kCtrlWords;
+  if (pass == 1 && ctrl[kNeedFull] == 0) return;
+  const uint32_t l0 = pass == 0 ? ctrl[kCtrlL0] : 0u;
   const int tid = threadIdx.x;
   unsigned long long own = 0;
   for (int j = 0; j < 32; ++j) own += hist[32 * tid + j];
@@ -65,18 +142,23 @@ __global__ __launch_bounds__(1024) void sparse_threshold_kernel(const uint32_t* 
     part[tid] += add;
     __syncthreads();
   }
-  const unsigned long long count = part[0];
+  const unsigned long long count = ctrl[kCtrlCount];
   const unsigned long long above = part[tid] - own;     // entries in bins of higher threads
   const double md = ceil(static_cast<double>(frac) * static_cast<double>(count));
   const unsigned long long m = md <= 0.0 ? 0ull : static_cast<unsigned long long>(md);
   if (tid == 0 && m == 0) tau_out[blockIdx.x] = 0x8000u;
-  if (m > 0 && above < m && above + own >= m) {
+  if (m > 0 && above < m && above + own >= m) {         // exactly one thread
     unsigned long long cum = above;
     for (int j = 31; j >= 0; --j) {
       cum += hist[32 * tid + j];
-      if (cum >= m) { tau_out[blockIdx.x] = static_cast<uint32_t>(32 * tid + j); break; }
+      if (cum >= m) {
+        const uint32_t bin = static_cast<uint32_t>(32 * tid + j);
+        if (bin >= l0) tau_out[blockIdx.x] = bin; else ctrl[kNeedFull] = 1u;
+        break;
+      }
     }
   }
+  if (m > 0 && tid == 0 && part[0] < m) ctrl[kNeedFull] = 1u;   // pass 0 only: the counted part is too small
 }
 
 // ---- in-place inclusive scan of int32 counts (three phases, 4096 items per workgroup) -------
@@ -186,7 +268,7 @@ size_t sparse_workspace_words(const kvs_desc* d) {
   const size_t rows = static_cast<size_t>(d->B) * d->Hkv * d->n;
   const size_t nblk = (rows + kScanBlock - 1) / kScanBlock;
   const size_t bases = rows / key_block_rows(d) + rows / KVS_V_TILE;
-  return 2 * kBins + 64 + 2 * (nblk + 1) + bases + 2 * static_cast<size_t>(d->sparse_cap);
+  return 4 * kBins + 64 + 2 * (nblk + 1) + bases + 2 * static_cast<size_t>(d->sparse_cap);
 }
 
 SparsePlan sparse_plan(const kvs_desc* d, void* workspace) {
@@ -195,30 +277,38 @@ SparsePlan sparse_plan(const kvs_desc* d, void* workspace) {
   const size_t rows = static_cast<size_t>(d->B) * d->Hkv * d->n;
   p.rows = rows;
   p.nblk = static_cast<int>((rows + kScanBlock - 1) / kScanBlock);
-  p.hist = w;
-  p.tau = w + 2 * kBins;                                   // words 0, 1 of a 64-word block
-  p.sums_k = reinterpret_cast<int*>(w + 2 * kBins + 64);
+  p.hist = w;                                              // [2][kBins] bounded, then [2][kBins] full
+  uint32_t* block = w + 4 * kBins;                         // 64 control words, zeroed with the histograms
+  p.tau = block;                                           // words 0, 1; 2, 3 staging counters; 8.. per-tensor control
+  p.sums_k = reinterpret_cast<int*>(block + 64);
   p.sums_v = p.sums_k + p.nblk + 1;
   p.rows_per_block_k = key_block_rows(d);
   int* bases = p.sums_v + p.nblk + 1;
   uint32_t* lists = reinterpret_cast<uint32_t*>(bases + rows / p.rows_per_block_k + rows / KVS_V_TILE);
-  p.emit_k = SparseEmit{lists, reinterpret_cast<int*>(w + 2 * kBins + 2), bases, d->sparse_cap};
-  p.emit_v = SparseEmit{lists + d->sparse_cap, reinterpret_cast<int*>(w + 2 * kBins + 3),
+  p.emit_k = SparseEmit{lists, reinterpret_cast<int*>(block + 2), bases, d->sparse_cap};
+  p.emit_v = SparseEmit{lists + d->sparse_cap, reinterpret_cast<int*>(block + 3),
                         bases + rows / p.rows_per_block_k, d->sparse_cap};
   return p;
 }
 
 void sparse_thresholds(const kvs_desc* d, const SparsePlan& p, const void* K, const void* V,
                        const uint8_t* mask, const kvs_cache* out, hipStream_t s) {
-  hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(1024), 0, s, p.hist, static_cast<size_t>(2 * kBins + 64), 0u);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(1024), 0, s, p.hist, static_cast<size_t>(4 * kBins + 64), 0u);
   hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(out->k_rowptr), size_t{1}, 0u);
   hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(out->v_rowptr), size_t{1}, 0u);
-  const int grid = 512;                                   // two workgroups per compute unit in turn
-  hipLaunchKernelGGL(sparse_hist_kernel, dim3(grid), dim3(kHistThreads), 0, s, static_cast<const uint4*>(K), mask,
-                     p.rows, d->n, d->Hkv, p.hist);
-  hipLaunchKernelGGL(sparse_hist_kernel, dim3(grid), dim3(kHistThreads), 0, s, static_cast<const uint4*>(V), mask,
-                     p.rows, d->n, d->Hkv, p.hist + kBins);
-  hipLaunchKernelGGL(sparse_threshold_kernel, dim3(2), dim3(1024), 0, s, p.hist, d->sparse_frac, p.tau);
+  // Two workgroups per compute unit in turn; fewer on small inputs, so that every workgroup still
+  // takes several times kSampleSteps grid-stride steps and the bounded count means something.
+  const size_t want_grid = p.rows * 16 / (static_cast<size_t>(kHistThreads) * 4 * kSampleSteps);   // >= 4 x the sample
+  const int grid = static_cast<int>(want_grid < 1 ? 1 : (want_grid > 512 ? 512 : want_grid));
+  uint32_t* ctrl = p.tau + 8;                             // [2][kCtrlWords]
+  const void* X[2] = {K, V};
+  for (int full = 0; full < 2; ++full) {                  // the second round returns at once unless asked for
+    uint32_t* hist = p.hist + full * 2 * kBins;
+    for (int t = 0; t < 2; ++t)
+      hipLaunchKernelGGL(sparse_hist_kernel, dim3(grid), dim3(kHistThreads), 0, s, static_cast<const uint4*>(X[t]),
+                         mask, p.rows, d->n, d->Hkv, d->sparse_frac, full, hist + t * kBins, ctrl + t * kCtrlWords);
+    hipLaunchKernelGGL(sparse_threshold_kernel, dim3(2), dim3(1024), 0, s, hist, ctrl, d->sparse_frac, full, p.tau);
+  }
 }
 
 void sparse_build_csr(const kvs_desc* d, const SparsePlan& p, const kvs_cache* out, hipStream_t s) {

@@ -253,6 +253,31 @@ def test_dense_and_sparse_small(bits, G, rep, frac, kind):
     assert np.all(np.isfinite(out2))
 
 
+def test_dense_and_sparse_threshold_when_the_sample_misleads():
+    """The threshold pass counts only magnitudes above a bound taken from the part of the tensor it
+    reads first.  Here that part (the first 512 token rows) is 100 times larger than the rest, so the
+    bound lies above the true threshold and the exact full histogram has to take over."""
+    rng = np.random.default_rng(5)
+    B, H, n, bits, G, frac = 2, 2, 640, 4, 64, 0.01
+    K = rng.standard_normal((B, H, n, 128))
+    V = rng.standard_normal((B, H, n, 128))
+    K[0, 0, :512] *= 100.0
+    V[0, 0, :512] *= 100.0
+    K, V = K.astype(np.float16), V.astype(np.float16)
+    mask = np.zeros((B, n), np.uint8)
+    mask[0, [0, 14]] = 1
+    mask[1, [3]] = 1
+    q = random_fp16(rng, (B, H, 128))
+    ref = O.quantize_kv(K, V, mask, bits, G, keep_cap=4, sparse_frac=frac)
+    cap = max(len(ref.k_col), len(ref.v_col)) + 16
+    desc, cache, ws = hip_quantize(K, V, mask, bits, G, keep_cap=4, sparse_frac=frac, sparse_cap=cap)
+    assert_cache_equal(cache, ref)
+    assert_csr_equal(cache, ref)
+    out, lse = hip_decode(desc, cache, ws, q)
+    _, ref_lse, ref64 = O.decode_attn(q, ref, Hq=H)
+    assert row_rel_err(out, ref64) <= OUT_TOL
+
+
 def test_dense_and_sparse_long_sequence():
     """More than 4096 tokens: the finishing kernel stages the sequence in two segments, the second one
     ragged (5 tiles), and the stream is cut into several parts per head."""
