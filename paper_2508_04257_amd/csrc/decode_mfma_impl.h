@@ -214,12 +214,6 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
   const Magic magic = make_magic();
   const int kcol = col < KCOLS ? col : KCOLS;      // table columns this lane's tile column reads
   const int vcol = col < VCOLS ? col : VCOLS;
-  {
-    uint32_t* zq = reinterpret_cast<uint32_t*>(&bq[wave][0][0]);
-    for (int i = lane; i < (KCOLS + 1) * TBL / 2; i += KVS_WAVE) zq[i] = 0;
-    uint32_t* zw = reinterpret_cast<uint32_t*>(&wh[wave][0][0][0]);
-    for (int i = lane; i < NTAB * (VCOLS + 1) * TBL / 2; i += KVS_WAVE) zw[i] = 0;
-  }
   const int n = a.n;
   const size_t bh = blockIdx.x / a.parts;
   const int part = blockIdx.x % a.parts;
@@ -237,25 +231,9 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
     keep_first_v = keep_rows_v[wave * 64];
   }
 
-  // Query of the lane's two channels (2 lane, 2 lane + 1), all R heads, scaled to log2 units;
-  // where those channels and the lane's two tokens (lane, lane + 64) sit in a table column.
-  float qf[R][2];
-#pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const uint32_t two = reinterpret_cast<const uint32_t*>(a.q + (static_cast<size_t>(b) * Hq + hq0 + r) * 128)[lane];
-    qf[r][0] = kvs::half_bits_to_float(static_cast<uint16_t>(two & 0xFFFFu)) * kLog2eRsqrtD;
-    qf[r][1] = kvs::half_bits_to_float(static_cast<uint16_t>(two >> 16)) * kLog2eRsqrtD;
-  }
-  const int cpos0 = S::table_pos(2 * lane), cpos1 = S::table_pos(2 * lane + 1);
-  const float coff0 = S::elem_offset(2 * lane), coff1 = S::elem_offset(2 * lane + 1);
-  const int tpos0 = S::table_pos(lane), tpos1 = S::table_pos(lane + 64);
-  const float toff0 = S::elem_offset(lane), toff1 = S::elem_offset(lane + 64);
-
   const int part_begin = min(n, part * a.part_tokens);
   const int part_end = min(n, part_begin + a.part_tokens);
   const int nchunks = (part_end - part_begin) / 128;       // chunks of this workgroup
-  if (threadIdx.x == 0) next_chunk = kWaves;               // chunks 0 .. kWaves - 1 are the waves' first
-  __syncthreads();
   const uint8_t* mask_b = a.keep_mask + static_cast<size_t>(b) * n;
   const uint32_t* kcodes = a.k_codes + bh * (n / 64) * (W * 64);
   const uint32_t* vcodes = a.v_codes + bh * (n / 128) * (W * 128);
@@ -365,6 +343,34 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
     load_value_params(s, ci);
     load_value_half(s, ci, 0);  load_value_half(s, ci, 1);
   };
+  // The wave's first chunk is its own index: request it before anything else is set up.
+  if (wave < nchunks) {
+    load_keys(keys, wave);
+    load_values(vals, wave);
+  }
+  if (threadIdx.x == 0) next_chunk = kWaves;               // chunks 0 .. kWaves - 1 are the waves' first
+  {
+    uint32_t* zq = reinterpret_cast<uint32_t*>(&bq[wave][0][0]);
+    for (int i = lane; i < (KCOLS + 1) * TBL / 2; i += KVS_WAVE) zq[i] = 0;
+    uint32_t* zw = reinterpret_cast<uint32_t*>(&wh[wave][0][0][0]);
+    for (int i = lane; i < NTAB * (VCOLS + 1) * TBL / 2; i += KVS_WAVE) zw[i] = 0;
+  }
+  // Query of the lane's two channels (2 lane, 2 lane + 1), all R heads, scaled to log2 units;
+  // where those channels and the lane's two tokens (lane, lane + 64) sit in a table column.
+  float qf[R][2];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const uint32_t two = reinterpret_cast<const uint32_t*>(a.q + (static_cast<size_t>(b) * Hq + hq0 + r) * 128)[lane];
+    qf[r][0] = kvs::half_bits_to_float(static_cast<uint16_t>(two & 0xFFFFu)) * kLog2eRsqrtD;
+    qf[r][1] = kvs::half_bits_to_float(static_cast<uint16_t>(two >> 16)) * kLog2eRsqrtD;
+  }
+  const int cpos0 = S::table_pos(2 * lane), cpos1 = S::table_pos(2 * lane + 1);
+  const float coff0 = S::elem_offset(2 * lane), coff1 = S::elem_offset(2 * lane + 1);
+  const int tpos0 = S::table_pos(lane), tpos1 = S::table_pos(lane + 64);
+  const float toff0 = S::elem_offset(lane), toff1 = S::elem_offset(lane + 64);
+
+  __syncthreads();                                         // the chunk counter is set
+
   float bias[NGK][R];                              // what the score product holds for offsets and zero points
 
   auto score_chunk = [&](KeyRegs& s, int refill) {
@@ -540,8 +546,6 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
   wave_lds_sync();                                     // tables zeroed
   if (wave < nchunks) {
     int nxt = take_chunk();
-    load_keys(keys, wave);
-    load_values(vals, wave);
     int cur = wave;
     while (true) {                                     // the registers hold chunk cur and are filled
       score_chunk(keys, nxt);                          // again, piece by piece, for chunk nxt
