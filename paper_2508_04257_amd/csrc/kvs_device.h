@@ -101,23 +101,52 @@ __device__ inline void unpack_param(uint32_t p, float& scale, int& zero) {
   zero = static_cast<int>(static_cast<int16_t>(p >> 16));
 }
 
+// Wave-wide reductions whose result every lane receives.  Inside a row of 16 lanes the partners
+// come through data-parallel-primitive moves (lane ^ 1, lane ^ 2, mirrored half row, mirrored
+// row), which cost one vector instruction each; the four row results are then read as scalars.
+// (A butterfly of lane shuffles would send all six steps through the LDS crossbar.)
+template <int CTRL>
+__device__ inline int dpp_move(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+
 __device__ inline float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, KVS_WAVE));
-  return v;
+  v = fmaxf(v, __builtin_bit_cast(float, dpp_move<kDppXor1>(__builtin_bit_cast(int, v))));
+  v = fmaxf(v, __builtin_bit_cast(float, dpp_move<kDppXor2>(__builtin_bit_cast(int, v))));
+  v = fmaxf(v, __builtin_bit_cast(float, dpp_move<kDppHalfMirror>(__builtin_bit_cast(int, v))));
+  v = fmaxf(v, __builtin_bit_cast(float, dpp_move<kDppMirror>(__builtin_bit_cast(int, v))));
+  const int i = __builtin_bit_cast(int, v);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 48));
+  return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 __device__ inline float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, KVS_WAVE);
-  return v;
+  v += __builtin_bit_cast(float, dpp_move<kDppXor1>(__builtin_bit_cast(int, v)));
+  v += __builtin_bit_cast(float, dpp_move<kDppXor2>(__builtin_bit_cast(int, v)));
+  v += __builtin_bit_cast(float, dpp_move<kDppHalfMirror>(__builtin_bit_cast(int, v)));
+  v += __builtin_bit_cast(float, dpp_move<kDppMirror>(__builtin_bit_cast(int, v)));
+  const int i = __builtin_bit_cast(int, v);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 48));
+  return (r0 + r1) + (r2 + r3);
 }
 __device__ inline uint32_t wave_max_u32(uint32_t v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    uint32_t other = static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), o, KVS_WAVE));
-    v = other > v ? other : v;
-  }
-  return v;
+  auto mx = [](uint32_t x, uint32_t y) { return x > y ? x : y; };
+  v = mx(v, static_cast<uint32_t>(dpp_move<kDppXor1>(static_cast<int>(v))));
+  v = mx(v, static_cast<uint32_t>(dpp_move<kDppXor2>(static_cast<int>(v))));
+  v = mx(v, static_cast<uint32_t>(dpp_move<kDppHalfMirror>(static_cast<int>(v))));
+  v = mx(v, static_cast<uint32_t>(dpp_move<kDppMirror>(static_cast<int>(v))));
+  const int i = static_cast<int>(v);
+  const uint32_t r0 = static_cast<uint32_t>(__builtin_amdgcn_readlane(i, 0));
+  const uint32_t r1 = static_cast<uint32_t>(__builtin_amdgcn_readlane(i, 16));
+  const uint32_t r2 = static_cast<uint32_t>(__builtin_amdgcn_readlane(i, 32));
+  const uint32_t r3 = static_cast<uint32_t>(__builtin_amdgcn_readlane(i, 48));
+  return mx(mx(r0, r1), mx(r2, r3));
 }
 
 }  // namespace kvs
