@@ -39,6 +39,8 @@ Readings taken where the paper is silent (every one is restated in the design no
       get code 0 and decode uses their fp16 value in place of the dequantised slot.
   R9  decode attends to the whole cache, no mask; Keys are taken as given (post-RoPE).
   R10 packed layout (a storage decision, not the paper's): see ``pack_k`` / ``pack_v``.
+  R13 a growing cache quantises whole 128-token blocks; later tokens wait in fp16 (see
+      ``GrowingCache``).
 
 PPL / MSE figures of the paper need model weights and datasets: parity unpinned for those
 (nothing here reproduces them).  Every function below is pinned by tests/test_oracle_*.py.
@@ -456,6 +458,113 @@ def decode_attn(q: np.ndarray, cache: Cache, Hq: int, pairs=None):
         o, l, _ = attention_row(q[b, hq], Kp, Vp)
         out64[b, hq] = o
         lse[b, hq] = l
+    return out64.astype(np.float16), lse, out64
+
+
+# ----------------------------------------------------------------------------------------
+# A cache that grows during decoding (Section 2, "KV cache": K_cache <- concat(K_cache, t_K),
+# V_cache <- concat(V_cache, t_V)).  Reading R13: quantisation groups are positional and the
+# largest one spans 128 tokens (the Value code tile), so tokens are quantised in whole
+# 128-token blocks; the tokens after the last whole block wait in fp16 (the residual window)
+# until their block is complete, and the block is then quantised like any other - the
+# accumulate-then-quantise scheme Appendix A describes for dynamic per-channel methods.
+# Consequence, pinned by the tests: the state after any number of appends equals the state a
+# prefill of the same tokens produces.
+# ----------------------------------------------------------------------------------------
+BLOCK = V_TILE
+
+
+@dataclass
+class GrowingCache:
+    bits: int
+    group: int
+    keep_cap: int
+    n_tokens: int
+    quant: Optional[Cache]         # tokens [0, n_quant), n_quant = 128 * (n_tokens // 128); None if 0
+    res_k: np.ndarray              # fp16 [B, Hkv, n_tokens - n_quant, D]
+    res_v: np.ndarray
+    res_mask: np.ndarray           # uint8 [B, n_tokens - n_quant]: keep flags of the residual tokens
+
+    @property
+    def n_quant(self) -> int:
+        return 0 if self.quant is None else self.quant.n
+
+
+def _concat_caches(a: Optional[Cache], b: Cache) -> Cache:
+    """Cache over the tokens of ``a`` followed by those of ``b`` (both whole blocks)."""
+    if a is None:
+        return b
+    cap = a.keep_cap
+    keep_k, keep_v, keep_idx = a.keep_k.copy(), a.keep_v.copy(), a.keep_idx.copy()
+    keep_cnt = a.keep_cnt + b.keep_cnt
+    status = max(a.status, b.status)
+    for bi in range(a.B):
+        ca, cb = int(a.keep_cnt[bi]), int(b.keep_cnt[bi])
+        for j in range(min(cb, b.keep_cap)):
+            if ca + j < cap:
+                keep_idx[bi, ca + j] = b.keep_idx[bi, j] + a.n
+                keep_k[bi, :, ca + j] = b.keep_k[bi, :, j]
+                keep_v[bi, :, ca + j] = b.keep_v[bi, :, j]
+            else:
+                status = STATUS_CAPACITY
+    cat = lambda x, y, ax: np.concatenate([x, y], axis=ax)
+    return Cache(a.B, a.n + b.n, a.Hkv, a.D, a.bits, a.group, cap,
+                 cat(a.k_codes, b.k_codes, 2), cat(a.v_codes, b.v_codes, 2),
+                 cat(a.k_params, b.k_params, 2), cat(a.v_params, b.v_params, 2),
+                 keep_k, keep_v, keep_idx, keep_cnt, cat(a.keep_mask, b.keep_mask, 1), status,
+                 k_codes_logical=cat(a.k_codes_logical, b.k_codes_logical, 2),
+                 v_codes_logical=cat(a.v_codes_logical, b.v_codes_logical, 2))
+
+
+def prefill_cache(K: np.ndarray, V: np.ndarray, keep_mask: np.ndarray, bits: int, group: int,
+                  keep_cap: int) -> GrowingCache:
+    """Cache of a prompt of any length: whole 128-token blocks quantised, the rest in fp16."""
+    K, V = np.asarray(K), np.asarray(V)
+    B, H, n, D = K.shape
+    keep_mask = (np.asarray(keep_mask) != 0).astype(np.uint8)
+    nq = (n // BLOCK) * BLOCK
+    quant = quantize_kv(K[:, :, :nq], V[:, :, :nq], keep_mask[:, :nq], bits, group, keep_cap) if nq else None
+    return GrowingCache(bits, group, keep_cap, n, quant, K[:, :, nq:].copy(), V[:, :, nq:].copy(),
+                        keep_mask[:, nq:].copy())
+
+
+def append_token(gc: GrowingCache, k_new: np.ndarray, v_new: np.ndarray, keep_new=None) -> GrowingCache:
+    """One decoding step's cache update: k_new, v_new fp16 [B, Hkv, D] join the residual window;
+    a window that reaches 128 tokens is quantised as one block and joins the quantised part."""
+    k_new, v_new = np.asarray(k_new), np.asarray(v_new)
+    assert k_new.dtype == np.float16 and v_new.dtype == np.float16
+    B = k_new.shape[0]
+    flag = np.zeros((B, 1), np.uint8) if keep_new is None else (np.asarray(keep_new).reshape(B, 1) != 0).astype(np.uint8)
+    res_k = np.concatenate([gc.res_k, k_new[:, :, None, :]], axis=2)
+    res_v = np.concatenate([gc.res_v, v_new[:, :, None, :]], axis=2)
+    res_mask = np.concatenate([gc.res_mask, flag], axis=1)
+    quant = gc.quant
+    if res_k.shape[2] == BLOCK:
+        block = quantize_kv(res_k, res_v, res_mask, gc.bits, gc.group, gc.keep_cap)
+        quant = _concat_caches(quant, block)
+        res_k, res_v, res_mask = res_k[:, :, :0], res_v[:, :, :0], res_mask[:, :0]
+    return GrowingCache(gc.bits, gc.group, gc.keep_cap, gc.n_tokens + 1, quant, res_k, res_v, res_mask)
+
+
+def decode_attn_growing(q: np.ndarray, gc: GrowingCache, Hq: int):
+    """Decode attention over all n_tokens cached tokens: the quantised part as ``decode_attn``
+    sees it, the residual tokens in fp16.  Returns (out fp16, lse float32, out64)."""
+    q = np.asarray(q)
+    B, D = q.shape[0], q.shape[2]
+    H = gc.res_k.shape[1]
+    rep = Hq // H
+    out64 = np.zeros((B, Hq, D), np.float64)
+    lse = np.zeros((B, Hq), np.float32)
+    for b in range(B):
+        for h in range(H):
+            Kp, Vp = gc.res_k[b, h].astype(np.float64), gc.res_v[b, h].astype(np.float64)
+            if gc.quant is not None:
+                Kq, Vq = effective_kv(gc.quant, b, h)
+                Kp, Vp = np.concatenate([Kq, Kp]), np.concatenate([Vq, Vp])
+            for r in range(rep):
+                o, l, _ = attention_row(q[b, h * rep + r], Kp, Vp)
+                out64[b, h * rep + r] = o
+                lse[b, h * rep + r] = l
     return out64.astype(np.float16), lse, out64
 
 
