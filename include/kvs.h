@@ -46,6 +46,8 @@
  *            rowptr int32 [B*Hkv*n + 1], col uint16 [sparse_cap] ascending per row, val fp16.
  *            Keys: row = (b, h, token), col = channel.  Values: row = (b, h, 128-token tile,
  *            channel), col = token inside the tile (the transposition of the Value code tiles).
+ *   Residual window (growing caches only): res_k / res_v fp16 [B, Hkv, 128, 128], row r = token
+ *            128 * (n_tokens / 128) + r of the sequence, still in 16 bit.
  */
 #ifndef KVS_H
 #define KVS_H
@@ -60,7 +62,7 @@ extern "C" {
 #define KVS_HEAD_DIM 128
 #define KVS_K_TILE 64
 #define KVS_V_TILE 128
-#define KVS_CACHE_FIELDS 16
+#define KVS_CACHE_FIELDS 18
 #define KVS_MAX_TOPK 1024
 #define KVS_MAX_PREDICT_TOKENS 65536
 
@@ -85,7 +87,7 @@ typedef struct kvs_desc {
 
 /* The quantised cache of one layer: device pointers to caller-owned buffers whose byte sizes
  * kvs_cache_bytes() returns in this field order.  The CSR fields may be NULL when
- * sparse_frac == 0. */
+ * sparse_frac == 0, res_k / res_v when the cache never grows. */
 typedef struct kvs_cache {
   uint32_t* k_codes;
   uint32_t* v_codes;
@@ -103,6 +105,8 @@ typedef struct kvs_cache {
   uint16_t* v_col;
   void* v_val;
   int32_t* status;
+  void* res_k;
+  void* res_v;
 } kvs_cache;
 
 /* Library version (major * 100 + minor). */
@@ -175,6 +179,34 @@ kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const void* V,
  */
 kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const kvs_cache* cache,
                            void* out, float* lse, void* workspace, void* stream);
+
+/*
+ * Growing caches (Section 2, "KV cache": in the decoding phase every new token's K and V are
+ * appended to the cache; Appendix A: quantisation once a number of local tokens has accumulated).
+ * desc->n is then the CAPACITY the buffers are laid out for and n_tokens says how many tokens
+ * they hold.  Quantisation groups are positional and the largest spans 128 tokens, so tokens are
+ * quantised in whole blocks of 128, exactly as kvs_quantize_kv quantises them; the tokens after
+ * the last whole block wait unchanged in res_k / res_v until their block is complete.  The state
+ * after any sequence of these calls equals what kvs_quantize_prefix makes of the same tokens.
+ * Not available with sparse_frac > 0 (KVS_ERR_UNSUPPORTED).
+ *
+ * kvs_quantize_prefix: a prompt of n_tokens in [0, desc->n] tokens, any length.
+ *   K, V fp16 [B, Hkv, n_tokens, 128];  keep_mask uint8 [B, n_tokens] (kept tokens of the last,
+ *   incomplete block are remembered in out->keep_mask and honoured when the block is quantised).
+ * kvs_append_kv: one more token per sequence; n_tokens in [0, desc->n) = tokens held before the call.
+ *   k_new, v_new fp16 [B, Hkv, 128].  The new token is not a kept token.  When it completes a
+ *   block, the block is quantised by the same call.
+ * kvs_decode_attn_n: kvs_decode_attn over the first n_tokens in [1, desc->n] tokens: quantised
+ *   blocks, kept rows and residual rows in one softmax.
+ * workspace: kvs_workspace_bytes(desc) bytes in all three.
+ */
+kvs_status kvs_quantize_prefix(const kvs_desc* desc, const void* K, const void* V,
+                               const uint8_t* keep_mask, int32_t n_tokens, const kvs_cache* out,
+                               void* workspace, void* stream);
+kvs_status kvs_append_kv(const kvs_desc* desc, const void* k_new, const void* v_new, int32_t n_tokens,
+                         const kvs_cache* cache, void* workspace, void* stream);
+kvs_status kvs_decode_attn_n(const kvs_desc* desc, const void* q, const kvs_cache* cache, int32_t n_tokens,
+                             void* out, float* lse, void* workspace, void* stream);
 
 #ifdef __cplusplus
 }

@@ -16,16 +16,18 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvs.so"
 _lib = None
 
 KVS_OK, KVS_ERR_INVALID, KVS_ERR_UNSUPPORTED, KVS_ERR_CAPACITY, KVS_ERR_DEVICE = range(5)
-KVS_CACHE_FIELDS = 16
+KVS_CACHE_FIELDS = 18
 CACHE_FIELD_NAMES = (
     "k_codes", "v_codes", "k_params", "v_params", "keep_k", "keep_v", "keep_idx", "keep_cnt",
     "keep_mask", "k_rowptr", "k_col", "k_val", "v_rowptr", "v_col", "v_val", "status",
+    "res_k", "res_v",
 )
 _FIELD_DTYPES = dict(
     k_codes=torch.int32, v_codes=torch.int32, k_params=torch.int32, v_params=torch.int32,
     keep_k=torch.float16, keep_v=torch.float16, keep_idx=torch.int32, keep_cnt=torch.int32,
     keep_mask=torch.uint8, k_rowptr=torch.int32, k_col=torch.int16, k_val=torch.float16,
     v_rowptr=torch.int32, v_col=torch.int16, v_val=torch.float16, status=torch.int32,
+    res_k=torch.float16, res_v=torch.float16,
 )
 
 
@@ -70,6 +72,15 @@ def lib() -> C.CDLL:
         L.kvs_quantize_kv.restype = C.c_int
         L.kvs_quantize_kv.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.POINTER(KvsCache), C.c_void_p, C.c_void_p]
+        L.kvs_quantize_prefix.restype = C.c_int
+        L.kvs_quantize_prefix.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                          C.POINTER(KvsCache), C.c_void_p, C.c_void_p]
+        L.kvs_append_kv.restype = C.c_int
+        L.kvs_append_kv.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(KvsCache),
+                                    C.c_void_p, C.c_void_p]
+        L.kvs_decode_attn_n.restype = C.c_int
+        L.kvs_decode_attn_n.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.POINTER(KvsCache), C.c_int32, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_void_p]
         L.kvs_decode_attn.restype = C.c_int
         L.kvs_decode_attn.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.POINTER(KvsCache), C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p]
@@ -210,3 +221,43 @@ def kvs_decode_attn(desc: KvsDesc, q: torch.Tensor, cache: CacheBuffers, out: to
                                _ptr(lse), workspace.data_ptr(), _stream_handle())
     if st != KVS_OK:
         raise KvsError("kvs_decode_attn", st)
+
+
+# ---- growing caches: desc.n is the capacity, n_tokens what the cache holds ---------------------
+def kvs_quantize_prefix(desc: KvsDesc, K: torch.Tensor, V: torch.Tensor, keep_mask: torch.Tensor, n_tokens: int,
+                        cache: CacheBuffers, workspace: Optional[torch.Tensor]) -> None:
+    shape = (desc.B, desc.Hkv, n_tokens, desc.D)
+    _check_tensor("K", K, shape, torch.float16)
+    _check_tensor("V", V, shape, torch.float16)
+    _check_tensor("keep_mask", keep_mask, (desc.B, n_tokens), torch.uint8)
+    _check_cache(desc, cache)
+    st = lib().kvs_quantize_prefix(C.byref(desc), K.data_ptr(), V.data_ptr(), keep_mask.data_ptr(), n_tokens,
+                                   C.byref(cache.struct), _ptr(workspace), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_quantize_prefix", st)
+
+
+def kvs_append_kv(desc: KvsDesc, k_new: torch.Tensor, v_new: torch.Tensor, n_tokens: int, cache: CacheBuffers,
+                  workspace: Optional[torch.Tensor]) -> None:
+    _check_tensor("k_new", k_new, (desc.B, desc.Hkv, desc.D), torch.float16)
+    _check_tensor("v_new", v_new, (desc.B, desc.Hkv, desc.D), torch.float16)
+    _check_cache(desc, cache)
+    st = lib().kvs_append_kv(C.byref(desc), k_new.data_ptr(), v_new.data_ptr(), n_tokens, C.byref(cache.struct),
+                             _ptr(workspace), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_append_kv", st)
+
+
+def kvs_decode_attn_n(desc: KvsDesc, q: torch.Tensor, cache: CacheBuffers, n_tokens: int, out: torch.Tensor,
+                      lse: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    _check_tensor("q", q, (desc.B, desc.Hq, desc.D), torch.float16)
+    _check_tensor("out", out, (desc.B, desc.Hq, desc.D), torch.float16)
+    if lse is not None:
+        _check_tensor("lse", lse, (desc.B, desc.Hq), torch.float32)
+    _check_cache(desc, cache)
+    if not workspace.is_cuda or workspace.numel() * workspace.element_size() < kvs_workspace_bytes(desc):
+        raise ValueError("workspace too small")
+    st = lib().kvs_decode_attn_n(C.byref(desc), q.data_ptr(), C.byref(cache.struct), n_tokens, out.data_ptr(),
+                                 _ptr(lse), workspace.data_ptr(), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_decode_attn_n", st)

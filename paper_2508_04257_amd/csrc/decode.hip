@@ -42,7 +42,7 @@ template <int BITS, int G, int R, bool SPARSE>
 __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
     const uint16_t* __restrict__ q, const uint32_t* __restrict__ k_codes,
     const uint32_t* __restrict__ v_codes, const uint32_t* __restrict__ k_params,
-    const uint32_t* __restrict__ v_params, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
+    const uint32_t* __restrict__ v_params, const uint8_t* __restrict__ keep_mask, int n, int n_used, int Hkv,
     int rep, int splits, int split_tokens, float* __restrict__ ws, SparseView sp) {
   constexpr int W = Fmt<BITS>::W, cpw = Fmt<BITS>::cpw;
   constexpr int NGK = 128 / G;   // Key token groups per 128-token chunk
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
   __syncthreads();
 
   const int tok_begin = split * split_tokens;
-  const int tok_end = min(n, tok_begin + split_tokens);
+  const int tok_end = min(n_used, tok_begin + split_tokens);   // n is the layout, n_used what is attended to
   const int chunks = (tok_end - tok_begin) / KVS_V_TILE;
   const int rounds = (chunks + kWaves - 1) / kWaves;
   const uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * n;
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
 // One wave per (b, hq), lane = channels 2 lane and 2 lane + 1: log-sum-exp merge of the splits,
 // then the kept tokens' fp16 rows join the same running softmax.
 __global__ __launch_bounds__(KVS_WAVE) void decode_combine_kernel(
-    const uint16_t* __restrict__ q, const float* __restrict__ ws, int splits, int Hq, int Hkv,
+    const uint16_t* __restrict__ q, const float* __restrict__ ws, const float* __restrict__ extra, int splits, int Hq, int Hkv,
     int cap, const uint16_t* __restrict__ keep_k, const uint16_t* __restrict__ keep_v,
     const int32_t* __restrict__ keep_cnt, uint16_t* __restrict__ out, float* __restrict__ lse) {
   const int lane = threadIdx.x;
@@ -292,10 +292,22 @@ __global__ __launch_bounds__(KVS_WAVE) void decode_combine_kernel(
   const float q0 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 & 0xFFFFu));
   const float q1 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 >> 16));
 
+  // One more part, if given: the fp16 rows of a growing cache's residual window (the same triple
+  // of unnormalised row, maximum and sum, one per (b, hq)).
+  const float* xrow = extra ? extra + bq * kWsRow : nullptr;
   float M = -INFINITY;
   for (int s = lane; s < splits; s += KVS_WAVE) M = fmaxf(M, row[s * kWsRow + 128]);
   M = kvs::wave_max(M);
+  if (xrow) M = fmaxf(M, xrow[128]);
   float L = 0.0f, O0 = 0.0f, O1 = 0.0f;
+  if (xrow) {
+    const float ms = xrow[128];
+    const float f = ms == -INFINITY ? 0.0f : __expf(ms - M);
+    const float2 o = reinterpret_cast<const float2*>(xrow)[lane];
+    L = xrow[129] * f;
+    O0 = o.x * f;
+    O1 = o.y * f;
+  }
 #pragma unroll 4
   for (int s = 0; s < splits; ++s) {
     const float ms = row[s * kWsRow + 128];
@@ -342,7 +354,7 @@ __global__ __launch_bounds__(KVS_WAVE) void decode_combine_kernel(
 
 template <int BITS, int G, int R>
 void launch_partial(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                    float* ws, hipStream_t s) {
+                    float* ws, int n_used, hipStream_t s) {
   const int rep = d->Hq / d->Hkv;
   const int grid = d->B * d->Hkv * (rep / R) * geo.splits;
   SparseView sp{c->k_rowptr, c->k_col, static_cast<const uint16_t*>(c->k_val),
@@ -351,37 +363,101 @@ void launch_partial(const kvs_desc* d, const kvs::DecodeGeometry& geo, const voi
   if (d->sparse_frac > 0.0f)
     hipLaunchKernelGGL((decode_partial_kernel<BITS, G, R, true>), dim3(grid), dim3(kThreads), 0, s,
                        static_cast<const uint16_t*>(q), c->k_codes, c->v_codes, c->k_params, c->v_params,
-                       c->keep_mask, d->n, d->Hkv, rep, geo.splits, geo.split_tokens, ws, sp);
+                       c->keep_mask, d->n, n_used, d->Hkv, rep, geo.splits, geo.split_tokens, ws, sp);
   else
     hipLaunchKernelGGL((decode_partial_kernel<BITS, G, R, false>), dim3(grid), dim3(kThreads), 0, s,
                        static_cast<const uint16_t*>(q), c->k_codes, c->v_codes, c->k_params, c->v_params,
-                       c->keep_mask, d->n, d->Hkv, rep, geo.splits, geo.split_tokens, ws, sp);
+                       c->keep_mask, d->n, n_used, d->Hkv, rep, geo.splits, geo.split_tokens, ws, sp);
 }
 
 template <int BITS, int G>
 void launch_partial_r(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                      float* ws, hipStream_t s) {
+                      float* ws, int n_used, hipStream_t s) {
   switch (d->Hq / d->Hkv) {
-    case 1: launch_partial<BITS, G, 1>(d, geo, q, c, ws, s); break;
-    case 2: launch_partial<BITS, G, 2>(d, geo, q, c, ws, s); break;
-    default: launch_partial<BITS, G, 4>(d, geo, q, c, ws, s); break;   // 8 = two groups of 4 heads
+    case 1: launch_partial<BITS, G, 1>(d, geo, q, c, ws, n_used, s); break;
+    case 2: launch_partial<BITS, G, 2>(d, geo, q, c, ws, n_used, s); break;
+    default: launch_partial<BITS, G, 4>(d, geo, q, c, ws, n_used, s); break;   // 8 = two groups of 4 heads
   }
 }
 
 template <int BITS>
 void launch_partial_g(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                      float* ws, hipStream_t s) {
+                      float* ws, int n_used, hipStream_t s) {
   switch (d->group) {
-    case 32: launch_partial_r<BITS, 32>(d, geo, q, c, ws, s); break;
-    case 64: launch_partial_r<BITS, 64>(d, geo, q, c, ws, s); break;
-    default: launch_partial_r<BITS, 128>(d, geo, q, c, ws, s); break;
+    case 32: launch_partial_r<BITS, 32>(d, geo, q, c, ws, n_used, s); break;
+    case 64: launch_partial_r<BITS, 64>(d, geo, q, c, ws, n_used, s); break;
+    default: launch_partial_r<BITS, 128>(d, geo, q, c, ws, n_used, s); break;
   }
 }
 
 }  // namespace
 
-extern "C" kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const kvs_cache* cache,
-                                       void* out, float* lse, void* workspace, void* stream) {
+// The residual window of a growing cache as one more part: softmax state of `rows` fp16 rows of one
+// (b, hq), unnormalised.  One workgroup of four waves per (b, hq); wave w takes rows w, w + 4, ...
+// eight at a time (their loads in flight together); lane = channels 2 lane, 2 lane + 1.
+__global__ __launch_bounds__(kThreads) void residual_part_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ res_k, const uint16_t* __restrict__ res_v,
+    int rows, int Hq, int Hkv, float* __restrict__ extra) {
+  __shared__ float part_o[kWaves][128];
+  __shared__ float part_m[kWaves], part_l[kWaves];
+  const int lane = threadIdx.x & (KVS_WAVE - 1), wave = threadIdx.x / KVS_WAVE;
+  const size_t bq = blockIdx.x;
+  const int b = static_cast<int>(bq / Hq), hq = static_cast<int>(bq % Hq);
+  const size_t bh = static_cast<size_t>(b) * Hkv + hq / (Hq / Hkv);
+  const uint32_t q2 = reinterpret_cast<const uint32_t*>(q + bq * 128)[lane];
+  const float q0 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 & 0xFFFFu)) * kRsqrtD;
+  const float q1 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 >> 16)) * kRsqrtD;
+  const uint32_t* kk = reinterpret_cast<const uint32_t*>(res_k) + bh * KVS_V_TILE * 64 + lane;
+  const uint32_t* kv = reinterpret_cast<const uint32_t*>(res_v) + bh * KVS_V_TILE * 64 + lane;
+  constexpr int kBatch = 8;
+  float M = -INFINITY, L = 0.0f, O0 = 0.0f, O1 = 0.0f;
+  for (int r0 = wave; r0 < rows; r0 += kWaves * kBatch) {
+    uint32_t kw[kBatch], vw[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int r = min(r0 + u * kWaves, rows - 1);
+      kw[u] = kk[r * 64];
+      vw[u] = kv[r * 64];
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      if (r0 + u * kWaves < rows) {                   // wave-uniform
+        const float s = kvs::wave_sum(q0 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] & 0xFFFFu)) +
+                                      q1 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] >> 16)));
+        const float m_new = fmaxf(M, s);
+        const float alpha = M == -INFINITY ? 0.0f : __expf(M - m_new);
+        const float p = __expf(s - m_new);
+        L = L * alpha + p;
+        O0 = O0 * alpha + p * kvs::half_bits_to_float(static_cast<uint16_t>(vw[u] & 0xFFFFu));
+        O1 = O1 * alpha + p * kvs::half_bits_to_float(static_cast<uint16_t>(vw[u] >> 16));
+        M = m_new;
+      }
+    }
+  }
+  reinterpret_cast<float2*>(&part_o[wave][0])[lane] = float2{O0, O1};
+  if (lane == 0) { part_m[wave] = M; part_l[wave] = L; }
+  __syncthreads();
+  if (wave == 0) {
+    float Mx = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) Mx = fmaxf(Mx, part_m[w]);
+    float Ls = 0.0f, A0 = 0.0f, A1 = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float f = part_m[w] == -INFINITY ? 0.0f : __expf(part_m[w] - Mx);
+      const float2 o = reinterpret_cast<const float2*>(&part_o[w][0])[lane];
+      Ls += part_l[w] * f;
+      A0 += o.x * f;
+      A1 += o.y * f;
+    }
+    float* dst = extra + bq * kWsRow;
+    reinterpret_cast<float2*>(dst)[lane] = float2{A0, A1};
+    if (lane == 0) { dst[128] = Mx; dst[129] = Ls; }
+  }
+}
+
+static kvs_status check_decode_args(const kvs_desc* desc, const void* q, const kvs_cache* cache, const void* out,
+                                    const void* workspace) {
   const kvs_status st = kvs::validate_desc(desc);
   if (st != KVS_OK) return st;
   if (!q || !cache || !out || !workspace) return KVS_ERR_INVALID;
@@ -392,30 +468,72 @@ extern "C" kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const
   if (desc->sparse_frac > 0.0f && (!cache->k_rowptr || !cache->k_col || !cache->k_val ||
                                    !cache->v_rowptr || !cache->v_col || !cache->v_val))
     return KVS_ERR_INVALID;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  const kvs::DecodeGeometry geo = kvs::decode_geometry(desc);
-  float* ws = static_cast<float*>(workspace);
+  return KVS_OK;
+}
 
-  if (geo.mfma && desc->sparse_frac > 0.0f) {        // Key corrections, matrix-core kernel, finish
-    float* cs = ws + kvs::decode_parts_floats(desc, geo);
-    kvs::launch_sparse_key_corr(desc, q, cache, cs, s);
-    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, cs, s);
-    kvs::launch_decode_finish_sparse(desc, geo, q, cache, ws, cs, out, lse, s);
-    return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
-  }
-  if (geo.mfma) {
-    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, nullptr, s);
-    if (geo.splits == 1) return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;   // finished in one kernel
-  } else {
-    switch (desc->bits) {
-      case 2: launch_partial_g<2>(desc, geo, q, cache, ws, s); break;
-      case 3: launch_partial_g<3>(desc, geo, q, cache, ws, s); break;
-      default: launch_partial_g<4>(desc, geo, q, cache, ws, s); break;
+// Dense caches: the first n_used tokens (whole blocks) through the stream kernels, then - unless
+// one matrix-core workgroup per head has already finished the rows - the combine kernel, which
+// also takes the residual rows' part when there is one.
+static void decode_dense(const kvs_desc* desc, const void* q, const kvs_cache* cache, int n_used, const float* extra,
+                         void* out, float* lse, float* ws, hipStream_t s) {
+  int splits = 0;
+  if (n_used > 0) {
+    const kvs::DecodeGeometry geo = kvs::decode_geometry(desc, n_used);
+    splits = geo.splits;
+    if (geo.mfma) {
+      kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, nullptr, n_used, extra != nullptr, s);
+      if (geo.splits == 1 && !extra) return;             // finished in one kernel
+    } else {
+      switch (desc->bits) {
+        case 2: launch_partial_g<2>(desc, geo, q, cache, ws, n_used, s); break;
+        case 3: launch_partial_g<3>(desc, geo, q, cache, ws, n_used, s); break;
+        default: launch_partial_g<4>(desc, geo, q, cache, ws, n_used, s); break;
+      }
     }
   }
   hipLaunchKernelGGL(decode_combine_kernel, dim3(desc->B * desc->Hq), dim3(KVS_WAVE), 0, s,
-                     static_cast<const uint16_t*>(q), ws, geo.splits, desc->Hq, desc->Hkv, desc->keep_cap,
+                     static_cast<const uint16_t*>(q), ws, extra, splits, desc->Hq, desc->Hkv, desc->keep_cap,
                      static_cast<const uint16_t*>(cache->keep_k), static_cast<const uint16_t*>(cache->keep_v),
                      cache->keep_cnt, static_cast<uint16_t*>(out), lse);
+}
+
+extern "C" kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const kvs_cache* cache,
+                                       void* out, float* lse, void* workspace, void* stream) {
+  const kvs_status st = check_decode_args(desc, q, cache, out, workspace);
+  if (st != KVS_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* ws = static_cast<float*>(workspace);
+  const kvs::DecodeGeometry geo = kvs::decode_geometry(desc);
+  if (geo.mfma && desc->sparse_frac > 0.0f) {        // Key corrections, matrix-core kernel, finish
+    float* cs = ws + kvs::decode_parts_floats(desc, geo);
+    kvs::launch_sparse_key_corr(desc, q, cache, cs, s);
+    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, cs, desc->n, false, s);
+    kvs::launch_decode_finish_sparse(desc, geo, q, cache, ws, cs, out, lse, s);
+  } else {
+    decode_dense(desc, q, cache, desc->n, nullptr, out, lse, ws, s);
+  }
+  return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
+}
+
+extern "C" kvs_status kvs_decode_attn_n(const kvs_desc* desc, const void* q, const kvs_cache* cache, int32_t n_tokens,
+                                         void* out, float* lse, void* workspace, void* stream) {
+  const kvs_status st = check_decode_args(desc, q, cache, out, workspace);
+  if (st != KVS_OK) return st;
+  if (desc->sparse_frac > 0.0f) return KVS_ERR_UNSUPPORTED;
+  if (n_tokens < 1 || n_tokens > desc->n) return KVS_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* ws = static_cast<float*>(workspace);
+  const int n_used = (n_tokens / KVS_V_TILE) * KVS_V_TILE;
+  const int rows = n_tokens - n_used;
+  float* extra = nullptr;
+  if (rows > 0) {
+    if (!cache->res_k || !cache->res_v) return KVS_ERR_INVALID;
+    // behind the parts of the stream kernels (sized for the most splits any token count can get)
+    extra = ws + static_cast<size_t>(desc->B) * desc->Hq * kvs::decode_max_splits(desc) * kWsRow;
+    hipLaunchKernelGGL(residual_part_kernel, dim3(desc->B * desc->Hq), dim3(kThreads), 0, s,
+                       static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(cache->res_k),
+                       static_cast<const uint16_t*>(cache->res_v), rows, desc->Hq, desc->Hkv, extra);
+  }
+  decode_dense(desc, q, cache, n_used, extra, out, lse, ws, s);
   return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
 }

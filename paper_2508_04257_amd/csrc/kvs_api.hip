@@ -33,17 +33,27 @@ kvs_status validate_desc(const kvs_desc* d) {
 // split, enough workgroups to cover 256 compute units several times over.  Matrix-core kernel:
 // one 8-wave workgroup per split, about one per compute unit, and a single split per (b, h)
 // whenever there are enough (b, h) pairs - then no second kernel is needed.
-DecodeGeometry decode_geometry(const kvs_desc* d) {
-  const int tiles = d->n / KVS_V_TILE;
+// Most splits any token count up to d->n can get (what the workspace is sized for).
+int decode_max_splits(const kvs_desc* d) {
   const int pairs = d->B * d->Hkv;
-  DecodeGeometry g;
-  g.mfma = decode_mfma_supported(d);
   int splits;
-  if (g.mfma) {
+  if (decode_mfma_supported(d)) {
     splits = pairs >= KVS_MFMA_TARGET_GROUPS ? 1 : (KVS_MFMA_TARGET_GROUPS + pairs / 2) / pairs;
   } else {
     splits = (2048 + pairs - 1) / pairs;
   }
+  const int tiles = d->n / KVS_V_TILE;
+  return splits > tiles ? tiles : (splits < 1 ? 1 : splits);
+}
+
+DecodeGeometry decode_geometry(const kvs_desc* d) { return decode_geometry(d, d->n); }
+
+// The same for the first n_used tokens (a multiple of 128, at least 128) of a cache laid out for d->n.
+DecodeGeometry decode_geometry(const kvs_desc* d, int n_used) {
+  const int tiles = n_used / KVS_V_TILE;
+  DecodeGeometry g;
+  g.mfma = decode_mfma_supported(d);
+  int splits = decode_max_splits(d);
   if (splits > tiles) splits = tiles;
   if (splits < 1) splits = 1;
   const int tiles_per_split = (tiles + splits - 1) / splits;
@@ -99,6 +109,8 @@ extern "C" kvs_status kvs_cache_bytes(const kvs_desc* d, size_t* sizes) {
       cap * 2,                                      // v_col
       cap * 2,                                      // v_val
       4,                                            // status
+      bh * KVS_V_TILE * KVS_HEAD_DIM * 2,           // res_k
+      bh * KVS_V_TILE * KVS_HEAD_DIM * 2,           // res_v
   };
   for (int i = 0; i < KVS_CACHE_FIELDS; ++i) {
     const bool csr_field = i >= 9 && i <= 14;
@@ -115,11 +127,14 @@ extern "C" int32_t kvs_decode_splits(const kvs_desc* d) {
 extern "C" size_t kvs_workspace_bytes(const kvs_desc* d) {
   if (kvs::validate_desc(d) != KVS_OK) return 0;
   const kvs::DecodeGeometry g = kvs::decode_geometry(d);
-  // decode: per (b, hq, split) the unnormalised fp32 output row plus running max and sum
-  size_t decode = static_cast<size_t>(d->B) * d->Hq * g.splits * (KVS_HEAD_DIM + 2) * 4;
+  // decode: per (b, hq, split) the unnormalised fp32 output row plus running max and sum (sized
+  // for the most splits any token count of a growing cache can get)
+  size_t decode = static_cast<size_t>(d->B) * d->Hq * kvs::decode_max_splits(d) * (KVS_HEAD_DIM + 2) * 4;
   if (g.mfma && d->sparse_frac > 0.0f)               // plus one score per (b, hq, token)
     decode = (kvs::decode_parts_floats(d, g) + kvs::decode_sparse_score_floats(d)) * 4;
   // quantise (dense-and-sparse only): two 32768-bin histograms, thresholds, scan scratch
   const size_t quant = d->sparse_frac > 0.0f ? kvs::sparse_workspace_words(d) * 4 : 0;
+  // growing caches: one more part per (b, hq) for the residual rows
+  decode += static_cast<size_t>(d->B) * d->Hq * (KVS_HEAD_DIM + 2) * 4;
   return round16(decode > quant ? decode : quant);
 }

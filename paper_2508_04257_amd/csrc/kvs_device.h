@@ -38,11 +38,13 @@ struct DecodeGeometry {
   bool mfma;         // matrix-core kernel instead of the generic one
 };
 DecodeGeometry decode_geometry(const kvs_desc* d);
+DecodeGeometry decode_geometry(const kvs_desc* d, int n_used);
+int decode_max_splits(const kvs_desc* d);
 // Matrix-core decode kernel (decode_mfma.hip).
 bool decode_mfma_supported(const kvs_desc* d);
 int decode_mfma_waves();
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                        void* out, float* lse, float* ws, float* cs, hipStream_t s);
+                        void* out, float* lse, float* ws, float* cs, int n_used, bool to_ws, hipStream_t s);
 // Dense-and-sparse companions of the matrix-core kernel (decode_sparse.hip).  The workspace then
 // holds the parts (B * Hq * splits rows of 130 floats, rounded up to 64 floats) followed by one
 // float per (b, hq, token).
@@ -55,10 +57,24 @@ void launch_sparse_key_corr(const kvs_desc* d, const void* q, const kvs_cache* c
 void launch_decode_finish_sparse(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
                                  const float* ws, const float* cs, void* out, float* lse, hipStream_t s);
 
-// Lean 2 / 4 bit dense quantisation kernels (quantize_fast.hip).
+// Which tokens a quantise launch reads and where they go.  A plain call quantises the whole
+// tensor in place (every field = desc->n, offsets 0); a growing cache quantises the whole blocks of
+// a prompt, or one block out of the residual window, into buffers laid out for the capacity.
+struct QuantSpan {
+  int n_in;         // tokens per (b, h) in the input tensors (their row stride)
+  int n_tokens;     // tokens to quantise per (b, h), from input token 0 on; a multiple of 128
+  int n_cap;        // tokens per (b, h) the cache buffers are laid out for
+  int t_out;        // cache token index of input token 0; a multiple of 128
+  int mask_stride;  // tokens per sequence in the keep mask that is passed along
+  int mask_t0;      // mask index of input token 0
+};
+inline QuantSpan whole_span(const kvs_desc* d) { return QuantSpan{d->n, d->n, d->n, 0, d->n, 0}; }
+
+// Lean 2 / 4 bit dense quantisation kernels (quantize_fast.hip).  own_keep: also build the keep
+// index and copy the kept rows (a plain call); otherwise the caller does both.
 bool quantize_fast_supported(const kvs_desc* d);
-void launch_quantize_fast(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask,
-                          const kvs_cache* out, hipStream_t s);
+void launch_quantize_fast(const kvs_desc* d, const QuantSpan& sp, bool own_keep, const void* K, const void* V,
+                          const uint8_t* mask, const kvs_cache* out, hipStream_t s);
 
 // Dense-and-sparse helpers (sparse.hip): where the scratch lives and the launch sequences.
 // Where a quantise kernel leaves the isolated entries of one tensor: every workgroup claims one

@@ -64,7 +64,7 @@ __device__ inline void unpack8(const uint4& raw, uint16_t h[8]) {
 // ---------------------------------------------------------------------------------------------
 template <int BITS, int G>
 __global__ __launch_bounds__(kThreads) void quantize_k_kernel(
-    const uint4* __restrict__ K, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
+    const uint4* __restrict__ K, const uint8_t* __restrict__ keep_mask, kvs::QuantSpan sp, int Hkv,
     const uint32_t* __restrict__ tau_ptr, uint32_t* __restrict__ k_codes, uint32_t* __restrict__ k_params,
     int32_t* __restrict__ row_count, kvs::SparseEmit emit) {
   constexpr int TB = G > 64 ? G : 64;
@@ -91,14 +91,15 @@ __global__ __launch_bounds__(kThreads) void quantize_k_kernel(
     for (int i = tid; i < TB * 4; i += kThreads) (&iso_s[0][0])[i] = 0;
     __syncthreads();
   }
-  const int blocks_per_head = n / TB;
+  const int blocks_per_head = sp.n_tokens / TB;
   const int blk = blockIdx.x % blocks_per_head;
   const size_t bh = blockIdx.x / blocks_per_head;       // b * Hkv + h
   const int b = static_cast<int>(bh / Hkv);
-  const int t0 = blk * TB;
+  const int n = sp.n_cap;                               // layout of everything written
+  const int t0 = sp.t_out + blk * TB;                   // cache token of the block's first row
 
-  const uint4* src = K + (bh * n + t0) * 16;            // 16 uint4 per 128-channel row
-  const uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * n + t0;
+  const uint4* src = K + (bh * sp.n_in + blk * TB) * 16;   // 16 uint4 per 128-channel row
+  const uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * sp.mask_stride + sp.mask_t0 + blk * TB;
 
   uint4 raw[ROWS];
   bool kept[ROWS];
@@ -249,7 +250,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_kernel(
 // ---------------------------------------------------------------------------------------------
 template <int BITS, int G>
 __global__ __launch_bounds__(kThreads) void quantize_v_kernel(
-    const uint4* __restrict__ V, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
+    const uint4* __restrict__ V, const uint8_t* __restrict__ keep_mask, kvs::QuantSpan sp, int Hkv,
     const uint32_t* __restrict__ tau_ptr, uint32_t* __restrict__ v_codes, uint32_t* __restrict__ v_params,
     int32_t* __restrict__ row_count, kvs::SparseEmit emit) {
   constexpr int ROWS = KVS_V_TILE / 16;  // 8 rows per lane
@@ -272,14 +273,17 @@ __global__ __launch_bounds__(kThreads) void quantize_v_kernel(
     for (int i = tid; i < 128 * 4; i += kThreads) (&iso_s[0][0])[i] = 0;
     __syncthreads();
   }
-  const int tiles_per_head = n / KVS_V_TILE;
-  const int tile = blockIdx.x % tiles_per_head;
-  const size_t bh = blockIdx.x / tiles_per_head;
+  const int tiles_in = sp.n_tokens / KVS_V_TILE;
+  const int tile_in = blockIdx.x % tiles_in;
+  const size_t bh = blockIdx.x / tiles_in;
   const int b = static_cast<int>(bh / Hkv);
-  const int t0 = tile * KVS_V_TILE;
+  const int n = sp.n_cap;                               // layout of everything written
+  const int tiles_per_head = n / KVS_V_TILE;
+  const int tile = sp.t_out / KVS_V_TILE + tile_in;
+  const int t0 = tile * KVS_V_TILE;                     // cache token of the tile's first row
 
-  const uint4* src = V + (bh * n + t0) * 16;
-  const uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * n + t0;
+  const uint4* src = V + (bh * sp.n_in + tile_in * KVS_V_TILE) * 16;
+  const uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * sp.mask_stride + sp.mask_t0 + tile_in * KVS_V_TILE;
 
   // Load; with isolated outliers, first mark them (per channel: which tokens), so that the counts
   // and the tile's place in the staging list are known while the codes are being computed.
@@ -409,20 +413,21 @@ __global__ __launch_bounds__(kThreads) void quantize_v_kernel(
 // ---------------------------------------------------------------------------------------------
 constexpr int kIndexThreads = 1024;
 
+// n tokens are indexed; both masks have `stride` bytes per sequence (they may be the same array).
 __global__ __launch_bounds__(kIndexThreads) void keep_index_kernel(
-    const uint8_t* __restrict__ keep_mask, int n, int cap, int32_t* __restrict__ keep_idx,
+    const uint8_t* __restrict__ keep_mask, int n, int stride, int cap, int32_t* __restrict__ keep_idx,
     int32_t* __restrict__ keep_cnt, uint8_t* __restrict__ mask_copy, int32_t* __restrict__ status) {
   __shared__ int wave_count[kIndexThreads / KVS_WAVE];
   __shared__ int base_s;
   const int b = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & (KVS_WAVE - 1), wave = tid / KVS_WAVE;
-  const uint8_t* m = keep_mask + static_cast<size_t>(b) * n;
+  const uint8_t* m = keep_mask + static_cast<size_t>(b) * stride;
   if (tid == 0) base_s = 0;
   __syncthreads();
   for (int i0 = 0; i0 < n; i0 += kIndexThreads) {
     const int i = i0 + tid;
     const bool flag = i < n && m[i] != 0;
-    if (i < n) mask_copy[static_cast<size_t>(b) * n + i] = flag ? 1 : 0;
+    if (i < n) mask_copy[static_cast<size_t>(b) * stride + i] = flag ? 1 : 0;
     const unsigned long long ballot = __ballot(flag);
     const int before = __popcll(ballot & ((1ull << lane) - 1ull));
     if (lane == 0) wave_count[wave] = __popcll(ballot);
@@ -447,9 +452,11 @@ __global__ __launch_bounds__(kIndexThreads) void keep_index_kernel(
   }
 }
 
-// One wave per (b, h, j): copies the 256-byte K row and V row of kept token j (zeros past the count).
+// One wave per (b, h, j): copies the 256-byte K row and V row of kept token j if it lies in the
+// span the input tensors hold (cache tokens t_out .. t_out + n_tokens), zeros past the count;
+// rows of other kept tokens, written by an earlier call, are left alone.
 __global__ __launch_bounds__(KVS_WAVE) void keep_gather_kernel(
-    const uint32_t* __restrict__ K, const uint32_t* __restrict__ V, int n, int Hkv, int cap,
+    const uint32_t* __restrict__ K, const uint32_t* __restrict__ V, kvs::QuantSpan sp, int Hkv, int cap,
     const int32_t* __restrict__ keep_idx, uint32_t* __restrict__ keep_k, uint32_t* __restrict__ keep_v) {
   const int j = blockIdx.x % cap;
   const size_t bh = blockIdx.x / cap;
@@ -457,11 +464,11 @@ __global__ __launch_bounds__(KVS_WAVE) void keep_gather_kernel(
   const int t = keep_idx[static_cast<size_t>(b) * cap + j];
   const int lane = threadIdx.x;
   const size_t dst = (bh * cap + j) * 64 + lane;       // 64 uint32 per row
-  if (t >= 0) {
-    const size_t srcw = (bh * n + t) * 64 + lane;
+  if (t >= sp.t_out && t < sp.t_out + sp.n_tokens) {
+    const size_t srcw = (bh * sp.n_in + (t - sp.t_out)) * 64 + lane;
     keep_k[dst] = K[srcw];
     keep_v[dst] = V[srcw];
-  } else {
+  } else if (t < 0) {
     keep_k[dst] = 0;
     keep_v[dst] = 0;
   }
@@ -469,69 +476,162 @@ __global__ __launch_bounds__(KVS_WAVE) void keep_gather_kernel(
 
 template <int BITS, int G>
 void launch_dense(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask,
-                  const kvs_cache* out, const uint32_t* tau, const kvs::SparsePlan& plan, hipStream_t stream) {
+                  const kvs_cache* out, const uint32_t* tau, const kvs::SparsePlan& plan, const kvs::QuantSpan& sp,
+                  hipStream_t stream) {
   constexpr int TB = G > 64 ? G : 64;
   const int bh = d->B * d->Hkv;
-  hipLaunchKernelGGL((quantize_k_kernel<BITS, G>), dim3(bh * (d->n / TB)), dim3(kThreads), 0, stream,
-                     static_cast<const uint4*>(K), mask, d->n, d->Hkv, tau, out->k_codes, out->k_params,
+  if (sp.n_tokens == 0) return;
+  hipLaunchKernelGGL((quantize_k_kernel<BITS, G>), dim3(bh * (sp.n_tokens / TB)), dim3(kThreads), 0, stream,
+                     static_cast<const uint4*>(K), mask, sp, d->Hkv, tau, out->k_codes, out->k_params,
                      tau ? out->k_rowptr + 1 : nullptr, plan.emit_k);
-  hipLaunchKernelGGL((quantize_v_kernel<BITS, G>), dim3(bh * (d->n / KVS_V_TILE)), dim3(kThreads), 0,
-                     stream, static_cast<const uint4*>(V), mask, d->n, d->Hkv, tau ? tau + 1 : nullptr,
+  hipLaunchKernelGGL((quantize_v_kernel<BITS, G>), dim3(bh * (sp.n_tokens / KVS_V_TILE)), dim3(kThreads), 0,
+                     stream, static_cast<const uint4*>(V), mask, sp, d->Hkv, tau ? tau + 1 : nullptr,
                      out->v_codes, out->v_params, tau ? out->v_rowptr + 1 : nullptr, plan.emit_v);
 }
 
 template <int BITS>
 void launch_dense_g(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask,
-                    const kvs_cache* out, const uint32_t* tau, const kvs::SparsePlan& plan, hipStream_t s) {
+                    const kvs_cache* out, const uint32_t* tau, const kvs::SparsePlan& plan, const kvs::QuantSpan& sp,
+                    hipStream_t s) {
   switch (d->group) {
-    case 32: launch_dense<BITS, 32>(d, K, V, mask, out, tau, plan, s); break;
-    case 64: launch_dense<BITS, 64>(d, K, V, mask, out, tau, plan, s); break;
-    default: launch_dense<BITS, 128>(d, K, V, mask, out, tau, plan, s); break;
+    case 32: launch_dense<BITS, 32>(d, K, V, mask, out, tau, plan, sp, s); break;
+    case 64: launch_dense<BITS, 64>(d, K, V, mask, out, tau, plan, sp, s); break;
+    default: launch_dense<BITS, 128>(d, K, V, mask, out, tau, plan, sp, s); break;
   }
 }
 
 }  // namespace
 
-extern "C" kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const void* V,
-                                       const uint8_t* keep_mask, const kvs_cache* out,
-                                       void* workspace, void* stream) {
+// Shared by the three quantising entry points: the quantise kernels over one span, then - unless
+// the lean kernels did it themselves - the keep index over the first n_index cache tokens and the
+// kept rows that lie in the span.
+static void quantize_span(const kvs_desc* desc, const kvs::QuantSpan& sp, bool whole, const void* K, const void* V,
+                          const uint8_t* mask, const uint8_t* index_mask, int n_index, const kvs_cache* out,
+                          void* workspace, hipStream_t s) {
+  const bool sparse = desc->sparse_frac > 0.0f;
+  if (kvs::quantize_fast_supported(desc)) {            // 2 / 4 bit without isolated outliers
+    kvs::launch_quantize_fast(desc, sp, whole, K, V, mask, out, s);
+    if (whole) return;
+  } else {
+    kvs::SparsePlan plan{};
+    const uint32_t* tau = nullptr;       // device [2]: thresholds of K and V
+    if (sparse) {
+      plan = kvs::sparse_plan(desc, workspace);
+      kvs::sparse_thresholds(desc, plan, K, V, mask, out, s);
+      tau = plan.tau;
+    }
+    switch (desc->bits) {
+      case 2: launch_dense_g<2>(desc, K, V, mask, out, tau, plan, sp, s); break;
+      case 3: launch_dense_g<3>(desc, K, V, mask, out, tau, plan, sp, s); break;
+      default: launch_dense_g<4>(desc, K, V, mask, out, tau, plan, sp, s); break;
+    }
+    if (sparse) kvs::sparse_build_csr(desc, plan, out, s);
+  }
+  hipLaunchKernelGGL(keep_index_kernel, dim3(desc->B), dim3(kIndexThreads), 0, s, index_mask, n_index,
+                     whole ? desc->n : sp.n_cap, desc->keep_cap, out->keep_idx, out->keep_cnt, out->keep_mask,
+                     out->status);
+  if (desc->keep_cap > 0)
+    hipLaunchKernelGGL(keep_gather_kernel, dim3(desc->B * desc->Hkv * desc->keep_cap), dim3(KVS_WAVE), 0, s,
+                       static_cast<const uint32_t*>(K), static_cast<const uint32_t*>(V), sp, desc->Hkv,
+                       desc->keep_cap, out->keep_idx, static_cast<uint32_t*>(out->keep_k),
+                       static_cast<uint32_t*>(out->keep_v));
+}
+
+static kvs_status check_quantize_args(const kvs_desc* desc, const kvs_cache* out) {
   const kvs_status st = kvs::validate_desc(desc);
   if (st != KVS_OK) return st;
-  if (!K || !V || !keep_mask || !out) return KVS_ERR_INVALID;
+  if (!out) return KVS_ERR_INVALID;
   if (!out->k_codes || !out->v_codes || !out->k_params || !out->v_params || !out->keep_idx ||
       !out->keep_cnt || !out->keep_mask || !out->status)
     return KVS_ERR_INVALID;
   if (desc->keep_cap > 0 && (!out->keep_k || !out->keep_v)) return KVS_ERR_INVALID;
+  return KVS_OK;
+}
+
+extern "C" kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const void* V,
+                                       const uint8_t* keep_mask, const kvs_cache* out,
+                                       void* workspace, void* stream) {
+  const kvs_status st = check_quantize_args(desc, out);
+  if (st != KVS_OK) return st;
+  if (!K || !V || !keep_mask) return KVS_ERR_INVALID;
   const bool sparse = desc->sparse_frac > 0.0f;
   if (sparse && (!workspace || !out->k_rowptr || !out->k_col || !out->k_val || !out->v_rowptr ||
                  !out->v_col || !out->v_val))
     return KVS_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  quantize_span(desc, kvs::whole_span(desc), true, K, V, keep_mask, keep_mask, desc->n, out, workspace, s);
+  return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
+}
 
-  if (kvs::quantize_fast_supported(desc)) {            // 2 / 4 bit without isolated outliers
-    kvs::launch_quantize_fast(desc, K, V, keep_mask, out, s);
-    return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
-  }
+// ---------------------------------------------------------------------------------------------
+// Growing caches (paper, Section 2 "KV cache": the decoding phase appends the new token's K, V).
+// Whole 128-token blocks are quantised; the tokens after the last whole block wait in fp16 rows
+// (res_k / res_v) until their block is complete.
+// ---------------------------------------------------------------------------------------------
+namespace {
 
-  kvs::SparsePlan plan{};
-  const uint32_t* tau = nullptr;       // device [2]: thresholds of K and V
-  if (sparse) {
-    plan = kvs::sparse_plan(desc, workspace);
-    kvs::sparse_thresholds(desc, plan, K, V, keep_mask, out, s);
-    tau = plan.tau;
+// Keep mask of a prompt into the cache's capacity-wide mask: flags normalised to 0 / 1, zeros
+// from the prompt's end to the capacity.
+__global__ void grow_mask_kernel(const uint8_t* __restrict__ mask, int n_tokens, int n_cap, uint8_t* __restrict__ dst) {
+  const int b = blockIdx.y;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_cap; i += gridDim.x * blockDim.x)
+    dst[static_cast<size_t>(b) * n_cap + i] = i < n_tokens && mask[static_cast<size_t>(b) * n_tokens + i] != 0 ? 1 : 0;
+}
+
+// rows tokens of each (b, h), starting at input token t_in of a [B*Hkv, n_in, 128] tensor pair, to
+// residual rows r_out .. of the [B*Hkv, 128, 128] windows.  One wave per (b, h, row).
+__global__ __launch_bounds__(KVS_WAVE) void residual_copy_kernel(
+    const uint32_t* __restrict__ K, const uint32_t* __restrict__ V, int n_in, int t_in, int rows, int r_out,
+    uint32_t* __restrict__ res_k, uint32_t* __restrict__ res_v) {
+  const int r = blockIdx.x % rows;
+  const size_t bh = blockIdx.x / rows;
+  const size_t src = (bh * n_in + t_in + r) * 64 + threadIdx.x;
+  const size_t dst = (bh * KVS_V_TILE + r_out + r) * 64 + threadIdx.x;
+  res_k[dst] = K[src];
+  res_v[dst] = V[src];
+}
+
+}  // namespace
+
+extern "C" kvs_status kvs_quantize_prefix(const kvs_desc* desc, const void* K, const void* V,
+                                           const uint8_t* keep_mask, int32_t n_tokens, const kvs_cache* out,
+                                           void* workspace, void* stream) {
+  const kvs_status st = check_quantize_args(desc, out);
+  if (st != KVS_OK) return st;
+  if (desc->sparse_frac > 0.0f) return KVS_ERR_UNSUPPORTED;
+  if (n_tokens < 0 || n_tokens > desc->n) return KVS_ERR_INVALID;
+  if (!out->res_k || !out->res_v) return KVS_ERR_INVALID;
+  if (n_tokens > 0 && (!K || !V || !keep_mask)) return KVS_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int nq = (n_tokens / KVS_V_TILE) * KVS_V_TILE;
+  hipLaunchKernelGGL(grow_mask_kernel, dim3((desc->n + 255) / 256, desc->B), dim3(256), 0, s, keep_mask, n_tokens,
+                     desc->n, out->keep_mask);
+  const kvs::QuantSpan sp{n_tokens, nq, desc->n, 0, n_tokens, 0};
+  quantize_span(desc, sp, false, K, V, keep_mask, out->keep_mask, nq, out, workspace, s);
+  if (n_tokens > nq)
+    hipLaunchKernelGGL(residual_copy_kernel, dim3(desc->B * desc->Hkv * (n_tokens - nq)), dim3(KVS_WAVE), 0, s,
+                       static_cast<const uint32_t*>(K), static_cast<const uint32_t*>(V), n_tokens, nq, n_tokens - nq,
+                       0, static_cast<uint32_t*>(out->res_k), static_cast<uint32_t*>(out->res_v));
+  return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
+}
+
+extern "C" kvs_status kvs_append_kv(const kvs_desc* desc, const void* k_new, const void* v_new, int32_t n_tokens,
+                                     const kvs_cache* cache, void* workspace, void* stream) {
+  const kvs_status st = check_quantize_args(desc, cache);
+  if (st != KVS_OK) return st;
+  if (desc->sparse_frac > 0.0f) return KVS_ERR_UNSUPPORTED;
+  if (n_tokens < 0 || n_tokens >= desc->n) return KVS_ERR_INVALID;     // no room for one more token
+  if (!k_new || !v_new || !cache->res_k || !cache->res_v) return KVS_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int nq = (n_tokens / KVS_V_TILE) * KVS_V_TILE;
+  const int r = n_tokens - nq;
+  hipLaunchKernelGGL(residual_copy_kernel, dim3(desc->B * desc->Hkv), dim3(KVS_WAVE), 0, s,
+                     static_cast<const uint32_t*>(k_new), static_cast<const uint32_t*>(v_new), 1, 0, 1, r,
+                     static_cast<uint32_t*>(cache->res_k), static_cast<uint32_t*>(cache->res_v));
+  if (r == KVS_V_TILE - 1) {                           // the window is a whole block now
+    const kvs::QuantSpan sp{KVS_V_TILE, KVS_V_TILE, desc->n, nq, desc->n, nq};
+    quantize_span(desc, sp, false, cache->res_k, cache->res_v, cache->keep_mask, cache->keep_mask,
+                  nq + KVS_V_TILE, cache, workspace, s);
   }
-  switch (desc->bits) {
-    case 2: launch_dense_g<2>(desc, K, V, keep_mask, out, tau, plan, s); break;
-    case 3: launch_dense_g<3>(desc, K, V, keep_mask, out, tau, plan, s); break;
-    default: launch_dense_g<4>(desc, K, V, keep_mask, out, tau, plan, s); break;
-  }
-  if (sparse) kvs::sparse_build_csr(desc, plan, out, s);
-  hipLaunchKernelGGL(keep_index_kernel, dim3(desc->B), dim3(kIndexThreads), 0, s, keep_mask, desc->n,
-                     desc->keep_cap, out->keep_idx, out->keep_cnt, out->keep_mask, out->status);
-  if (desc->keep_cap > 0)
-    hipLaunchKernelGGL(keep_gather_kernel, dim3(desc->B * desc->Hkv * desc->keep_cap), dim3(KVS_WAVE), 0, s,
-                       static_cast<const uint32_t*>(K), static_cast<const uint32_t*>(V), desc->n, desc->Hkv,
-                       desc->keep_cap, out->keep_idx, static_cast<uint32_t*>(out->keep_k),
-                       static_cast<uint32_t*>(out->keep_v));
   return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
 }

@@ -106,7 +106,7 @@ __device__ inline int keep_slot(const int32_t* __restrict__ keep_idx, int cnt, i
 // ---------------------------------------------------------------------------------------------
 template <int BITS, int G>
 __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
-    const uint4* __restrict__ K, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
+    const uint4* __restrict__ K, const uint8_t* __restrict__ keep_mask, kvs::QuantSpan sp, int Hkv,
     uint32_t* __restrict__ k_codes, uint32_t* __restrict__ k_params, const int32_t* __restrict__ keep_idx,
     const int32_t* __restrict__ keep_cnt, int cap, uint4* __restrict__ keep_k) {
   constexpr int TB = G > 64 ? G : 64;
@@ -126,13 +126,15 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
   const int tid = threadIdx.x;
   const int chunk = tid & 15;
   const int rslot = tid >> 4;
-  const int blocks_per_head = n / TB;
+  const int blocks_per_head = sp.n_tokens / TB;
   const int blk = blockIdx.x % blocks_per_head;
   const size_t bh = blockIdx.x / blocks_per_head;
   const int b = static_cast<int>(bh / Hkv);
-  const int t0 = blk * TB;
-  const uint4* src = K + (bh * n + t0) * 16;
-  const uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * n + t0;
+  const int t0 = blk * TB;                      // input token; the cache token is sp.t_out + t0
+  const int n = sp.n_cap;                       // layout of everything written
+  const int tc0 = sp.t_out + t0;
+  const uint4* src = K + (bh * sp.n_in + t0) * 16;
+  const uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * sp.mask_stride + sp.mask_t0 + t0;
 
   uint4 raw[ROWS];
   bool kept[ROWS];
@@ -176,7 +178,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
     const Param p1 = make_param<BITS>(hi_half(a), hi_half(z), any);
     inv_s[g][2 * cp] = p0.inv;  inv_s[g][2 * cp + 1] = p1.inv;
     zero_s[g][2 * cp] = p0.zero;  zero_s[g][2 * cp + 1] = p1.zero;
-    reinterpret_cast<uint2*>(k_params + (bh * (n / G) + static_cast<size_t>(t0 / G + g)) * 128)[cp] = uint2{p0.word, p1.word};
+    reinterpret_cast<uint2*>(k_params + (bh * (n / G) + static_cast<size_t>(tc0 / G + g)) * 128)[cp] = uint2{p0.word, p1.word};
   }
   __syncthreads();
 
@@ -198,7 +200,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
       if (LANES_PER_WORD == 1 || (chunk & 1) == 0)
         tile_s[((r / KVS_K_TILE) * W + chunk / LANES_PER_WORD) * TILE_STRIDE + (r % KVS_K_TILE)] = word;
       if (kept[i]) {                              // exact copy of the row into the fp16 side buffer
-        const int j = keep_slot(keep_idx + static_cast<size_t>(b) * cap, cnt, t0 + r);
+        const int j = keep_slot(keep_idx + static_cast<size_t>(b) * cap, cnt, tc0 + r);
         if (j >= 0) keep_k[(bh * cap + j) * 16 + chunk] = raw[i];
       }
     }
@@ -206,7 +208,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
   __syncthreads();
 
   // The block's words are contiguous in global memory in (tile, w, t) order: 128-bit stores.
-  uint4* out = reinterpret_cast<uint4*>(k_codes + (bh * (n / KVS_K_TILE) + static_cast<size_t>(t0 / KVS_K_TILE)) * (W * KVS_K_TILE));
+  uint4* out = reinterpret_cast<uint4*>(k_codes + (bh * (n / KVS_K_TILE) + static_cast<size_t>(tc0 / KVS_K_TILE)) * (W * KVS_K_TILE));
   constexpr int quads = (TB / KVS_K_TILE) * W * (KVS_K_TILE / 4);
   for (int qi = tid; qi < quads; qi += kThreads) {
     const int row = qi / (KVS_K_TILE / 4), t4 = qi % (KVS_K_TILE / 4);
@@ -220,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
 // ---------------------------------------------------------------------------------------------
 template <int BITS, int G>
 __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
-    const uint4* __restrict__ V, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
+    const uint4* __restrict__ V, const uint8_t* __restrict__ keep_mask, kvs::QuantSpan sp, int Hkv,
     uint32_t* __restrict__ v_codes, uint32_t* __restrict__ v_params, const int32_t* __restrict__ keep_idx,
     const int32_t* __restrict__ keep_cnt, int cap, uint4* __restrict__ keep_v) {
   constexpr int W = Fmt<BITS>::W;
@@ -232,13 +234,24 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
   const int lane = tid & (KVS_WAVE - 1);
   const int chunk = tid & 15;
   const int rs = tid >> 4;                      // token word: tokens 8 rs .. 8 rs + 7
-  const int tiles_per_head = n / KVS_V_TILE;
-  const int tile = blockIdx.x % tiles_per_head;
-  const size_t bh = blockIdx.x / tiles_per_head;
+  const int tiles_in = sp.n_tokens / KVS_V_TILE;
+  const int tile_in = blockIdx.x % tiles_in;
+  const size_t bh = blockIdx.x / tiles_in;
   const int b = static_cast<int>(bh / Hkv);
-  const int t0 = tile * KVS_V_TILE;
-  const uint4* src = V + (bh * n + t0 + 8 * rs) * 16 + chunk;
-  const uint2 mask8 = *reinterpret_cast<const uint2*>(keep_mask + static_cast<size_t>(b) * n + t0 + 8 * rs);
+  const int n = sp.n_cap;                       // layout of everything written
+  const int tiles_per_head = n / KVS_V_TILE;
+  const int tile = sp.t_out / KVS_V_TILE + tile_in;
+  const int t0 = tile * KVS_V_TILE;             // cache token of the tile's first row
+  const uint4* src = V + (bh * sp.n_in + tile_in * KVS_V_TILE + 8 * rs) * 16 + chunk;
+  // (a prompt's mask rows may start at any byte)
+  const uint8_t* mrow = keep_mask + static_cast<size_t>(b) * sp.mask_stride + sp.mask_t0 + tile_in * KVS_V_TILE + 8 * rs;
+  uint2 mask8;
+  if (((sp.mask_stride | sp.mask_t0) & 7) == 0) {
+    mask8 = *reinterpret_cast<const uint2*>(mrow);
+  } else {
+    mask8.x = mrow[0] | (mrow[1] << 8) | (mrow[2] << 16) | (static_cast<uint32_t>(mrow[3]) << 24);
+    mask8.y = mrow[4] | (mrow[5] << 8) | (mrow[6] << 16) | (static_cast<uint32_t>(mrow[7]) << 24);
+  }
 
   uint4 raw[8];
 #pragma unroll
@@ -375,28 +388,31 @@ __global__ __launch_bounds__(KVS_WAVE) void keep_index_fast_kernel(
 }
 
 template <int BITS, int G>
-void launch_fast(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask, const kvs_cache* out,
-                 hipStream_t s) {
+void launch_fast(const kvs_desc* d, const kvs::QuantSpan& sp, bool own_keep, const void* K, const void* V,
+                 const uint8_t* mask, const kvs_cache* out, hipStream_t s) {
   constexpr int TB = G > 64 ? G : 64;
   const int bh = d->B * d->Hkv;
-  hipLaunchKernelGGL(keep_index_fast_kernel, dim3(d->B), dim3(KVS_WAVE), 0, s, mask, d->n, d->Hkv, d->keep_cap,
-                     out->keep_idx, out->keep_cnt, out->keep_mask, out->status, static_cast<uint4*>(out->keep_k),
-                     static_cast<uint4*>(out->keep_v));
-  hipLaunchKernelGGL((quantize_k_fast_kernel<BITS, G>), dim3(bh * (d->n / TB)), dim3(kThreads), 0, s,
-                     static_cast<const uint4*>(K), mask, d->n, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
-                     out->keep_cnt, d->keep_cap, static_cast<uint4*>(out->keep_k));
-  hipLaunchKernelGGL((quantize_v_fast_kernel<BITS, G>), dim3(bh * (d->n / KVS_V_TILE)), dim3(kThreads), 0, s,
-                     static_cast<const uint4*>(V), mask, d->n, d->Hkv, out->v_codes, out->v_params, out->keep_idx,
-                     out->keep_cnt, d->keep_cap, static_cast<uint4*>(out->keep_v));
+  const int cap = own_keep ? d->keep_cap : 0;            // 0: the kernels copy no kept rows themselves
+  if (own_keep)
+    hipLaunchKernelGGL(keep_index_fast_kernel, dim3(d->B), dim3(KVS_WAVE), 0, s, mask, d->n, d->Hkv, d->keep_cap,
+                       out->keep_idx, out->keep_cnt, out->keep_mask, out->status, static_cast<uint4*>(out->keep_k),
+                       static_cast<uint4*>(out->keep_v));
+  if (sp.n_tokens == 0) return;
+  hipLaunchKernelGGL((quantize_k_fast_kernel<BITS, G>), dim3(bh * (sp.n_tokens / TB)), dim3(kThreads), 0, s,
+                     static_cast<const uint4*>(K), mask, sp, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
+                     out->keep_cnt, cap, static_cast<uint4*>(out->keep_k));
+  hipLaunchKernelGGL((quantize_v_fast_kernel<BITS, G>), dim3(bh * (sp.n_tokens / KVS_V_TILE)), dim3(kThreads), 0, s,
+                     static_cast<const uint4*>(V), mask, sp, d->Hkv, out->v_codes, out->v_params, out->keep_idx,
+                     out->keep_cnt, cap, static_cast<uint4*>(out->keep_v));
 }
 
 template <int BITS>
-void launch_fast_g(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask, const kvs_cache* out,
-                   hipStream_t s) {
+void launch_fast_g(const kvs_desc* d, const kvs::QuantSpan& sp, bool own_keep, const void* K, const void* V,
+                   const uint8_t* mask, const kvs_cache* out, hipStream_t s) {
   switch (d->group) {
-    case 32: launch_fast<BITS, 32>(d, K, V, mask, out, s); break;
-    case 64: launch_fast<BITS, 64>(d, K, V, mask, out, s); break;
-    default: launch_fast<BITS, 128>(d, K, V, mask, out, s); break;
+    case 32: launch_fast<BITS, 32>(d, sp, own_keep, K, V, mask, out, s); break;
+    case 64: launch_fast<BITS, 64>(d, sp, own_keep, K, V, mask, out, s); break;
+    default: launch_fast<BITS, 128>(d, sp, own_keep, K, V, mask, out, s); break;
   }
 }
 
@@ -408,10 +424,10 @@ bool quantize_fast_supported(const kvs_desc* d) {
   return (d->bits == 2 || d->bits == 4) && d->sparse_frac == 0.0f;
 }
 
-void launch_quantize_fast(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask,
-                          const kvs_cache* out, hipStream_t s) {
-  if (d->bits == 2) launch_fast_g<2>(d, K, V, mask, out, s);
-  else launch_fast_g<4>(d, K, V, mask, out, s);
+void launch_quantize_fast(const kvs_desc* d, const QuantSpan& sp, bool own_keep, const void* K, const void* V,
+                          const uint8_t* mask, const kvs_cache* out, hipStream_t s) {
+  if (d->bits == 2) launch_fast_g<2>(d, sp, own_keep, K, V, mask, out, s);
+  else launch_fast_g<4>(d, sp, own_keep, K, V, mask, out, s);
 }
 
 }  // namespace kvs

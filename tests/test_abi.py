@@ -20,7 +20,7 @@ def _declared_symbols():
 def test_library_exports_every_declared_symbol():
     names = _declared_symbols()
     assert {"kvs_predict_sinks", "kvs_quantize_kv", "kvs_decode_attn", "kvs_cache_bytes",
-            "kvs_workspace_bytes"} <= set(names)
+            "kvs_workspace_bytes", "kvs_quantize_prefix", "kvs_append_kv", "kvs_decode_attn_n"} <= set(names)
     L = kb.lib()
     for name in names:
         assert hasattr(L, name), name
@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_the_header():
     assert C.sizeof(kb.KvsDesc) == 48                  # 9 x 4 bytes, padding, one int64
     assert kb.KvsDesc.sparse_cap.offset == 40
-    assert C.sizeof(kb.KvsCache) == 16 * 8
+    assert C.sizeof(kb.KvsCache) == 18 * 8
     text = open(os.path.join(ROOT, "include", "kvs.h")).read()
     body = text[text.index("typedef struct kvs_cache {"):text.index("} kvs_cache;")]
     fields = re.findall(r"\b(\w+);", body)
@@ -86,3 +86,24 @@ def test_null_pointers_are_rejected_on_the_host():
     assert L.kvs_predict_sinks(16, 1, 128, 4096, ch, 1, 200, 0, 16, 16, None, None) == kb.KVS_ERR_INVALID  # k > n
     assert L.kvs_predict_sinks(16, 1, 1 << 20, 4096, ch, 1, 2, 0, 16, 16, None, None) == kb.KVS_ERR_UNSUPPORTED
     assert kb.kvs_predict_workspace_bytes(4, 32768, 8) == 4 * 8 * 8 * 4 and kb.kvs_predict_workspace_bytes(8, 4096, 5) == 0
+
+
+def test_growing_cache_calls_check_their_arguments_on_the_host():
+    d = kb.make_desc(B=2, n=1024, Hq=32, Hkv=32, bits=4, group=128, keep_cap=2)
+    L = kb.lib()
+    cache = kb.KvsCache()                              # all NULL
+    assert L.kvs_quantize_prefix(C.byref(d), 16, 16, 16, 300, C.byref(cache), None, None) == kb.KVS_ERR_INVALID
+    assert L.kvs_append_kv(C.byref(d), 16, 16, 300, C.byref(cache), None, None) == kb.KVS_ERR_INVALID
+    assert L.kvs_decode_attn_n(C.byref(d), 16, C.byref(cache), 300, 16, None, 16, None) == kb.KVS_ERR_INVALID
+    full = kb.KvsCache(**{name: 16 for name in kb.CACHE_FIELD_NAMES})   # non-NULL everywhere: only sizes are wrong
+    assert L.kvs_quantize_prefix(C.byref(d), 16, 16, 16, 1025, C.byref(full), None, None) == kb.KVS_ERR_INVALID
+    assert L.kvs_quantize_prefix(C.byref(d), 16, 16, 16, -1, C.byref(full), None, None) == kb.KVS_ERR_INVALID
+    assert L.kvs_append_kv(C.byref(d), 16, 16, 1024, C.byref(full), None, None) == kb.KVS_ERR_INVALID   # full
+    assert L.kvs_decode_attn_n(C.byref(d), 16, C.byref(full), 0, 16, None, 16, None) == kb.KVS_ERR_INVALID
+    assert L.kvs_decode_attn_n(C.byref(d), 16, C.byref(full), 1025, 16, None, 16, None) == kb.KVS_ERR_INVALID
+    ds = kb.make_desc(B=2, n=1024, Hq=32, Hkv=32, bits=3, group=128, keep_cap=2, sparse_frac=0.01, sparse_cap=1000)
+    assert L.kvs_quantize_prefix(C.byref(ds), 16, 16, 16, 300, C.byref(full), 16, None) == kb.KVS_ERR_UNSUPPORTED
+    assert L.kvs_append_kv(C.byref(ds), 16, 16, 300, C.byref(full), 16, None) == kb.KVS_ERR_UNSUPPORTED
+    assert L.kvs_decode_attn_n(C.byref(ds), 16, C.byref(full), 300, 16, None, 16, None) == kb.KVS_ERR_UNSUPPORTED
+    s = kb.kvs_cache_bytes(d)
+    assert s["res_k"] == s["res_v"] == 2 * 32 * 128 * 128 * 2
