@@ -481,8 +481,8 @@ static void decode_dense(const kvs_desc* desc, const void* q, const kvs_cache* c
     const kvs::DecodeGeometry geo = kvs::decode_geometry(desc, n_used);
     splits = geo.splits;
     if (geo.mfma) {
-      kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, nullptr, n_used, extra != nullptr, s);
-      if (geo.splits == 1 && !extra) return;             // finished in one kernel
+      kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, nullptr, n_used, extra, s);
+      if (geo.splits == 1) return;                       // finished in one kernel, the extra part included
     } else {
       switch (desc->bits) {
         case 2: launch_partial_g<2>(desc, geo, q, cache, ws, n_used, s); break;
@@ -507,7 +507,7 @@ extern "C" kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const
   if (geo.mfma && desc->sparse_frac > 0.0f) {        // Key corrections, matrix-core kernel, finish
     float* cs = ws + kvs::decode_parts_floats(desc, geo);
     kvs::launch_sparse_key_corr(desc, q, cache, cs, s);
-    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, cs, desc->n, false, s);
+    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, cs, desc->n, nullptr, s);
     kvs::launch_decode_finish_sparse(desc, geo, q, cache, ws, cs, out, lse, s);
   } else {
     decode_dense(desc, q, cache, desc->n, nullptr, out, lse, ws, s);

@@ -8,9 +8,9 @@
 
 namespace kvs {
 
-void launch_decode_mfma_b2(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, int, bool, hipStream_t);
-void launch_decode_mfma_b3(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, int, bool, hipStream_t);
-void launch_decode_mfma_b4(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, int, bool, hipStream_t);
+void launch_decode_mfma_b2(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, int, const float*, hipStream_t);
+void launch_decode_mfma_b3(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, int, const float*, hipStream_t);
+void launch_decode_mfma_b4(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, int, const float*, hipStream_t);
 
 bool decode_mfma_supported(const kvs_desc* d) {
   const int rep = d->Hq / d->Hkv;
@@ -22,10 +22,10 @@ bool decode_mfma_supported(const kvs_desc* d) {
 int decode_mfma_waves() { return KVS_MFMA_WAVES; }
 
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                        void* out, float* lse, float* ws, float* cs, int n_used, bool to_ws, hipStream_t s) {
-  if (d->bits == 2) launch_decode_mfma_b2(d, geo, q, c, out, lse, ws, cs, n_used, to_ws, s);
-  else if (d->bits == 3) launch_decode_mfma_b3(d, geo, q, c, out, lse, ws, cs, n_used, to_ws, s);
-  else launch_decode_mfma_b4(d, geo, q, c, out, lse, ws, cs, n_used, to_ws, s);
+                        void* out, float* lse, float* ws, float* cs, int n_used, const float* extra, hipStream_t s) {
+  if (d->bits == 2) launch_decode_mfma_b2(d, geo, q, c, out, lse, ws, cs, n_used, extra, s);
+  else if (d->bits == 3) launch_decode_mfma_b3(d, geo, q, c, out, lse, ws, cs, n_used, extra, s);
+  else launch_decode_mfma_b4(d, geo, q, c, out, lse, ws, cs, n_used, extra, s);
 }
 
 }  // namespace kvs

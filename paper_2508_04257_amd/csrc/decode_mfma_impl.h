@@ -176,7 +176,7 @@ struct MfmaArgs {
   float* cs;         // dense-and-sparse only: per (b, hq, token) score correction in, final score out
   int n, Hkv, cap;   // n: tokens per (b, h) the buffers are laid out for
   int n_used;        // tokens to attend to (the first n_used; a multiple of 128)
-  int to_ws;         // always leave the state in the workspace (another kernel adds more rows)
+  const float* extra;   // one more softmax state per (b, hq) to merge (a growing cache's residual rows), or null
   int parts;         // workgroups per (b, h)
   int part_tokens;   // tokens per workgroup
 };
@@ -228,7 +228,16 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
   const uint32_t* keep_rows_k = reinterpret_cast<const uint32_t*>(a.keep_k) + bh * a.cap * 64 + lane;
   const uint32_t* keep_rows_v = reinterpret_cast<const uint32_t*>(a.keep_v) + bh * a.cap * 64 + lane;
   uint32_t keep_first_k = 0, keep_first_v = 0;
-  if (a.parts == 1 && !SPARSE && !a.to_ws && wave < a.cap) {
+  // The finishing wave of head r also requests the extra state now, if there is one.
+  float2 extra_o = {0.0f, 0.0f};
+  float extra_m = -INFINITY, extra_l = 0.0f;
+  if (a.extra && a.parts == 1 && !SPARSE && wave < R) {
+    const float* x = a.extra + (static_cast<size_t>(b) * (a.Hkv * R) + h * R + wave) * kWsRow;
+    extra_o = reinterpret_cast<const float2*>(x)[lane];
+    extra_m = x[128];
+    extra_l = x[129];
+  }
+  if (a.parts == 1 && !SPARSE && wave < a.cap) {
     keep_first_k = keep_rows_k[wave * 64];
     keep_first_v = keep_rows_v[wave * 64];
   }
@@ -562,7 +571,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
   // (only when this workgroup covers the whole sequence; otherwise the combine kernel does it).
   // Lane = channels 2 lane, 2 lane + 1; the wave's score exchange area is free by now and takes
   // the unnormalised row.  The first row was requested at kernel start.
-  const bool fold_keep = a.parts == 1 && !SPARSE && !a.to_ws;
+  const bool fold_keep = a.parts == 1 && !SPARSE;
   if (fold_keep) {
     const int cnt = min(keep_cnt_b, a.cap);
     float ms[R], ls[R], o0[R], o1[R];
@@ -645,8 +654,15 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
     if (fold_keep) {
 #pragma unroll
       for (int w = kWaves; w < 2 * kWaves; ++w) M = fmaxf(M, part_m[w][r]);
+      M = fmaxf(M, extra_m);
     }
     float L = 0.0f, O0 = 0.0f, O1 = 0.0f;
+    if (fold_keep && extra_m != -INFINITY) {
+      const float f = __expf(extra_m - M);
+      L = extra_l * f;
+      O0 = extra_o.x * f;
+      O1 = extra_o.y * f;
+    }
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
       const float ms = part_m[w][r];
@@ -656,7 +672,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
       O0 += o.x * f;
       O1 += o.y * f;
     }
-    if (a.parts > 1 || SPARSE || a.to_ws) {            // another kernel finishes
+    if (a.parts > 1 || SPARSE) {                       // another kernel finishes
       float* dst = a.ws + (bq_row * a.parts + part) * kWsRow;
       reinterpret_cast<float2*>(dst)[lane] = float2{O0, O1};
       if (lane == 0) { dst[128] = M; dst[129] = L; }
@@ -680,7 +696,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
 }
 
 inline MfmaArgs make_args(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                          void* out, float* lse, float* ws, float* cs, int n_used, bool to_ws) {
+                          void* out, float* lse, float* ws, float* cs, int n_used, const float* extra) {
   MfmaArgs a;
   a.q = static_cast<const uint16_t*>(q);
   a.k_codes = c->k_codes; a.v_codes = c->v_codes; a.k_params = c->k_params; a.v_params = c->v_params;
@@ -689,7 +705,7 @@ inline MfmaArgs make_args(const kvs_desc* d, const kvs::DecodeGeometry& geo, con
   a.keep_cnt = c->keep_cnt;
   a.out = static_cast<uint16_t*>(out); a.lse = lse; a.ws = ws; a.cs = cs;
   a.n = d->n; a.Hkv = d->Hkv; a.cap = d->keep_cap;
-  a.n_used = n_used; a.to_ws = to_ws ? 1 : 0;
+  a.n_used = n_used; a.extra = extra;
   a.parts = geo.splits; a.part_tokens = geo.split_tokens;
   return a;
 }
@@ -711,8 +727,8 @@ void launch_one(const kvs_desc* d, const kvs::DecodeGeometry& geo, const MfmaArg
 // The dense-and-sparse variant exists for one query head per KV head.
 template <int BITS>
 void launch_bits(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c, void* out,
-                 float* lse, float* ws, float* cs, int n_used, bool to_ws, hipStream_t s) {
-  const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws, cs, n_used, to_ws);
+                 float* lse, float* ws, float* cs, int n_used, const float* extra, hipStream_t s) {
+  const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws, cs, n_used, extra);
   const int rep = d->Hq / d->Hkv;
   if (d->group == 128) {
     if (rep == 1) launch_one<BITS, 128, 1>(d, geo, a, s);

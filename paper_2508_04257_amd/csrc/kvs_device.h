@@ -44,7 +44,7 @@ int decode_max_splits(const kvs_desc* d);
 bool decode_mfma_supported(const kvs_desc* d);
 int decode_mfma_waves();
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                        void* out, float* lse, float* ws, float* cs, int n_used, bool to_ws, hipStream_t s);
+                        void* out, float* lse, float* ws, float* cs, int n_used, const float* extra, hipStream_t s);
 // Dense-and-sparse companions of the matrix-core kernel (decode_sparse.hip).  The workspace then
 // holds the parts (B * Hq * splits rows of 130 floats, rounded up to 64 floats) followed by one
 // float per (b, hq, token).
