@@ -1,8 +1,8 @@
-// Lean 2-bit / 4-bit quantisation kernels for the dense (no isolated outliers) case of
+// Lean quantisation kernels for the dense (no isolated outliers) case of
 // kvs_quantize_kv (paper, Appendix C equations; Algorithm 1's two quantise steps).  Same results
-// bit for bit as the general kernels of quantize.hip, which also cover 3 bit and the
-// dense-and-sparse variant; these exist because the general ones spend ~17 vector instructions
-// per element and are bound by the ALU, not by the 2-byte-per-element fp16 read.
+// bit for bit as the general kernels of quantize.hip, which also cover the dense-and-sparse
+// variant; these exist because the general ones spend ~17 vector instructions per element and
+// are bound by the ALU, not by the 2-byte-per-element fp16 read.
 //
 // What is different here:
 //   * group minima / maxima are taken on the raw fp16 pairs (v_pk_min_f16 / v_pk_max_f16): the
@@ -12,6 +12,8 @@
 //   * Values: a lane owns 8 consecutive tokens x 8 channels, which is exactly eight 4-bit words of
 //     the token-packed layout, so nothing is staged in LDS; Keys: one word per (token, lane), moved
 //     through a padded LDS tile so that the global stores are contiguous.
+//   * 3 bit: ten codes per word do not line up with eight-element lanes, so a lane first makes a
+//     24-bit piece (eight codes) and the words are cut out of the row's sixteen pieces in LDS;
 //   * rows of kept tokens go straight from registers to the fp16 side buffer.
 // Compiled with floating-point contraction off and correctly rounded division, like quantize.hip.
 #include "kvs_device.h"
@@ -94,6 +96,19 @@ __device__ inline uint32_t codes8(const uint4& raw, const float inv[8], const fl
   return out;
 }
 
+// 3 bit: a row of 128 codes is first held as sixteen 24-bit pieces (eight codes each, 3 bits per
+// code); word w of the packed layout is codes 10 w .. 10 w + 9 of that 384-bit string, five in bits
+// 0-14 and five in bits 16-30 (the last word holds eight codes).
+constexpr int kPieceStride = 17;                // 16 pieces per row + 1: keeps the LDS banks spread
+__device__ inline uint32_t compose3(const uint32_t* pieces, int w) {
+  const int o = 30 * w, p0 = o / 24, sh = o % 24;
+  unsigned long long x = pieces[p0];
+  if (p0 + 1 < 16) x |= static_cast<unsigned long long>(pieces[p0 + 1]) << 24;
+  if (p0 + 2 < 16) x |= static_cast<unsigned long long>(pieces[p0 + 2]) << 48;
+  x >>= sh;
+  return static_cast<uint32_t>(x & 0x7FFFu) | (static_cast<uint32_t>((x >> 15) & 0x7FFFu) << 16);
+}
+
 // Slot of token t in the ascending keep list of its sequence, or -1.
 __device__ inline int keep_slot(const int32_t* __restrict__ keep_idx, int cnt, int t) {
   for (int j = 0; j < cnt; ++j)
@@ -115,13 +130,14 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
   constexpr int RPG = G / 16;                   // rows of one lane that fall into one group
   constexpr int W = Fmt<BITS>::W;
   constexpr int TILE_STRIDE = 68;               // padded token stride of the staged word tile
-  constexpr int LANES_PER_WORD = Fmt<BITS>::cpw / 8;   // 1 (4 bit) or 2 (2 bit)
+  constexpr int LANES_PER_WORD = BITS == 2 ? 2 : 1;    // 2 bit: two lanes share a word
+  constexpr int kStage = BITS == 3 ? TB * kPieceStride : (TB / KVS_K_TILE) * W * TILE_STRIDE;
 
   __shared__ uint32_t red_mn[NG][16][64];       // [group][row slot][channel pair] packed fp16 minima
   __shared__ uint32_t red_mx[NG][16][64];
   __shared__ float inv_s[NG][128];
   __shared__ float zero_s[NG][128];
-  __shared__ __align__(16) uint32_t tile_s[(TB / KVS_K_TILE) * W * TILE_STRIDE];
+  __shared__ __align__(16) uint32_t tile_s[kStage];     // words as [tile][w][token]; 3 bit: pieces [token][16]
 
   const int tid = threadIdx.x;
   const int chunk = tid & 15;
@@ -197,7 +213,9 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
         const uint32_t other = static_cast<uint32_t>(__shfl_xor(static_cast<int>(word), 1, KVS_WAVE));
         word = word | (other << 16);
       }
-      if (LANES_PER_WORD == 1 || (chunk & 1) == 0)
+      if (BITS == 3)
+        tile_s[r * kPieceStride + chunk] = word;
+      else if (LANES_PER_WORD == 1 || (chunk & 1) == 0)
         tile_s[((r / KVS_K_TILE) * W + chunk / LANES_PER_WORD) * TILE_STRIDE + (r % KVS_K_TILE)] = word;
       if (kept[i]) {                              // exact copy of the row into the fp16 side buffer
         const int j = keep_slot(keep_idx + static_cast<size_t>(b) * cap, cnt, tc0 + r);
@@ -212,7 +230,14 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
   constexpr int quads = (TB / KVS_K_TILE) * W * (KVS_K_TILE / 4);
   for (int qi = tid; qi < quads; qi += kThreads) {
     const int row = qi / (KVS_K_TILE / 4), t4 = qi % (KVS_K_TILE / 4);
-    store_stream(out + qi, *reinterpret_cast<const uint4*>(&tile_s[row * TILE_STRIDE + 4 * t4]));
+    if (BITS == 3) {
+      const int tile = row / W, w = row % W;
+      const uint32_t* p = &tile_s[(tile * KVS_K_TILE + 4 * t4) * kPieceStride];
+      store_stream(out + qi, uint4{compose3(p, w), compose3(p + kPieceStride, w), compose3(p + 2 * kPieceStride, w),
+                                   compose3(p + 3 * kPieceStride, w)});
+    } else {
+      store_stream(out + qi, *reinterpret_cast<const uint4*>(&tile_s[row * TILE_STRIDE + 4 * t4]));
+    }
   }
 }
 
@@ -311,6 +336,20 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
       const int j = keep_slot(keep_idx + static_cast<size_t>(b) * cap, cnt, t0 + 8 * rs + i);
       if (j >= 0) keep_v[(bh * cap + j) * 16 + chunk] = raw[i];
     }
+  }
+  if (BITS == 3) {                              // pieces [channel][token octet] -> 13 words per channel
+    __shared__ uint32_t piece_s[128 * kPieceStride];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) piece_s[(8 * chunk + j) * kPieceStride + rs] = words[j];
+    __syncthreads();
+    uint4* out = reinterpret_cast<uint4*>(v_codes + (bh * tiles_per_head + static_cast<size_t>(tile)) * (W * 128));
+    for (int qi = tid; qi < W * 32; qi += kThreads) {      // four channels of one word row per step
+      const int u = qi / 32, c4 = qi % 32;
+      const uint32_t* p = &piece_s[4 * c4 * kPieceStride];
+      store_stream(out + qi, uint4{compose3(p, u), compose3(p + kPieceStride, u), compose3(p + 2 * kPieceStride, u),
+                                   compose3(p + 3 * kPieceStride, u)});
+    }
+    return;
   }
   if (BITS == 2) {                              // 16 tokens per word: row slots (even, odd) share it
 #pragma unroll
@@ -421,12 +460,13 @@ void launch_fast_g(const kvs_desc* d, const kvs::QuantSpan& sp, bool own_keep, c
 namespace kvs {
 
 bool quantize_fast_supported(const kvs_desc* d) {
-  return (d->bits == 2 || d->bits == 4) && d->sparse_frac == 0.0f;
+  return d->sparse_frac == 0.0f;
 }
 
 void launch_quantize_fast(const kvs_desc* d, const QuantSpan& sp, bool own_keep, const void* K, const void* V,
                           const uint8_t* mask, const kvs_cache* out, hipStream_t s) {
   if (d->bits == 2) launch_fast_g<2>(d, sp, own_keep, K, V, mask, out, s);
+  else if (d->bits == 3) launch_fast_g<3>(d, sp, own_keep, K, V, mask, out, s);
   else launch_fast_g<4>(d, sp, own_keep, K, V, mask, out, s);
 }
 
