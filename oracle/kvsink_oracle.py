@@ -41,6 +41,9 @@ Readings taken where the paper is silent (every one is restated in the design no
   R10 packed layout (a storage decision, not the paper's): see ``pack_k`` / ``pack_v``.
   R13 a growing cache quantises whole 128-token blocks; later tokens wait in fp16 (see
       ``GrowingCache``).
+  R14 static quantisation: one parameter pair per Key channel and per Value channel group of a
+      KV head, from the global min / max of a calibration that leaves kept tokens out (see
+      ``static_params``).
 
 PPL / MSE figures of the paper need model weights and datasets: parity unpinned for those
 (nothing here reproduces them).  Every function below is pinned by tests/test_oracle_*.py.
@@ -566,6 +569,79 @@ def decode_attn_growing(q: np.ndarray, gc: GrowingCache, Hq: int):
                 out64[b, h * rep + r] = o
                 lse[b, h * rep + r] = l
     return out64.astype(np.float16), lse, out64
+
+
+# ----------------------------------------------------------------------------------------
+# Static quantisation (Appendix C, "Dynamic and static quantization": the range is estimated
+# from calibration data before inference and the parameters stay fixed; Section 4.1 / Table 1:
+# global min-max, and Algorithm 1's note that sink tokens are excluded from the calibration
+# too).  Reading R14: one parameter pair per Key channel of a KV head (per-channel scheme: the
+# token groups of the dynamic scheme collapse into one) and one per Value channel group of a
+# KV head (per-token scheme with fixed parameters), from the global min / max over every
+# non-kept token the calibration has seen; values outside the calibrated range clamp to code
+# 0 or qmax (the clamp of the Q(X) equation).
+# ----------------------------------------------------------------------------------------
+@dataclass
+class Calibration:
+    k_min: np.ndarray   # float32 [Hkv, D], +inf where nothing was seen
+    k_max: np.ndarray
+    v_min: np.ndarray   # float32 [Hkv, D] (per channel; reduced to channel groups by static_params)
+    v_max: np.ndarray
+
+
+def new_calibration(Hkv: int, D: int = HEAD_DIM) -> Calibration:
+    inf = np.full((Hkv, D), np.inf, np.float32)
+    return Calibration(inf.copy(), -inf, inf.copy(), -inf.copy())
+
+
+def calibrate(cal: Calibration, K: np.ndarray, V: np.ndarray, keep_mask: np.ndarray) -> Calibration:
+    """Running global min / max per (KV head, channel) over the tokens outside the keep set."""
+    K, V = np.asarray(K), np.asarray(V)
+    B, H, n, D = K.shape
+    kept = (np.asarray(keep_mask) != 0)[:, None, :, None]
+    Kf, Vf = K.astype(np.float32), V.astype(np.float32)
+    hi, lo = np.float32(np.inf), np.float32(-np.inf)
+    return Calibration(
+        np.minimum(cal.k_min, np.where(kept, hi, Kf).min(axis=(0, 2))),
+        np.maximum(cal.k_max, np.where(kept, lo, Kf).max(axis=(0, 2))),
+        np.minimum(cal.v_min, np.where(kept, hi, Vf).min(axis=(0, 2))),
+        np.maximum(cal.v_max, np.where(kept, lo, Vf).max(axis=(0, 2))))
+
+
+def static_params(cal: Calibration, bits: int, group: int):
+    """Parameter words: Keys uint32 [Hkv, D] (one per channel), Values uint32 [Hkv, D/G] (one per
+    channel group), by the same scale / zero equations as the dynamic scheme."""
+    H, D = cal.k_min.shape
+    seen_k = (cal.k_min <= cal.k_max).astype(np.int64)
+    sk, zk = group_params(cal.k_min, cal.k_max, seen_k, bits)
+    vmn = cal.v_min.reshape(H, D // group, group).min(axis=2)
+    vmx = cal.v_max.reshape(H, D // group, group).max(axis=2)
+    sv, zv = group_params(vmn, vmx, (vmn <= vmx).astype(np.int64), bits)
+    return encode_params(sk, zk), encode_params(sv, zv)
+
+
+def quantize_kv_static(K: np.ndarray, V: np.ndarray, keep_mask: np.ndarray, bits: int, group: int,
+                       keep_cap: int, k_static: np.ndarray, v_static: np.ndarray) -> Cache:
+    """As quantize_kv, with the given fixed parameters instead of per-group statistics.  The cache
+    has the same layout: every group's parameter word is its channel's (channel group's) static
+    word, so the decode step reads it like any other cache."""
+    dyn = quantize_kv(K, V, keep_mask, bits, group, keep_cap)      # layout, keep rows, mask
+    B, H, n, D = K.shape
+    kept = (np.asarray(keep_mask) != 0)
+    sk, zk = decode_params(k_static)                               # [H, D]
+    sv, zv = decode_params(v_static)                               # [H, D/G]
+    for b in range(B):
+        row_mask = np.broadcast_to(kept[b][:, None], (n, D))
+        for h in range(H):
+            ck = quantize_entries(K[b, h].astype(np.float32), sk[h][None, :], zk[h][None, :], bits, row_mask)
+            xv = V[b, h].astype(np.float32).reshape(n, D // group, group)
+            cv = quantize_entries(xv, sv[h][None, :, None], zv[h][None, :, None], bits,
+                                  row_mask.reshape(n, D // group, group)).reshape(n, D)
+            dyn.k_codes_logical[b, h], dyn.v_codes_logical[b, h] = ck, cv
+            dyn.k_codes[b, h], dyn.v_codes[b, h] = pack_k(ck, bits), pack_v(cv, bits)
+            dyn.k_params[b, h] = np.broadcast_to(np.asarray(k_static, np.uint32)[h][None, :], (n // group, D))
+            dyn.v_params[b, h] = np.broadcast_to(np.asarray(v_static, np.uint32)[h][None, :], (n, D // group))
+    return dyn
 
 
 # ----------------------------------------------------------------------------------------
