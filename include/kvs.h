@@ -208,6 +208,35 @@ kvs_status kvs_append_kv(const kvs_desc* desc, const void* k_new, const void* v_
 kvs_status kvs_decode_attn_n(const kvs_desc* desc, const void* q, const kvs_cache* cache, int32_t n_tokens,
                              void* out, float* lse, void* workspace, void* stream);
 
+/*
+ * Static quantisation (Appendix C, "Dynamic and static quantization": the range is estimated from
+ * calibration data before inference and the parameters stay fixed; Table 1's setting: global
+ * min-max, kept tokens left out of the calibration as well as of the quantisation).
+ * One parameter pair per Key channel of a KV head and one per Value channel group of a KV head.
+ *   calib     kvs_calibration_bytes(desc) bytes of device memory: running minimum and maximum per
+ *             (KV head, channel) of K and of V over every non-kept token of every kvs_calibrate
+ *             call since kvs_calibrate_reset.  Calls on one stream accumulate in order; calls on
+ *             several streams may run concurrently (integer atomics).
+ *   kvs_calibrate: K, V fp16 [B, Hkv, n, 128], keep_mask uint8 [B, n] as in kvs_quantize_kv.
+ *   kvs_static_params: k_static uint32 [Hkv, 128], v_static uint32 [Hkv, 128 / G] parameter words
+ *             (fp16 scale | int16 zero << 16) by the scale / zero equations of kvs_quantize_kv
+ *             applied to the calibrated range (nothing seen: scale 1, zero 0).
+ *   kvs_quantize_kv_static: kvs_quantize_kv with those words instead of per-group statistics;
+ *             values outside the calibrated range clamp to code 0 or 2^bits - 1.  The cache has
+ *             the ordinary layout (every group's parameter word is the static word), so
+ *             kvs_decode_attn reads it like any other.  Not with sparse_frac > 0.
+ */
+size_t kvs_calibration_bytes(const kvs_desc* desc);
+kvs_status kvs_calibrate_reset(const kvs_desc* desc, void* calib, void* stream);
+kvs_status kvs_calibrate(const kvs_desc* desc, const void* K, const void* V, const uint8_t* keep_mask,
+                         void* calib, void* stream);
+kvs_status kvs_static_params(const kvs_desc* desc, const void* calib, uint32_t* k_static,
+                             uint32_t* v_static, void* stream);
+kvs_status kvs_quantize_kv_static(const kvs_desc* desc, const void* K, const void* V,
+                                  const uint8_t* keep_mask, const uint32_t* k_static,
+                                  const uint32_t* v_static, const kvs_cache* out, void* workspace,
+                                  void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -81,6 +81,17 @@ def lib() -> C.CDLL:
         L.kvs_decode_attn_n.restype = C.c_int
         L.kvs_decode_attn_n.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.POINTER(KvsCache), C.c_int32, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_void_p]
+        L.kvs_calibration_bytes.restype = C.c_size_t
+        L.kvs_calibration_bytes.argtypes = [C.POINTER(KvsDesc)]
+        L.kvs_calibrate_reset.restype = C.c_int
+        L.kvs_calibrate_reset.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p]
+        L.kvs_calibrate.restype = C.c_int
+        L.kvs_calibrate.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.kvs_static_params.restype = C.c_int
+        L.kvs_static_params.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.kvs_quantize_kv_static.restype = C.c_int
+        L.kvs_quantize_kv_static.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.POINTER(KvsCache), C.c_void_p, C.c_void_p]
         L.kvs_decode_attn.restype = C.c_int
         L.kvs_decode_attn.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.POINTER(KvsCache), C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p]
@@ -261,3 +272,56 @@ def kvs_decode_attn_n(desc: KvsDesc, q: torch.Tensor, cache: CacheBuffers, n_tok
                                  _ptr(lse), workspace.data_ptr(), _stream_handle())
     if st != KVS_OK:
         raise KvsError("kvs_decode_attn_n", st)
+
+
+# ---- static quantisation -------------------------------------------------------------------------
+def kvs_calibration_bytes(desc: KvsDesc) -> int:
+    return int(lib().kvs_calibration_bytes(C.byref(desc)))
+
+
+def alloc_calibration(desc: KvsDesc, device="cuda") -> torch.Tensor:
+    calib = torch.empty(kvs_calibration_bytes(desc) // 4, dtype=torch.int32, device=device)
+    st = lib().kvs_calibrate_reset(C.byref(desc), calib.data_ptr(), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_calibrate_reset", st)
+    return calib
+
+
+def kvs_calibrate(desc: KvsDesc, K: torch.Tensor, V: torch.Tensor, keep_mask: torch.Tensor, calib: torch.Tensor) -> None:
+    shape = (desc.B, desc.Hkv, desc.n, desc.D)
+    _check_tensor("K", K, shape, torch.float16)
+    _check_tensor("V", V, shape, torch.float16)
+    _check_tensor("keep_mask", keep_mask, (desc.B, desc.n), torch.uint8)
+    _check_tensor("calib", calib, (kvs_calibration_bytes(desc) // 4,), torch.int32)
+    st = lib().kvs_calibrate(C.byref(desc), K.data_ptr(), V.data_ptr(), keep_mask.data_ptr(), calib.data_ptr(),
+                             _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_calibrate", st)
+
+
+def kvs_static_params(desc: KvsDesc, calib: torch.Tensor):
+    """-> (k_static int32 [Hkv, 128], v_static int32 [Hkv, 128 / G]) parameter words on the device."""
+    _check_tensor("calib", calib, (kvs_calibration_bytes(desc) // 4,), torch.int32)
+    ks = torch.empty((desc.Hkv, desc.D), dtype=torch.int32, device=calib.device)
+    vs = torch.empty((desc.Hkv, desc.D // desc.group), dtype=torch.int32, device=calib.device)
+    st = lib().kvs_static_params(C.byref(desc), calib.data_ptr(), ks.data_ptr(), vs.data_ptr(), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_static_params", st)
+    return ks, vs
+
+
+def kvs_quantize_kv_static(desc: KvsDesc, K: torch.Tensor, V: torch.Tensor, keep_mask: torch.Tensor,
+                           k_static: torch.Tensor, v_static: torch.Tensor, cache: CacheBuffers,
+                           workspace: Optional[torch.Tensor]) -> None:
+    shape = (desc.B, desc.Hkv, desc.n, desc.D)
+    _check_tensor("K", K, shape, torch.float16)
+    _check_tensor("V", V, shape, torch.float16)
+    _check_tensor("keep_mask", keep_mask, (desc.B, desc.n), torch.uint8)
+    _check_tensor("k_static", k_static, (desc.Hkv, desc.D), torch.int32)
+    _check_tensor("v_static", v_static, (desc.Hkv, desc.D // desc.group), torch.int32)
+    _check_cache(desc, cache)
+    st = lib().kvs_quantize_kv_static(C.byref(desc), K.data_ptr(), V.data_ptr(), keep_mask.data_ptr(),
+                                      k_static.data_ptr(), v_static.data_ptr(), C.byref(cache.struct),
+                                      _ptr(workspace), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_quantize_kv_static", st)

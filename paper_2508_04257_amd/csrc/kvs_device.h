@@ -74,7 +74,12 @@ inline QuantSpan whole_span(const kvs_desc* d) { return QuantSpan{d->n, d->n, d-
 // index and copy the kept rows (a plain call); otherwise the caller does both.
 bool quantize_fast_supported(const kvs_desc* d);
 void launch_quantize_fast(const kvs_desc* d, const QuantSpan& sp, bool own_keep, const void* K, const void* V,
-                          const uint8_t* mask, const kvs_cache* out, hipStream_t s);
+                          const uint8_t* mask, const kvs_cache* out, const uint32_t* static_k, const uint32_t* static_v,
+                          hipStream_t s);
+// Static quantisation: calibration state [4][Hkv][128] uint32 (order-preserving float encoding).
+void launch_calibrate_reset(const kvs_desc* d, uint32_t* calib, hipStream_t s);
+void launch_calibrate(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask, uint32_t* calib, hipStream_t s);
+void launch_static_params(const kvs_desc* d, const uint32_t* calib, uint32_t* static_k, uint32_t* static_v, hipStream_t s);
 
 // Dense-and-sparse helpers (sparse.hip): where the scratch lives and the launch sequences.
 // Where a quantise kernel leaves the isolated entries of one tensor: every workgroup claims one

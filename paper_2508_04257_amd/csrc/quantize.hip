@@ -507,10 +507,11 @@ void launch_dense_g(const kvs_desc* d, const void* K, const void* V, const uint8
 // kept rows that lie in the span.
 static void quantize_span(const kvs_desc* desc, const kvs::QuantSpan& sp, bool whole, const void* K, const void* V,
                           const uint8_t* mask, const uint8_t* index_mask, int n_index, const kvs_cache* out,
-                          void* workspace, hipStream_t s) {
+                          void* workspace, hipStream_t s, const uint32_t* static_k = nullptr,
+                          const uint32_t* static_v = nullptr) {
   const bool sparse = desc->sparse_frac > 0.0f;
   if (kvs::quantize_fast_supported(desc)) {            // 2 / 4 bit without isolated outliers
-    kvs::launch_quantize_fast(desc, sp, whole, K, V, mask, out, s);
+    kvs::launch_quantize_fast(desc, sp, whole, K, V, mask, out, static_k, static_v, s);
     if (whole) return;
   } else {
     kvs::SparsePlan plan{};
@@ -633,5 +634,55 @@ extern "C" kvs_status kvs_append_kv(const kvs_desc* desc, const void* k_new, con
     quantize_span(desc, sp, false, cache->res_k, cache->res_v, cache->keep_mask, cache->keep_mask,
                   nq + KVS_V_TILE, cache, workspace, s);
   }
+  return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Static quantisation (paper, Appendix C "Dynamic and static quantization"): calibrate, derive
+// fixed parameters, quantise with them.
+// ---------------------------------------------------------------------------------------------
+extern "C" size_t kvs_calibration_bytes(const kvs_desc* desc) {
+  if (kvs::validate_desc(desc) != KVS_OK) return 0;
+  return static_cast<size_t>(4) * desc->Hkv * KVS_HEAD_DIM * sizeof(uint32_t);
+}
+
+extern "C" kvs_status kvs_calibrate_reset(const kvs_desc* desc, void* calib, void* stream) {
+  const kvs_status st = kvs::validate_desc(desc);
+  if (st != KVS_OK) return st;
+  if (!calib) return KVS_ERR_INVALID;
+  kvs::launch_calibrate_reset(desc, static_cast<uint32_t*>(calib), static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
+}
+
+extern "C" kvs_status kvs_calibrate(const kvs_desc* desc, const void* K, const void* V, const uint8_t* keep_mask,
+                                     void* calib, void* stream) {
+  const kvs_status st = kvs::validate_desc(desc);
+  if (st != KVS_OK) return st;
+  if (!K || !V || !keep_mask || !calib) return KVS_ERR_INVALID;
+  kvs::launch_calibrate(desc, K, V, keep_mask, static_cast<uint32_t*>(calib), static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
+}
+
+extern "C" kvs_status kvs_static_params(const kvs_desc* desc, const void* calib, uint32_t* k_static,
+                                         uint32_t* v_static, void* stream) {
+  const kvs_status st = kvs::validate_desc(desc);
+  if (st != KVS_OK) return st;
+  if (!calib || !k_static || !v_static) return KVS_ERR_INVALID;
+  kvs::launch_static_params(desc, static_cast<const uint32_t*>(calib), k_static, v_static,
+                            static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
+}
+
+extern "C" kvs_status kvs_quantize_kv_static(const kvs_desc* desc, const void* K, const void* V,
+                                              const uint8_t* keep_mask, const uint32_t* k_static,
+                                              const uint32_t* v_static, const kvs_cache* out, void* workspace,
+                                              void* stream) {
+  const kvs_status st = check_quantize_args(desc, out);
+  if (st != KVS_OK) return st;
+  if (desc->sparse_frac > 0.0f) return KVS_ERR_UNSUPPORTED;
+  if (!K || !V || !keep_mask || !k_static || !v_static) return KVS_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  quantize_span(desc, kvs::whole_span(desc), true, K, V, keep_mask, keep_mask, desc->n, out, workspace, s,
+                k_static, v_static);
   return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
 }

@@ -75,6 +75,15 @@ __device__ inline Param make_param(float mn, float mx, bool any) {
   return p;
 }
 
+// The same from a stored parameter word (static quantisation: the parameters are given).
+__device__ inline Param param_of_word(uint32_t word) {
+  Param p;
+  p.inv = 1.0f / kvs::half_bits_to_float(static_cast<uint16_t>(word & 0xFFFFu));
+  p.zero = static_cast<float>(static_cast<int>(static_cast<int16_t>(word >> 16)));
+  p.word = word;
+  return p;
+}
+
 // clamp(rne(x / scale) + zero, 0, qmax) as an unsigned integer; every intermediate is an exact
 // integer in fp32, so clamping before the conversion gives the same code as clamping after it.
 template <int BITS>
@@ -123,7 +132,8 @@ template <int BITS, int G>
 __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
     const uint4* __restrict__ K, const uint8_t* __restrict__ keep_mask, kvs::QuantSpan sp, int Hkv,
     uint32_t* __restrict__ k_codes, uint32_t* __restrict__ k_params, const int32_t* __restrict__ keep_idx,
-    const int32_t* __restrict__ keep_cnt, int cap, uint4* __restrict__ keep_k) {
+    const int32_t* __restrict__ keep_cnt, int cap, uint4* __restrict__ keep_k,
+    const uint32_t* __restrict__ static_k) {          // [Hkv, 128] fixed parameter words, or null
   constexpr int TB = G > 64 ? G : 64;
   constexpr int NG = TB / G;
   constexpr int ROWS = TB / 16;
@@ -190,8 +200,15 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
 #pragma unroll
     for (int s = 0; s < 16; ++s) { a = pk_min(a, red_mn[g][s][cp]); z = pk_max(z, red_mx[g][s][cp]); }
     const bool any = any_g[g];
-    const Param p0 = make_param<BITS>(lo_half(a), lo_half(z), any);
-    const Param p1 = make_param<BITS>(hi_half(a), hi_half(z), any);
+    Param p0, p1;
+    if (static_k) {
+      const uint2 w = reinterpret_cast<const uint2*>(static_k + (bh % Hkv) * 128)[cp];
+      p0 = param_of_word(w.x);
+      p1 = param_of_word(w.y);
+    } else {
+      p0 = make_param<BITS>(lo_half(a), lo_half(z), any);
+      p1 = make_param<BITS>(hi_half(a), hi_half(z), any);
+    }
     inv_s[g][2 * cp] = p0.inv;  inv_s[g][2 * cp + 1] = p1.inv;
     zero_s[g][2 * cp] = p0.zero;  zero_s[g][2 * cp + 1] = p1.zero;
     reinterpret_cast<uint2*>(k_params + (bh * (n / G) + static_cast<size_t>(tc0 / G + g)) * 128)[cp] = uint2{p0.word, p1.word};
@@ -249,7 +266,8 @@ template <int BITS, int G>
 __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
     const uint4* __restrict__ V, const uint8_t* __restrict__ keep_mask, kvs::QuantSpan sp, int Hkv,
     uint32_t* __restrict__ v_codes, uint32_t* __restrict__ v_params, const int32_t* __restrict__ keep_idx,
-    const int32_t* __restrict__ keep_cnt, int cap, uint4* __restrict__ keep_v) {
+    const int32_t* __restrict__ keep_cnt, int cap, uint4* __restrict__ keep_v,
+    const uint32_t* __restrict__ static_v) {          // [Hkv, 128 / G] fixed parameter words, or null
   constexpr int W = Fmt<BITS>::W;
   constexpr int LPG = G / 8;                    // lanes per channel group: 4, 8, 16
   constexpr int NGC = 128 / G;
@@ -308,7 +326,8 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
 #pragma unroll
     for (int i = 1; i < 8; ++i) s = row == i ? stat[i] : s;
     const bool kept = row < 8 && ((row < 4 ? mask8.x >> (8 * row) : mask8.y >> (8 * (row - 4))) & 0xFFu) != 0;
-    const Param prm = make_param<BITS>(lo_half(s), -hi_half(s), !kept);
+    const Param prm = static_v ? param_of_word(static_v[(bh % Hkv) * NGC + chunk / LPG])
+                               : make_param<BITS>(lo_half(s), -hi_half(s), !kept);
     inv_mine[k] = prm.inv;
     zero_mine[k] = prm.zero;
     if (row < 8) v_params[(bh * n + static_cast<size_t>(t0 + 8 * rs + row)) * NGC + chunk / LPG] = prm.word;
@@ -426,9 +445,92 @@ __global__ __launch_bounds__(KVS_WAVE) void keep_index_fast_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Static quantisation (paper, Appendix C "Dynamic and static quantization"; Table 1's setting:
+// global min-max, kept tokens left out of the calibration).  The calibration state is four
+// arrays [Hkv, 128] - Key minimum, Key maximum, Value minimum, Value maximum per channel - of
+// floats in an order-preserving unsigned encoding, so that they can be lowered / raised with
+// integer atomics by any number of calls.
+// ---------------------------------------------------------------------------------------------
+constexpr int kCalibTokens = 1024;              // tokens of one (b, h) per workgroup
+__device__ inline uint32_t order_key(float f) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ inline float order_value(uint32_t k) {
+  return __builtin_bit_cast(float, (k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
+__global__ void calibrate_reset_kernel(uint32_t* __restrict__ calib, int Hkv) {
+  const int i = blockIdx.x * 128 + threadIdx.x;
+  const int plane = Hkv * 128;
+  calib[i] = order_key(INFINITY);                // Key minimum
+  calib[plane + i] = order_key(-INFINITY);       // Key maximum
+  calib[2 * plane + i] = order_key(INFINITY);    // Value minimum
+  calib[3 * plane + i] = order_key(-INFINITY);   // Value maximum
+}
+
+// blockIdx.y: 0 = Keys, 1 = Values.  Lane = 8 channels of every 16th row of the segment.
+__global__ __launch_bounds__(kThreads) void calibrate_kernel(
+    const uint4* __restrict__ K, const uint4* __restrict__ V, const uint8_t* __restrict__ keep_mask, int n, int Hkv,
+    uint32_t* __restrict__ calib) {
+  __shared__ uint32_t red_mn[16][64], red_mx[16][64];
+  const int tid = threadIdx.x, chunk = tid & 15, rslot = tid >> 4;
+  const int segs = (n + kCalibTokens - 1) / kCalibTokens;
+  const int seg = blockIdx.x % segs;
+  const size_t bh = blockIdx.x / segs;
+  const int b = static_cast<int>(bh / Hkv), h = static_cast<int>(bh % Hkv);
+  const uint4* X = (blockIdx.y == 0 ? K : V) + bh * n * 16;
+  const uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * n;
+  const int t_end = min(n, (seg + 1) * kCalibTokens);
+  uint32_t mn[4] = {kPosMax2, kPosMax2, kPosMax2, kPosMax2};
+  uint32_t mx[4] = {kNegMax2, kNegMax2, kNegMax2, kNegMax2};
+  bool any = false;
+  for (int t = seg * kCalibTokens + rslot; t < t_end; t += 16) {
+    if (mask_b[t]) continue;
+    const uint4 raw = load_stream(X + static_cast<size_t>(t) * 16 + chunk);
+    mn[0] = pk_min(mn[0], raw.x); mn[1] = pk_min(mn[1], raw.y); mn[2] = pk_min(mn[2], raw.z); mn[3] = pk_min(mn[3], raw.w);
+    mx[0] = pk_max(mx[0], raw.x); mx[1] = pk_max(mx[1], raw.y); mx[2] = pk_max(mx[2], raw.z); mx[3] = pk_max(mx[3], raw.w);
+    any = true;
+  }
+  *reinterpret_cast<uint4*>(&red_mn[rslot][4 * chunk]) = uint4{mn[0], mn[1], mn[2], mn[3]};
+  *reinterpret_cast<uint4*>(&red_mx[rslot][4 * chunk]) = uint4{mx[0], mx[1], mx[2], mx[3]};
+  const bool any_wg = __syncthreads_or(any ? 1 : 0) != 0;
+  if (any_wg && tid < 64) {                       // channel pair tid
+    uint32_t a = kPosMax2, z = kNegMax2;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) { a = pk_min(a, red_mn[s][tid]); z = pk_max(z, red_mx[s][tid]); }
+    const int plane = Hkv * 128;
+    uint32_t* base = calib + (blockIdx.y == 0 ? 0 : 2 * plane) + h * 128 + 2 * tid;
+    atomicMin(base, order_key(lo_half(a)));
+    atomicMin(base + 1, order_key(hi_half(a)));
+    atomicMax(base + plane, order_key(lo_half(z)));
+    atomicMax(base + plane + 1, order_key(hi_half(z)));
+  }
+}
+
+// One workgroup per KV head: the parameter word of every Key channel and Value channel group.
+template <int BITS>
+__global__ void static_params_kernel(const uint32_t* __restrict__ calib, int Hkv, int group,
+                                     uint32_t* __restrict__ static_k, uint32_t* __restrict__ static_v) {
+  const int h = blockIdx.x, c = threadIdx.x;
+  const int plane = Hkv * 128;
+  const float kmn = order_value(calib[h * 128 + c]), kmx = order_value(calib[plane + h * 128 + c]);
+  static_k[h * 128 + c] = make_param<BITS>(kmn, kmx, kmn <= kmx).word;
+  if (c < 128 / group) {
+    float vmn = INFINITY, vmx = -INFINITY;
+    for (int j = 0; j < group; ++j) {
+      vmn = fminf(vmn, order_value(calib[2 * plane + h * 128 + c * group + j]));
+      vmx = fmaxf(vmx, order_value(calib[3 * plane + h * 128 + c * group + j]));
+    }
+    static_v[h * (128 / group) + c] = make_param<BITS>(vmn, vmx, vmn <= vmx).word;
+  }
+}
+
 template <int BITS, int G>
 void launch_fast(const kvs_desc* d, const kvs::QuantSpan& sp, bool own_keep, const void* K, const void* V,
-                 const uint8_t* mask, const kvs_cache* out, hipStream_t s) {
+                 const uint8_t* mask, const kvs_cache* out, const uint32_t* static_k, const uint32_t* static_v,
+                 hipStream_t s) {
   constexpr int TB = G > 64 ? G : 64;
   const int bh = d->B * d->Hkv;
   const int cap = own_keep ? d->keep_cap : 0;            // 0: the kernels copy no kept rows themselves
@@ -439,19 +541,20 @@ void launch_fast(const kvs_desc* d, const kvs::QuantSpan& sp, bool own_keep, con
   if (sp.n_tokens == 0) return;
   hipLaunchKernelGGL((quantize_k_fast_kernel<BITS, G>), dim3(bh * (sp.n_tokens / TB)), dim3(kThreads), 0, s,
                      static_cast<const uint4*>(K), mask, sp, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
-                     out->keep_cnt, cap, static_cast<uint4*>(out->keep_k));
+                     out->keep_cnt, cap, static_cast<uint4*>(out->keep_k), static_k);
   hipLaunchKernelGGL((quantize_v_fast_kernel<BITS, G>), dim3(bh * (sp.n_tokens / KVS_V_TILE)), dim3(kThreads), 0, s,
                      static_cast<const uint4*>(V), mask, sp, d->Hkv, out->v_codes, out->v_params, out->keep_idx,
-                     out->keep_cnt, cap, static_cast<uint4*>(out->keep_v));
+                     out->keep_cnt, cap, static_cast<uint4*>(out->keep_v), static_v);
 }
 
 template <int BITS>
 void launch_fast_g(const kvs_desc* d, const kvs::QuantSpan& sp, bool own_keep, const void* K, const void* V,
-                   const uint8_t* mask, const kvs_cache* out, hipStream_t s) {
+                   const uint8_t* mask, const kvs_cache* out, const uint32_t* static_k, const uint32_t* static_v,
+                   hipStream_t s) {
   switch (d->group) {
-    case 32: launch_fast<BITS, 32>(d, sp, own_keep, K, V, mask, out, s); break;
-    case 64: launch_fast<BITS, 64>(d, sp, own_keep, K, V, mask, out, s); break;
-    default: launch_fast<BITS, 128>(d, sp, own_keep, K, V, mask, out, s); break;
+    case 32: launch_fast<BITS, 32>(d, sp, own_keep, K, V, mask, out, static_k, static_v, s); break;
+    case 64: launch_fast<BITS, 64>(d, sp, own_keep, K, V, mask, out, static_k, static_v, s); break;
+    default: launch_fast<BITS, 128>(d, sp, own_keep, K, V, mask, out, static_k, static_v, s); break;
   }
 }
 
@@ -464,10 +567,27 @@ bool quantize_fast_supported(const kvs_desc* d) {
 }
 
 void launch_quantize_fast(const kvs_desc* d, const QuantSpan& sp, bool own_keep, const void* K, const void* V,
-                          const uint8_t* mask, const kvs_cache* out, hipStream_t s) {
-  if (d->bits == 2) launch_fast_g<2>(d, sp, own_keep, K, V, mask, out, s);
-  else if (d->bits == 3) launch_fast_g<3>(d, sp, own_keep, K, V, mask, out, s);
-  else launch_fast_g<4>(d, sp, own_keep, K, V, mask, out, s);
+                          const uint8_t* mask, const kvs_cache* out, const uint32_t* static_k, const uint32_t* static_v,
+                          hipStream_t s) {
+  if (d->bits == 2) launch_fast_g<2>(d, sp, own_keep, K, V, mask, out, static_k, static_v, s);
+  else if (d->bits == 3) launch_fast_g<3>(d, sp, own_keep, K, V, mask, out, static_k, static_v, s);
+  else launch_fast_g<4>(d, sp, own_keep, K, V, mask, out, static_k, static_v, s);
+}
+
+void launch_calibrate_reset(const kvs_desc* d, uint32_t* calib, hipStream_t s) {
+  hipLaunchKernelGGL(calibrate_reset_kernel, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv);
+}
+void launch_calibrate(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask, uint32_t* calib,
+                      hipStream_t s) {
+  const int segs = (d->n + kCalibTokens - 1) / kCalibTokens;
+  hipLaunchKernelGGL(calibrate_kernel, dim3(d->B * d->Hkv * segs, 2), dim3(kThreads), 0, s,
+                     static_cast<const uint4*>(K), static_cast<const uint4*>(V), mask, d->n, d->Hkv, calib);
+}
+void launch_static_params(const kvs_desc* d, const uint32_t* calib, uint32_t* static_k, uint32_t* static_v,
+                          hipStream_t s) {
+  if (d->bits == 2) hipLaunchKernelGGL(static_params_kernel<2>, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv, d->group, static_k, static_v);
+  else if (d->bits == 3) hipLaunchKernelGGL(static_params_kernel<3>, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv, d->group, static_k, static_v);
+  else hipLaunchKernelGGL(static_params_kernel<4>, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv, d->group, static_k, static_v);
 }
 
 }  // namespace kvs

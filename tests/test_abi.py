@@ -20,7 +20,9 @@ def _declared_symbols():
 def test_library_exports_every_declared_symbol():
     names = _declared_symbols()
     assert {"kvs_predict_sinks", "kvs_quantize_kv", "kvs_decode_attn", "kvs_cache_bytes",
-            "kvs_workspace_bytes", "kvs_quantize_prefix", "kvs_append_kv", "kvs_decode_attn_n"} <= set(names)
+            "kvs_workspace_bytes", "kvs_quantize_prefix", "kvs_append_kv", "kvs_decode_attn_n",
+            "kvs_calibrate", "kvs_calibrate_reset", "kvs_static_params", "kvs_quantize_kv_static",
+            "kvs_calibration_bytes"} <= set(names)
     L = kb.lib()
     for name in names:
         assert hasattr(L, name), name
@@ -107,3 +109,18 @@ def test_growing_cache_calls_check_their_arguments_on_the_host():
     assert L.kvs_decode_attn_n(C.byref(ds), 16, C.byref(full), 300, 16, None, 16, None) == kb.KVS_ERR_UNSUPPORTED
     s = kb.kvs_cache_bytes(d)
     assert s["res_k"] == s["res_v"] == 2 * 32 * 128 * 128 * 2
+
+
+def test_static_quantisation_calls_check_their_arguments_on_the_host():
+    d = kb.make_desc(B=2, n=1024, Hq=32, Hkv=8, bits=4, group=64, keep_cap=2)
+    L = kb.lib()
+    assert kb.kvs_calibration_bytes(d) == 4 * 8 * 128 * 4
+    assert L.kvs_calibrate_reset(C.byref(d), None, None) == kb.KVS_ERR_INVALID
+    assert L.kvs_calibrate(C.byref(d), 16, 16, 16, None, None) == kb.KVS_ERR_INVALID
+    assert L.kvs_static_params(C.byref(d), 16, None, 16, None) == kb.KVS_ERR_INVALID
+    full = kb.KvsCache(**{name: 16 for name in kb.CACHE_FIELD_NAMES})
+    assert L.kvs_quantize_kv_static(C.byref(d), 16, 16, 16, None, 16, C.byref(full), None, None) == kb.KVS_ERR_INVALID
+    ds = kb.make_desc(B=2, n=1024, Hq=32, Hkv=32, bits=3, group=128, keep_cap=2, sparse_frac=0.01, sparse_cap=1000)
+    assert L.kvs_quantize_kv_static(C.byref(ds), 16, 16, 16, 16, 16, C.byref(full), 16, None) == kb.KVS_ERR_UNSUPPORTED
+    bad = kb.make_desc(B=2, n=1000, Hq=32, Hkv=32, bits=4, group=128, keep_cap=2)
+    assert kb.kvs_calibration_bytes(bad) == 0

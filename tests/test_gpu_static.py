@@ -1,0 +1,71 @@
+"""Parity of the static-quantisation calls (kvs_calibrate, kvs_static_params, kvs_quantize_kv_static)
+with the oracle: parameter words, codes and kept rows bit-exact, attention outputs within 2e-3."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvsink_oracle as O
+from paper_2508_04257_amd import binding as kb
+from tests.helpers import random_fp16
+from tests.test_gpu_parity import DEV, OUT_TOL, assert_cache_equal, hip_decode, row_rel_err, u32
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+
+
+@pytest.mark.parametrize("bits,G,rep", [(4, 128, 1), (3, 64, 4), (2, 32, 1), (4, 32, 2), (3, 128, 8)])
+def test_calibrate_then_static_quantise(bits, G, rep):
+    rng = np.random.default_rng(bits * 100 + G)
+    B, H, n, cap = 2, 3, 1152, 4                                   # 9 tiles: a ragged calibration segment too
+    batches = []
+    for i in range(2):                                             # two calibration batches, then a third tensor
+        K, V = random_fp16(rng, (B, H, n, 128)), random_fp16(rng, (B, H, n, 128))
+        K[:, :, :, [7, 90]] *= np.float16(6)
+        mask = np.zeros((B, n), np.uint8)
+        mask[0, [0, 14]] = 1
+        mask[1, [n - 1]] = 1
+        K[0, :, 0] *= np.float16(40); V[0, :, 14] *= np.float16(40)          # wild kept rows: must not count
+        batches.append((K, V, mask))
+    desc = kb.make_desc(B, n, H * rep, H, bits, G, cap)
+    calib = kb.alloc_calibration(desc, DEV)
+    cal = O.new_calibration(H)
+    for K, V, mask in batches:
+        kb.kvs_calibrate(desc, dev(K), dev(V), dev(mask), calib)
+        cal = O.calibrate(cal, K, V, mask)
+    ks, vs = kb.kvs_static_params(desc, calib)
+    torch.cuda.synchronize()
+    ref_ks, ref_vs = O.static_params(cal, bits, G)
+    assert np.array_equal(u32(ks), ref_ks) and np.array_equal(u32(vs), ref_vs)
+
+    Kt, Vt = random_fp16(rng, (B, H, n, 128)), random_fp16(rng, (B, H, n, 128))
+    Kt[:, :, :, [7, 90]] *= np.float16(6)
+    Kt[1, 2, 100, 5] = np.float16(3000); Vt[0, 1, 200, 77] = np.float16(-3000)   # outside the calibrated range
+    mask = batches[0][2]
+    cache, ws = kb.alloc_cache(desc, DEV), kb.alloc_workspace(desc, DEV)
+    kb.kvs_quantize_kv_static(desc, dev(Kt), dev(Vt), dev(mask), ks, vs, cache, ws)
+    torch.cuda.synchronize()
+    ref = O.quantize_kv_static(Kt, Vt, mask, bits, G, cap, ref_ks, ref_vs)
+    assert_cache_equal(cache, ref)
+    q = random_fp16(rng, (B, H * rep, 128))
+    out, lse = hip_decode(desc, cache, ws, q)
+    _, ref_lse, ref64 = O.decode_attn(q, ref, Hq=H * rep)
+    assert row_rel_err(out, ref64) <= OUT_TOL
+    assert np.abs(lse - ref_lse).max() <= 2e-3 * max(1.0, np.abs(ref_lse).max())
+
+
+def test_empty_calibration_and_reset():
+    desc = kb.make_desc(1, 128, 2, 2, 4, 64, 1)
+    calib = kb.alloc_calibration(desc, DEV)
+    ks, vs = kb.kvs_static_params(desc, calib)
+    torch.cuda.synchronize()
+    ref_ks, ref_vs = O.static_params(O.new_calibration(2), 4, 64)
+    assert np.array_equal(u32(ks), ref_ks) and np.array_equal(u32(vs), ref_vs)
+    # a fully kept tensor leaves the state untouched
+    K = random_fp16(np.random.default_rng(0), (1, 2, 128, 128))
+    kb.kvs_calibrate(desc, dev(K), dev(K), dev(np.ones((1, 128), np.uint8)), calib)
+    ks2, _ = kb.kvs_static_params(desc, calib)
+    torch.cuda.synchronize()
+    assert torch.equal(ks, ks2)
