@@ -156,6 +156,40 @@ def growing_cache_leg(w, kv, q, dec_bytes):
     }
 
 
+def static_leg(w, inputs, bufs, qnt_bytes):
+    """Calibration and fixed-parameter quantisation on the same shapes (rotating inputs and caches),
+    reported beside the headline numbers."""
+    import torch
+
+    from paper_2508_04257_amd import binding as kb
+
+    desc = bufs[0].desc
+    calib = kb.alloc_calibration(desc, inputs[0][0].device)
+    slots = len(inputs)
+    for i in range(slots):
+        kb.kvs_calibrate(desc, inputs[i][0], inputs[i][1], bufs[i].keep_mask, calib)
+    ks, vs = kb.kvs_static_params(desc, calib)
+    torch.cuda.synchronize()
+    reps = 12
+    e = [HipEvent() for _ in range(3)]
+    e[0].record()
+    for i in range(reps):
+        kb.kvs_calibrate(desc, inputs[i % slots][0], inputs[i % slots][1], bufs[i % slots].keep_mask, calib)
+    e[1].record()
+    for i in range(reps):
+        kb.kvs_quantize_kv_static(desc, inputs[i % slots][0], inputs[i % slots][1], bufs[i % slots].keep_mask, ks, vs,
+                                  bufs[i % slots].cache, bufs[i % slots].workspace)
+    e[2].record()
+    torch.cuda.synchronize()
+    ms_cal, ms_q = e[0].elapsed_time(e[1]) / reps, e[1].elapsed_time(e[2]) / reps
+    read = 2 * w.B * w.Hkv * w.n * w.D * 2
+    return {
+        "ms_calibrate": round(ms_cal, 4), "calibrate_gbps": round(read / (ms_cal * 1e-3) / 1e9, 2),
+        "ms_quantize_kv_static": round(ms_q, 4), "quantize_static_gbps": round(qnt_bytes / (ms_q * 1e-3) / 1e9, 2),
+        "quantize_static_tokens_per_s": round(w.B * w.n / (ms_q * 1e-3), 1),
+    }
+
+
 def cpu_baseline(w, budget_s: float = 12.0):
     """The oracle as it stands, timed on this host on a bounded sample of the same workload:
     whole (sequence 0, head h) slices, one at a time, until the budget is used."""
@@ -379,6 +413,7 @@ def main() -> int:
     }
     if w.sparse_frac == 0:
         result["growing_cache"] = growing_cache_leg(w, inputs[0], q, dec_bytes)
+        result["static_quantisation"] = static_leg(w, inputs, bufs, qnt_bytes)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result))
