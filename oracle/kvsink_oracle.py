@@ -44,6 +44,10 @@ Readings taken where the paper is silent (every one is restated in the design no
   R14 static quantisation: one parameter pair per Key channel and per Value channel group of a
       KV head, from the global min / max of a calibration that leaves kept tokens out (see
       ``static_params``).
+  R15 per-token Keys (the other Key scheme of Section 5.1's comparison): a Key row is quantised
+      exactly like a Value row - groups of G consecutive channels of one token - and only the
+      parameter array changes shape ([B, Hkv, n, D/G]); the packed Key codes keep their layout.
+      With static parameters that is one pair per Key channel group of a KV head.
 
 PPL / MSE figures of the paper need model weights and datasets: parity unpinned for those
 (nothing here reproduces them).  Every function below is pinned by tests/test_oracle_*.py.
@@ -290,7 +294,7 @@ class Cache:
     keep_cap: int
     k_codes: np.ndarray            # uint32 [B, Hkv, n/64, W, 64]
     v_codes: np.ndarray            # uint32 [B, Hkv, n/128, W, 128]
-    k_params: np.ndarray           # uint32 [B, Hkv, n/G, D]
+    k_params: np.ndarray           # uint32 [B, Hkv, n/G, D]; per-token Keys: [B, Hkv, n, D/G]
     v_params: np.ndarray           # uint32 [B, Hkv, n, D/G]
     keep_k: np.ndarray             # fp16 [B, Hkv, cap, D]
     keep_v: np.ndarray
@@ -312,6 +316,7 @@ class Cache:
     # logical (unpacked) codes, kept for tests
     k_codes_logical: Optional[np.ndarray] = None    # uint8 [B, Hkv, n, D]
     v_codes_logical: Optional[np.ndarray] = None
+    key_per_token: bool = False    # Keys quantised per token (groups along channels), like Values
 
 
 def _csr_from_mask(X: np.ndarray, outlier: np.ndarray, by_channel: bool):
@@ -333,11 +338,12 @@ def _csr_from_mask(X: np.ndarray, outlier: np.ndarray, by_channel: bool):
 
 def quantize_kv(K: np.ndarray, V: np.ndarray, keep_mask: np.ndarray, bits: int, group: int,
                 keep_cap: int, sparse_frac: float = 0.0, sparse_cap: Optional[int] = None,
-                taus: Optional[tuple] = None) -> Cache:
+                taus: Optional[tuple] = None, key_per_token: bool = False) -> Cache:
     """Algorithm 1's two quantise steps for one layer: K and V rows of tokens outside the
     keep set are quantised, rows inside it are copied unchanged into the fp16 side buffer.
     ``taus`` = (k_tau, v_tau) supplies thresholds that ``sparse_threshold`` found on a larger
-    tensor of which K, V are a slice (the threshold is a property of the whole layer)."""
+    tensor of which K, V are a slice (the threshold is a property of the whole layer).
+    ``key_per_token`` selects the per-token Key scheme (Section 5.1; reading R15)."""
     K = np.asarray(K)
     V = np.asarray(V)
     assert K.dtype == np.float16 and V.dtype == np.float16 and K.shape == V.shape
@@ -360,14 +366,15 @@ def quantize_kv(K: np.ndarray, V: np.ndarray, keep_mask: np.ndarray, bits: int, 
 
     k_codes = np.zeros((B, H, n // K_TILE, W, K_TILE), np.uint32)
     v_codes = np.zeros((B, H, n // V_TILE, W, V_TILE), np.uint32)
-    k_params = np.zeros((B, H, n // group, D), np.uint32)
+    k_params = np.zeros((B, H, n, D // group) if key_per_token else (B, H, n // group, D), np.uint32)
     v_params = np.zeros((B, H, n, D // group), np.uint32)
     k_log = np.zeros((B, H, n, D), np.uint8)
     v_log = np.zeros((B, H, n, D), np.uint8)
     for b in range(B):
         row_mask = np.broadcast_to(kept[b][:, None], (n, D))
         for h in range(H):
-            ck, sk, zk = quantize_k_head(K[b, h], row_mask | out_k[b, h], bits, group)
+            quantize_keys = quantize_v_head if key_per_token else quantize_k_head
+            ck, sk, zk = quantize_keys(K[b, h], row_mask | out_k[b, h], bits, group)
             cv, sv, zv = quantize_v_head(V[b, h], row_mask | out_v[b, h], bits, group)
             k_log[b, h], v_log[b, h] = ck, cv
             k_codes[b, h], v_codes[b, h] = pack_k(ck, bits), pack_v(cv, bits)
@@ -389,7 +396,8 @@ def quantize_kv(K: np.ndarray, V: np.ndarray, keep_mask: np.ndarray, bits: int, 
 
     cache = Cache(B, n, H, D, bits, group, keep_cap, k_codes, v_codes, k_params, v_params,
                   keep_k, keep_v, keep_idx, keep_cnt, keep_mask, status,
-                  k_tau=tau_k, v_tau=tau_v, k_codes_logical=k_log, v_codes_logical=v_log)
+                  k_tau=tau_k, v_tau=tau_v, k_codes_logical=k_log, v_codes_logical=v_log,
+                  key_per_token=key_per_token)
     if sparse_frac > 0:
         cache.k_rowptr, cache.k_col, cache.k_val = _csr_from_mask(K, out_k, by_channel=False)
         cache.v_rowptr, cache.v_col, cache.v_val = _csr_from_mask(V, out_v, by_channel=True)
@@ -406,11 +414,14 @@ def effective_kv(cache: Cache, b: int, h: int):
     """K', V' float64 [n, D] as the decode step sees them: dequantised entries, sparse
     outliers replaced by their fp16 value, kept rows replaced by the fp16 side buffer."""
     n, D, G, bits = cache.n, cache.D, cache.group, cache.bits
-    sk, zk = decode_params(cache.k_params[b, h])                     # [n/G, D]
+    sk, zk = decode_params(cache.k_params[b, h])                     # [n/G, D] ([n, D/G] per token)
     sv, zv = decode_params(cache.v_params[b, h])                     # [n, D/G]
     ck = unpack_k(cache.k_codes[b, h], bits)                         # [n, D]
     cv = unpack_v(cache.v_codes[b, h], bits)
-    Kd = dequantize_entries(ck.reshape(n // G, G, D), sk[:, None, :], zk[:, None, :]).reshape(n, D)
+    if cache.key_per_token:
+        Kd = dequantize_entries(ck.reshape(n, D // G, G), sk[:, :, None], zk[:, :, None]).reshape(n, D)
+    else:
+        Kd = dequantize_entries(ck.reshape(n // G, G, D), sk[:, None, :], zk[:, None, :]).reshape(n, D)
     Vd = dequantize_entries(cv.reshape(n, D // G, G), sv[:, :, None], zv[:, :, None]).reshape(n, D)
     Kd = Kd.astype(np.float64)
     Vd = Vd.astype(np.float64)
@@ -487,6 +498,7 @@ class GrowingCache:
     res_k: np.ndarray              # fp16 [B, Hkv, n_tokens - n_quant, D]
     res_v: np.ndarray
     res_mask: np.ndarray           # uint8 [B, n_tokens - n_quant]: keep flags of the residual tokens
+    key_per_token: bool = False
 
     @property
     def n_quant(self) -> int:
@@ -516,19 +528,21 @@ def _concat_caches(a: Optional[Cache], b: Cache) -> Cache:
                  cat(a.k_params, b.k_params, 2), cat(a.v_params, b.v_params, 2),
                  keep_k, keep_v, keep_idx, keep_cnt, cat(a.keep_mask, b.keep_mask, 1), status,
                  k_codes_logical=cat(a.k_codes_logical, b.k_codes_logical, 2),
-                 v_codes_logical=cat(a.v_codes_logical, b.v_codes_logical, 2))
+                 v_codes_logical=cat(a.v_codes_logical, b.v_codes_logical, 2),
+                 key_per_token=a.key_per_token)
 
 
 def prefill_cache(K: np.ndarray, V: np.ndarray, keep_mask: np.ndarray, bits: int, group: int,
-                  keep_cap: int) -> GrowingCache:
+                  keep_cap: int, key_per_token: bool = False) -> GrowingCache:
     """Cache of a prompt of any length: whole 128-token blocks quantised, the rest in fp16."""
     K, V = np.asarray(K), np.asarray(V)
     B, H, n, D = K.shape
     keep_mask = (np.asarray(keep_mask) != 0).astype(np.uint8)
     nq = (n // BLOCK) * BLOCK
-    quant = quantize_kv(K[:, :, :nq], V[:, :, :nq], keep_mask[:, :nq], bits, group, keep_cap) if nq else None
+    quant = quantize_kv(K[:, :, :nq], V[:, :, :nq], keep_mask[:, :nq], bits, group, keep_cap,
+                        key_per_token=key_per_token) if nq else None
     return GrowingCache(bits, group, keep_cap, n, quant, K[:, :, nq:].copy(), V[:, :, nq:].copy(),
-                        keep_mask[:, nq:].copy())
+                        keep_mask[:, nq:].copy(), key_per_token)
 
 
 def append_token(gc: GrowingCache, k_new: np.ndarray, v_new: np.ndarray, keep_new=None) -> GrowingCache:
@@ -543,10 +557,12 @@ def append_token(gc: GrowingCache, k_new: np.ndarray, v_new: np.ndarray, keep_ne
     res_mask = np.concatenate([gc.res_mask, flag], axis=1)
     quant = gc.quant
     if res_k.shape[2] == BLOCK:
-        block = quantize_kv(res_k, res_v, res_mask, gc.bits, gc.group, gc.keep_cap)
+        block = quantize_kv(res_k, res_v, res_mask, gc.bits, gc.group, gc.keep_cap,
+                            key_per_token=gc.key_per_token)
         quant = _concat_caches(quant, block)
         res_k, res_v, res_mask = res_k[:, :, :0], res_v[:, :, :0], res_mask[:, :0]
-    return GrowingCache(gc.bits, gc.group, gc.keep_cap, gc.n_tokens + 1, quant, res_k, res_v, res_mask)
+    return GrowingCache(gc.bits, gc.group, gc.keep_cap, gc.n_tokens + 1, quant, res_k, res_v, res_mask,
+                        gc.key_per_token)
 
 
 def decode_attn_growing(q: np.ndarray, gc: GrowingCache, Hq: int):
@@ -608,12 +624,16 @@ def calibrate(cal: Calibration, K: np.ndarray, V: np.ndarray, keep_mask: np.ndar
         np.maximum(cal.v_max, np.where(kept, lo, Vf).max(axis=(0, 2))))
 
 
-def static_params(cal: Calibration, bits: int, group: int):
-    """Parameter words: Keys uint32 [Hkv, D] (one per channel), Values uint32 [Hkv, D/G] (one per
-    channel group), by the same scale / zero equations as the dynamic scheme."""
+def static_params(cal: Calibration, bits: int, group: int, key_per_token: bool = False):
+    """Parameter words: Keys uint32 [Hkv, D] (one per channel; per-token Keys: [Hkv, D/G], one per
+    channel group), Values uint32 [Hkv, D/G] (one per channel group), by the same scale / zero
+    equations as the dynamic scheme."""
     H, D = cal.k_min.shape
-    seen_k = (cal.k_min <= cal.k_max).astype(np.int64)
-    sk, zk = group_params(cal.k_min, cal.k_max, seen_k, bits)
+    kmn, kmx = cal.k_min, cal.k_max
+    if key_per_token:
+        kmn = kmn.reshape(H, D // group, group).min(axis=2)
+        kmx = kmx.reshape(H, D // group, group).max(axis=2)
+    sk, zk = group_params(kmn, kmx, (kmn <= kmx).astype(np.int64), bits)
     vmn = cal.v_min.reshape(H, D // group, group).min(axis=2)
     vmx = cal.v_max.reshape(H, D // group, group).max(axis=2)
     sv, zv = group_params(vmn, vmx, (vmn <= vmx).astype(np.int64), bits)
@@ -621,25 +641,31 @@ def static_params(cal: Calibration, bits: int, group: int):
 
 
 def quantize_kv_static(K: np.ndarray, V: np.ndarray, keep_mask: np.ndarray, bits: int, group: int,
-                       keep_cap: int, k_static: np.ndarray, v_static: np.ndarray) -> Cache:
+                       keep_cap: int, k_static: np.ndarray, v_static: np.ndarray,
+                       key_per_token: bool = False) -> Cache:
     """As quantize_kv, with the given fixed parameters instead of per-group statistics.  The cache
     has the same layout: every group's parameter word is its channel's (channel group's) static
     word, so the decode step reads it like any other cache."""
-    dyn = quantize_kv(K, V, keep_mask, bits, group, keep_cap)      # layout, keep rows, mask
+    dyn = quantize_kv(K, V, keep_mask, bits, group, keep_cap, key_per_token=key_per_token)   # layout, keep rows, mask
     B, H, n, D = K.shape
     kept = (np.asarray(keep_mask) != 0)
-    sk, zk = decode_params(k_static)                               # [H, D]
+    sk, zk = decode_params(k_static)                               # [H, D] ([H, D/G] per token)
     sv, zv = decode_params(v_static)                               # [H, D/G]
     for b in range(B):
         row_mask = np.broadcast_to(kept[b][:, None], (n, D))
         for h in range(H):
-            ck = quantize_entries(K[b, h].astype(np.float32), sk[h][None, :], zk[h][None, :], bits, row_mask)
+            if key_per_token:
+                xk = K[b, h].astype(np.float32).reshape(n, D // group, group)
+                ck = quantize_entries(xk, sk[h][None, :, None], zk[h][None, :, None], bits,
+                                      row_mask.reshape(n, D // group, group)).reshape(n, D)
+            else:
+                ck = quantize_entries(K[b, h].astype(np.float32), sk[h][None, :], zk[h][None, :], bits, row_mask)
             xv = V[b, h].astype(np.float32).reshape(n, D // group, group)
             cv = quantize_entries(xv, sv[h][None, :, None], zv[h][None, :, None], bits,
                                   row_mask.reshape(n, D // group, group)).reshape(n, D)
             dyn.k_codes_logical[b, h], dyn.v_codes_logical[b, h] = ck, cv
             dyn.k_codes[b, h], dyn.v_codes[b, h] = pack_k(ck, bits), pack_v(cv, bits)
-            dyn.k_params[b, h] = np.broadcast_to(np.asarray(k_static, np.uint32)[h][None, :], (n // group, D))
+            dyn.k_params[b, h] = np.broadcast_to(np.asarray(k_static, np.uint32)[h][None, :], dyn.k_params[b, h].shape)
             dyn.v_params[b, h] = np.broadcast_to(np.asarray(v_static, np.uint32)[h][None, :], (n, D // group))
     return dyn
 
