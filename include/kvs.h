@@ -35,7 +35,8 @@
  *   3j and slots 5-9 at bits 16 + 3(j - 5), bits 15 and 31 are zero.  Unused slots are zero.
  *   k_codes  uint32 [B, Hkv, n/64, W, 64]   word (T, w, t): channels cpw*w .. of token 64T + t.
  *   v_codes  uint32 [B, Hkv, n/128, W, 128] word (T, u, c): tokens 128T + cpw*u .. of channel c.
- *   k_params uint32 [B, Hkv, n/G, 128]      one per (token group, channel).
+ *   k_params uint32 [B, Hkv, n/G, 128]      one per (token group, channel); with per-token Keys
+ *            (desc->key_per_token) [B, Hkv, n, 128/G], one per (token, channel group), like v_params.
  *   v_params uint32 [B, Hkv, n, 128/G]      one per (token, channel group).
  *            parameter word = fp16 scale in bits 0-15 | int16 zero in bits 16-31;
  *            dequantised value = scale * (code - zero).
@@ -82,6 +83,10 @@ typedef struct kvs_desc {
   int32_t group;            /* G: 32, 64 or 128.  K groups run along tokens, V along channels */
   int32_t keep_cap;         /* rows of the fp16 side buffer per sequence (>= 0)               */
   float sparse_frac;        /* fraction of entries isolated in fp16; 0 = off                  */
+  int32_t key_per_token;    /* 0: per-channel Keys (above); 1: Keys quantised like Values, groups */
+                            /* of G channels of one token (the per-token scheme of Section 5.1) - */
+                            /* k_params is then [B, Hkv, n, 128/G].  Not with sparse_frac > 0,    */
+                            /* and not with G = 32 and Hq / Hkv > 2 (KVS_ERR_UNSUPPORTED).        */
   int64_t sparse_cap;       /* CSR capacity in entries per tensor when sparse_frac > 0        */
 } kvs_desc;
 
@@ -218,7 +223,8 @@ kvs_status kvs_decode_attn_n(const kvs_desc* desc, const void* q, const kvs_cach
  *             call since kvs_calibrate_reset.  Calls on one stream accumulate in order; calls on
  *             several streams may run concurrently (integer atomics).
  *   kvs_calibrate: K, V fp16 [B, Hkv, n, 128], keep_mask uint8 [B, n] as in kvs_quantize_kv.
- *   kvs_static_params: k_static uint32 [Hkv, 128], v_static uint32 [Hkv, 128 / G] parameter words
+ *   kvs_static_params: k_static uint32 [Hkv, 128] (with desc->key_per_token: [Hkv, 128 / G], one
+ *             per Key channel group), v_static uint32 [Hkv, 128 / G] parameter words
  *             (fp16 scale | int16 zero << 16) by the scale / zero equations of kvs_quantize_kv
  *             applied to the calibrated range (nothing seen: scale 1, zero 0).
  *   kvs_quantize_kv_static: kvs_quantize_kv with those words instead of per-group statistics;

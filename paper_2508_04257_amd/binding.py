@@ -34,7 +34,8 @@ _FIELD_DTYPES = dict(
 class KvsDesc(C.Structure):
     _fields_ = [("B", C.c_int32), ("n", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32),
                 ("D", C.c_int32), ("bits", C.c_int32), ("group", C.c_int32),
-                ("keep_cap", C.c_int32), ("sparse_frac", C.c_float), ("sparse_cap", C.c_int64)]
+                ("keep_cap", C.c_int32), ("sparse_frac", C.c_float), ("key_per_token", C.c_int32),
+                ("sparse_cap", C.c_int64)]
 
 
 class KvsCache(C.Structure):
@@ -103,8 +104,9 @@ def status_string(status: int) -> str:
     return lib().kvs_status_string(int(status)).decode()
 
 
-def make_desc(B, n, Hq, Hkv, bits, group, keep_cap, D=128, sparse_frac=0.0, sparse_cap=0) -> KvsDesc:
-    return KvsDesc(B, n, Hq, Hkv, D, bits, group, keep_cap, sparse_frac, sparse_cap)
+def make_desc(B, n, Hq, Hkv, bits, group, keep_cap, D=128, sparse_frac=0.0, sparse_cap=0,
+              key_per_token=False) -> KvsDesc:
+    return KvsDesc(B, n, Hq, Hkv, D, bits, group, keep_cap, sparse_frac, int(bool(key_per_token)), sparse_cap)
 
 
 def kvs_cache_bytes(desc: KvsDesc) -> Dict[str, int]:
@@ -300,9 +302,11 @@ def kvs_calibrate(desc: KvsDesc, K: torch.Tensor, V: torch.Tensor, keep_mask: to
 
 
 def kvs_static_params(desc: KvsDesc, calib: torch.Tensor):
-    """-> (k_static int32 [Hkv, 128], v_static int32 [Hkv, 128 / G]) parameter words on the device."""
+    """-> (k_static int32 [Hkv, 128] - [Hkv, 128 / G] with per-token Keys -, v_static int32
+    [Hkv, 128 / G]) parameter words on the device."""
     _check_tensor("calib", calib, (kvs_calibration_bytes(desc) // 4,), torch.int32)
-    ks = torch.empty((desc.Hkv, desc.D), dtype=torch.int32, device=calib.device)
+    ks = torch.empty((desc.Hkv, desc.D // desc.group if desc.key_per_token else desc.D), dtype=torch.int32,
+                     device=calib.device)
     vs = torch.empty((desc.Hkv, desc.D // desc.group), dtype=torch.int32, device=calib.device)
     st = lib().kvs_static_params(C.byref(desc), calib.data_ptr(), ks.data_ptr(), vs.data_ptr(), _stream_handle())
     if st != KVS_OK:
@@ -317,7 +321,7 @@ def kvs_quantize_kv_static(desc: KvsDesc, K: torch.Tensor, V: torch.Tensor, keep
     _check_tensor("K", K, shape, torch.float16)
     _check_tensor("V", V, shape, torch.float16)
     _check_tensor("keep_mask", keep_mask, (desc.B, desc.n), torch.uint8)
-    _check_tensor("k_static", k_static, (desc.Hkv, desc.D), torch.int32)
+    _check_tensor("k_static", k_static, (desc.Hkv, desc.D // desc.group if desc.key_per_token else desc.D), torch.int32)
     _check_tensor("v_static", v_static, (desc.Hkv, desc.D // desc.group), torch.int32)
     _check_cache(desc, cache)
     st = lib().kvs_quantize_kv_static(C.byref(desc), K.data_ptr(), V.data_ptr(), keep_mask.data_ptr(),

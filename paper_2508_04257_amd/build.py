@@ -29,6 +29,9 @@ SOURCES = {
     "decode_mfma_b2.hip": [],
     "decode_mfma_b3.hip": [],
     "decode_mfma_b4.hip": [],
+    "decode_mfma_kpt_b2.hip": [],
+    "decode_mfma_kpt_b3.hip": [],
+    "decode_mfma_kpt_b4.hip": [],
 }
 
 COMMON = [

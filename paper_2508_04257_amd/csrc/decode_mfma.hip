@@ -12,8 +12,13 @@ void launch_decode_mfma_b2(const kvs_desc*, const DecodeGeometry&, const void*, 
 void launch_decode_mfma_b3(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, int, const float*, hipStream_t);
 void launch_decode_mfma_b4(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, int, const float*, hipStream_t);
 
+void launch_decode_mfma_kpt_b2(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, int, const float*, hipStream_t);
+void launch_decode_mfma_kpt_b3(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, int, const float*, hipStream_t);
+void launch_decode_mfma_kpt_b4(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, int, const float*, hipStream_t);
+
 bool decode_mfma_supported(const kvs_desc* d) {
   const int rep = d->Hq / d->Hkv;
+  if (d->key_per_token) return true;                 // every shape the descriptor check lets through
   if (d->sparse_frac != 0.0f) return rep == 1;       // isolated outliers: one query head per KV head
   if (rep == 1 || rep == 4) return true;
   return d->group == 128;                            // 2 or 8 query heads per KV head
@@ -23,6 +28,12 @@ int decode_mfma_waves() { return KVS_MFMA_WAVES; }
 
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
                         void* out, float* lse, float* ws, float* cs, int n_used, const float* extra, hipStream_t s) {
+  if (d->key_per_token) {
+    if (d->bits == 2) launch_decode_mfma_kpt_b2(d, geo, q, c, out, lse, ws, n_used, extra, s);
+    else if (d->bits == 3) launch_decode_mfma_kpt_b3(d, geo, q, c, out, lse, ws, n_used, extra, s);
+    else launch_decode_mfma_kpt_b4(d, geo, q, c, out, lse, ws, n_used, extra, s);
+    return;
+  }
   if (d->bits == 2) launch_decode_mfma_b2(d, geo, q, c, out, lse, ws, cs, n_used, extra, s);
   else if (d->bits == 3) launch_decode_mfma_b3(d, geo, q, c, out, lse, ws, cs, n_used, extra, s);
   else launch_decode_mfma_b4(d, geo, q, c, out, lse, ws, cs, n_used, extra, s);

@@ -186,8 +186,17 @@ struct MfmaArgs {
 // score (a.cs, log2 units); it is added before the softmax, the corrected score is written back in
 // its place, and the workgroup's state always goes to the workspace: the finishing kernel applies
 // the Value-side corrections, which need the final softmax weights.
-template <int BITS, int G, int R, bool SPARSE>
+//
+// KPT (per-token Keys, the other Key scheme of the paper's Section 5.1): a Key row carries one
+// parameter pair per group of G channels, like a Value row.  The scale then depends on the token
+// - the M row of the score product - and cannot be folded into the query; instead the B operand
+// is the bare query, cut into one pair of (hi, lo) columns per channel group, built once per
+// workgroup, and the softmax stage combines the per-group sums with the token's parameters:
+//   score[t] = sum_g scale[t, g] (raw_g[t] - C_g - zero[t, g] Q_g),
+// C_g = what the product holds for the operand offsets, Q_g = the query's sum over the group.
+template <int BITS, int G, int R, bool SPARSE, bool KPT = false>
 __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(MfmaArgs a) {
+  static_assert(!(KPT && SPARSE), "per-token Keys are dense only");
   constexpr int kWaves = waves_for(R);
   using S = Shape<BITS>;
   constexpr int W = S::W, KW = S::KW, RPW = S::RPW, NOPS = S::NOPS, TBL = S::TBL;
@@ -195,15 +204,17 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
   constexpr int NGT = G < 64 ? 2 : 1;              // Key token groups per 64-token tile
   constexpr int NGC = 128 / G;                     // Value channel groups
   constexpr int NTAB = G == 128 ? 1 : 2;           // Value operand tables (one per channel half)
-  constexpr int KCOLS = 2 * R * NGT;               // [hi | lo] per group of the tile
+  constexpr int KCOLS = KPT ? 2 * R * NGC : 2 * R * NGT;   // [hi | lo] per token group of the tile (KPT: per channel group)
+  constexpr int NSC = KPT ? R * NGC : R;           // score rows a chunk leaves in LDS
+  constexpr int KTABS = KPT ? 1 : kWaves;          // KPT: one table for the workgroup, built by wave 0
   constexpr int VCOLS = G == 32 ? 4 * R : 2 * R;   // [hi | lo] per channel group of the half
   static_assert(KCOLS <= 16 && VCOLS <= 16, "tile columns");
   constexpr int LOG2G = G == 32 ? 5 : (G == 64 ? 6 : 7);
 
   // Per-wave LDS: operand tables in the instruction's slot order (column *COLS stays zero: the
   // lanes of the unused tile columns read it, and so do padded slots), and the score exchange.
-  __shared__ __align__(16) _Float16 bq[kWaves][KCOLS + 1][TBL];          // query x Key scale
-  __shared__ __align__(16) float sc[kWaves][R][128];                     // scores, token order
+  __shared__ __align__(16) _Float16 bq[KTABS][KCOLS + 1][TBL];           // query x Key scale (KPT: the query)
+  __shared__ __align__(16) float sc[kWaves][NSC][128];                   // scores, token order
   __shared__ __align__(16) _Float16 wh[kWaves][NTAB][VCOLS + 1][TBL];    // weight x Value scale
   // At the end each wave leaves its unnormalised output rows (R x 128 floats) in its own table.
   static_assert(sizeof(wh[0]) >= R * 128 * sizeof(float), "output rows must fit the weight table");
@@ -248,7 +259,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
   const uint8_t* mask_b = a.keep_mask + static_cast<size_t>(b) * n;
   const uint32_t* kcodes = a.k_codes + bh * (n / 64) * (W * 64);
   const uint32_t* vcodes = a.v_codes + bh * (n / 128) * (W * 128);
-  const uint32_t* kparams = a.k_params + bh * (n / G) * 128;
+  const uint32_t* kparams = a.k_params + bh * (n / G) * 128;     // KPT: bh * n * NGC, the same number
   const uint32_t* vparams = a.v_params + bh * n * NGC;
 
   float m_run[R], l_run[R], z_run[R][NGC];         // running max (log2 units), lane-partial sums
@@ -279,6 +290,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
   struct ValueRegs {
     uint4 vx[KW][2];       // [token word row 4 k + grp][channel half], channels 4 col .. + 3
     uint32_t vp0[NGC], vp1[NGC];   // parameters of tokens lane, lane + 64
+    uint32_t kq0[KPT ? NGC : 1], kq1[KPT ? NGC : 1];   // KPT: Key parameters of the same tokens
     float c0[SPARSE ? R : 1], c1[SPARSE ? R : 1];   // score corrections of the same tokens
     uint8_t mask0, mask1;  // keep-mask bytes of the same tokens
   };
@@ -307,7 +319,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
     const bool real = ci < nchunks;
     const int t0 = real ? part_begin + ci * 128 : 0;
     const int lane_pair = real ? lane : 0;
-    if (G == 128 && kt == 1) return;
+    if (KPT || (G == 128 && kt == 1)) return;
 #pragma unroll
     for (int ga = 0; ga < NGT; ++ga) {
       const int g = G == 128 ? 0 : kt * NGT + ga;
@@ -322,6 +334,10 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
     for (int g = 0; g < NGC; ++g) {
       s.vp0[g] = vparams[static_cast<size_t>(t0 + lane_tok) * NGC + g];
       s.vp1[g] = vparams[static_cast<size_t>(t0 + 64 + lane_tok) * NGC + g];
+      if (KPT) {
+        s.kq0[g] = kparams[static_cast<size_t>(t0 + lane_tok) * NGC + g];
+        s.kq1[g] = kparams[static_cast<size_t>(t0 + 64 + lane_tok) * NGC + g];
+      }
     }
     s.mask0 = mask_b[t0 + lane_tok];
     s.mask1 = mask_b[t0 + 64 + lane_tok];
@@ -361,8 +377,10 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
   }
   if (threadIdx.x == 0) next_chunk = kWaves;               // chunks 0 .. kWaves - 1 are the waves' first
   {
-    uint32_t* zq = reinterpret_cast<uint32_t*>(&bq[wave][0][0]);
-    for (int i = lane; i < (KCOLS + 1) * TBL / 2; i += KVS_WAVE) zq[i] = 0;
+    if (!KPT || wave == 0) {
+      uint32_t* zq = reinterpret_cast<uint32_t*>(&bq[KPT ? 0 : wave][0][0]);
+      for (int i = lane; i < (KCOLS + 1) * TBL / 2; i += KVS_WAVE) zq[i] = 0;
+    }
     uint32_t* zw = reinterpret_cast<uint32_t*>(&wh[wave][0][0][0]);
     for (int i = lane; i < NTAB * (VCOLS + 1) * TBL / 2; i += KVS_WAVE) zw[i] = 0;
   }
@@ -380,7 +398,37 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
   const int tpos0 = S::table_pos(lane), tpos1 = S::table_pos(lane + 64);
   const float toff0 = S::elem_offset(lane), toff1 = S::elem_offset(lane + 64);
 
-  __syncthreads();                                         // the chunk counter is set
+  // KPT: the score product's B operand is the query alone, in the columns of the lane's channel
+  // group; kc / kqs are what the product holds for the operand offsets, and the query's sum.
+  float kc[KPT ? NGC : 1][R], kqs[KPT ? NGC : 1][R];
+  if (KPT) {
+    const int gk = (2 * lane) >> LOG2G;                    // channel group of the lane's two channels
+    if (wave == 0) wave_lds_sync();                        // the table is zeroed
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const _Float16 h0 = static_cast<_Float16>(qf[r][0]), h1 = static_cast<_Float16>(qf[r][1]);
+      const _Float16 e0 = static_cast<_Float16>(qf[r][0] - static_cast<float>(h0));
+      const _Float16 e1 = static_cast<_Float16>(qf[r][1] - static_cast<float>(h1));
+      if (wave == 0) {
+        bq[0][gk * 2 * R + r][cpos0] = h0;  bq[0][gk * 2 * R + r][cpos1] = h1;
+        bq[0][gk * 2 * R + R + r][cpos0] = e0;  bq[0][gk * 2 * R + R + r][cpos1] = e1;
+      }
+      const float q0 = static_cast<float>(h0) + static_cast<float>(e0), q1 = static_cast<float>(h1) + static_cast<float>(e1);
+#pragma unroll
+      for (int g = 0; g < NGC; ++g) {
+        kc[g][r] = uniform(kvs::wave_sum(gk == g ? q0 * coff0 + q1 * coff1 : 0.0f));
+        kqs[g][r] = uniform(kvs::wave_sum(gk == g ? q0 + q1 : 0.0f));
+      }
+    }
+  }
+
+  __syncthreads();                                         // the chunk counter (and the KPT table) is set
+
+  half8 bq_fixed[NOPS];                            // KPT: the B operand never changes
+  if (KPT) {
+#pragma unroll
+    for (int m = 0; m < NOPS; ++m) bq_fixed[m] = *reinterpret_cast<const half8*>(&bq[0][kcol][(4 * m + grp) * 8]);
+  }
 
   float bias[NGK][R];                              // what the score product holds for offsets and zero points
 
@@ -388,7 +436,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
       // ---- (1) B operand of the score product: q x scale as hi + lo halves, per token group ----
-      if (G < 128 || kt == 0) {
+      if (!KPT && (G < 128 || kt == 0)) {
 #pragma unroll
         for (int ga = 0; ga < NGT; ++ga) {
           const int gi = G == 128 ? 0 : kt * NGT + ga;       // group inside the chunk
@@ -413,7 +461,8 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
       }
       half8 bqr[NOPS];
 #pragma unroll
-      for (int m = 0; m < NOPS; ++m) bqr[m] = *reinterpret_cast<const half8*>(&bq[wave][kcol][(4 * m + grp) * 8]);
+      for (int m = 0; m < NOPS; ++m)
+        bqr[m] = KPT ? bq_fixed[m] : *reinterpret_cast<const half8*>(&bq[KPT ? 0 : wave][kcol][(4 * m + grp) * 8]);
 
       // ---- (2) scores on the matrix cores; hi + lo columns merged; to LDS in token order -------
       float4v d[4];                                    // [r]: rows = tokens 64 kt + 4 m + r, m = 0..15
@@ -436,7 +485,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           float v = d[r][i] + row_shift_down<R>(d[r][i]);            // hi + lo
-          if (NGT == 2) {                                            // rows of lane groups 2, 3 belong to the
+          if (!KPT && NGT == 2) {                                    // rows of lane groups 2, 3 belong to the
             const float w2 = row_shift_down<(2 * R) % 16 == 0 ? 1 : (2 * R) % 16>(v);   // tile's second token group
             v = grp >= 2 ? w2 : v;
           }
@@ -446,12 +495,19 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
       load_key_tile(s, refill, kt);
       load_key_params(s, refill, kt);
       __builtin_amdgcn_sched_barrier(0);
-      if (col < R) {
+      if (KPT) {                                       // column g 2R + r: head r, channel group g
+        if (col < KCOLS && (col % (2 * R)) < R) {
+          const int slot = (col / (2 * R)) * R + col % (2 * R);
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<float4v*>(&sc[wave][slot][64 * kt + 16 * grp + 4 * i]) = out[i];
+        }
+      } else if (col < R) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
           *reinterpret_cast<float4v*>(&sc[wave][col][64 * kt + 16 * grp + 4 * i]) = out[i];
       }
-      if (G < 128 && kt == 0) wave_lds_sync();         // the table is rebuilt for the second tile
+      if (!KPT && G < 128 && kt == 0) wave_lds_sync(); // the table is rebuilt for the second tile
     }
     wave_lds_sync();
   };
@@ -461,6 +517,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
     float alpha[R];
     {
       float sv0[NGC], sv1[NGC], zf0[NGC], zf1[NGC];
+      float sk0[KPT ? NGC : 1], sk1[KPT ? NGC : 1], zk0[KPT ? NGC : 1], zk1[KPT ? NGC : 1];
 #pragma unroll
       for (int g = 0; g < NGC; ++g) {
         int z0, z1;
@@ -471,15 +528,34 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
         // Convert here and now: the parameter registers are about to be loaded again, and a
         // conversion postponed past that load would keep them alive in a second set.
         asm volatile("" : "+v"(sv0[g]), "+v"(sv1[g]), "+v"(zf0[g]), "+v"(zf1[g]));
+        if (KPT) {
+          kvs::unpack_param(s.kq0[g], sk0[g], z0);
+          kvs::unpack_param(s.kq1[g], sk1[g], z1);
+          zk0[g] = static_cast<float>(z0);
+          zk1[g] = static_cast<float>(z1);
+          asm volatile("" : "+v"(sk0[g]), "+v"(sk1[g]), "+v"(zk0[g]), "+v"(zk1[g]));
+        }
       }
 #pragma unroll
       for (int r = 0; r < R; ++r) {
-        // token lane is in Key group lane / G of the chunk, token lane + 64 in group (lane + 64) / G
-        float b0 = bias[0][r], b1 = bias[NGK - 1][r];
-        if (NGK == 2) { b0 = bias[0][r]; b1 = bias[1][r]; }
-        if (NGK == 4) { b0 = lane >= 32 ? bias[1][r] : bias[0][r]; b1 = lane >= 32 ? bias[3][r] : bias[2][r]; }
-        float s0 = s.mask0 ? -INFINITY : sc[wave][r][lane] - b0;
-        float s1 = s.mask1 ? -INFINITY : sc[wave][r][64 + lane] - b1;
+        float s0, s1;
+        if (KPT) {
+          s0 = 0.0f;  s1 = 0.0f;
+#pragma unroll
+          for (int g = 0; g < NGC; ++g) {
+            s0 += sk0[g] * (sc[wave][g * R + r][lane] - kc[g][r] - zk0[g] * kqs[g][r]);
+            s1 += sk1[g] * (sc[wave][g * R + r][64 + lane] - kc[g][r] - zk1[g] * kqs[g][r]);
+          }
+          s0 = s.mask0 ? -INFINITY : s0;
+          s1 = s.mask1 ? -INFINITY : s1;
+        } else {
+          // token lane is in Key group lane / G of the chunk, token lane + 64 in group (lane + 64) / G
+          float b0 = bias[0][r], b1 = bias[NGK - 1][r];
+          if (NGK == 2) { b0 = bias[0][r]; b1 = bias[1][r]; }
+          if (NGK == 4) { b0 = lane >= 32 ? bias[1][r] : bias[0][r]; b1 = lane >= 32 ? bias[3][r] : bias[2][r]; }
+          s0 = s.mask0 ? -INFINITY : sc[wave][r][lane] - b0;
+          s1 = s.mask1 ? -INFINITY : sc[wave][r][64 + lane] - b1;
+        }
         if (SPARSE) {
           s0 += s.c0[r];  s1 += s.c1[r];
           float* row = a.cs + (static_cast<size_t>(b) * Hq + hq0 + r) * n + part_begin + cur * 128 + lane;
@@ -708,6 +784,33 @@ inline MfmaArgs make_args(const kvs_desc* d, const kvs::DecodeGeometry& geo, con
   a.n_used = n_used; a.extra = extra;
   a.parts = geo.splits; a.part_tokens = geo.split_tokens;
   return a;
+}
+
+template <int BITS, int G, int R>
+void launch_one_kpt(const kvs_desc* d, const kvs::DecodeGeometry& geo, const MfmaArgs& args, hipStream_t s) {
+  const dim3 grid(d->B * d->Hkv * geo.splits), block(waves_for(R) * KVS_WAVE);
+  hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, false, true>), grid, block, 0, s, args);
+}
+
+// Per-token Keys: every shape with heads x channel groups <= 8 (the 16 tile columns).
+template <int BITS>
+void launch_bits_kpt(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c, void* out,
+                     float* lse, float* ws, int n_used, const float* extra, hipStream_t s) {
+  const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws, nullptr, n_used, extra);
+  const int rep = d->Hq / d->Hkv;
+  if (d->group == 128) {
+    if (rep == 1) launch_one_kpt<BITS, 128, 1>(d, geo, a, s);
+    else if (rep == 2) launch_one_kpt<BITS, 128, 2>(d, geo, a, s);
+    else if (rep == 4) launch_one_kpt<BITS, 128, 4>(d, geo, a, s);
+    else launch_one_kpt<BITS, 128, 8>(d, geo, a, s);
+  } else if (d->group == 64) {
+    if (rep == 1) launch_one_kpt<BITS, 64, 1>(d, geo, a, s);
+    else if (rep == 2) launch_one_kpt<BITS, 64, 2>(d, geo, a, s);
+    else launch_one_kpt<BITS, 64, 4>(d, geo, a, s);
+  } else {
+    if (rep == 1) launch_one_kpt<BITS, 32, 1>(d, geo, a, s);
+    else launch_one_kpt<BITS, 32, 2>(d, geo, a, s);
+  }
 }
 
 template <int BITS, int G, int R>

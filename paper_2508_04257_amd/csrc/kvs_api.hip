@@ -9,12 +9,15 @@ kvs_status validate_desc(const kvs_desc* d) {
   if (d->keep_cap < 0 || !(d->sparse_frac >= 0.0f) || d->sparse_frac >= 1.0f) return KVS_ERR_INVALID;
   if (d->Hq % d->Hkv != 0) return KVS_ERR_INVALID;
   if (d->sparse_frac > 0.0f && d->sparse_cap < 1) return KVS_ERR_INVALID;
+  if (d->key_per_token != 0 && d->key_per_token != 1) return KVS_ERR_INVALID;
   if (d->D != KVS_HEAD_DIM) return KVS_ERR_UNSUPPORTED;
   if (d->bits != 2 && d->bits != 3 && d->bits != 4) return KVS_ERR_UNSUPPORTED;
   if (d->group != 32 && d->group != 64 && d->group != 128) return KVS_ERR_UNSUPPORTED;
   if (d->n % KVS_V_TILE != 0) return KVS_ERR_UNSUPPORTED;      // also a multiple of 64 and of G
   const int rep = d->Hq / d->Hkv;
   if (rep != 1 && rep != 2 && rep != 4 && rep != 8) return KVS_ERR_UNSUPPORTED;
+  // Per-token Keys: dense caches only; the score tile has 16 columns for heads x channel groups x 2.
+  if (d->key_per_token && (d->sparse_frac > 0.0f || rep * (KVS_HEAD_DIM / d->group) > 8)) return KVS_ERR_UNSUPPORTED;
   // CSR rows and word offsets are 32-bit quantities in places; keep a wide margin.
   const int64_t rows = static_cast<int64_t>(d->B) * d->Hkv * d->n;
   if (rows >= (int64_t{1} << 30)) return KVS_ERR_UNSUPPORTED;

@@ -259,6 +259,121 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
+// Keys of the per-token scheme (paper, Section 5.1): a Key row is quantised like a Value row,
+// groups of G consecutive channels of one token; the packed words keep the Key layout.  Block =
+// one 64-token code tile; a lane owns channels 8 chunk .. + 7 of rows rslot, rslot + 16, ...
+// ---------------------------------------------------------------------------------------------
+template <int BITS, int G>
+__global__ __launch_bounds__(kThreads) void quantize_k_token_fast_kernel(
+    const uint4* __restrict__ K, const uint8_t* __restrict__ keep_mask, kvs::QuantSpan sp, int Hkv,
+    uint32_t* __restrict__ k_codes, uint32_t* __restrict__ k_params, const int32_t* __restrict__ keep_idx,
+    const int32_t* __restrict__ keep_cnt, int cap, uint4* __restrict__ keep_k,
+    const uint32_t* __restrict__ static_k) {          // [Hkv, 128 / G] fixed parameter words, or null
+  constexpr int TB = KVS_K_TILE;
+  constexpr int ROWS = TB / 16;                 // 4 rows per lane
+  constexpr int LPG = G / 8;                    // lanes per channel group: 4, 8, 16
+  constexpr int NGC = 128 / G;
+  constexpr int W = Fmt<BITS>::W;
+  constexpr int TILE_STRIDE = 68;
+  constexpr int LANES_PER_WORD = BITS == 2 ? 2 : 1;
+  constexpr int kStage = BITS == 3 ? TB * kPieceStride : W * TILE_STRIDE;
+  static_assert(ROWS <= LPG, "lane p of a group derives the parameters of row p");
+
+  __shared__ __align__(16) uint32_t tile_s[kStage];     // words as [w][token]; 3 bit: pieces [token][16]
+
+  const int tid = threadIdx.x;
+  const int lane = tid & (KVS_WAVE - 1);
+  const int chunk = tid & 15;
+  const int rslot = tid >> 4;
+  const int blocks_per_head = sp.n_tokens / TB;
+  const int blk = blockIdx.x % blocks_per_head;
+  const size_t bh = blockIdx.x / blocks_per_head;
+  const int b = static_cast<int>(bh / Hkv);
+  const int t0 = blk * TB;                      // input token; the cache token is sp.t_out + t0
+  const int n = sp.n_cap;
+  const int tc0 = sp.t_out + t0;
+  const uint4* src = K + (bh * sp.n_in + t0) * 16;
+  const uint8_t* mask_b = keep_mask + static_cast<size_t>(b) * sp.mask_stride + sp.mask_t0 + t0;
+
+  uint4 raw[ROWS];
+  bool kept[ROWS];
+#pragma unroll
+  for (int i = 0; i < ROWS; ++i) {
+    const int r = rslot + 16 * i;
+    raw[i] = load_stream(src + r * 16 + chunk);
+    kept[i] = mask_b[r] != 0;
+  }
+
+  // (min, -max) of each row's group as one packed pair, reduced across the group's lanes.
+  uint32_t stat[ROWS];
+#pragma unroll
+  for (int i = 0; i < ROWS; ++i) {
+    const uint32_t mn2 = pk_min(pk_min(raw[i].x, raw[i].y), pk_min(raw[i].z, raw[i].w));
+    const uint32_t mx2 = pk_max(pk_max(raw[i].x, raw[i].y), pk_max(raw[i].z, raw[i].w));
+    const uint32_t mn1 = pk_min(mn2, mn2 >> 16) & 0xFFFFu;
+    const uint32_t mx1 = pk_max(mx2, mx2 >> 16) & 0xFFFFu;
+    uint32_t s = mn1 | ((mx1 ^ 0x8000u) << 16);
+#pragma unroll
+    for (int o = 1; o < LPG; o <<= 1) s = pk_min(s, static_cast<uint32_t>(__shfl_xor(static_cast<int>(s), o, KVS_WAVE)));
+    stat[i] = s;
+  }
+
+  // Lane p of a group derives the parameters of the lane's row p (p < 4); the others fetch them.
+  const int p = chunk % LPG;
+  const int group_base = lane - p;
+  float inv_mine = 1.0f, zero_mine = 0.0f;
+  if (p < ROWS) {
+    uint32_t s = stat[0];
+    bool k = kept[0];
+#pragma unroll
+    for (int i = 1; i < ROWS; ++i) { s = p == i ? stat[i] : s; k = p == i ? kept[i] : k; }
+    const Param prm = static_k ? param_of_word(static_k[(bh % Hkv) * NGC + chunk / LPG])
+                               : make_param<BITS>(lo_half(s), -hi_half(s), !k);
+    inv_mine = prm.inv;
+    zero_mine = prm.zero;
+    k_params[(bh * n + static_cast<size_t>(tc0 + rslot + 16 * p)) * NGC + chunk / LPG] = prm.word;
+  }
+
+  const int cnt = min(keep_cnt[b], cap);
+#pragma unroll
+  for (int i = 0; i < ROWS; ++i) {
+    const int r = rslot + 16 * i;
+    const float inv1 = __shfl(inv_mine, group_base + i, KVS_WAVE);
+    const float zero1 = __shfl(zero_mine, group_base + i, KVS_WAVE);
+    float inv[8], zero[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { inv[j] = inv1; zero[j] = zero1; }
+    uint32_t word = kept[i] ? 0u : codes8<BITS>(raw[i], inv, zero);
+    if (LANES_PER_WORD == 2) {                  // 2 bit: lanes (even, odd) share a word
+      const uint32_t other = static_cast<uint32_t>(__shfl_xor(static_cast<int>(word), 1, KVS_WAVE));
+      word = word | (other << 16);
+    }
+    if (BITS == 3)
+      tile_s[r * kPieceStride + chunk] = word;
+    else if (LANES_PER_WORD == 1 || (chunk & 1) == 0)
+      tile_s[(chunk / LANES_PER_WORD) * TILE_STRIDE + r] = word;
+    if (kept[i]) {                              // exact copy of the row into the fp16 side buffer
+      const int j = keep_slot(keep_idx + static_cast<size_t>(b) * cap, cnt, tc0 + r);
+      if (j >= 0) keep_k[(bh * cap + j) * 16 + chunk] = raw[i];
+    }
+  }
+  __syncthreads();
+
+  uint4* out = reinterpret_cast<uint4*>(k_codes + (bh * (n / KVS_K_TILE) + static_cast<size_t>(tc0 / KVS_K_TILE)) * (W * KVS_K_TILE));
+  constexpr int quads = W * (KVS_K_TILE / 4);
+  for (int qi = tid; qi < quads; qi += kThreads) {
+    const int w = qi / (KVS_K_TILE / 4), t4 = qi % (KVS_K_TILE / 4);
+    if (BITS == 3) {
+      const uint32_t* pc = &tile_s[4 * t4 * kPieceStride];
+      store_stream(out + qi, uint4{compose3(pc, w), compose3(pc + kPieceStride, w), compose3(pc + 2 * kPieceStride, w),
+                                   compose3(pc + 3 * kPieceStride, w)});
+    } else {
+      store_stream(out + qi, *reinterpret_cast<const uint4*>(&tile_s[w * TILE_STRIDE + 4 * t4]));
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Values: per token, groups of G consecutive channels.  Block = one 128-token tile; a lane owns
 // tokens 8 rs .. 8 rs + 7 and channels 8 chunk .. 8 chunk + 7.
 // ---------------------------------------------------------------------------------------------
@@ -511,12 +626,21 @@ __global__ __launch_bounds__(kThreads) void calibrate_kernel(
 
 // One workgroup per KV head: the parameter word of every Key channel and Value channel group.
 template <int BITS>
-__global__ void static_params_kernel(const uint32_t* __restrict__ calib, int Hkv, int group,
+__global__ void static_params_kernel(const uint32_t* __restrict__ calib, int Hkv, int group, int key_per_token,
                                      uint32_t* __restrict__ static_k, uint32_t* __restrict__ static_v) {
   const int h = blockIdx.x, c = threadIdx.x;
   const int plane = Hkv * 128;
-  const float kmn = order_value(calib[h * 128 + c]), kmx = order_value(calib[plane + h * 128 + c]);
-  static_k[h * 128 + c] = make_param<BITS>(kmn, kmx, kmn <= kmx).word;
+  if (!key_per_token) {
+    const float kmn = order_value(calib[h * 128 + c]), kmx = order_value(calib[plane + h * 128 + c]);
+    static_k[h * 128 + c] = make_param<BITS>(kmn, kmx, kmn <= kmx).word;
+  } else if (c < 128 / group) {                  // one word per Key channel group, as for Values
+    float kmn = INFINITY, kmx = -INFINITY;
+    for (int j = 0; j < group; ++j) {
+      kmn = fminf(kmn, order_value(calib[h * 128 + c * group + j]));
+      kmx = fmaxf(kmx, order_value(calib[plane + h * 128 + c * group + j]));
+    }
+    static_k[h * (128 / group) + c] = make_param<BITS>(kmn, kmx, kmn <= kmx).word;
+  }
   if (c < 128 / group) {
     float vmn = INFINITY, vmx = -INFINITY;
     for (int j = 0; j < group; ++j) {
@@ -539,9 +663,14 @@ void launch_fast(const kvs_desc* d, const kvs::QuantSpan& sp, bool own_keep, con
                        out->keep_idx, out->keep_cnt, out->keep_mask, out->status, static_cast<uint4*>(out->keep_k),
                        static_cast<uint4*>(out->keep_v));
   if (sp.n_tokens == 0) return;
-  hipLaunchKernelGGL((quantize_k_fast_kernel<BITS, G>), dim3(bh * (sp.n_tokens / TB)), dim3(kThreads), 0, s,
-                     static_cast<const uint4*>(K), mask, sp, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
-                     out->keep_cnt, cap, static_cast<uint4*>(out->keep_k), static_k);
+  if (d->key_per_token)
+    hipLaunchKernelGGL((quantize_k_token_fast_kernel<BITS, G>), dim3(bh * (sp.n_tokens / KVS_K_TILE)), dim3(kThreads), 0, s,
+                       static_cast<const uint4*>(K), mask, sp, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
+                       out->keep_cnt, cap, static_cast<uint4*>(out->keep_k), static_k);
+  else
+    hipLaunchKernelGGL((quantize_k_fast_kernel<BITS, G>), dim3(bh * (sp.n_tokens / TB)), dim3(kThreads), 0, s,
+                       static_cast<const uint4*>(K), mask, sp, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
+                       out->keep_cnt, cap, static_cast<uint4*>(out->keep_k), static_k);
   hipLaunchKernelGGL((quantize_v_fast_kernel<BITS, G>), dim3(bh * (sp.n_tokens / KVS_V_TILE)), dim3(kThreads), 0, s,
                      static_cast<const uint4*>(V), mask, sp, d->Hkv, out->v_codes, out->v_params, out->keep_idx,
                      out->keep_cnt, cap, static_cast<uint4*>(out->keep_v), static_v);
@@ -585,9 +714,9 @@ void launch_calibrate(const kvs_desc* d, const void* K, const void* V, const uin
 }
 void launch_static_params(const kvs_desc* d, const uint32_t* calib, uint32_t* static_k, uint32_t* static_v,
                           hipStream_t s) {
-  if (d->bits == 2) hipLaunchKernelGGL(static_params_kernel<2>, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv, d->group, static_k, static_v);
-  else if (d->bits == 3) hipLaunchKernelGGL(static_params_kernel<3>, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv, d->group, static_k, static_v);
-  else hipLaunchKernelGGL(static_params_kernel<4>, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv, d->group, static_k, static_v);
+  if (d->bits == 2) hipLaunchKernelGGL(static_params_kernel<2>, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv, d->group, d->key_per_token, static_k, static_v);
+  else if (d->bits == 3) hipLaunchKernelGGL(static_params_kernel<3>, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv, d->group, d->key_per_token, static_k, static_v);
+  else hipLaunchKernelGGL(static_params_kernel<4>, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv, d->group, d->key_per_token, static_k, static_v);
 }
 
 }  // namespace kvs

@@ -16,7 +16,7 @@ def desc_for(w: Workload, sparse_cap: int = 0) -> kb.KvsDesc:
         # room for the requested fraction plus ties at the threshold
         sparse_cap = int(w.B * w.Hkv * w.n * w.D * w.sparse_frac * 1.25) + 4096
     return kb.make_desc(w.B, w.n, w.Hq, w.Hkv, w.bits, w.group, max(w.keep_cap, 1),
-                        sparse_frac=w.sparse_frac, sparse_cap=sparse_cap)
+                        sparse_frac=w.sparse_frac, sparse_cap=sparse_cap, key_per_token=w.key_per_token)
 
 
 @dataclass

@@ -46,6 +46,7 @@ class Workload:
     k_sinks: int = 2          # sink tokens planted per sequence == top-k asked of the predictor
     first_n: int = 0          # Preserve-First-N part of the keep set
     sparse_frac: float = 0.0  # dense-and-sparse fp16 outlier fraction
+    key_per_token: bool = False   # per-token Keys (the other Key scheme of Section 5.1)
     layers: int = 1
     student_t: bool = False   # heavy-tailed K/V (Student-t, nu = 4) instead of N(0,1)
     d_hidden: int = LLAMA2_7B_HIDDEN
@@ -68,6 +69,8 @@ WORKLOADS = {
     "cfg1": Workload("cfg1", B=8, n=4096, Hq=32, Hkv=32, bits=4, group=128, k_sinks=5),
     "cfg2": Workload("cfg2", B=16, n=8192, Hq=32, Hkv=8, bits=3, group=64, k_sinks=4),
     "cfg3": Workload("cfg3", B=4, n=32768, Hq=32, Hkv=32, bits=2, group=32, k_sinks=8, first_n=16),
+    "cfg1_per_token_keys": Workload("cfg1_per_token_keys", B=8, n=4096, Hq=32, Hkv=32, bits=4, group=128, k_sinks=5,
+                                    key_per_token=True),
     "cfg4": Workload("cfg4", B=32, n=4096, Hq=32, Hkv=32, bits=3, group=128, k_sinks=5,
                      sparse_frac=0.01, layers=32, student_t=True),
 }

@@ -60,6 +60,7 @@ def test_cache_bytes_for_the_headline_workload():
     ("group", 16, kb.KVS_ERR_UNSUPPORTED), ("n", 1000, kb.KVS_ERR_UNSUPPORTED),
     ("n", 0, kb.KVS_ERR_INVALID), ("Hkv", 5, kb.KVS_ERR_INVALID), ("keep_cap", -1, kb.KVS_ERR_INVALID),
     ("Hq", 512, kb.KVS_ERR_UNSUPPORTED), ("sparse_frac", 1.5, kb.KVS_ERR_INVALID),
+    ("key_per_token", 2, kb.KVS_ERR_INVALID),
 ])
 def test_bad_descriptors_are_rejected_on_the_host(field, value, expected):
     d = kb.make_desc(B=2, n=1024, Hq=32, Hkv=32, bits=4, group=128, keep_cap=2)
@@ -71,6 +72,21 @@ def test_bad_descriptors_are_rejected_on_the_host(field, value, expected):
     cache = kb.KvsCache()
     assert kb.lib().kvs_quantize_kv(C.byref(d), 16, 16, 16, C.byref(cache), None, None) == expected
     assert kb.lib().kvs_decode_attn(C.byref(d), 16, C.byref(cache), 16, None, 16, None) == expected
+
+
+def test_per_token_key_descriptors():
+    sizes = (C.c_size_t * kb.KVS_CACHE_FIELDS)()
+    ok = kb.make_desc(B=2, n=1024, Hq=32, Hkv=8, bits=4, group=64, keep_cap=2, key_per_token=True)
+    assert kb.KvsDesc.key_per_token.offset == 36 and ok.key_per_token == 1
+    assert kb.lib().kvs_cache_bytes(C.byref(ok), sizes) == kb.KVS_OK
+    plain = kb.make_desc(B=2, n=1024, Hq=32, Hkv=8, bits=4, group=64, keep_cap=2)
+    assert kb.kvs_cache_bytes(ok) == kb.kvs_cache_bytes(plain)          # the parameter array only changes shape
+    # heads x channel groups beyond the 16 tile columns, and isolated outliers: not with per-token Keys
+    wide = kb.make_desc(B=2, n=1024, Hq=32, Hkv=8, bits=4, group=32, keep_cap=2, key_per_token=True)
+    assert kb.lib().kvs_cache_bytes(C.byref(wide), sizes) == kb.KVS_ERR_UNSUPPORTED
+    sp = kb.make_desc(B=2, n=1024, Hq=32, Hkv=32, bits=4, group=128, keep_cap=2, sparse_frac=0.01, sparse_cap=100,
+                      key_per_token=True)
+    assert kb.lib().kvs_cache_bytes(C.byref(sp), sizes) == kb.KVS_ERR_UNSUPPORTED
 
 
 def test_null_pointers_are_rejected_on_the_host():

@@ -26,11 +26,12 @@ def assert_growing_equal(desc, cache, gc: O.GrowingCache):
         ref = gc.quant
         kc = u32(cache.k_codes)[:B * H * (n_cap // 64) * W * 64].reshape(B, H, n_cap // 64, W, 64)
         vc = u32(cache.v_codes)[:B * H * (n_cap // 128) * W * 128].reshape(B, H, n_cap // 128, W, 128)
-        kp = u32(cache.k_params)[:B * H * (n_cap // G) * 128].reshape(B, H, n_cap // G, 128)
+        kp = u32(cache.k_params)[:B * H * (n_cap // G) * 128]
+        kp = kp.reshape(B, H, n_cap, 128 // G) if gc.key_per_token else kp.reshape(B, H, n_cap // G, 128)
         vp = u32(cache.v_params)[:B * H * n_cap * (128 // G)].reshape(B, H, n_cap, 128 // G)
         assert np.array_equal(kc[:, :, :nq // 64], ref.k_codes)
         assert np.array_equal(vc[:, :, :nq // 128], ref.v_codes)
-        assert np.array_equal(kp[:, :, :nq // G], ref.k_params)
+        assert np.array_equal(kp[:, :, :(nq if gc.key_per_token else nq // G)], ref.k_params)
         assert np.array_equal(vp[:, :, :nq], ref.v_params)
         assert np.array_equal(cache.keep_cnt.cpu().numpy()[:B], ref.keep_cnt)
         assert int(cache.status.cpu()[0]) == ref.status

@@ -351,7 +351,8 @@ def _sampled_full_size(name, n_pairs=3):
 
     kc = shaped(buf.cache.k_codes, w.B, w.Hkv, w.n // 64, W, 64)
     vc = shaped(buf.cache.v_codes, w.B, w.Hkv, w.n // 128, W, 128)
-    kp = shaped(buf.cache.k_params, w.B, w.Hkv, w.n // w.group, 128)
+    kp = (shaped(buf.cache.k_params, w.B, w.Hkv, w.n, 128 // w.group) if w.key_per_token
+          else shaped(buf.cache.k_params, w.B, w.Hkv, w.n // w.group, 128))
     vp = shaped(buf.cache.v_params, w.B, w.Hkv, w.n, 128 // w.group)
     keep_k = shaped(buf.cache.keep_k, w.B, w.Hkv, cap, 128)
     keep_v = shaped(buf.cache.keep_v, w.B, w.Hkv, cap, 128)
@@ -362,7 +363,8 @@ def _sampled_full_size(name, n_pairs=3):
     for _ in range(n_pairs):
         b, h = int(rng.integers(0, w.B)), int(rng.integers(0, w.Hkv))
         Ks, Vs = K[b:b + 1, h:h + 1].cpu().numpy(), V[b:b + 1, h:h + 1].cpu().numpy()
-        ref = O.quantize_kv(Ks, Vs, ref_mask[b:b + 1], w.bits, w.group, cap, sparse_frac=w.sparse_frac, taus=taus)
+        ref = O.quantize_kv(Ks, Vs, ref_mask[b:b + 1], w.bits, w.group, cap, sparse_frac=w.sparse_frac, taus=taus,
+                            key_per_token=w.key_per_token)
         if taus is not None:                                # this slice's rows of the two CSR structures
             base = (b * w.Hkv + h) * w.n
             for rp, col, val, rref, cref, vref in (
@@ -399,6 +401,10 @@ def _sampled_full_size(name, n_pairs=3):
 
 def test_full_size_headline_workload():
     _sampled_full_size("cfg1")
+
+
+def test_full_size_headline_shape_with_per_token_keys():
+    _sampled_full_size("cfg1_per_token_keys")
 
 
 def test_full_size_gqa_int3_workload():
