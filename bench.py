@@ -190,6 +190,45 @@ def static_leg(w, inputs, bufs, qnt_bytes):
     }
 
 
+def per_token_key_leg(w, inputs, bufs, q, dec_bytes, qnt_bytes):
+    """The per-token Key scheme on the same shapes: quantise and decode over rotating inputs and
+    caches of their own, back to back.  None where the scheme does not apply."""
+    import torch
+
+    from paper_2508_04257_amd import binding as kb
+    from paper_2508_04257_amd import pipeline
+
+    if w.key_per_token or w.sparse_frac > 0 or (w.Hq // w.Hkv) * (w.D // w.group) > 8:
+        return None
+    dev = q.device
+    desc = pipeline.desc_for(w.scaled(key_per_token=True))
+    slots = len(inputs)
+    caches = [kb.alloc_cache(desc, dev) for _ in range(slots)]
+    ws = kb.alloc_workspace(desc, dev)
+    out = torch.empty((w.B, w.Hq, w.D), dtype=torch.float16, device=dev)
+    for i in range(slots):
+        kb.kvs_quantize_kv(desc, inputs[i][0], inputs[i][1], bufs[i].keep_mask, caches[i], ws)
+        kb.kvs_decode_attn(desc, q, caches[i], out, None, ws)
+    torch.cuda.synchronize()
+    reps = 12
+    e = [HipEvent() for _ in range(3)]
+    e[0].record()
+    for i in range(reps):
+        kb.kvs_quantize_kv(desc, inputs[i % slots][0], inputs[i % slots][1], bufs[i % slots].keep_mask, caches[i % slots], ws)
+    e[1].record()
+    for i in range(reps):
+        kb.kvs_decode_attn(desc, q, caches[i % slots], out, None, ws)
+    e[2].record()
+    torch.cuda.synchronize()
+    ms_q, ms_d = e[0].elapsed_time(e[1]) / reps, e[1].elapsed_time(e[2]) / reps
+    return {
+        "ms_quantize_kv": round(ms_q, 4), "quantize_gbps": round(qnt_bytes / (ms_q * 1e-3) / 1e9, 2),
+        "ms_decode_attn": round(ms_d, 4), "decode_gbps": round(dec_bytes / (ms_d * 1e-3) / 1e9, 2),
+        "note": "same bytes per call as the per-channel scheme (the Key parameter array only changes shape); "
+                "calls back to back over rotating cold caches",
+    }
+
+
 def cpu_baseline(w, budget_s: float = 12.0):
     """The oracle as it stands, timed on this host on a bounded sample of the same workload:
     whole (sequence 0, head h) slices, one at a time, until the budget is used."""
@@ -210,7 +249,8 @@ def cpu_baseline(w, budget_s: float = 12.0):
             K, V = synth.make_kv(small.scaled(seed=small.seed + done))
             K, V = K.numpy(), V.numpy()
             t0 = time.perf_counter()
-            cache = O.quantize_kv(K, V, mask, small.bits, small.group, max(small.keep_cap, 1))
+            cache = O.quantize_kv(K, V, mask, small.bits, small.group, max(small.keep_cap, 1),
+                                  key_per_token=small.key_per_token)
             t1 = time.perf_counter()
             O.decode_attn(q, cache, Hq=small.Hq)
             t2 = time.perf_counter()
@@ -378,7 +418,8 @@ def main() -> int:
             "decode_splits": kb.kvs_decode_splits(bufs[0].desc),
         },
         "roofline": {
-            "kernel": ("kvs_decode_attn = decode_mfma_kernel<%d,%d,%d>" % (w.bits, w.group, w.Hq // w.Hkv)
+            "kernel": ("kvs_decode_attn = decode_mfma_kernel<%d,%d,%d%s>" % (w.bits, w.group, w.Hq // w.Hkv,
+                                                                            ",per-token Keys" if w.key_per_token else "")
                        + ("" if kb.kvs_decode_splits(bufs[0].desc) == 1 else " + decode_combine_kernel"))
                       if w.sparse_frac == 0 else
                       "kvs_decode_attn = decode_partial_kernel + decode_combine_kernel",
@@ -399,8 +440,9 @@ def main() -> int:
                              "note": "same call repeated over the rotating cold caches, no events between launches"},
         },
         "roofline_quantize": {
-            "kernel": "kvs_quantize_kv = keep_index_fast_kernel + quantize_k_fast_kernel + quantize_v_fast_kernel"
-                      if (w.bits != 3 and w.sparse_frac == 0) else
+            "kernel": ("kvs_quantize_kv = keep_index_fast_kernel + quantize_k%s_fast_kernel + quantize_v_fast_kernel"
+                       % ("_token" if w.key_per_token else ""))
+                      if w.sparse_frac == 0 else
                       "kvs_quantize_kv = quantize_k_kernel + quantize_v_kernel + keep rows (+ histogram, scan, CSR fill)",
             "bound": "hbm",
             "achieved": round(qnt_gbps, 2),
@@ -414,6 +456,9 @@ def main() -> int:
     if w.sparse_frac == 0:
         result["growing_cache"] = growing_cache_leg(w, inputs[0], q, dec_bytes)
         result["static_quantisation"] = static_leg(w, inputs, bufs, qnt_bytes)
+        kpt = per_token_key_leg(w, inputs, bufs, q, dec_bytes, qnt_bytes)
+        if kpt is not None:
+            result["per_token_keys"] = kpt
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result))

@@ -261,7 +261,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
 // ---------------------------------------------------------------------------------------------
 // Keys of the per-token scheme (paper, Section 5.1): a Key row is quantised like a Value row,
 // groups of G consecutive channels of one token; the packed words keep the Key layout.  Block =
-// one 64-token code tile; a lane owns channels 8 chunk .. + 7 of rows rslot, rslot + 16, ...
+// two 64-token code tiles; a lane owns channels 8 chunk .. + 7 of rows rslot, rslot + 16, ...
 // ---------------------------------------------------------------------------------------------
 template <int BITS, int G>
 __global__ __launch_bounds__(kThreads) void quantize_k_token_fast_kernel(
@@ -269,17 +269,17 @@ __global__ __launch_bounds__(kThreads) void quantize_k_token_fast_kernel(
     uint32_t* __restrict__ k_codes, uint32_t* __restrict__ k_params, const int32_t* __restrict__ keep_idx,
     const int32_t* __restrict__ keep_cnt, int cap, uint4* __restrict__ keep_k,
     const uint32_t* __restrict__ static_k) {          // [Hkv, 128 / G] fixed parameter words, or null
-  constexpr int TB = KVS_K_TILE;
-  constexpr int ROWS = TB / 16;                 // 4 rows per lane
+  constexpr int TB = 2 * KVS_K_TILE;            // two code tiles per block
+  constexpr int ROWS = TB / 16;                 // 8 rows per lane
   constexpr int LPG = G / 8;                    // lanes per channel group: 4, 8, 16
   constexpr int NGC = 128 / G;
+  constexpr int ROWS_PER_LANE = LPG >= ROWS ? 1 : ROWS / LPG;   // rows whose parameters one lane derives
   constexpr int W = Fmt<BITS>::W;
   constexpr int TILE_STRIDE = 68;
   constexpr int LANES_PER_WORD = BITS == 2 ? 2 : 1;
-  constexpr int kStage = BITS == 3 ? TB * kPieceStride : W * TILE_STRIDE;
-  static_assert(ROWS <= LPG, "lane p of a group derives the parameters of row p");
+  constexpr int kStage = BITS == 3 ? TB * kPieceStride : (TB / KVS_K_TILE) * W * TILE_STRIDE;
 
-  __shared__ __align__(16) uint32_t tile_s[kStage];     // words as [w][token]; 3 bit: pieces [token][16]
+  __shared__ __align__(16) uint32_t tile_s[kStage];     // words as [tile][w][token]; 3 bit: pieces [token][16]
 
   const int tid = threadIdx.x;
   const int lane = tid & (KVS_WAVE - 1);
@@ -318,28 +318,32 @@ __global__ __launch_bounds__(kThreads) void quantize_k_token_fast_kernel(
     stat[i] = s;
   }
 
-  // Lane p of a group derives the parameters of the lane's row p (p < 4); the others fetch them.
+  // Lane p of a group derives the parameters of the lane's rows p, p + LPG, ...; the others fetch them.
   const int p = chunk % LPG;
   const int group_base = lane - p;
-  float inv_mine = 1.0f, zero_mine = 0.0f;
-  if (p < ROWS) {
-    uint32_t s = stat[0];
-    bool k = kept[0];
+  float inv_mine[ROWS_PER_LANE], zero_mine[ROWS_PER_LANE];
 #pragma unroll
-    for (int i = 1; i < ROWS; ++i) { s = p == i ? stat[i] : s; k = p == i ? kept[i] : k; }
+  for (int k = 0; k < ROWS_PER_LANE; ++k) {
+    const int row = p + k * LPG;                // may exceed ROWS - 1 for idle lanes of wide groups
+    uint32_t s = stat[0];
+    bool kp = kept[0];
+#pragma unroll
+    for (int i = 1; i < ROWS; ++i) { s = row == i ? stat[i] : s; kp = row == i ? kept[i] : kp; }
     const Param prm = static_k ? param_of_word(static_k[(bh % Hkv) * NGC + chunk / LPG])
-                               : make_param<BITS>(lo_half(s), -hi_half(s), !k);
-    inv_mine = prm.inv;
-    zero_mine = prm.zero;
-    k_params[(bh * n + static_cast<size_t>(tc0 + rslot + 16 * p)) * NGC + chunk / LPG] = prm.word;
+                               : make_param<BITS>(lo_half(s), -hi_half(s), !kp);
+    inv_mine[k] = prm.inv;
+    zero_mine[k] = prm.zero;
+    if (row < ROWS) k_params[(bh * n + static_cast<size_t>(tc0 + rslot + 16 * row)) * NGC + chunk / LPG] = prm.word;
   }
 
   const int cnt = min(keep_cnt[b], cap);
 #pragma unroll
   for (int i = 0; i < ROWS; ++i) {
     const int r = rslot + 16 * i;
-    const float inv1 = __shfl(inv_mine, group_base + i, KVS_WAVE);
-    const float zero1 = __shfl(zero_mine, group_base + i, KVS_WAVE);
+    const int owner = group_base + (i % LPG);
+    const int k = i / LPG;                      // compile-time after unrolling
+    const float inv1 = __shfl(inv_mine[k < ROWS_PER_LANE ? k : 0], owner, KVS_WAVE);
+    const float zero1 = __shfl(zero_mine[k < ROWS_PER_LANE ? k : 0], owner, KVS_WAVE);
     float inv[8], zero[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) { inv[j] = inv1; zero[j] = zero1; }
@@ -351,7 +355,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_token_fast_kernel(
     if (BITS == 3)
       tile_s[r * kPieceStride + chunk] = word;
     else if (LANES_PER_WORD == 1 || (chunk & 1) == 0)
-      tile_s[(chunk / LANES_PER_WORD) * TILE_STRIDE + r] = word;
+      tile_s[((r / KVS_K_TILE) * W + chunk / LANES_PER_WORD) * TILE_STRIDE + (r % KVS_K_TILE)] = word;
     if (kept[i]) {                              // exact copy of the row into the fp16 side buffer
       const int j = keep_slot(keep_idx + static_cast<size_t>(b) * cap, cnt, tc0 + r);
       if (j >= 0) keep_k[(bh * cap + j) * 16 + chunk] = raw[i];
@@ -359,16 +363,18 @@ __global__ __launch_bounds__(kThreads) void quantize_k_token_fast_kernel(
   }
   __syncthreads();
 
+  // The block's words are contiguous in global memory in (tile, w, t) order: 128-bit stores.
   uint4* out = reinterpret_cast<uint4*>(k_codes + (bh * (n / KVS_K_TILE) + static_cast<size_t>(tc0 / KVS_K_TILE)) * (W * KVS_K_TILE));
-  constexpr int quads = W * (KVS_K_TILE / 4);
+  constexpr int quads = (TB / KVS_K_TILE) * W * (KVS_K_TILE / 4);
   for (int qi = tid; qi < quads; qi += kThreads) {
-    const int w = qi / (KVS_K_TILE / 4), t4 = qi % (KVS_K_TILE / 4);
+    const int row = qi / (KVS_K_TILE / 4), t4 = qi % (KVS_K_TILE / 4);
     if (BITS == 3) {
-      const uint32_t* pc = &tile_s[4 * t4 * kPieceStride];
+      const int tile = row / W, w = row % W;
+      const uint32_t* pc = &tile_s[(tile * KVS_K_TILE + 4 * t4) * kPieceStride];
       store_stream(out + qi, uint4{compose3(pc, w), compose3(pc + kPieceStride, w), compose3(pc + 2 * kPieceStride, w),
                                    compose3(pc + 3 * kPieceStride, w)});
     } else {
-      store_stream(out + qi, *reinterpret_cast<const uint4*>(&tile_s[w * TILE_STRIDE + 4 * t4]));
+      store_stream(out + qi, *reinterpret_cast<const uint4*>(&tile_s[row * TILE_STRIDE + 4 * t4]));
     }
   }
 }
@@ -664,7 +670,7 @@ void launch_fast(const kvs_desc* d, const kvs::QuantSpan& sp, bool own_keep, con
                        static_cast<uint4*>(out->keep_v));
   if (sp.n_tokens == 0) return;
   if (d->key_per_token)
-    hipLaunchKernelGGL((quantize_k_token_fast_kernel<BITS, G>), dim3(bh * (sp.n_tokens / KVS_K_TILE)), dim3(kThreads), 0, s,
+    hipLaunchKernelGGL((quantize_k_token_fast_kernel<BITS, G>), dim3(bh * (sp.n_tokens / (2 * KVS_K_TILE))), dim3(kThreads), 0, s,
                        static_cast<const uint4*>(K), mask, sp, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
                        out->keep_cnt, cap, static_cast<uint4*>(out->keep_k), static_k);
   else
