@@ -48,6 +48,9 @@ Readings taken where the paper is silent (every one is restated in the design no
       exactly like a Value row - groups of G consecutive channels of one token - and only the
       parameter array changes shape ([B, Hkv, n, D/G]); the packed Key codes keep their layout.
       With static parameters that is one pair per Key channel group of a KV head.
+  R16 error report (the structure of Table 1): squared error of every cache entry of a non-kept
+      token, summed separately over quantisation groups that contain a flagged (sink) token and
+      groups that do not (see ``quant_error``).
 
 PPL / MSE figures of the paper need model weights and datasets: parity unpinned for those
 (nothing here reproduces them).  Every function below is pinned by tests/test_oracle_*.py.
@@ -668,6 +671,40 @@ def quantize_kv_static(K: np.ndarray, V: np.ndarray, keep_mask: np.ndarray, bits
             dyn.k_params[b, h] = np.broadcast_to(np.asarray(k_static, np.uint32)[h][None, :], dyn.k_params[b, h].shape)
             dyn.v_params[b, h] = np.broadcast_to(np.asarray(v_static, np.uint32)[h][None, :], (n, D // group))
     return dyn
+
+
+# ----------------------------------------------------------------------------------------
+# Quantisation-error report (Section 4.1, Table 1: mean squared error of the quantised Keys and
+# Values, overall and split into the quantisation groups that contain a sink token and those that
+# do not).  Reading R16: the error of an entry is x - x' with x' what the decode step sees; entries
+# of kept tokens are stored exactly and are left out of sums and counts; a per-channel Key group
+# (G consecutive tokens of one channel) "contains a sink" if any of its tokens is flagged in
+# ``sink_mask``, a per-token group (G channels of one token) if its token is.  ``sink_mask`` only
+# classifies: whether the flagged tokens were kept or quantised is the cache's business.
+# ----------------------------------------------------------------------------------------
+def quant_error(K: np.ndarray, V: np.ndarray, cache: Cache, sink_mask: np.ndarray):
+    """-> {"k": (sse_without, n_without, sse_with, n_with), "v": (...)}: sums of squared errors
+    (float64) and entry counts (int) over the two classes of groups."""
+    K, V = np.asarray(K), np.asarray(V)
+    B, H, n, D = K.shape
+    G = cache.group
+    flagged = np.asarray(sink_mask) != 0                                        # [B, n]
+    in_group = flagged.reshape(B, n // G, G).any(axis=2).repeat(G, axis=1)      # token's Key group holds a sink
+    counted = cache.keep_mask == 0
+    out = {}
+    for name, X, cls in (("k", K, flagged if cache.key_per_token else in_group), ("v", V, flagged)):
+        sse = [0.0, 0.0]
+        cnt = [0, 0]
+        for b in range(B):
+            for h in range(H):
+                Kd, Vd = effective_kv(cache, b, h)
+                err = X[b, h].astype(np.float64) - (Kd if name == "k" else Vd)
+                for c in (0, 1):
+                    rows = counted[b] & (cls[b] == bool(c))
+                    sse[c] += float((err[rows] ** 2).sum())
+                    cnt[c] += int(rows.sum()) * D
+        out[name] = (sse[0], cnt[0], sse[1], cnt[1])
+    return out
 
 
 # ----------------------------------------------------------------------------------------
