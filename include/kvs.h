@@ -243,6 +243,25 @@ kvs_status kvs_quantize_kv_static(const kvs_desc* desc, const void* K, const voi
                                   const uint32_t* v_static, const kvs_cache* out, void* workspace,
                                   void* stream);
 
+/*
+ * Quantisation-error report with the structure of the paper's Table 1 (Section 4.1): for Keys and
+ * for Values, the sum of squared errors x - scale * (code - zero) and the number of entries, split
+ * into the quantisation groups that contain a flagged token and those that do not.  Entries of
+ * kept tokens (cache->keep_mask) are stored exactly and are left out.  A per-channel Key group
+ * (G consecutive tokens of one channel) counts as flagged if any of its tokens is; a per-token
+ * group (Values; Keys with desc->key_per_token) if its token is.
+ *   K, V       fp16 [B, Hkv, n, 128], the tensors `cache` was quantised from (kvs_quantize_kv or
+ *              kvs_quantize_kv_static with this desc)
+ *   sink_mask  uint8 [B, n]: the tokens that classify the groups (nonzero = flagged); it need not
+ *              be the mask the cache was built with
+ *   report     DEVICE, 64 bytes, overwritten: double sse[2][2] then uint64 count[2][2], indexed
+ *              [0 Keys / 1 Values][0 groups without / 1 groups with a flagged token]
+ * The squared differences are formed and summed in fp64; the order of the sums varies from run to
+ * run (atomics), so results agree to ~1e-12 relative, not bit for bit.  Not with sparse_frac > 0.
+ */
+kvs_status kvs_quant_error(const kvs_desc* desc, const void* K, const void* V, const kvs_cache* cache,
+                           const uint8_t* sink_mask, void* report, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

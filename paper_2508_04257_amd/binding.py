@@ -93,6 +93,9 @@ def lib() -> C.CDLL:
         L.kvs_quantize_kv_static.restype = C.c_int
         L.kvs_quantize_kv_static.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                              C.c_void_p, C.POINTER(KvsCache), C.c_void_p, C.c_void_p]
+        L.kvs_quant_error.restype = C.c_int
+        L.kvs_quant_error.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p, C.POINTER(KvsCache), C.c_void_p,
+                                      C.c_void_p, C.c_void_p]
         L.kvs_decode_attn.restype = C.c_int
         L.kvs_decode_attn.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.POINTER(KvsCache), C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p]
@@ -329,3 +332,22 @@ def kvs_quantize_kv_static(desc: KvsDesc, K: torch.Tensor, V: torch.Tensor, keep
                                       _ptr(workspace), _stream_handle())
     if st != KVS_OK:
         raise KvsError("kvs_quantize_kv_static", st)
+
+
+def kvs_quant_error(desc: KvsDesc, K: torch.Tensor, V: torch.Tensor, cache: CacheBuffers,
+                    sink_mask: torch.Tensor) -> Dict[str, tuple]:
+    """-> {"k": (sse_without, n_without, sse_with, n_with), "v": (...)} (synchronises)."""
+    shape = (desc.B, desc.Hkv, desc.n, desc.D)
+    _check_tensor("K", K, shape, torch.float16)
+    _check_tensor("V", V, shape, torch.float16)
+    _check_tensor("sink_mask", sink_mask, (desc.B, desc.n), torch.uint8)
+    _check_cache(desc, cache)
+    report = torch.empty(8, dtype=torch.int64, device=K.device)
+    st = lib().kvs_quant_error(C.byref(desc), K.data_ptr(), V.data_ptr(), C.byref(cache.struct), sink_mask.data_ptr(),
+                               report.data_ptr(), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_quant_error", st)
+    host = report.cpu()
+    sse = host[:4].view(torch.float64).tolist()
+    cnt = host[4:].tolist()
+    return {"k": (sse[0], cnt[0], sse[1], cnt[1]), "v": (sse[2], cnt[2], sse[3], cnt[3])}

@@ -24,6 +24,7 @@ SOURCES = {
     "quantize_fast.hip": ["-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt"],
     "sparse.hip": [],
     "decode.hip": [],
+    "error_report.hip": ["-ffp-contract=off"],
     "decode_sparse.hip": [],
     "decode_mfma.hip": [],
     "decode_mfma_b2.hip": [],

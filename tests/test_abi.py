@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
     assert {"kvs_predict_sinks", "kvs_quantize_kv", "kvs_decode_attn", "kvs_cache_bytes",
             "kvs_workspace_bytes", "kvs_quantize_prefix", "kvs_append_kv", "kvs_decode_attn_n",
             "kvs_calibrate", "kvs_calibrate_reset", "kvs_static_params", "kvs_quantize_kv_static",
-            "kvs_calibration_bytes"} <= set(names)
+            "kvs_calibration_bytes", "kvs_quant_error"} <= set(names)
     L = kb.lib()
     for name in names:
         assert hasattr(L, name), name
