@@ -47,6 +47,8 @@ class Workload:
     first_n: int = 0          # Preserve-First-N part of the keep set
     sparse_frac: float = 0.0  # dense-and-sparse fp16 outlier fraction
     key_per_token: bool = False   # per-token Keys (the other Key scheme of Section 5.1)
+    key_channel_offset: float = 0.0   # mean of the Key outlier channels (0: centred, as in the benchmark workloads)
+    sink_kv_spike: float = 0.0        # magnitude of two spike channels in the sink tokens' K / V rows (0: none)
     layers: int = 1
     student_t: bool = False   # heavy-tailed K/V (Student-t, nu = 4) instead of N(0,1)
     d_hidden: int = LLAMA2_7B_HIDDEN
@@ -128,8 +130,9 @@ def make_kv(w: Workload, device="cpu", layer: int = 0,
             sinks: np.ndarray | None = None) -> Tuple[torch.Tensor, torch.Tensor]:
     """K, V fp16 [B, Hkv, n, D] of one layer.
 
-    N(0,1) (or Student-t with 4 degrees of freedom), four key channels per head x10, and the
-    K/V rows of the sink tokens x0.1.
+    N(0,1) (or Student-t with 4 degrees of freedom), four key channels per head x10 (plus an
+    optional mean, so that a suppressed sink row lies outside the other tokens' range in those
+    channels), and the K/V rows of the sink tokens x0.1.
     """
     sinks = sink_positions(w) if sinks is None else sinks
     shape = (w.B, w.Hkv, w.n, w.D)
@@ -146,9 +149,16 @@ def make_kv(w: Workload, device="cpu", layer: int = 0,
         if tensor_id == 0:
             ch = key_outlier_channels(w)
             for h in range(w.Hkv):
-                X[:, h, :, torch.as_tensor(ch[h], device=X.device)] *= KEY_CHANNEL_SCALE
+                cols = torch.as_tensor(ch[h], device=X.device)
+                X[:, h, :, cols] *= KEY_CHANNEL_SCALE
+                if w.key_channel_offset:
+                    X[:, h, :, cols] += w.key_channel_offset
         for b in range(w.B):
-            X[b, :, torch.as_tensor(sinks[b], device=X.device), :] *= SINK_ROW_SCALE
+            rows = torch.as_tensor(sinks[b], device=X.device)
+            X[b, :, rows, :] *= SINK_ROW_SCALE
+            if w.sink_kv_spike:                      # a suppressed row with two extreme entries
+                X[b, :, rows, 17] = w.sink_kv_spike
+                X[b, :, rows, 101] = -w.sink_kv_spike
         # fp16 inputs must be finite (a precondition of the library); the heavy tail could overflow.
         out.append(X.clamp_(-60000.0, 60000.0).to(torch.float16))
         del X
