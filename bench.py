@@ -443,7 +443,7 @@ def main() -> int:
             "kernel": ("kvs_quantize_kv = keep_index_fast_kernel + quantize_k%s_fast_kernel + quantize_v_fast_kernel"
                        % ("_token" if w.key_per_token else ""))
                       if w.sparse_frac == 0 else
-                      "kvs_quantize_kv = quantize_k_kernel + quantize_v_kernel + keep rows (+ histogram, scan, CSR fill)",
+                      "kvs_quantize_kv = sparse_hist_kernel x2 + quantize_{k,v}_fast_kernel<SPARSE> + scan + csr_move_kernel",
             "bound": "hbm",
             "achieved": round(qnt_gbps, 2),
             "peak": HBM_PEAK_GBPS,

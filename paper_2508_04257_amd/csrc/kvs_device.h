@@ -70,12 +70,13 @@ struct QuantSpan {
 };
 inline QuantSpan whole_span(const kvs_desc* d) { return QuantSpan{d->n, d->n, d->n, 0, d->n, 0}; }
 
-// Lean 2 / 4 bit dense quantisation kernels (quantize_fast.hip).  own_keep: also build the keep
-// index and copy the kept rows (a plain call); otherwise the caller does both.
-bool quantize_fast_supported(const kvs_desc* d);
+// Lean quantisation kernels (quantize_fast.hip), every bit width; with `plan` (dense-and-sparse)
+// they also mark the isolated entries and park them in the plan's staging lists.  own_keep: also
+// build the keep index and copy the kept rows (a plain call); otherwise the caller does both.
+struct SparsePlan;
 void launch_quantize_fast(const kvs_desc* d, const QuantSpan& sp, bool own_keep, const void* K, const void* V,
                           const uint8_t* mask, const kvs_cache* out, const uint32_t* static_k, const uint32_t* static_v,
-                          hipStream_t s);
+                          const SparsePlan* plan, hipStream_t s);
 // Static quantisation: calibration state [4][Hkv][128] uint32 (order-preserving float encoding).
 void launch_calibrate_reset(const kvs_desc* d, uint32_t* calib, hipStream_t s);
 void launch_calibrate(const kvs_desc* d, const void* K, const void* V, const uint8_t* mask, uint32_t* calib, hipStream_t s);

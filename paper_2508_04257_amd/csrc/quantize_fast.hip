@@ -1,10 +1,10 @@
-// Lean quantisation kernels for the dense (no isolated outliers) case of
-// kvs_quantize_kv (paper, Appendix C equations; Algorithm 1's two quantise steps).  Same results
-// bit for bit as the general kernels of quantize.hip, which also cover the dense-and-sparse
-// variant; these exist because the general ones spend ~17 vector instructions per element and
-// are bound by the ALU, not by the 2-byte-per-element fp16 read.
+// The quantisation kernels of kvs_quantize_kv and the calls built on it (paper, Appendix C
+// equations for Q(X), scale and zero; Algorithm 1's two quantise steps; Section 4.1 for the
+// per-channel Key / per-token Value grouping; Section 5.1 for the per-token Key scheme and the
+// dense-and-sparse variant).  One pass over the fp16 tensors, bound by that 2-byte-per-element
+// read; the quantiser arithmetic is the exact fp32 sequence the ABI header documents.
 //
-// What is different here:
+// How the work is laid out:
 //   * group minima / maxima are taken on the raw fp16 pairs (v_pk_min_f16 / v_pk_max_f16): the
 //     minimum of the fp16 values converted to fp32 is the converted fp16 minimum;
 //   * one lane per group derives scale / zero (two IEEE divisions) and the others receive them;
@@ -14,8 +14,12 @@
 //     through a padded LDS tile so that the global stores are contiguous.
 //   * 3 bit: ten codes per word do not line up with eight-element lanes, so a lane first makes a
 //     24-bit piece (eight codes) and the words are cut out of the row's sixteen pieces in LDS;
-//   * rows of kept tokens go straight from registers to the fp16 side buffer.
-// Compiled with floating-point contraction off and correctly rounded division, like quantize.hip.
+//   * rows of kept tokens go straight from registers to the fp16 side buffer;
+//   * SPARSE variants: entries at or above the threshold are marked with packed 16-bit
+//     arithmetic, leave the statistics, get code 0, and are written - by the lane that holds them,
+//     in final order - to the workgroup's run of a staging list (see the helpers below).
+// Compiled with floating-point contraction off and correctly rounded division, so that no
+// multiply-add fuses across the quantiser's operations.
 #include "kvs_device.h"
 
 namespace {
@@ -118,6 +122,63 @@ __device__ inline uint32_t compose3(const uint32_t* pieces, int w) {
   return static_cast<uint32_t>(x & 0x7FFFu) | (static_cast<uint32_t>((x >> 15) & 0x7FFFu) << 16);
 }
 
+// Dense-and-sparse support (paper, Section 5.1: the largest-magnitude entries are isolated in
+// 16 bit).  An entry whose fp16 magnitude pattern reaches tau leaves the statistics, gets code 0
+// and is recorded in a bit mask per CSR row; the masks then drive the emission.
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+typedef short short2v __attribute__((ext_vector_type(2)));
+// 0xFFFF in every half of w whose magnitude pattern is below tau (tau2 = tau in both halves,
+// tau <= 0x8000), 0 in the others.
+__device__ inline uint32_t below_mask(uint32_t w, uint32_t tau2) {
+  const ushort2v d = __builtin_bit_cast(ushort2v, w & 0x7FFF7FFFu) - __builtin_bit_cast(ushort2v, tau2);
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2v, d) >> 15);
+}
+__device__ inline uint32_t select_halves(uint32_t m, uint32_t a, uint32_t b) { return (a & m) | (b & ~m); }
+// Bit j = element j of the uint4 (eight halves) is at or above tau.  Each mask contributes the
+// two bits of its pair: the low half's at bit 2 k, the high half's at bit 16 + 2 k + 1.
+__device__ inline uint32_t isolated8(const uint32_t m[4]) {
+  uint32_t x = m[0] & 0x00020001u;
+  x |= m[1] & 0x00080004u;
+  x |= m[2] & 0x00200010u;
+  x |= m[3] & 0x00800040u;
+  return ((x | (x >> 16)) & 0xFFu) ^ 0xFFu;
+}
+// Field mask of a lane's eight codes: bit j of `bits` -> the BITS-wide field of code j.
+template <int BITS>
+__device__ inline void fill_spread_table(uint32_t* table, int tid) {
+  if (tid < 256) {
+    uint32_t m = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) m |= ((tid >> j) & 1) ? static_cast<uint32_t>(Fmt<BITS>::qmax) << (BITS * j) : 0u;
+    table[tid] = m;
+  }
+}
+// Transpose of an 8 x 8 bit matrix held as row i = byte i (lo: rows 0-3, hi: rows 4-7), bit j = column j.
+__device__ inline void transpose8x8(uint32_t& lo, uint32_t& hi) {
+  unsigned long long x = static_cast<unsigned long long>(lo) | (static_cast<unsigned long long>(hi) << 32);
+  unsigned long long t;
+  t = 0x0F0F0F0F00000000ull & (x ^ (x << 28)); x ^= t ^ (t >> 28);
+  t = 0x3333000033330000ull & (x ^ (x << 14)); x ^= t ^ (t >> 14);
+  t = 0x5500550055005500ull & (x ^ (x << 7));  x ^= t ^ (t >> 7);
+  lo = static_cast<uint32_t>(x);
+  hi = static_cast<uint32_t>(x >> 32);
+}
+
+// Number of set bits of a 128-bit mask row (four words) below byte `byte` (0 .. 15).
+__device__ inline int bits_below_byte(const uint32_t* row, int byte) {
+  const uint4 m = *reinterpret_cast<const uint4*>(row);
+  const int q = byte >> 2;
+  int pre = (q > 0 ? __popc(m.x) : 0) + (q > 1 ? __popc(m.y) : 0) + (q > 2 ? __popc(m.z) : 0);
+  const uint32_t wq = q == 0 ? m.x : (q == 1 ? m.y : (q == 2 ? m.z : m.w));
+  return pre + __popc(wq & ((1u << (8 * (byte & 3))) - 1u));
+}
+// Half j (0 .. 7) of a uint4 of fp16 values, j known only at run time.
+__device__ inline uint32_t half_of(const uint4& v, int j) {
+  const int k = j >> 1;
+  const uint32_t w = k == 0 ? v.x : (k == 1 ? v.y : (k == 2 ? v.z : v.w));
+  return (j & 1) ? w >> 16 : w & 0xFFFFu;
+}
+
 // Slot of token t in the ascending keep list of its sequence, or -1.
 __device__ inline int keep_slot(const int32_t* __restrict__ keep_idx, int cnt, int t) {
   for (int j = 0; j < cnt; ++j)
@@ -128,12 +189,13 @@ __device__ inline int keep_slot(const int32_t* __restrict__ keep_idx, int cnt, i
 // ---------------------------------------------------------------------------------------------
 // Keys: per channel, groups of G consecutive tokens.  Block = TB = max(G, 64) tokens.
 // ---------------------------------------------------------------------------------------------
-template <int BITS, int G>
+template <int BITS, int G, bool SPARSE>
 __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
     const uint4* __restrict__ K, const uint8_t* __restrict__ keep_mask, kvs::QuantSpan sp, int Hkv,
     uint32_t* __restrict__ k_codes, uint32_t* __restrict__ k_params, const int32_t* __restrict__ keep_idx,
     const int32_t* __restrict__ keep_cnt, int cap, uint4* __restrict__ keep_k,
-    const uint32_t* __restrict__ static_k) {          // [Hkv, 128] fixed parameter words, or null
+    const uint32_t* __restrict__ static_k,            // [Hkv, 128] fixed parameter words, or null
+    const uint32_t* __restrict__ tau_ptr, int32_t* __restrict__ row_count, kvs::SparseEmit emit) {   // SPARSE only
   constexpr int TB = G > 64 ? G : 64;
   constexpr int NG = TB / G;
   constexpr int ROWS = TB / 16;
@@ -148,10 +210,23 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
   __shared__ float inv_s[NG][128];
   __shared__ float zero_s[NG][128];
   __shared__ __align__(16) uint32_t tile_s[kStage];     // words as [tile][w][token]; 3 bit: pieces [token][16]
+  // SPARSE: which entries of each row are isolated (128 bits per row = CSR row (b, h, token)),
+  // where the row's entries start inside the block's run, where that run starts in the staging
+  // list, and the field masks that clear the codes of isolated entries.
+  __shared__ uint32_t iso_s[SPARSE ? TB : 1][4];
+  __shared__ int row_off_s[SPARSE ? TB : 1];
+  __shared__ int run_base_s;
+  __shared__ uint32_t spread_s[SPARSE ? 256 : 1];
 
   const int tid = threadIdx.x;
   const int chunk = tid & 15;
   const int rslot = tid >> 4;
+  uint32_t tau2 = 0;
+  if (SPARSE) {
+    const uint32_t tau = *tau_ptr;                 // 0x8000: no magnitude pattern reaches it
+    tau2 = tau | (tau << 16);
+    fill_spread_table<BITS>(spread_s, tid);
+  }
   const int blocks_per_head = sp.n_tokens / TB;
   const int blk = blockIdx.x % blocks_per_head;
   const size_t bh = blockIdx.x / blocks_per_head;
@@ -173,6 +248,8 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
 
   // Lane-local packed minima / maxima per group over the rows that are not kept.
   bool any_g[NG];                               // does any token of the group survive?
+  uint32_t iso8[SPARSE ? ROWS : 1];             // SPARSE: isolated entries of the lane's piece of each row
+  int run_claim = 0;                            // SPARSE, last lane: start of the block's run in the staging list
 #pragma unroll
   for (int g = 0; g < NG; ++g) {
     uint32_t mn[4] = {kPosMax2, kPosMax2, kPosMax2, kPosMax2};
@@ -180,7 +257,22 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
     bool any = false;
 #pragma unroll
     for (int i = g * RPG; i < (g + 1) * RPG; ++i) {
-      if (!kept[i]) {
+      if (SPARSE) {
+        const uint32_t w4[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
+        uint32_t m[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) m[k] = below_mask(w4[k], tau2);
+        iso8[i] = kept[i] ? 0u : isolated8(m);
+        if (!kept[i]) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            mn[k] = pk_min(mn[k], select_halves(m[k], w4[k], kPosMax2));
+            mx[k] = pk_max(mx[k], select_halves(m[k], w4[k], kNegMax2));
+          }
+          any = true;
+        }
+        reinterpret_cast<uint8_t*>(&iso_s[0][0])[(rslot + 16 * i) * 16 + chunk] = static_cast<uint8_t>(iso8[i]);
+      } else if (!kept[i]) {
         mn[0] = pk_min(mn[0], raw[i].x); mn[1] = pk_min(mn[1], raw[i].y);
         mn[2] = pk_min(mn[2], raw[i].z); mn[3] = pk_min(mn[3], raw[i].w);
         mx[0] = pk_max(mx[0], raw[i].x); mx[1] = pk_max(mx[1], raw[i].y);
@@ -205,6 +297,9 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
       const uint2 w = reinterpret_cast<const uint2*>(static_k + (bh % Hkv) * 128)[cp];
       p0 = param_of_word(w.x);
       p1 = param_of_word(w.y);
+    } else if (SPARSE) {                          // a channel can lose every entry of the group to the CSR
+      p0 = make_param<BITS>(lo_half(a), lo_half(z), any && lo_half(a) <= lo_half(z));
+      p1 = make_param<BITS>(hi_half(a), hi_half(z), any && hi_half(a) <= hi_half(z));
     } else {
       p0 = make_param<BITS>(lo_half(a), lo_half(z), any);
       p1 = make_param<BITS>(hi_half(a), hi_half(z), any);
@@ -212,6 +307,30 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
     inv_s[g][2 * cp] = p0.inv;  inv_s[g][2 * cp + 1] = p1.inv;
     zero_s[g][2 * cp] = p0.zero;  zero_s[g][2 * cp + 1] = p1.zero;
     reinterpret_cast<uint2*>(k_params + (bh * (n / G) + static_cast<size_t>(tc0 / G + g)) * 128)[cp] = uint2{p0.word, p1.word};
+  }
+  if (SPARSE && tid >= kThreads - KVS_WAVE) {
+    // Meanwhile the last wave: row counts (CSR row = token), their exclusive scan over the block,
+    // and one claim in the staging list for the block's whole run.
+    const int lane = tid - (kThreads - KVS_WAVE);
+    int cnt[TB / KVS_WAVE], mine = 0;
+#pragma unroll
+    for (int k = 0; k < TB / KVS_WAVE; ++k) {
+      const int r = lane * (TB / KVS_WAVE) + k;
+      cnt[k] = __popc(iso_s[r][0]) + __popc(iso_s[r][1]) + __popc(iso_s[r][2]) + __popc(iso_s[r][3]);
+      row_count[bh * n + tc0 + r] = cnt[k];
+      mine += cnt[k];
+    }
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < KVS_WAVE; o <<= 1) {
+      const int up = __shfl_up(incl, o, KVS_WAVE);
+      if (lane >= o) incl += up;
+    }
+    int run = incl - mine;
+#pragma unroll
+    for (int k = 0; k < TB / KVS_WAVE; ++k) { row_off_s[lane * (TB / KVS_WAVE) + k] = run; run += cnt[k]; }
+    // requested now, needed only when the entries are written out
+    if (lane == KVS_WAVE - 1 && incl > 0) run_claim = atomicAdd(emit.counter, incl);
   }
   __syncthreads();
 
@@ -226,6 +345,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
     for (int i = g * RPG; i < (g + 1) * RPG; ++i) {
       const int r = rslot + 16 * i;
       uint32_t word = kept[i] ? 0u : codes8<BITS>(raw[i], inv, zero);
+      if (SPARSE) word &= ~spread_s[iso8[i]];     // isolated entries hold code 0
       if (LANES_PER_WORD == 2) {                  // 2 bit: lanes (even, odd) share a word
         const uint32_t other = static_cast<uint32_t>(__shfl_xor(static_cast<int>(word), 1, KVS_WAVE));
         word = word | (other << 16);
@@ -240,7 +360,31 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
       }
     }
   }
+  if (SPARSE && tid == kThreads - 1) {            // the claim has had the whole code phase to return
+    emit.block_base[blockIdx.x] = run_claim;
+    run_base_s = run_claim;
+  }
   __syncthreads();
+
+  if (SPARSE) {
+    // Isolated entries to the block's run of the staging list, in final order (rows ascending,
+    // channels ascending inside a row): the lane that holds an entry writes it from its
+    // registers; its place is the row's start plus the entries of the row to its left.
+    const int run_base = run_base_s;
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) {
+      uint32_t bits = iso8[i];
+      if (bits == 0) continue;
+      const int r = rslot + 16 * i;
+      long long pos = static_cast<long long>(run_base) + row_off_s[r] + bits_below_byte(&iso_s[r][0], chunk);
+      while (bits) {
+        const int j = __builtin_ctz(bits);
+        bits &= bits - 1;
+        if (pos < emit.cap) emit.list[pos] = static_cast<uint32_t>(8 * chunk + j) | (half_of(raw[i], j) << 16);
+        ++pos;
+      }
+    }
+  }
 
   // The block's words are contiguous in global memory in (tile, w, t) order: 128-bit stores.
   uint4* out = reinterpret_cast<uint4*>(k_codes + (bh * (n / KVS_K_TILE) + static_cast<size_t>(tc0 / KVS_K_TILE)) * (W * KVS_K_TILE));
@@ -383,13 +527,20 @@ __global__ __launch_bounds__(kThreads) void quantize_k_token_fast_kernel(
 // Values: per token, groups of G consecutive channels.  Block = one 128-token tile; a lane owns
 // tokens 8 rs .. 8 rs + 7 and channels 8 chunk .. 8 chunk + 7.
 // ---------------------------------------------------------------------------------------------
-template <int BITS, int G>
+template <int BITS, int G, bool SPARSE>
 __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
     const uint4* __restrict__ V, const uint8_t* __restrict__ keep_mask, kvs::QuantSpan sp, int Hkv,
     uint32_t* __restrict__ v_codes, uint32_t* __restrict__ v_params, const int32_t* __restrict__ keep_idx,
     const int32_t* __restrict__ keep_cnt, int cap, uint4* __restrict__ keep_v,
-    const uint32_t* __restrict__ static_v) {          // [Hkv, 128 / G] fixed parameter words, or null
+    const uint32_t* __restrict__ static_v,            // [Hkv, 128 / G] fixed parameter words, or null
+    const uint32_t* __restrict__ tau_ptr, int32_t* __restrict__ row_count, kvs::SparseEmit emit) {   // SPARSE only
   constexpr int W = Fmt<BITS>::W;
+  // SPARSE: which tokens of each channel are isolated (128 bits per channel = CSR row (b, h, tile,
+  // channel)), where the channel's entries start inside the tile's run, where the run starts.
+  __shared__ uint32_t iso_s[SPARSE ? 128 : 1][4];
+  __shared__ int chan_off_s[SPARSE ? 128 : 1];
+  __shared__ int run_base_s;
+  __shared__ uint32_t spread_s[SPARSE ? 256 : 1];
   constexpr int LPG = G / 8;                    // lanes per channel group: 4, 8, 16
   constexpr int NGC = 128 / G;
   constexpr int ROWS_PER_LANE = LPG >= 8 ? 1 : 8 / LPG;   // rows whose parameters one lane derives
@@ -421,19 +572,77 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
 #pragma unroll
   for (int i = 0; i < 8; ++i) raw[i] = load_stream(src + i * 16);
 
+  uint32_t tau2 = 0;
+  if (SPARSE) {
+    const uint32_t tau = *tau_ptr;                 // 0x8000: no magnitude pattern reaches it
+    tau2 = tau | (tau << 16);
+    fill_spread_table<BITS>(spread_s, tid);
+  }
+  uint32_t iso_lo = 0, iso_hi = 0;                // SPARSE: byte i = isolated channels of the lane's token i;
+  uint32_t row_lo = 0, row_hi = 0;                // after the transposition byte j = isolated tokens of channel j
+  int run_claim = 0;                              // SPARSE, last lane: start of the tile's run in the staging list
+
   // (min, -max) of the lane's 8 values of each row as one packed pair, then across the group's
   // lanes: one packed minimum per step does both.
   uint32_t stat[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const uint32_t mn2 = pk_min(pk_min(raw[i].x, raw[i].y), pk_min(raw[i].z, raw[i].w));
-    const uint32_t mx2 = pk_max(pk_max(raw[i].x, raw[i].y), pk_max(raw[i].z, raw[i].w));
+    uint32_t a4[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};   // operands of the minimum
+    uint32_t z4[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};   // operands of the maximum
+    if (SPARSE) {
+      uint32_t m[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        m[k] = below_mask(a4[k], tau2);
+        z4[k] = select_halves(m[k], a4[k], kNegMax2);
+        a4[k] = select_halves(m[k], a4[k], kPosMax2);
+      }
+      const bool kept_i = ((i < 4 ? mask8.x >> (8 * i) : mask8.y >> (8 * (i - 4))) & 0xFFu) != 0;
+      const uint32_t bits = kept_i ? 0u : isolated8(m);
+      if (i < 4) iso_lo |= bits << (8 * i); else iso_hi |= bits << (8 * (i - 4));
+    }
+    const uint32_t mn2 = pk_min(pk_min(a4[0], a4[1]), pk_min(a4[2], a4[3]));
+    const uint32_t mx2 = pk_max(pk_max(z4[0], z4[1]), pk_max(z4[2], z4[3]));
     const uint32_t mn1 = pk_min(mn2, mn2 >> 16) & 0xFFFFu;
     const uint32_t mx1 = pk_max(mx2, mx2 >> 16) & 0xFFFFu;
     uint32_t s = mn1 | ((mx1 ^ 0x8000u) << 16);
 #pragma unroll
     for (int o = 1; o < LPG; o <<= 1) s = pk_min(s, static_cast<uint32_t>(__shfl_xor(static_cast<int>(s), o, KVS_WAVE)));
     stat[i] = s;
+  }
+
+  if (SPARSE) {
+    // Channel-major masks: byte rs of channel 8 chunk + j = which of the lane's eight tokens are
+    // isolated in that channel.  Then the last wave turns them into channel counts (CSR row =
+    // (tile, channel)), scans them over the tile and claims the tile's run in the staging list.
+    row_lo = iso_lo;  row_hi = iso_hi;
+    transpose8x8(iso_lo, iso_hi);
+    uint8_t* iso_b = reinterpret_cast<uint8_t*>(&iso_s[0][0]);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      iso_b[(8 * chunk + j) * 16 + rs] = static_cast<uint8_t>((j < 4 ? iso_lo >> (8 * j) : iso_hi >> (8 * (j - 4))) & 0xFFu);
+    __syncthreads();
+    if (tid >= kThreads - KVS_WAVE) {
+      const int sl = tid - (kThreads - KVS_WAVE);
+      int cnt[2], mine = 0;
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int c = 2 * sl + k;
+        cnt[k] = __popc(iso_s[c][0]) + __popc(iso_s[c][1]) + __popc(iso_s[c][2]) + __popc(iso_s[c][3]);
+        row_count[(bh * tiles_per_head + static_cast<size_t>(tile)) * 128 + c] = cnt[k];
+        mine += cnt[k];
+      }
+      int incl = mine;
+#pragma unroll
+      for (int o = 1; o < KVS_WAVE; o <<= 1) {
+        const int up = __shfl_up(incl, o, KVS_WAVE);
+        if (sl >= o) incl += up;
+      }
+      chan_off_s[2 * sl] = incl - mine;
+      chan_off_s[2 * sl + 1] = incl - mine + cnt[0];
+      // requested now, needed only when the entries are written out
+      if (sl == KVS_WAVE - 1 && incl > 0) run_claim = atomicAdd(emit.counter, incl);
+    }
   }
 
   // Lane p of a group derives the parameters of rows p, p + LPG, ...; the others fetch them.
@@ -447,8 +656,10 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
 #pragma unroll
     for (int i = 1; i < 8; ++i) s = row == i ? stat[i] : s;
     const bool kept = row < 8 && ((row < 4 ? mask8.x >> (8 * row) : mask8.y >> (8 * (row - 4))) & 0xFFu) != 0;
+    // SPARSE: a group can lose every entry to the CSR
+    const bool any = !kept && (!SPARSE || lo_half(s) <= -hi_half(s));
     const Param prm = static_v ? param_of_word(static_v[(bh % Hkv) * NGC + chunk / LPG])
-                               : make_param<BITS>(lo_half(s), -hi_half(s), !kept);
+                               : make_param<BITS>(lo_half(s), -hi_half(s), any);
     inv_mine[k] = prm.inv;
     zero_mine[k] = prm.zero;
     if (row < 8) v_params[(bh * n + static_cast<size_t>(t0 + 8 * rs + row)) * NGC + chunk / LPG] = prm.word;
@@ -475,6 +686,33 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
     } else {
       const int j = keep_slot(keep_idx + static_cast<size_t>(b) * cap, cnt, t0 + 8 * rs + i);
       if (j >= 0) keep_v[(bh * cap + j) * 16 + chunk] = raw[i];
+    }
+  }
+  if (SPARSE) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)                   // isolated entries hold code 0
+      words[j] &= ~spread_s[(j < 4 ? iso_lo >> (8 * j) : iso_hi >> (8 * (j - 4))) & 0xFFu];
+    // Isolated entries to the tile's run of the staging list in final order (channels ascending,
+    // tokens ascending inside a channel): the lane that holds an entry writes it from its
+    // registers; its place is the channel's start plus the channel's entries at earlier tokens.
+    if (tid == kThreads - 1) {                    // the claim has had the whole code phase to return
+      emit.block_base[blockIdx.x] = run_claim;
+      run_base_s = run_claim;
+    }
+    __syncthreads();
+    const int run_base = run_base_s;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      uint32_t bits = (i < 4 ? row_lo >> (8 * i) : row_hi >> (8 * (i - 4))) & 0xFFu;   // channels of token 8 rs + i
+      while (bits) {
+        const int j = __builtin_ctz(bits);
+        bits &= bits - 1;
+        const int c = 8 * chunk + j;
+        const uint32_t tokens = (j < 4 ? iso_lo >> (8 * j) : iso_hi >> (8 * (j - 4))) & 0xFFu;   // the lane's tokens of channel c
+        const long long pos = static_cast<long long>(run_base) + chan_off_s[c] + bits_below_byte(&iso_s[c][0], rs) +
+                              __popc(tokens & ((1u << i) - 1u));
+        if (pos < emit.cap) emit.list[pos] = static_cast<uint32_t>(8 * rs + i) | (half_of(raw[i], j) << 16);
+      }
     }
   }
   if (BITS == 3) {                              // pieces [channel][token octet] -> 13 words per channel
@@ -660,7 +898,7 @@ __global__ void static_params_kernel(const uint32_t* __restrict__ calib, int Hkv
 template <int BITS, int G>
 void launch_fast(const kvs_desc* d, const kvs::QuantSpan& sp, bool own_keep, const void* K, const void* V,
                  const uint8_t* mask, const kvs_cache* out, const uint32_t* static_k, const uint32_t* static_v,
-                 hipStream_t s) {
+                 const kvs::SparsePlan* plan, hipStream_t s) {
   constexpr int TB = G > 64 ? G : 64;
   const int bh = d->B * d->Hkv;
   const int cap = own_keep ? d->keep_cap : 0;            // 0: the kernels copy no kept rows themselves
@@ -673,23 +911,36 @@ void launch_fast(const kvs_desc* d, const kvs::QuantSpan& sp, bool own_keep, con
     hipLaunchKernelGGL((quantize_k_token_fast_kernel<BITS, G>), dim3(bh * (sp.n_tokens / (2 * KVS_K_TILE))), dim3(kThreads), 0, s,
                        static_cast<const uint4*>(K), mask, sp, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
                        out->keep_cnt, cap, static_cast<uint4*>(out->keep_k), static_k);
-  else
-    hipLaunchKernelGGL((quantize_k_fast_kernel<BITS, G>), dim3(bh * (sp.n_tokens / TB)), dim3(kThreads), 0, s,
+  else if (plan)      // isolated outliers: thresholds plan->tau[0 / 1], row counts behind the row pointers' first word
+    hipLaunchKernelGGL((quantize_k_fast_kernel<BITS, G, true>), dim3(bh * (sp.n_tokens / TB)), dim3(kThreads), 0, s,
                        static_cast<const uint4*>(K), mask, sp, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
-                       out->keep_cnt, cap, static_cast<uint4*>(out->keep_k), static_k);
-  hipLaunchKernelGGL((quantize_v_fast_kernel<BITS, G>), dim3(bh * (sp.n_tokens / KVS_V_TILE)), dim3(kThreads), 0, s,
-                     static_cast<const uint4*>(V), mask, sp, d->Hkv, out->v_codes, out->v_params, out->keep_idx,
-                     out->keep_cnt, cap, static_cast<uint4*>(out->keep_v), static_v);
+                       out->keep_cnt, cap, static_cast<uint4*>(out->keep_k), static_k, plan->tau, out->k_rowptr + 1,
+                       plan->emit_k);
+  else
+    hipLaunchKernelGGL((quantize_k_fast_kernel<BITS, G, false>), dim3(bh * (sp.n_tokens / TB)), dim3(kThreads), 0, s,
+                       static_cast<const uint4*>(K), mask, sp, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
+                       out->keep_cnt, cap, static_cast<uint4*>(out->keep_k), static_k, nullptr, nullptr,
+                       kvs::SparseEmit{});
+  if (plan)
+    hipLaunchKernelGGL((quantize_v_fast_kernel<BITS, G, true>), dim3(bh * (sp.n_tokens / KVS_V_TILE)), dim3(kThreads), 0, s,
+                       static_cast<const uint4*>(V), mask, sp, d->Hkv, out->v_codes, out->v_params, out->keep_idx,
+                       out->keep_cnt, cap, static_cast<uint4*>(out->keep_v), static_v, plan->tau + 1, out->v_rowptr + 1,
+                       plan->emit_v);
+  else
+    hipLaunchKernelGGL((quantize_v_fast_kernel<BITS, G, false>), dim3(bh * (sp.n_tokens / KVS_V_TILE)), dim3(kThreads), 0, s,
+                       static_cast<const uint4*>(V), mask, sp, d->Hkv, out->v_codes, out->v_params, out->keep_idx,
+                       out->keep_cnt, cap, static_cast<uint4*>(out->keep_v), static_v, nullptr, nullptr,
+                       kvs::SparseEmit{});
 }
 
 template <int BITS>
 void launch_fast_g(const kvs_desc* d, const kvs::QuantSpan& sp, bool own_keep, const void* K, const void* V,
                    const uint8_t* mask, const kvs_cache* out, const uint32_t* static_k, const uint32_t* static_v,
-                   hipStream_t s) {
+                   const kvs::SparsePlan* plan, hipStream_t s) {
   switch (d->group) {
-    case 32: launch_fast<BITS, 32>(d, sp, own_keep, K, V, mask, out, static_k, static_v, s); break;
-    case 64: launch_fast<BITS, 64>(d, sp, own_keep, K, V, mask, out, static_k, static_v, s); break;
-    default: launch_fast<BITS, 128>(d, sp, own_keep, K, V, mask, out, static_k, static_v, s); break;
+    case 32: launch_fast<BITS, 32>(d, sp, own_keep, K, V, mask, out, static_k, static_v, plan, s); break;
+    case 64: launch_fast<BITS, 64>(d, sp, own_keep, K, V, mask, out, static_k, static_v, plan, s); break;
+    default: launch_fast<BITS, 128>(d, sp, own_keep, K, V, mask, out, static_k, static_v, plan, s); break;
   }
 }
 
@@ -697,16 +948,12 @@ void launch_fast_g(const kvs_desc* d, const kvs::QuantSpan& sp, bool own_keep, c
 
 namespace kvs {
 
-bool quantize_fast_supported(const kvs_desc* d) {
-  return d->sparse_frac == 0.0f;
-}
-
 void launch_quantize_fast(const kvs_desc* d, const QuantSpan& sp, bool own_keep, const void* K, const void* V,
                           const uint8_t* mask, const kvs_cache* out, const uint32_t* static_k, const uint32_t* static_v,
-                          hipStream_t s) {
-  if (d->bits == 2) launch_fast_g<2>(d, sp, own_keep, K, V, mask, out, static_k, static_v, s);
-  else if (d->bits == 3) launch_fast_g<3>(d, sp, own_keep, K, V, mask, out, static_k, static_v, s);
-  else launch_fast_g<4>(d, sp, own_keep, K, V, mask, out, static_k, static_v, s);
+                          const SparsePlan* plan, hipStream_t s) {
+  if (d->bits == 2) launch_fast_g<2>(d, sp, own_keep, K, V, mask, out, static_k, static_v, plan, s);
+  else if (d->bits == 3) launch_fast_g<3>(d, sp, own_keep, K, V, mask, out, static_k, static_v, plan, s);
+  else launch_fast_g<4>(d, sp, own_keep, K, V, mask, out, static_k, static_v, plan, s);
 }
 
 void launch_calibrate_reset(const kvs_desc* d, uint32_t* calib, hipStream_t s) {
