@@ -164,6 +164,31 @@ def test_other_gqa_ratios(rep):
     assert row_rel_err(out, O.decode_attn(q, ref, Hq=H * rep)[2]) <= OUT_TOL
 
 
+@pytest.mark.parametrize("bits,G,rep,kpt", [(4, 128, 1, False), (2, 32, 4, False), (3, 64, 2, True)])
+def test_one_very_long_sequence(bits, G, rep, kpt):
+    """A single (sequence, KV head) of 131072 tokens: 1024 Value tiles over 256 parts, the combine
+    kernel merging all of them; everything compared."""
+    rng = np.random.default_rng(bits + G)
+    B, H, n, cap = 1, 1, 131072, 8
+    K, V = random_fp16(rng, (B, H, n, 128)), random_fp16(rng, (B, H, n, 128))
+    K[:, :, :, [3, 77]] *= np.float16(10)
+    mask = np.zeros((B, n), np.uint8)
+    mask[0, [0, 14, 65536, n - 1]] = 1
+    q = random_fp16(rng, (B, H * rep, 128))
+    desc = kb.make_desc(B, n, H * rep, H, bits, G, cap, key_per_token=kpt)
+    cache, ws = kb.alloc_cache(desc, DEV), kb.alloc_workspace(desc, DEV)
+    kb.kvs_quantize_kv(desc, torch.from_numpy(K).to(DEV), torch.from_numpy(V).to(DEV), torch.from_numpy(mask).to(DEV),
+                       cache, ws)
+    torch.cuda.synchronize()
+    assert kb.kvs_decode_splits(desc) == 256
+    ref = O.quantize_kv(K, V, mask, bits, G, cap, key_per_token=kpt)
+    assert_cache_equal(cache, ref)
+    out, lse = hip_decode(desc, cache, ws, q)
+    _, ref_lse, ref64 = O.decode_attn(q, ref, Hq=H * rep)
+    assert row_rel_err(out, ref64) <= OUT_TOL
+    assert np.abs(lse - ref_lse).max() <= 1e-3
+
+
 @pytest.mark.parametrize("case", ["group_all_kept", "all_kept", "none_kept", "constant", "zeros",
                                   "huge", "tiny", "overflow"])
 def test_degenerate_inputs(case):
