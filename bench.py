@@ -33,8 +33,8 @@ HBM_PEAK_GBPS = 8000.0
 DECODE_TRAFFIC = {
     "workload": "cfg1",
     "sources": ["decode_mfma_impl.h", "decode_mfma_b4.hip", "decode_mfma.hip", "kvs_device.h", "kvs_api.hip"],
-    "sha256_16": "2953485f98f14cc5",
-    "fetch_bytes": 144083878,
+    "sha256_16": "988a5a7b269c772b",
+    "fetch_bytes": 144085071,
     "write_bytes": 73728,
 }
 
