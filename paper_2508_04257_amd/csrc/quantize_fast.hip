@@ -745,31 +745,61 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
 }
 
 // Index list of the kept tokens (ascending), count, mask copy, overflow status, and zero padding
-// of the unused rows of the fp16 side buffers.  One wave per sequence, 16 mask bytes per lane
-// and step.
-__global__ __launch_bounds__(KVS_WAVE) void keep_index_fast_kernel(
+// of the unused rows of the fp16 side buffers.  One workgroup of 16 waves per sequence: wave w
+// owns one contiguous segment of the mask (a multiple of 1024 bytes: 16 per lane and step), first
+// counts its kept tokens, then - knowing how many lie before its segment - writes their indices.
+constexpr int kIndexWaves = 16;
+__global__ __launch_bounds__(kIndexWaves * KVS_WAVE) void keep_index_fast_kernel(
     const uint8_t* __restrict__ keep_mask, int n, int Hkv, int cap, int32_t* __restrict__ keep_idx,
     int32_t* __restrict__ keep_cnt, uint8_t* __restrict__ mask_copy, int32_t* __restrict__ status,
     uint4* __restrict__ keep_k, uint4* __restrict__ keep_v) {
-  const int b = blockIdx.x, lane = threadIdx.x;
+  __shared__ int wave_count[kIndexWaves];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int lane = tid & (KVS_WAVE - 1), wave = tid / KVS_WAVE;
   const uint8_t* m = keep_mask + static_cast<size_t>(b) * n;
   uint8_t* mc = mask_copy + static_cast<size_t>(b) * n;
-  int base = 0;
-  for (int i0 = 0; i0 < n; i0 += KVS_WAVE * 16) {        // n is a multiple of 128, not of 1024
-    const int i = i0 + lane * 16;
+  constexpr int kStep = KVS_WAVE * 16;                   // bytes one wave takes per step
+  const int seg = ((n + kIndexWaves * kStep - 1) / (kIndexWaves * kStep)) * kStep;   // bytes per wave
+  const int seg_begin = min(n, wave * seg), seg_end = min(n, seg_begin + seg);
+
+  // bit 0 of each byte of the result = the mask byte is nonzero (n is a multiple of 128, so a
+  // lane's 16 bytes are either all inside the sequence or all outside)
+  auto load_norm = [&](int i, uint32_t (&norm)[4]) -> int {
     uint4 v = {0, 0, 0, 0};
-    if (i < n) v = *reinterpret_cast<const uint4*>(m + i);
+    if (i < seg_end) v = *reinterpret_cast<const uint4*>(m + i);
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    uint32_t norm[4];
     int mine = 0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       uint32_t nz = w[k] | (w[k] >> 4);
-      nz |= nz >> 2;  nz |= nz >> 1;                     // bit 0 of each byte = byte != 0
+      nz |= nz >> 2;  nz |= nz >> 1;
       norm[k] = nz & 0x01010101u;
       mine += __popc(norm[k]);
     }
-    if (i < n) *reinterpret_cast<uint4*>(mc + i) = uint4{norm[0], norm[1], norm[2], norm[3]};
+    return mine;
+  };
+
+  int count = 0;
+  for (int i0 = seg_begin; i0 < seg_end; i0 += kStep) {
+    uint32_t norm[4];
+    count += load_norm(i0 + lane * 16, norm);
+  }
+#pragma unroll
+  for (int o = KVS_WAVE / 2; o > 0; o >>= 1) count += __shfl_xor(count, o, KVS_WAVE);
+  if (lane == 0) wave_count[wave] = count;
+  __syncthreads();
+  int base = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < kIndexWaves; ++w) {
+    base += w < wave ? wave_count[w] : 0;
+    total += wave_count[w];
+  }
+
+  for (int i0 = seg_begin; i0 < seg_end; i0 += kStep) {  // the segment again (cache hits)
+    const int i = i0 + lane * 16;
+    uint32_t norm[4];
+    const int mine = load_norm(i, norm);
+    if (i < seg_end) *reinterpret_cast<uint4*>(mc + i) = uint4{norm[0], norm[1], norm[2], norm[3]};
     int incl = mine;
 #pragma unroll
     for (int o = 1; o < KVS_WAVE; o <<= 1) {
@@ -787,17 +817,18 @@ __global__ __launch_bounds__(KVS_WAVE) void keep_index_fast_kernel(
         }
     base += __shfl(incl, KVS_WAVE - 1, KVS_WAVE);
   }
-  for (int j = base + lane; j < cap; j += KVS_WAVE) keep_idx[static_cast<size_t>(b) * cap + j] = -1;
-  if (lane == 0) {
-    keep_cnt[b] = base;
-    if (base > cap) atomicCAS(status, 0, static_cast<int>(KVS_ERR_CAPACITY));
+
+  for (int j = total + tid; j < cap; j += kIndexWaves * KVS_WAVE) keep_idx[static_cast<size_t>(b) * cap + j] = -1;
+  if (tid == 0) {
+    keep_cnt[b] = total;
+    if (total > cap) atomicCAS(status, 0, static_cast<int>(KVS_ERR_CAPACITY));
   }
   // zero the rows past the count, for every head of this sequence (16 uint4 per row)
-  const int first = min(base, cap);
+  const int first = min(total, cap);
   const int per_head = (cap - first) * 16;
   for (int h = 0; h < Hkv; ++h) {
     const size_t row0 = ((static_cast<size_t>(b) * Hkv + h) * cap + first) * 16;
-    for (int e = lane; e < per_head; e += KVS_WAVE) {
+    for (int e = tid; e < per_head; e += kIndexWaves * KVS_WAVE) {
       keep_k[row0 + e] = uint4{0, 0, 0, 0};
       keep_v[row0 + e] = uint4{0, 0, 0, 0};
     }
@@ -903,7 +934,7 @@ void launch_fast(const kvs_desc* d, const kvs::QuantSpan& sp, bool own_keep, con
   const int bh = d->B * d->Hkv;
   const int cap = own_keep ? d->keep_cap : 0;            // 0: the kernels copy no kept rows themselves
   if (own_keep)
-    hipLaunchKernelGGL(keep_index_fast_kernel, dim3(d->B), dim3(KVS_WAVE), 0, s, mask, d->n, d->Hkv, d->keep_cap,
+    hipLaunchKernelGGL(keep_index_fast_kernel, dim3(d->B), dim3(kIndexWaves * KVS_WAVE), 0, s, mask, d->n, d->Hkv, d->keep_cap,
                        out->keep_idx, out->keep_cnt, out->keep_mask, out->status, static_cast<uint4*>(out->keep_k),
                        static_cast<uint4*>(out->keep_v));
   if (sp.n_tokens == 0) return;
