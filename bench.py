@@ -229,6 +229,27 @@ def per_token_key_leg(w, inputs, bufs, q, dec_bytes, qnt_bytes):
     }
 
 
+def graph_leg(w, hidden, inputs, q, bufs):
+    """The same steps replayed from one HIP graph (all slots in sequence per replay): what the
+    launch gaps of the eager loop cost."""
+    import torch
+
+    from paper_2508_04257_amd import pipeline
+
+    graph = pipeline.capture_steps(w, hidden, inputs, q, bufs)
+    for _ in range(2):
+        graph.replay()
+    torch.cuda.synchronize()
+    reps = 10
+    e0, e1 = HipEvent(), HipEvent()
+    e0.record()
+    for _ in range(reps):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return {"ms_per_step": round(e0.elapsed_time(e1) / (reps * len(bufs)), 4), "steps_per_replay": len(bufs)}
+
+
 def cpu_baseline(w, budget_s: float = 12.0):
     """The oracle as it stands, timed on this host on a bounded sample of the same workload:
     whole (sequence 0, head h) slices, one at a time, until the budget is used."""
@@ -453,6 +474,7 @@ def main() -> int:
             "algorithmic_bytes": qnt_bytes,
         },
     }
+    result["graph_replay"] = graph_leg(w, hidden, inputs, q, bufs)
     if w.sparse_frac == 0:
         result["growing_cache"] = growing_cache_leg(w, inputs[0], q, dec_bytes)
         result["static_quantisation"] = static_leg(w, inputs, bufs, qnt_bytes)

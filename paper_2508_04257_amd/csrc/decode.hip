@@ -150,8 +150,8 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
         if constexpr (SPARSE) {
           const size_t row = bh * n + static_cast<size_t>(t0 + tl);
           const int e1 = min(sp.k_rowptr[row + 1], sp.cap);
-          for (int e = sp.k_rowptr[row]; e < e1; ++e) {
-            const int c = sp.k_col[e];
+          for (int e = max(sp.k_rowptr[row], 0); e < e1; ++e) {   // (a never-quantised cache must not walk out of the arrays)
+            const int c = sp.k_col[e] & 127;
             const float v = kvs::half_bits_to_float(sp.k_val[e]);
 #pragma unroll
             for (int r = 0; r < R; ++r) dot[r] += qf[r][c] * v + qs[wave][gl][r][c] * kz[wave][gl][c];
@@ -230,8 +230,8 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
           const int g = half ? g1 : g0;
           const size_t row = (bh * (n / KVS_V_TILE) + static_cast<size_t>(t0 / KVS_V_TILE)) * 128 + lane + 64 * half;
           const int e1 = min(sp.v_rowptr[row + 1], sp.cap);
-          for (int e = sp.v_rowptr[row]; e < e1; ++e) {
-            const int tl = sp.v_col[e];
+          for (int e = max(sp.v_rowptr[row], 0); e < e1; ++e) {
+            const int tl = sp.v_col[e] & 127;
             const float v = kvs::half_bits_to_float(sp.v_val[e]);
 #pragma unroll
             for (int r = 0; r < R; ++r) acc[r][half] += pl[wave][r][tl] * v + wz[wave][r][g][tl];

@@ -40,8 +40,9 @@ __global__ __launch_bounds__(128) void sparse_key_corr_kernel(
 #pragma unroll
   for (int u = 0; u < kKeyIlp; ++u) {
     const int t = min(t0 + 128 * u, n - 1);
-    e0[u] = min(k_rowptr[bh * n + t], cap);
-    e1[u] = min(k_rowptr[bh * n + t + 1], cap);
+    // (clamped on both sides: a cache that was never quantised must not send the walk out of the arrays)
+    e0[u] = max(0, min(k_rowptr[bh * n + t], cap));
+    e1[u] = max(0, min(k_rowptr[bh * n + t + 1], cap));
   }
   float acc[kKeyIlp];
   int len = 0;
@@ -54,7 +55,7 @@ __global__ __launch_bounds__(128) void sparse_key_corr_kernel(
 #pragma unroll
     for (int u = 0; u < kKeyIlp; ++u) {
       const int e = min(e0[u] + i, max(e1[u], 1) - 1);      // clamped; unused when the row is shorter
-      c[u] = k_col[e];
+      c[u] = k_col[e] & 127;
       v[u] = kvs::half_bits_to_float(k_val[e]);
     }
 #pragma unroll
@@ -136,8 +137,8 @@ __global__ __launch_bounds__(kFinishThreads) void decode_finish_sparse_kernel(
     for (int u = 0; u < kValIlp; ++u) {               // row pointers in flight while the segment is staged
       const int tile = min(seg_tile + tg + kStride * u, tiles - 1);
       const size_t row = bh * n + static_cast<size_t>(tile) * 128 + c;
-      e0[u] = min(v_rowptr[row], sparse_cap);
-      e1[u] = seg_tile + tg + kStride * u < tiles ? min(v_rowptr[row + 1], sparse_cap) : e0[u];
+      e0[u] = max(0, min(v_rowptr[row], sparse_cap));
+      e1[u] = seg_tile + tg + kStride * u < tiles ? max(0, min(v_rowptr[row + 1], sparse_cap)) : e0[u];
     }
     __syncthreads();
     for (int i = tid; i < seg_tokens; i += kFinishThreads) sc_s[i] = cs[bq * n + seg_tile * 128 + i];
@@ -152,7 +153,7 @@ __global__ __launch_bounds__(kFinishThreads) void decode_finish_sparse_kernel(
 #pragma unroll
       for (int u = 0; u < kValIlp; ++u) {
         const int e = min(e0[u] + i, max(e1[u], 1) - 1);    // clamped; unused when the row is shorter
-        tok[u] = (tg + kStride * u) * 128 + v_col[e];       // token inside the segment
+        tok[u] = (tg + kStride * u) * 128 + (v_col[e] & 127);   // token inside the segment
         val[u] = kvs::half_bits_to_float(v_val[e]);
       }
 #pragma unroll

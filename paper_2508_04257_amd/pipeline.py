@@ -64,3 +64,24 @@ def run_step(w: Workload, hidden: torch.Tensor, K: torch.Tensor, V: torch.Tensor
     predict(w, hidden, buf)
     quantize(K, V, buf)
     decode(q, buf)
+
+
+def step_in_bench_order(w: Workload, hidden: torch.Tensor, K: torch.Tensor, V: torch.Tensor, q: torch.Tensor,
+                        cur: StepBuffers, old: StepBuffers) -> None:
+    """The order a serving loop runs them in: this step's prediction, decode over a cache quantised
+    earlier (no dependence on this step), then this step's quantisation."""
+    predict(w, hidden, cur)
+    decode(q, old)
+    quantize(K, V, cur)
+
+
+def capture_steps(w: Workload, hidden: torch.Tensor, inputs, q: torch.Tensor, bufs) -> torch.cuda.CUDAGraph:
+    """One HIP graph holding len(bufs) consecutive steps over the rotating slots (step i: predict
+    and quantise into slot i, decode slot i + 1).  Every call of the library only launches kernels
+    on the current stream - no allocation, copy or synchronisation - so the calls can be captured
+    as they are; a replay then costs one launch for the whole sequence."""
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for i in range(len(bufs)):
+            step_in_bench_order(w, hidden, inputs[i][0], inputs[i][1], q, bufs[i], bufs[(i + 1) % len(bufs)])
+    return graph

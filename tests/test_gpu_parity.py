@@ -278,6 +278,35 @@ def test_dense_and_sparse_small(bits, G, rep, frac, kind):
     assert np.all(np.isfinite(out2))
 
 
+@pytest.mark.parametrize("rep", [1, 4])
+def test_decode_stays_inside_the_arrays_on_a_cache_with_corrupt_row_pointers(rep):
+    """The decode kernels clamp row pointers to [0, sparse_cap] and column indices to 0..127, so a
+    cache whose CSR arrays hold garbage (one that was never quantised, say) yields garbage but
+    reads nothing outside its buffers.  Afterwards the same buffers, quantised properly, decode
+    to the oracle's result."""
+    rng = np.random.default_rng(rep)
+    B, H, n, bits, G, frac = 2, 2, 640, 3, 128, 0.01
+    K, V = random_fp16(rng, (B, H, n, 128)), random_fp16(rng, (B, H, n, 128))
+    mask = np.zeros((B, n), np.uint8)
+    mask[0, [0, 14]] = 1
+    q = random_fp16(rng, (B, H * rep, 128))
+    desc, cache, ws = hip_quantize(K, V, mask, bits, G, keep_cap=2, Hq=H * rep, sparse_frac=frac, sparse_cap=4000)
+    rows = B * H * n
+    for name in ("k_rowptr", "v_rowptr"):
+        t = getattr(cache, name)
+        t.copy_(torch.from_numpy(rng.integers(-2 ** 31, 2 ** 31 - 1, t.numel(), dtype=np.int64).astype(np.int32)).to(DEV))
+    for name in ("k_col", "v_col"):
+        t = getattr(cache, name)
+        t.copy_(torch.from_numpy(rng.integers(-2 ** 15, 2 ** 15 - 1, t.numel(), dtype=np.int64).astype(np.int16)).to(DEV))
+    out, _ = hip_decode(desc, cache, ws, q)                # must come back; the values mean nothing
+    assert out.shape == (B, H * rep, 128)
+    kb.kvs_quantize_kv(desc, torch.from_numpy(K).to(DEV), torch.from_numpy(V).to(DEV), torch.from_numpy(mask).to(DEV),
+                       cache, ws)
+    out, _ = hip_decode(desc, cache, ws, q)
+    ref = O.quantize_kv(K, V, mask, bits, G, 2, sparse_frac=frac, sparse_cap=4000)
+    assert row_rel_err(out, O.decode_attn(q, ref, Hq=H * rep)[2]) <= OUT_TOL
+
+
 def test_dense_and_sparse_threshold_when_the_sample_misleads():
     """The threshold pass counts only magnitudes above a bound taken from the part of the tensor it
     reads first.  Here that part (the first 512 token rows) is 100 times larger than the rest, so the
