@@ -10,6 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # The tests load the in-tree library; it is compiled here only when none has been built yet.
+    from paper_2508_04257_amd import build as kbuild
+
+    if not os.path.exists(kbuild.LIB):
+        kbuild.build(verbose=False)
 
 
 def pytest_collection_modifyitems(config, items):
