@@ -21,6 +21,7 @@
 // Compiled with floating-point contraction off and correctly rounded division, so that no
 // multiply-add fuses across the quantiser's operations.
 #include "kvs_device.h"
+#include "sparse_emit.h"
 
 namespace {
 
@@ -31,11 +32,18 @@ constexpr int kThreads = 256;
 constexpr uint32_t kPosMax2 = 0x7BFF7BFFu;   // (+65504, +65504)
 constexpr uint32_t kNegMax2 = 0xFBFFFBFFu;   // (-65504, -65504)
 
+// Packed fp16 minimum / maximum of two register pairs.  Written as the instruction itself: the
+// generic elementwise builtins first canonicalise each operand (one more instruction per
+// operand) in case it holds a signalling NaN, and the inputs here are finite by contract.
 __device__ inline uint32_t pk_min(uint32_t a, uint32_t b) {
-  return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b)));
+  uint32_t r;
+  asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
 }
 __device__ inline uint32_t pk_max(uint32_t a, uint32_t b) {
-  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b)));
+  uint32_t r;
+  asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
 }
 // Streaming store of 16 bytes: the packed cache is written once and read much later, so it
 // should not linger as dirty lines in the last-level cache (whoever streams next would pay for
@@ -330,7 +338,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
 #pragma unroll
     for (int k = 0; k < TB / KVS_WAVE; ++k) { row_off_s[lane * (TB / KVS_WAVE) + k] = run; run += cnt[k]; }
     // requested now, needed only when the entries are written out
-    if (lane == KVS_WAVE - 1 && incl > 0) run_claim = atomicAdd(emit.counter, incl);
+    if (lane == KVS_WAVE - 1 && incl > 0) run_claim = kvs::claim_run(emit, incl);
   }
   __syncthreads();
 
@@ -371,6 +379,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
     // channels ascending inside a row): the lane that holds an entry writes it from its
     // registers; its place is the row's start plus the entries of the row to its left.
     const int run_base = run_base_s;
+    const long long list_words = kvs::emit_list_words(emit.cap);
 #pragma unroll
     for (int i = 0; i < ROWS; ++i) {
       uint32_t bits = iso8[i];
@@ -380,7 +389,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
       while (bits) {
         const int j = __builtin_ctz(bits);
         bits &= bits - 1;
-        if (pos < emit.cap) emit.list[pos] = static_cast<uint32_t>(8 * chunk + j) | (half_of(raw[i], j) << 16);
+        if (pos < list_words) emit.list[pos] = static_cast<uint32_t>(8 * chunk + j) | (half_of(raw[i], j) << 16);
         ++pos;
       }
     }
@@ -641,7 +650,7 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
       chan_off_s[2 * sl] = incl - mine;
       chan_off_s[2 * sl + 1] = incl - mine + cnt[0];
       // requested now, needed only when the entries are written out
-      if (sl == KVS_WAVE - 1 && incl > 0) run_claim = atomicAdd(emit.counter, incl);
+      if (sl == KVS_WAVE - 1 && incl > 0) run_claim = kvs::claim_run(emit, incl);
     }
   }
 
@@ -701,6 +710,7 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
     }
     __syncthreads();
     const int run_base = run_base_s;
+    const long long list_words = kvs::emit_list_words(emit.cap);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       uint32_t bits = (i < 4 ? row_lo >> (8 * i) : row_hi >> (8 * (i - 4))) & 0xFFu;   // channels of token 8 rs + i
@@ -711,7 +721,7 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
         const uint32_t tokens = (j < 4 ? iso_lo >> (8 * j) : iso_hi >> (8 * (j - 4))) & 0xFFu;   // the lane's tokens of channel c
         const long long pos = static_cast<long long>(run_base) + chan_off_s[c] + bits_below_byte(&iso_s[c][0], rs) +
                               __popc(tokens & ((1u << i) - 1u));
-        if (pos < emit.cap) emit.list[pos] = static_cast<uint32_t>(8 * rs + i) | (half_of(raw[i], j) << 16);
+        if (pos < list_words) emit.list[pos] = static_cast<uint32_t>(8 * rs + i) | (half_of(raw[i], j) << 16);
       }
     }
   }

@@ -11,6 +11,7 @@
 // into row pointers and one small kernel moves every block's run to its place.  K and V are
 // read twice in all (histogram, quantise).
 #include "kvs_device.h"
+#include "sparse_emit.h"
 
 namespace {
 
@@ -242,14 +243,15 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(int* __restric
 // fit the list (a reported overflow) is replaced by harmless entries.
 __global__ __launch_bounds__(KVS_WAVE) void csr_move_kernel(
     const uint32_t* __restrict__ list, const int* __restrict__ block_base, int rows_per_block,
-    const int32_t* __restrict__ rowptr, long long cap, uint16_t* __restrict__ col, uint16_t* __restrict__ val) {
+    const int32_t* __restrict__ rowptr, long long cap, long long list_words, uint16_t* __restrict__ col,
+    uint16_t* __restrict__ val) {
   const size_t first_row = blockIdx.x * static_cast<size_t>(rows_per_block);
   const long long dst0 = rowptr[first_row];
   const int cnt = static_cast<int>(rowptr[first_row + rows_per_block] - dst0);
   const long long src0 = block_base[blockIdx.x];
   for (int e = threadIdx.x; e < cnt; e += KVS_WAVE) {
     if (dst0 + e < cap) {
-      const uint32_t w = src0 + e < cap ? list[src0 + e] : 0u;
+      const uint32_t w = src0 + e < list_words ? list[src0 + e] : 0u;
       col[dst0 + e] = static_cast<uint16_t>(w & 0xFFFFu);
       val[dst0 + e] = static_cast<uint16_t>(w >> 16);
     }
@@ -260,15 +262,18 @@ __global__ __launch_bounds__(KVS_WAVE) void csr_move_kernel(
 
 namespace kvs {
 
-// Workspace layout in uint32 words: histograms, thresholds and the two staging counters (zeroed
-// together), scan scratch, the per-workgroup run starts, the two staging lists.
+// Workspace layout in uint32 words: histograms and the control block - thresholds, per-tensor
+// control words, the staging counters of both tensors - (zeroed together), scan scratch, the
+// per-workgroup run starts, the two staging lists.
+constexpr int kCtrlBlock = 256;                  // words: 0-1 tau, 8-15 per-tensor control, 32.. / 128.. staging counters
+static_assert(32 + kEmitCounters <= 128 && 128 + kEmitCounters <= kCtrlBlock, "control block layout");
 static int key_block_rows(const kvs_desc* d) { return d->group > 64 ? d->group : 64; }
 
 size_t sparse_workspace_words(const kvs_desc* d) {
   const size_t rows = static_cast<size_t>(d->B) * d->Hkv * d->n;
   const size_t nblk = (rows + kScanBlock - 1) / kScanBlock;
   const size_t bases = rows / key_block_rows(d) + rows / KVS_V_TILE;
-  return 4 * kBins + 64 + 2 * (nblk + 1) + bases + 2 * static_cast<size_t>(d->sparse_cap);
+  return 4 * kBins + kCtrlBlock + 2 * (nblk + 1) + bases + 2 * static_cast<size_t>(emit_list_words(d->sparse_cap));
 }
 
 SparsePlan sparse_plan(const kvs_desc* d, void* workspace) {
@@ -278,22 +283,22 @@ SparsePlan sparse_plan(const kvs_desc* d, void* workspace) {
   p.rows = rows;
   p.nblk = static_cast<int>((rows + kScanBlock - 1) / kScanBlock);
   p.hist = w;                                              // [2][kBins] bounded, then [2][kBins] full
-  uint32_t* block = w + 4 * kBins;                         // 64 control words, zeroed with the histograms
-  p.tau = block;                                           // words 0, 1; 2, 3 staging counters; 8.. per-tensor control
-  p.sums_k = reinterpret_cast<int*>(block + 64);
+  uint32_t* block = w + 4 * kBins;                         // the control block, zeroed with the histograms
+  p.tau = block;
+  p.sums_k = reinterpret_cast<int*>(block + kCtrlBlock);
   p.sums_v = p.sums_k + p.nblk + 1;
   p.rows_per_block_k = key_block_rows(d);
   int* bases = p.sums_v + p.nblk + 1;
   uint32_t* lists = reinterpret_cast<uint32_t*>(bases + rows / p.rows_per_block_k + rows / KVS_V_TILE);
-  p.emit_k = SparseEmit{lists, reinterpret_cast<int*>(block + 2), bases, d->sparse_cap};
-  p.emit_v = SparseEmit{lists + d->sparse_cap, reinterpret_cast<int*>(block + 3),
+  p.emit_k = SparseEmit{lists, reinterpret_cast<int*>(block + 32), bases, d->sparse_cap};
+  p.emit_v = SparseEmit{lists + emit_list_words(d->sparse_cap), reinterpret_cast<int*>(block + 128),
                         bases + rows / p.rows_per_block_k, d->sparse_cap};
   return p;
 }
 
 void sparse_thresholds(const kvs_desc* d, const SparsePlan& p, const void* K, const void* V,
                        const uint8_t* mask, const kvs_cache* out, hipStream_t s) {
-  hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(1024), 0, s, p.hist, static_cast<size_t>(4 * kBins + 64), 0u);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(1024), 0, s, p.hist, static_cast<size_t>(4 * kBins + kCtrlBlock), 0u);
   hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(out->k_rowptr), size_t{1}, 0u);
   hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(out->v_rowptr), size_t{1}, 0u);
   // Two workgroups per compute unit in turn; fewer on small inputs, so that every workgroup still
@@ -321,10 +326,10 @@ void sparse_build_csr(const kvs_desc* d, const SparsePlan& p, const kvs_cache* o
     hipLaunchKernelGGL(scan_apply_kernel, dim3(p.nblk), dim3(kScanThreads), 0, s, xs[i], p.rows, sums[i]);
   }
   hipLaunchKernelGGL(csr_move_kernel, dim3(static_cast<unsigned>(p.rows / p.rows_per_block_k)), dim3(KVS_WAVE), 0, s,
-                     p.emit_k.list, p.emit_k.block_base, p.rows_per_block_k, out->k_rowptr, cap, out->k_col,
+                     p.emit_k.list, p.emit_k.block_base, p.rows_per_block_k, out->k_rowptr, cap, emit_list_words(cap), out->k_col,
                      static_cast<uint16_t*>(out->k_val));
   hipLaunchKernelGGL(csr_move_kernel, dim3(static_cast<unsigned>(p.rows / KVS_V_TILE)), dim3(KVS_WAVE), 0, s,
-                     p.emit_v.list, p.emit_v.block_base, KVS_V_TILE, out->v_rowptr, cap, out->v_col,
+                     p.emit_v.list, p.emit_v.block_base, KVS_V_TILE, out->v_rowptr, cap, emit_list_words(cap), out->v_col,
                      static_cast<uint16_t*>(out->v_val));
 }
 

@@ -1,0 +1,48 @@
+// Where a quantise workgroup parks its isolated entries until the row pointers are known
+// (dense-and-sparse variant; paper, Section 5.1).  The staging list of one tensor is cut into
+// kEmitSegments segments, each with a counter of its own, plus one overflow region as large as the
+// CSR capacity: a workgroup claims room for its whole run with one atomic on the counter of
+// segment (workgroup index mod kEmitSegments), and only if the run does not fit there any more
+// with a second atomic on the overflow counter.  One counter for everything serialised the claims
+// of tens of thousands of workgroups on a single address and bounded the whole kernel.  Whatever
+// the distribution, a tensor with no more than `cap` isolated entries fits: the overflow region
+// alone could hold them all.
+#pragma once
+
+#include "kvs_device.h"
+
+namespace kvs {
+
+constexpr int kEmitSegments = 64;
+
+// Positions are 32-bit: with a capacity too large for two regions of that size there is one
+// segment and no overflow region (the behaviour of a single counter).
+__host__ __device__ inline int emit_segments(long long cap) {
+  return cap <= (1ll << 30) - kEmitSegments ? kEmitSegments : 1;
+}
+__host__ __device__ inline long long emit_segment_cap(long long cap) {
+  const int s = emit_segments(cap);
+  return s == 1 ? cap : (cap + s - 1) / s;
+}
+// Words of one tensor's staging list.
+__host__ __device__ inline long long emit_list_words(long long cap) {
+  const int s = emit_segments(cap);
+  return s == 1 ? cap : s * emit_segment_cap(cap) + cap;
+}
+// Counters per tensor: one per segment, then the overflow counter.
+constexpr int kEmitCounters = kEmitSegments + 1;
+
+#ifdef __HIPCC__
+// Start of a run of `count` entries for this workgroup (called by one lane).
+__device__ inline int claim_run(const SparseEmit& emit, int count) {
+  const int segs = emit_segments(emit.cap);
+  if (segs == 1) return atomicAdd(emit.counter, count);
+  const int seg_cap = static_cast<int>(emit_segment_cap(emit.cap));
+  const int seg = static_cast<int>(blockIdx.x % kEmitSegments);
+  const int base = atomicAdd(emit.counter + seg, count);
+  if (base <= seg_cap - count) return seg * seg_cap + base;
+  return segs * seg_cap + atomicAdd(emit.counter + kEmitSegments, count);
+}
+#endif
+
+}  // namespace kvs
