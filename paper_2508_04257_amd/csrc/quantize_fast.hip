@@ -133,24 +133,7 @@ __device__ inline uint32_t compose3(const uint32_t* pieces, int w) {
 // Dense-and-sparse support (paper, Section 5.1: the largest-magnitude entries are isolated in
 // 16 bit).  An entry whose fp16 magnitude pattern reaches tau leaves the statistics, gets code 0
 // and is recorded in a bit mask per CSR row; the masks then drive the emission.
-typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
-typedef short short2v __attribute__((ext_vector_type(2)));
-// 0xFFFF in every half of w whose magnitude pattern is below tau (tau2 = tau in both halves,
-// tau <= 0x8000), 0 in the others.
-__device__ inline uint32_t below_mask(uint32_t w, uint32_t tau2) {
-  const ushort2v d = __builtin_bit_cast(ushort2v, w & 0x7FFF7FFFu) - __builtin_bit_cast(ushort2v, tau2);
-  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2v, d) >> 15);
-}
 __device__ inline uint32_t select_halves(uint32_t m, uint32_t a, uint32_t b) { return (a & m) | (b & ~m); }
-// Bit j = element j of the uint4 (eight halves) is at or above tau.  Each mask contributes the
-// two bits of its pair: the low half's at bit 2 k, the high half's at bit 16 + 2 k + 1.
-__device__ inline uint32_t isolated8(const uint32_t m[4]) {
-  uint32_t x = m[0] & 0x00020001u;
-  x |= m[1] & 0x00080004u;
-  x |= m[2] & 0x00200010u;
-  x |= m[3] & 0x00800040u;
-  return ((x | (x >> 16)) & 0xFFu) ^ 0xFFu;
-}
 // Field mask of a lane's eight codes: bit j of `bits` -> the BITS-wide field of code j.
 template <int BITS>
 __device__ inline void fill_spread_table(uint32_t* table, int tid) {
@@ -269,8 +252,8 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
         const uint32_t w4[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
         uint32_t m[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) m[k] = below_mask(w4[k], tau2);
-        iso8[i] = kept[i] ? 0u : isolated8(m);
+        for (int k = 0; k < 4; ++k) m[k] = kvs::below_mask(w4[k], tau2);
+        iso8[i] = kept[i] ? 0u : kvs::isolated8(m);
         if (!kept[i]) {
 #pragma unroll
           for (int k = 0; k < 4; ++k) {
@@ -602,12 +585,12 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
       uint32_t m[4];
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
-        m[k] = below_mask(a4[k], tau2);
+        m[k] = kvs::below_mask(a4[k], tau2);
         z4[k] = select_halves(m[k], a4[k], kNegMax2);
         a4[k] = select_halves(m[k], a4[k], kPosMax2);
       }
       const bool kept_i = ((i < 4 ? mask8.x >> (8 * i) : mask8.y >> (8 * (i - 4))) & 0xFFu) != 0;
-      const uint32_t bits = kept_i ? 0u : isolated8(m);
+      const uint32_t bits = kept_i ? 0u : kvs::isolated8(m);
       if (i < 4) iso_lo |= bits << (8 * i); else iso_hi |= bits << (8 * (i - 4));
     }
     const uint32_t mn2 = pk_min(pk_min(a4[0], a4[1]), pk_min(a4[2], a4[3]));

@@ -24,6 +24,21 @@ __global__ void fill_u32_kernel(uint32_t* __restrict__ p, size_t count, uint32_t
     p[i] = value;
 }
 
+// Division of a row index (below 2^31) by a run-time constant as a multiply and a shift; the
+// general 64-bit division the index arithmetic would otherwise compile to costs over a hundred
+// instructions per load and was what bounded the histogram pass.
+struct FastDiv {
+  uint32_t d, m;
+  int l;
+};
+FastDiv make_fastdiv(uint32_t d) {
+  int l = 0;
+  while ((1u << l) < d) ++l;
+  const unsigned long long m = ((1ull << 32) * ((1ull << l) - d)) / d + 1;
+  return FastDiv{d, static_cast<uint32_t>(m), l};
+}
+__device__ inline uint32_t fastdiv(uint32_t x, const FastDiv& f) { return (__umulhi(f.m, x) + x) >> f.l; }
+
 // X: fp16 [B*Hkv*n, 128] viewed as uint4 (8 values); entries on kept tokens are skipped.
 //
 // Only the top of the histogram decides tau, and one LDS atomic per element is what this pass
@@ -39,7 +54,7 @@ constexpr float kSampleMargin = 3.0f;
 enum { kCtrlCount = 0, kCtrlL0 = 1, kNeedFull = 2, kCtrlWords = 4 };   // per tensor, in the control block
 
 __global__ __launch_bounds__(kHistThreads) void sparse_hist_kernel(
-    const uint4* __restrict__ X, const uint8_t* __restrict__ keep_mask, size_t rows, int n, int Hkv,
+    const uint4* __restrict__ X, const uint8_t* __restrict__ keep_mask, size_t rows, FastDiv by_n, FastDiv by_heads,
     float frac, int full, uint32_t* __restrict__ hist, uint32_t* __restrict__ ctrl) {
   __shared__ uint32_t h[kBins];
   __shared__ unsigned long long part[kHistThreads];
@@ -87,29 +102,52 @@ __global__ __launch_bounds__(kHistThreads) void sparse_hist_kernel(
     bool use[U];
 #pragma unroll
     for (int k = 0; k < U; ++k) {
-      const size_t u = blockIdx.x * static_cast<size_t>(kHistThreads) + tid + (static_cast<size_t>(step) * U + k) * stride;
+      // step-major, then workgroup, then the U loads of a step: a workgroup's loads of one step are contiguous
+      const size_t u = ((static_cast<size_t>(step) * gridDim.x + blockIdx.x) * U + k) * kHistThreads + tid;
       use[k] = u < units;
       const size_t uc = use[k] ? u : 0;
-      const size_t row = uc >> 4;
-      const size_t b = row / (static_cast<size_t>(Hkv) * n);
-      const int t = static_cast<int>(row % n);
-      use[k] = use[k] && keep_mask[b * n + t] == 0;
+      const uint32_t row = static_cast<uint32_t>(uc >> 4);      // (b * Hkv + h) * n + t, below 2^30
+      const uint32_t bh = fastdiv(row, by_n);
+      const uint32_t t = row - bh * by_n.d;
+      const uint32_t b = fastdiv(bh, by_heads);
+      use[k] = use[k] && keep_mask[static_cast<size_t>(b) * by_n.d + t] == 0;
       v[k] = X[uc];
     }
+    const uint32_t l0_2 = l0 | (l0 << 16);
 #pragma unroll
     for (int k = 0; k < U; ++k) {
       if (!use[k]) continue;
       ++seen;
-      const uint32_t m[8] = {v[k].x & 0x7FFFu, (v[k].x >> 16) & 0x7FFFu, v[k].y & 0x7FFFu, (v[k].y >> 16) & 0x7FFFu,
-                             v[k].z & 0x7FFFu, (v[k].z >> 16) & 0x7FFFu, v[k].w & 0x7FFFu, (v[k].w >> 16) & 0x7FFFu};
+      const uint32_t w[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+      if (l0 == 0) {                                   // (uniform) everything is counted
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (m[j] >= l0) atomicAdd(&h[m[j]], 1u);
+        for (int j = 0; j < 4; ++j) {
+          atomicAdd(&h[w[j] & 0x7FFFu], 1u);
+          atomicAdd(&h[(w[j] >> 16) & 0x7FFFu], 1u);
+        }
+      } else {
+        // Few entries reach the bound: find them with packed arithmetic and walk only those.
+        uint32_t m[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) m[j] = kvs::below_mask(w[j], l0_2);
+        uint32_t bits = kvs::isolated8(m);
+        while (bits) {
+          const int j = __builtin_ctz(bits);
+          bits &= bits - 1;
+          const int q = j >> 1;
+          const uint32_t wq = q == 0 ? w[0] : (q == 1 ? w[1] : (q == 2 ? w[2] : w[3]));
+          atomicAdd(&h[((j & 1) ? wq >> 16 : wq) & 0x7FFFu], 1u);
+        }
+      }
     }
   }
   atomicAdd(&seen_s, seen);
   __syncthreads();
-  for (int i = tid; i < kBins; i += kHistThreads)
+  // Only bins at or above this workgroup's own bound can matter (the threshold kernel never looks
+  // below the largest bound); the sample's counts in the bins below it are dropped, which spares
+  // most of the global atomics.
+  const int first_bin = full ? 0 : static_cast<int>(l0_s);
+  for (int i = first_bin + tid; i < kBins; i += kHistThreads)
     if (h[i]) atomicAdd(&hist[i], h[i]);
   if (tid == 0) {
     if (!full) {
@@ -311,7 +349,8 @@ void sparse_thresholds(const kvs_desc* d, const SparsePlan& p, const void* K, co
     uint32_t* hist = p.hist + full * 2 * kBins;
     for (int t = 0; t < 2; ++t)
       hipLaunchKernelGGL(sparse_hist_kernel, dim3(grid), dim3(kHistThreads), 0, s, static_cast<const uint4*>(X[t]),
-                         mask, p.rows, d->n, d->Hkv, d->sparse_frac, full, hist + t * kBins, ctrl + t * kCtrlWords);
+                         mask, p.rows, make_fastdiv(static_cast<uint32_t>(d->n)), make_fastdiv(static_cast<uint32_t>(d->Hkv)),
+                         d->sparse_frac, full, hist + t * kBins, ctrl + t * kCtrlWords);
     hipLaunchKernelGGL(sparse_threshold_kernel, dim3(2), dim3(1024), 0, s, hist, ctrl, d->sparse_frac, full, p.tau);
   }
 }

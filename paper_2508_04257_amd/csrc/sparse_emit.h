@@ -33,6 +33,26 @@ __host__ __device__ inline long long emit_list_words(long long cap) {
 constexpr int kEmitCounters = kEmitSegments + 1;
 
 #ifdef __HIPCC__
+// Which halves of a register pair hold a magnitude at or above a threshold, with packed 16-bit
+// arithmetic (used by the quantise kernels to mark isolated entries and by the histogram pass to
+// find the few entries above its bound).
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+typedef short short2v __attribute__((ext_vector_type(2)));
+// 0xFFFF in every half of w whose magnitude pattern is below tau (tau2 = tau in both halves,
+// tau <= 0x8000), 0 in the others.
+__device__ inline uint32_t below_mask(uint32_t w, uint32_t tau2) {
+  const ushort2v d = __builtin_bit_cast(ushort2v, w & 0x7FFF7FFFu) - __builtin_bit_cast(ushort2v, tau2);
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2v, d) >> 15);
+}
+// Bit j = element j of the uint4 (eight halves) is at or above tau.  Each mask contributes the
+// two bits of its pair: the low half's at bit 2 k, the high half's at bit 16 + 2 k + 1.
+__device__ inline uint32_t isolated8(const uint32_t m[4]) {
+  uint32_t x = m[0] & 0x00020001u;
+  x |= m[1] & 0x00080004u;
+  x |= m[2] & 0x00200010u;
+  x |= m[3] & 0x00800040u;
+  return ((x | (x >> 16)) & 0xFFu) ^ 0xFFu;
+}
 // Start of a run of `count` entries for this workgroup (called by one lane).
 __device__ inline int claim_run(const SparseEmit& emit, int count) {
   const int segs = emit_segments(emit.cap);
