@@ -292,6 +292,21 @@ __global__ __launch_bounds__(KVS_WAVE) void decode_combine_kernel(
   const float q0 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 & 0xFFFFu));
   const float q1 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 >> 16));
 
+  // The first kept rows are requested before anything else is read.
+  constexpr int kKeepBatch = 8;
+  const uint32_t* kk = reinterpret_cast<const uint32_t*>(keep_k) + (static_cast<size_t>(b) * Hkv + h) * cap * 64 + lane;
+  const uint32_t* kv = reinterpret_cast<const uint32_t*>(keep_v) + (static_cast<size_t>(b) * Hkv + h) * cap * 64 + lane;
+  uint32_t kw_next[kKeepBatch], vw_next[kKeepBatch];
+#pragma unroll
+  for (int u = 0; u < kKeepBatch; ++u) {
+    kw_next[u] = 0;  vw_next[u] = 0;
+    if (cnt > 0) {
+      const int j = min(u, cnt - 1);
+      kw_next[u] = kk[j * 64];
+      vw_next[u] = kv[j * 64];
+    }
+  }
+
   // One more part, if given: the fp16 rows of a growing cache's residual window (the same triple
   // of unnormalised row, maximum and sum, one per (b, hq)).
   const float* xrow = extra ? extra + bq * kWsRow : nullptr;
@@ -318,26 +333,31 @@ __global__ __launch_bounds__(KVS_WAVE) void decode_combine_kernel(
     O1 += o.y * f;
   }
 
-  // Kept tokens: exact fp16 rows.  Four rows per step so that their loads overlap.
-  const uint32_t* kk = reinterpret_cast<const uint32_t*>(keep_k) + (static_cast<size_t>(b) * Hkv + h) * cap * 64 + lane;
-  const uint32_t* kv = reinterpret_cast<const uint32_t*>(keep_v) + (static_cast<size_t>(b) * Hkv + h) * cap * 64 + lane;
-  for (int j0 = 0; j0 < cnt; j0 += 4) {
-    uint32_t kw[4], vw[4];
+  // Kept tokens: exact fp16 rows, eight per step; the step after next is requested before this
+  // one is folded in (the first one was requested at the top of the kernel).
+  for (int j0 = 0; j0 < cnt; j0 += kKeepBatch) {
+    uint32_t kw[kKeepBatch], vw[kKeepBatch];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int j = min(j0 + u, cnt - 1);
-      kw[u] = kk[j * 64];
-      vw[u] = kv[j * 64];
+    for (int u = 0; u < kKeepBatch; ++u) { kw[u] = kw_next[u]; vw[u] = vw_next[u]; }
+    if (j0 + kKeepBatch < cnt) {
+#pragma unroll
+      for (int u = 0; u < kKeepBatch; ++u) {
+        const int j = min(j0 + kKeepBatch + u, cnt - 1);
+        kw_next[u] = kk[j * 64];
+        vw_next[u] = kv[j * 64];
+      }
     }
+    float sc[kKeepBatch];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kKeepBatch; ++u)               // the reductions of one step are independent of each other
+      sc[u] = kvs::wave_sum(q0 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] & 0xFFFFu)) +
+                            q1 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] >> 16))) * kRsqrtD;
+#pragma unroll
+    for (int u = 0; u < kKeepBatch; ++u) {
       if (j0 + u < cnt) {
-        const float part = q0 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] & 0xFFFFu)) +
-                           q1 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] >> 16));
-        const float s = kvs::wave_sum(part) * kRsqrtD;
-        const float m_new = fmaxf(M, s);
+        const float m_new = fmaxf(M, sc[u]);
         const float alpha = M == -INFINITY ? 0.0f : __expf(M - m_new);
-        const float p = __expf(s - m_new);
+        const float p = __expf(sc[u] - m_new);
         L = L * alpha + p;
         O0 = O0 * alpha + p * kvs::half_bits_to_float(static_cast<uint16_t>(vw[u] & 0xFFFFu));
         O1 = O1 * alpha + p * kvs::half_bits_to_float(static_cast<uint16_t>(vw[u] >> 16));
