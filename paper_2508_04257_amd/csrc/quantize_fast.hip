@@ -170,11 +170,15 @@ __device__ inline uint32_t half_of(const uint4& v, int j) {
   return (j & 1) ? w >> 16 : w & 0xFFFFu;
 }
 
-// Slot of token t in the ascending keep list of its sequence, or -1.
+// Slot of token t in the ascending keep list of its sequence, or -1 (binary search: the list can
+// be long when a first-N policy keeps many tokens).
 __device__ inline int keep_slot(const int32_t* __restrict__ keep_idx, int cnt, int t) {
-  for (int j = 0; j < cnt; ++j)
-    if (keep_idx[j] == t) return j;
-  return -1;
+  int lo = 0, hi = cnt;                          // first index whose token is >= t
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (keep_idx[mid] < t) lo = mid + 1; else hi = mid;
+  }
+  return lo < cnt && keep_idx[lo] == t ? lo : -1;
 }
 
 // ---------------------------------------------------------------------------------------------

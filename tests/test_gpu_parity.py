@@ -164,6 +164,27 @@ def test_other_gqa_ratios(rep):
     assert row_rel_err(out, O.decode_attn(q, ref, Hq=H * rep)[2]) <= OUT_TOL
 
 
+@pytest.mark.parametrize("bits,G", [(4, 128), (2, 32)])
+def test_many_kept_tokens(bits, G):
+    """A first-N policy with a large N: 600 leading tokens plus scattered sinks are kept."""
+    rng = np.random.default_rng(bits)
+    B, H, n, cap = 2, 2, 2048, 640
+    K, V = random_fp16(rng, (B, H, n, 128)), random_fp16(rng, (B, H, n, 128))
+    mask = np.zeros((B, n), np.uint8)
+    mask[:, :600] = 1
+    mask[0, [700, 1500, 2047]] = 1
+    mask[1, 601:640:3] = 1
+    q = random_fp16(rng, (B, H, 128))
+    desc, cache, ws = hip_quantize(K, V, mask, bits, G, keep_cap=cap)
+    ref = O.quantize_kv(K, V, mask, bits, G, keep_cap=cap)
+    assert ref.status == O.STATUS_OK
+    assert_cache_equal(cache, ref)
+    out, lse = hip_decode(desc, cache, ws, q)
+    _, ref_lse, ref64 = O.decode_attn(q, ref, Hq=H)
+    assert row_rel_err(out, ref64) <= OUT_TOL
+    assert np.abs(lse - ref_lse).max() <= 1e-3
+
+
 @pytest.mark.parametrize("bits,G,rep,kpt", [(4, 128, 1, False), (2, 32, 4, False), (3, 64, 2, True)])
 def test_one_very_long_sequence(bits, G, rep, kpt):
     """A single (sequence, KV head) of 131072 tokens: 1024 Value tiles over 256 parts, the combine
