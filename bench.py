@@ -152,7 +152,8 @@ def growing_cache_leg(w, kv, q, dec_bytes):
         "ms_append_kv_mean": round(ms_append, 4),
         "appends_timed": len(rows),
         "note": "decode over n - 64 tokens incl. 64 fp16 residual rows, back to back on one cache (last-level-cache "
-                "resident); append = mean over 64 calls, the last of which quantises a completed block",
+                "resident); append = mean over 64 calls issued from Python (one 2 us copy kernel each, so this is the host's launch rate), "
+                "the last of which quantises a completed block",
     }
 
 
