@@ -140,3 +140,32 @@ def test_static_quantisation_calls_check_their_arguments_on_the_host():
     assert L.kvs_quantize_kv_static(C.byref(ds), 16, 16, 16, 16, 16, C.byref(full), 16, None) == kb.KVS_ERR_UNSUPPORTED
     bad = kb.make_desc(B=2, n=1000, Hq=32, Hkv=32, bits=4, group=128, keep_cap=2)
     assert kb.kvs_calibration_bytes(bad) == 0
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 with a C compiler, and a C program
+    must link against the library's host-side calls."""
+    import shutil
+    import subprocess
+
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_kvs.c"
+    src.write_text(
+        '#include "kvs.h"\n'
+        "int main(void) {\n"
+        "  kvs_desc d = {0};\n"
+        "  size_t sizes[KVS_CACHE_FIELDS];\n"
+        "  d.B = 2; d.n = 1024; d.Hq = 32; d.Hkv = 32; d.D = 128; d.bits = 4; d.group = 128; d.keep_cap = 2;\n"
+        "  if (kvs_cache_bytes(&d, sizes) != KVS_OK) return 1;\n"
+        "  if (sizes[0] != (size_t)2 * 32 * 1024 * 64) return 2;\n"
+        "  d.bits = 5;\n"
+        "  return kvs_cache_bytes(&d, sizes) == KVS_ERR_UNSUPPORTED ? 0 : 3;\n"
+        "}\n")
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    libdir = os.path.dirname(kb._LIB_PATH)
+    exe = tmp_path / "use_kvs"
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-lkvs",
+                    "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    assert subprocess.run([str(exe)]).returncode == 0
