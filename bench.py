@@ -33,8 +33,8 @@ HBM_PEAK_GBPS = 8000.0
 DECODE_TRAFFIC = {
     "workload": "cfg1",
     "sources": ["decode_mfma_impl.h", "decode_mfma_b4.hip", "decode_mfma.hip", "kvs_device.h", "kvs_api.hip"],
-    "sha256_16": "988a5a7b269c772b",
-    "fetch_bytes": 144085071,
+    "sha256_16": "7e1a55974d715dbb",
+    "fetch_bytes": 144036216,
     "write_bytes": 73728,
 }
 
@@ -199,7 +199,7 @@ def per_token_key_leg(w, inputs, bufs, q, dec_bytes, qnt_bytes):
     from paper_2508_04257_amd import binding as kb
     from paper_2508_04257_amd import pipeline
 
-    if w.key_per_token or w.sparse_frac > 0 or (w.Hq // w.Hkv) * (w.D // w.group) > 8:
+    if w.key_per_token or w.sparse_frac > 0:
         return None
     dev = q.device
     desc = pipeline.desc_for(w.scaled(key_per_token=True))

@@ -85,8 +85,8 @@ typedef struct kvs_desc {
   float sparse_frac;        /* fraction of entries isolated in fp16; 0 = off                  */
   int32_t key_per_token;    /* 0: per-channel Keys (above); 1: Keys quantised like Values, groups */
                             /* of G channels of one token (the per-token scheme of Section 5.1) - */
-                            /* k_params is then [B, Hkv, n, 128/G].  Not with sparse_frac > 0,    */
-                            /* and not when (Hq / Hkv) * (128 / G) > 8 (KVS_ERR_UNSUPPORTED).     */
+                            /* k_params is then [B, Hkv, n, 128/G].  Not with sparse_frac > 0     */
+                            /* (KVS_ERR_UNSUPPORTED).                                             */
   int64_t sparse_cap;       /* CSR capacity in entries per tensor when sparse_frac > 0        */
 } kvs_desc;
 

@@ -18,7 +18,7 @@ void launch_decode_mfma_kpt_b4(const kvs_desc*, const DecodeGeometry&, const voi
 
 bool decode_mfma_supported(const kvs_desc* d) {
   const int rep = d->Hq / d->Hkv;
-  if (d->key_per_token) return true;                 // every shape the descriptor check lets through
+  if (d->key_per_token) return rep * (KVS_HEAD_DIM / d->group) <= 8;   // heads x channel groups x [hi | lo] <= 16 columns
   if (d->sparse_frac != 0.0f) return rep == 1;       // isolated outliers: one query head per KV head
   if (rep == 1 || rep == 4) return true;
   return d->group == 128;                            // 2 or 8 query heads per KV head

@@ -16,8 +16,7 @@ kvs_status validate_desc(const kvs_desc* d) {
   if (d->n % KVS_V_TILE != 0) return KVS_ERR_UNSUPPORTED;      // also a multiple of 64 and of G
   const int rep = d->Hq / d->Hkv;
   if (rep != 1 && rep != 2 && rep != 4 && rep != 8) return KVS_ERR_UNSUPPORTED;
-  // Per-token Keys: dense caches only; the score tile has 16 columns for heads x channel groups x 2.
-  if (d->key_per_token && (d->sparse_frac > 0.0f || rep * (KVS_HEAD_DIM / d->group) > 8)) return KVS_ERR_UNSUPPORTED;
+  if (d->key_per_token && d->sparse_frac > 0.0f) return KVS_ERR_UNSUPPORTED;   // per-token Keys: dense caches only
   // CSR rows and word offsets are 32-bit quantities in places; keep a wide margin.
   const int64_t rows = static_cast<int64_t>(d->B) * d->Hkv * d->n;
   if (rows >= (int64_t{1} << 30)) return KVS_ERR_UNSUPPORTED;

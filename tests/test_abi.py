@@ -81,9 +81,9 @@ def test_per_token_key_descriptors():
     assert kb.lib().kvs_cache_bytes(C.byref(ok), sizes) == kb.KVS_OK
     plain = kb.make_desc(B=2, n=1024, Hq=32, Hkv=8, bits=4, group=64, keep_cap=2)
     assert kb.kvs_cache_bytes(ok) == kb.kvs_cache_bytes(plain)          # the parameter array only changes shape
-    # heads x channel groups beyond the 16 tile columns, and isolated outliers: not with per-token Keys
     wide = kb.make_desc(B=2, n=1024, Hq=32, Hkv=8, bits=4, group=32, keep_cap=2, key_per_token=True)
-    assert kb.lib().kvs_cache_bytes(C.byref(wide), sizes) == kb.KVS_ERR_UNSUPPORTED
+    assert kb.lib().kvs_cache_bytes(C.byref(wide), sizes) == kb.KVS_OK
+    # isolated outliers: not with per-token Keys
     sp = kb.make_desc(B=2, n=1024, Hq=32, Hkv=32, bits=4, group=128, keep_cap=2, sparse_frac=0.01, sparse_cap=100,
                       key_per_token=True)
     assert kb.lib().kvs_cache_bytes(C.byref(sp), sizes) == kb.KVS_ERR_UNSUPPORTED

@@ -13,7 +13,9 @@ from tests.test_gpu_parity import DEV, OUT_TOL, assert_cache_equal, hip_decode, 
 
 pytestmark = pytest.mark.gpu
 
-SHAPES = [(128, 1), (128, 2), (128, 4), (128, 8), (64, 1), (64, 2), (64, 4), (32, 1), (32, 2)]
+# the last three (heads x channel groups > 8) have no room in the matrix-core score tile: stream kernel
+SHAPES = [(128, 1), (128, 2), (128, 4), (128, 8), (64, 1), (64, 2), (64, 4), (32, 1), (32, 2), (64, 8), (32, 4),
+          (32, 8)]
 
 
 def dev(x):
@@ -54,6 +56,7 @@ def test_quantize_and_decode(bits, G, rep):
     (4, 64, 4, 1, 1, 4096),       # one (sequence, head): many parts, the combine kernel finishes
     (2, 32, 2, 1, 2, 2048),
     (3, 128, 8, 1, 1, 1280),
+    (4, 32, 8, 1, 1, 4096),       # stream kernel, two groups of four heads, many parts
 ])
 def test_single_part_and_many_parts(bits, G, rep, B, H, n):
     rng = np.random.default_rng(bits + G + n)
@@ -93,7 +96,7 @@ def test_degenerate_rows_and_everything_kept():
     assert row_rel_err(out[:1], ref64[:1]) <= OUT_TOL     # sequence 0 is an ordinary one
 
 
-@pytest.mark.parametrize("bits,G,rep", [(4, 128, 1), (3, 64, 4), (2, 32, 2)])
+@pytest.mark.parametrize("bits,G,rep", [(4, 128, 1), (3, 64, 4), (2, 32, 2), (4, 32, 4)])
 def test_static_parameters(bits, G, rep):
     rng = np.random.default_rng(50 + bits)
     B, H, n, cap = 2, 3, 1152, 6
@@ -122,7 +125,7 @@ def test_static_parameters(bits, G, rep):
     assert np.abs(lse - ref_lse).max() <= 2e-3 * max(1.0, np.abs(ref_lse).max())
 
 
-@pytest.mark.parametrize("bits,G,rep,n0", [(4, 128, 1, 300), (3, 64, 2, 257), (2, 32, 1, 100)])
+@pytest.mark.parametrize("bits,G,rep,n0", [(4, 128, 1, 300), (3, 64, 2, 257), (2, 32, 1, 100), (3, 64, 8, 200)])
 def test_growing_cache(bits, G, rep, n0):
     rng = np.random.default_rng(bits * 7 + n0)
     B, H, n_cap, cap, n1 = 2, 2, 640, 6, n0 + 140

@@ -14,18 +14,15 @@ pytestmark = pytest.mark.gpu
 
 
 def _draw(rng):
-    while True:
-        bits = int(rng.choice([2, 3, 4]))
-        G = int(rng.choice([32, 64, 128]))
-        rep = int(rng.choice([1, 2, 4, 8]))
-        kpt = bool(rng.integers(0, 2))
-        sparse = (not kpt) and rng.random() < 0.3
-        if kpt and rep * (128 // G) > 8:
-            continue
-        B = int(rng.integers(1, 4))
-        H = int(rng.integers(1, 4))
-        n = 128 * int(rng.integers(1, 13))
-        return bits, G, rep, kpt, sparse, B, H, n
+    bits = int(rng.choice([2, 3, 4]))
+    G = int(rng.choice([32, 64, 128]))
+    rep = int(rng.choice([1, 2, 4, 8]))
+    kpt = bool(rng.integers(0, 2))
+    sparse = (not kpt) and rng.random() < 0.3
+    B = int(rng.integers(1, 4))
+    H = int(rng.integers(1, 4))
+    n = 128 * int(rng.integers(1, 13))
+    return bits, G, rep, kpt, sparse, B, H, n
 
 
 @pytest.mark.parametrize("case", range(64))
