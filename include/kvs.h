@@ -2,7 +2,7 @@
  * kvs.h - C ABI of the KVSink hot path on AMD Instinct MI355X (gfx950).
  *
  * KVSink (arXiv 2508.04257) keeps the Key/Value rows of attention-sink tokens in 16 bit while
- * the rest of the KV cache is quantised to 2-4 bits, and finds those tokens from the extreme
+ * the rest of the KV cache is quantised to 2-4 (or 8) bits, and finds those tokens from the extreme
  * activation outliers of one hidden-state channel.  The three calls below are the data-parallel
  * part of that method:
  *
@@ -30,8 +30,9 @@
  *   - fp16 is IEEE binary16; inputs must be finite.  All tensors are dense, row-major.
  *
  * Packed cache layout (D = 128 only)
- *   cpw = codes per 32-bit word: 16 (2 bit), 10 (3 bit), 8 (4 bit);  W = ceil(128 / cpw) = 8, 13, 16.
- *   Slot j of a word sits at bit 2j (2 bit) / 4j (4 bit); for 3 bit, slots 0-4 sit at bits
+ *   cpw = codes per 32-bit word: 16 (2 bit), 10 (3 bit), 8 (4 bit), 4 (8 bit);
+ *   W = ceil(128 / cpw) = 8, 13, 16, 32.
+ *   Slot j of a word sits at bit 2j (2 bit) / 4j (4 bit) / 8j (8 bit); for 3 bit, slots 0-4 sit at bits
  *   3j and slots 5-9 at bits 16 + 3(j - 5), bits 15 and 31 are zero.  Unused slots are zero.
  *   k_codes  uint32 [B, Hkv, n/64, W, 64]   word (T, w, t): channels cpw*w .. of token 64T + t.
  *   v_codes  uint32 [B, Hkv, n/128, W, 128] word (T, u, c): tokens 128T + cpw*u .. of channel c.
@@ -79,7 +80,7 @@ typedef enum {
 typedef struct kvs_desc {
   int32_t B, n, Hq, Hkv, D; /* batch, cached tokens, query heads, KV heads, head dim (128)    */
                             /* Hq / Hkv in {1, 2, 4, 8};  n % 128 == 0                        */
-  int32_t bits;             /* 2, 3 or 4                                                      */
+  int32_t bits;             /* 2, 3, 4 or 8 (8: not with sparse_frac > 0, KVS_ERR_UNSUPPORTED)    */
   int32_t group;            /* G: 32, 64 or 128.  K groups run along tokens, V along channels */
   int32_t keep_cap;         /* rows of the fp16 side buffer per sequence (>= 0)               */
   float sparse_frac;        /* fraction of entries isolated in fp16; 0 = off                  */
@@ -161,7 +162,10 @@ kvs_status kvs_predict_sinks(const void* hidden, int32_t B, int32_t n, int32_t d
  *   scale = fp16_round_up((max - min) / (2^bits - 1)),  zero = -round(min / scale),
  *   code  = clamp(round(x / scale) + zero, 0, 2^bits - 1)
  * in fp32 with round-half-to-even and x / scale evaluated as x * (1 / scale); kept and isolated
- * entries get code 0.  A group with no such entry gets (scale 1, zero 0); a constant group gets
+ * entries get code 0.  At 8 bit the scale is max((max - min) / 255, |min| / 32766) before the
+ * rounding to fp16, which keeps the zero point inside its int16 half (up to 4 bit it always is
+ * for fp16 data); the bound only binds for groups whose values lie within 1/128 of their
+ * distance from zero, and the step it gives is finer than the fp16 spacing of such data.  A group with no such entry gets (scale 1, zero 0); a constant group gets
  * scale |min| (1 if min == 0).  Rows of kept tokens are copied bit for bit to keep_k / keep_v.
  * With sparse_frac > 0 the entries with |x| >= tau go to the CSR arrays with their fp16 value,
  * tau being the magnitude at which the descending cumulative count over all non-kept entries

@@ -30,9 +30,11 @@ SOURCES = {
     "decode_mfma_b2.hip": [],
     "decode_mfma_b3.hip": [],
     "decode_mfma_b4.hip": [],
+    "decode_mfma_b8.hip": [],
     "decode_mfma_kpt_b2.hip": [],
     "decode_mfma_kpt_b3.hip": [],
     "decode_mfma_kpt_b4.hip": [],
+    "decode_mfma_kpt_b8.hip": [],
 }
 
 COMMON = [

@@ -426,14 +426,17 @@ void launch_partial(const kvs_desc* d, const kvs::DecodeGeometry& geo, const voi
       return;
     }
   }
-  if (d->sparse_frac > 0.0f)
-    hipLaunchKernelGGL((decode_partial_kernel<BITS, G, R, true>), dim3(grid), dim3(kThreads), 0, s,
-                       static_cast<const uint16_t*>(q), c->k_codes, c->v_codes, c->k_params, c->v_params,
-                       c->keep_mask, d->n, n_used, d->Hkv, rep, geo.splits, geo.split_tokens, ws, sp);
-  else
-    hipLaunchKernelGGL((decode_partial_kernel<BITS, G, R, false>), dim3(grid), dim3(kThreads), 0, s,
-                       static_cast<const uint16_t*>(q), c->k_codes, c->v_codes, c->k_params, c->v_params,
-                       c->keep_mask, d->n, n_used, d->Hkv, rep, geo.splits, geo.split_tokens, ws, sp);
+  if constexpr (BITS != 8) {                           // (no isolated outliers at 8 bit)
+    if (d->sparse_frac > 0.0f) {
+      hipLaunchKernelGGL((decode_partial_kernel<BITS, G, R, true>), dim3(grid), dim3(kThreads), 0, s,
+                         static_cast<const uint16_t*>(q), c->k_codes, c->v_codes, c->k_params, c->v_params,
+                         c->keep_mask, d->n, n_used, d->Hkv, rep, geo.splits, geo.split_tokens, ws, sp);
+      return;
+    }
+  }
+  hipLaunchKernelGGL((decode_partial_kernel<BITS, G, R, false>), dim3(grid), dim3(kThreads), 0, s,
+                     static_cast<const uint16_t*>(q), c->k_codes, c->v_codes, c->k_params, c->v_params,
+                     c->keep_mask, d->n, n_used, d->Hkv, rep, geo.splits, geo.split_tokens, ws, sp);
 }
 
 template <int BITS, int G>
@@ -553,7 +556,8 @@ static void decode_dense(const kvs_desc* desc, const void* q, const kvs_cache* c
       switch (desc->bits) {
         case 2: launch_partial_g<2>(desc, geo, q, cache, ws, n_used, s); break;
         case 3: launch_partial_g<3>(desc, geo, q, cache, ws, n_used, s); break;
-        default: launch_partial_g<4>(desc, geo, q, cache, ws, n_used, s); break;
+        case 4: launch_partial_g<4>(desc, geo, q, cache, ws, n_used, s); break;
+        default: launch_partial_g<8>(desc, geo, q, cache, ws, n_used, s); break;
       }
     }
   }

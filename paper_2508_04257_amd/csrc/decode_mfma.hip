@@ -11,10 +11,12 @@ namespace kvs {
 void launch_decode_mfma_b2(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, int, const float*, hipStream_t);
 void launch_decode_mfma_b3(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, int, const float*, hipStream_t);
 void launch_decode_mfma_b4(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, int, const float*, hipStream_t);
+void launch_decode_mfma_b8(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, int, const float*, hipStream_t);
 
 void launch_decode_mfma_kpt_b2(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, int, const float*, hipStream_t);
 void launch_decode_mfma_kpt_b3(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, int, const float*, hipStream_t);
 void launch_decode_mfma_kpt_b4(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, int, const float*, hipStream_t);
+void launch_decode_mfma_kpt_b8(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, int, const float*, hipStream_t);
 
 bool decode_mfma_supported(const kvs_desc* d) {
   const int rep = d->Hq / d->Hkv;
@@ -31,12 +33,14 @@ void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void
   if (d->key_per_token) {
     if (d->bits == 2) launch_decode_mfma_kpt_b2(d, geo, q, c, out, lse, ws, n_used, extra, s);
     else if (d->bits == 3) launch_decode_mfma_kpt_b3(d, geo, q, c, out, lse, ws, n_used, extra, s);
-    else launch_decode_mfma_kpt_b4(d, geo, q, c, out, lse, ws, n_used, extra, s);
+    else if (d->bits == 4) launch_decode_mfma_kpt_b4(d, geo, q, c, out, lse, ws, n_used, extra, s);
+    else launch_decode_mfma_kpt_b8(d, geo, q, c, out, lse, ws, n_used, extra, s);
     return;
   }
   if (d->bits == 2) launch_decode_mfma_b2(d, geo, q, c, out, lse, ws, cs, n_used, extra, s);
   else if (d->bits == 3) launch_decode_mfma_b3(d, geo, q, c, out, lse, ws, cs, n_used, extra, s);
-  else launch_decode_mfma_b4(d, geo, q, c, out, lse, ws, cs, n_used, extra, s);
+  else if (d->bits == 4) launch_decode_mfma_b4(d, geo, q, c, out, lse, ws, cs, n_used, extra, s);
+  else launch_decode_mfma_b8(d, geo, q, c, out, lse, ws, cs, n_used, extra, s);
 }
 
 }  // namespace kvs

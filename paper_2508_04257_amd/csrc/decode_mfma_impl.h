@@ -110,14 +110,24 @@ struct Pack<2> {
   }
 };
 
+template <>
+struct Pack<8> {   // bytes 0 and 2 already sit at mantissa bit 0 of their halves; bytes 1 and 3 after one shift
+  static constexpr int CPW = 4, RPW = 2, W = 32;
+  __device__ static constexpr float offset(int) { return 1024.0f; }
+  __device__ static inline void unpack(uint32_t w, uint32_t* r, const Magic& m) {
+    r[0] = (w & 0x00FF00FFu) | m.m0;
+    r[1] = ((w >> 8) & 0x00FF00FFu) | m.m0;
+  }
+};
+
 // Lane group g (= lane / 16) streams word rows g, 4 + g, 8 + g, ... of a tile; its unpacked
 // registers, in that order, are cut into operands of 4 registers (8 contraction slots).
 template <int BITS>
 struct Shape {
   static constexpr int CPW = Pack<BITS>::CPW, RPW = Pack<BITS>::RPW, W = Pack<BITS>::W;
   static constexpr int KW = (W + 3) / 4;            // word rows per lane group (the last may be missing)
-  static constexpr int NREG = KW * RPW;             // registers per lane and row: 16, 20, 16
-  static constexpr int NOPS = NREG / 4;             // matrix instructions per 16 rows: 4, 5, 4
+  static constexpr int NREG = KW * RPW;             // registers per lane and row: 16, 20, 16, 16
+  static constexpr int NOPS = NREG / 4;             // matrix instructions per 16 rows: 4, 5, 4, 4
   static constexpr int TBL = NOPS * 32;             // halves of one operand-table column
   static_assert(NREG % 4 == 0, "operands must be whole");
   // Position in a table column of element e (a channel for Keys, a token of the tile for Values).
@@ -816,7 +826,7 @@ void launch_bits_kpt(const kvs_desc* d, const kvs::DecodeGeometry& geo, const vo
 template <int BITS, int G, int R>
 void launch_one(const kvs_desc* d, const kvs::DecodeGeometry& geo, const MfmaArgs& args, hipStream_t s) {
   const dim3 grid(d->B * d->Hkv * geo.splits), block(waves_for(R) * KVS_WAVE);
-  if constexpr (R == 1) {
+  if constexpr (R == 1 && BITS != 8) {
     if (d->sparse_frac > 0.0f) {
       hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, true>), grid, block, 0, s, args);
       return;

@@ -173,7 +173,8 @@ extern "C" kvs_status kvs_quant_error(const kvs_desc* desc, const void* K, const
                      desc->key_per_token, total_tiles, r)
   if (desc->bits == 2) KVS_LAUNCH_REPORT(2);
   else if (desc->bits == 3) KVS_LAUNCH_REPORT(3);
-  else KVS_LAUNCH_REPORT(4);
+  else if (desc->bits == 4) KVS_LAUNCH_REPORT(4);
+  else KVS_LAUNCH_REPORT(8);
 #undef KVS_LAUNCH_REPORT
   return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
 }

@@ -11,7 +11,8 @@ kvs_status validate_desc(const kvs_desc* d) {
   if (d->sparse_frac > 0.0f && d->sparse_cap < 1) return KVS_ERR_INVALID;
   if (d->key_per_token != 0 && d->key_per_token != 1) return KVS_ERR_INVALID;
   if (d->D != KVS_HEAD_DIM) return KVS_ERR_UNSUPPORTED;
-  if (d->bits != 2 && d->bits != 3 && d->bits != 4) return KVS_ERR_UNSUPPORTED;
+  if (d->bits != 2 && d->bits != 3 && d->bits != 4 && d->bits != 8) return KVS_ERR_UNSUPPORTED;
+  if (d->bits == 8 && d->sparse_frac > 0.0f) return KVS_ERR_UNSUPPORTED;       // isolated outliers are a low-bit remedy
   if (d->group != 32 && d->group != 64 && d->group != 128) return KVS_ERR_UNSUPPORTED;
   if (d->n % KVS_V_TILE != 0) return KVS_ERR_UNSUPPORTED;      // also a multiple of 64 and of G
   const int rep = d->Hq / d->Hkv;

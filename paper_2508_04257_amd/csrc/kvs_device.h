@@ -29,6 +29,11 @@ struct Fmt<4> {
   static constexpr int cpw = 8, W = 16, qmax = 15;
   __host__ __device__ static constexpr int shift(int j) { return 4 * j; }
 };
+template <>
+struct Fmt<8> {
+  static constexpr int cpw = 4, W = 32, qmax = 255;
+  __host__ __device__ static constexpr int shift(int j) { return 8 * j; }
+};
 
 // Host-side checks and launch geometry shared by the entry points (kvs_api.hip).
 kvs_status validate_desc(const kvs_desc* d);
@@ -108,7 +113,7 @@ void sparse_thresholds(const kvs_desc* d, const SparsePlan& p, const void* K, co
                        const uint8_t* mask, const kvs_cache* out, hipStream_t s);
 void sparse_build_csr(const kvs_desc* d, const SparsePlan& p, const kvs_cache* out, hipStream_t s);
 
-__host__ __device__ inline int words_per_128(int bits) { return bits == 2 ? 8 : (bits == 3 ? 13 : 16); }
+__host__ __device__ inline int words_per_128(int bits) { return bits == 2 ? 8 : (bits == 3 ? 13 : (bits == 4 ? 16 : 32)); }
 
 __device__ inline float half_bits_to_float(uint16_t h) {
   return static_cast<float>(__builtin_bit_cast(_Float16, h));

@@ -75,7 +75,10 @@ __device__ inline Param make_param(float mn, float mx, bool any) {
   if (mx == mn) {
     hbits = kvs::float_to_half_bits_rn(mn != 0.0f ? fabsf(mn) : 1.0f);
   } else {
-    const float s32 = (mx - mn) / qmax;
+    float s32 = (mx - mn) / qmax;
+    // 8 bit: the zero point must still fit its int16 half.  (Up to 4 bit it always does for fp16
+    // data: max - min is at least |min| / 2048.)
+    if constexpr (BITS == 8) s32 = fmaxf(s32, fabsf(mn) / 32766.0f);
     hbits = kvs::float_to_half_bits_rn(s32);
     if (kvs::half_bits_to_float(hbits) < s32) hbits += 1;   // next fp16 up (positive values)
   }
@@ -115,6 +118,15 @@ __device__ inline uint32_t codes8(const uint4& raw, const float inv[8], const fl
     out |= code_of<BITS>(hi_half(w[k]), inv[2 * k + 1], zero[2 * k + 1]) << (BITS * (2 * k + 1));
   }
   return out;
+}
+
+// 8 bit: the same eight codes fill two words (channels 8 chunk .. + 3, then + 4 .. + 7).
+__device__ inline void codes8_bytes(const uint4& raw, const float inv[8], const float zero[8], uint32_t& lo, uint32_t& hi) {
+  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+  lo = code_of<8>(lo_half(w[0]), inv[0], zero[0]) | (code_of<8>(hi_half(w[0]), inv[1], zero[1]) << 8) |
+       (code_of<8>(lo_half(w[1]), inv[2], zero[2]) << 16) | (code_of<8>(hi_half(w[1]), inv[3], zero[3]) << 24);
+  hi = code_of<8>(lo_half(w[2]), inv[4], zero[4]) | (code_of<8>(hi_half(w[2]), inv[5], zero[5]) << 8) |
+       (code_of<8>(lo_half(w[3]), inv[6], zero[6]) << 16) | (code_of<8>(hi_half(w[3]), inv[7], zero[7]) << 24);
 }
 
 // 3 bit: a row of 128 codes is first held as sixteen 24-bit pieces (eight codes each, 3 bits per
@@ -220,7 +232,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
   if (SPARSE) {
     const uint32_t tau = *tau_ptr;                 // 0x8000: no magnitude pattern reaches it
     tau2 = tau | (tau << 16);
-    fill_spread_table<BITS>(spread_s, tid);
+    if constexpr (BITS != 8) fill_spread_table<BITS>(spread_s, tid);
   }
   const int blocks_per_head = sp.n_tokens / TB;
   const int blk = blockIdx.x % blocks_per_head;
@@ -339,16 +351,23 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
 #pragma unroll
     for (int i = g * RPG; i < (g + 1) * RPG; ++i) {
       const int r = rslot + 16 * i;
-      uint32_t word = kept[i] ? 0u : codes8<BITS>(raw[i], inv, zero);
-      if (SPARSE) word &= ~spread_s[iso8[i]];     // isolated entries hold code 0
-      if (LANES_PER_WORD == 2) {                  // 2 bit: lanes (even, odd) share a word
-        const uint32_t other = static_cast<uint32_t>(__shfl_xor(static_cast<int>(word), 1, KVS_WAVE));
-        word = word | (other << 16);
+      if constexpr (BITS == 8) {                  // two words per row and lane
+        uint32_t lo = 0, hi = 0;
+        if (!kept[i]) codes8_bytes(raw[i], inv, zero, lo, hi);
+        tile_s[((r / KVS_K_TILE) * W + 2 * chunk) * TILE_STRIDE + (r % KVS_K_TILE)] = lo;
+        tile_s[((r / KVS_K_TILE) * W + 2 * chunk + 1) * TILE_STRIDE + (r % KVS_K_TILE)] = hi;
+      } else {
+        uint32_t word = kept[i] ? 0u : codes8<BITS>(raw[i], inv, zero);
+        if (SPARSE) word &= ~spread_s[iso8[i]];     // isolated entries hold code 0
+        if (LANES_PER_WORD == 2) {                  // 2 bit: lanes (even, odd) share a word
+          const uint32_t other = static_cast<uint32_t>(__shfl_xor(static_cast<int>(word), 1, KVS_WAVE));
+          word = word | (other << 16);
+        }
+        if (BITS == 3)
+          tile_s[r * kPieceStride + chunk] = word;
+        else if (LANES_PER_WORD == 1 || (chunk & 1) == 0)
+          tile_s[((r / KVS_K_TILE) * W + chunk / LANES_PER_WORD) * TILE_STRIDE + (r % KVS_K_TILE)] = word;
       }
-      if (BITS == 3)
-        tile_s[r * kPieceStride + chunk] = word;
-      else if (LANES_PER_WORD == 1 || (chunk & 1) == 0)
-        tile_s[((r / KVS_K_TILE) * W + chunk / LANES_PER_WORD) * TILE_STRIDE + (r % KVS_K_TILE)] = word;
       if (kept[i]) {                              // exact copy of the row into the fp16 side buffer
         const int j = keep_slot(keep_idx + static_cast<size_t>(b) * cap, cnt, tc0 + r);
         if (j >= 0) keep_k[(bh * cap + j) * 16 + chunk] = raw[i];
@@ -487,15 +506,22 @@ __global__ __launch_bounds__(kThreads) void quantize_k_token_fast_kernel(
     float inv[8], zero[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) { inv[j] = inv1; zero[j] = zero1; }
-    uint32_t word = kept[i] ? 0u : codes8<BITS>(raw[i], inv, zero);
-    if (LANES_PER_WORD == 2) {                  // 2 bit: lanes (even, odd) share a word
-      const uint32_t other = static_cast<uint32_t>(__shfl_xor(static_cast<int>(word), 1, KVS_WAVE));
-      word = word | (other << 16);
+    if constexpr (BITS == 8) {                  // two words per row and lane
+      uint32_t lo = 0, hi = 0;
+      if (!kept[i]) codes8_bytes(raw[i], inv, zero, lo, hi);
+      tile_s[((r / KVS_K_TILE) * W + 2 * chunk) * TILE_STRIDE + (r % KVS_K_TILE)] = lo;
+      tile_s[((r / KVS_K_TILE) * W + 2 * chunk + 1) * TILE_STRIDE + (r % KVS_K_TILE)] = hi;
+    } else {
+      uint32_t word = kept[i] ? 0u : codes8<BITS>(raw[i], inv, zero);
+      if (LANES_PER_WORD == 2) {                  // 2 bit: lanes (even, odd) share a word
+        const uint32_t other = static_cast<uint32_t>(__shfl_xor(static_cast<int>(word), 1, KVS_WAVE));
+        word = word | (other << 16);
+      }
+      if (BITS == 3)
+        tile_s[r * kPieceStride + chunk] = word;
+      else if (LANES_PER_WORD == 1 || (chunk & 1) == 0)
+        tile_s[((r / KVS_K_TILE) * W + chunk / LANES_PER_WORD) * TILE_STRIDE + (r % KVS_K_TILE)] = word;
     }
-    if (BITS == 3)
-      tile_s[r * kPieceStride + chunk] = word;
-    else if (LANES_PER_WORD == 1 || (chunk & 1) == 0)
-      tile_s[((r / KVS_K_TILE) * W + chunk / LANES_PER_WORD) * TILE_STRIDE + (r % KVS_K_TILE)] = word;
     if (kept[i]) {                              // exact copy of the row into the fp16 side buffer
       const int j = keep_slot(keep_idx + static_cast<size_t>(b) * cap, cnt, tc0 + r);
       if (j >= 0) keep_k[(bh * cap + j) * 16 + chunk] = raw[i];
@@ -572,7 +598,7 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
   if (SPARSE) {
     const uint32_t tau = *tau_ptr;                 // 0x8000: no magnitude pattern reaches it
     tau2 = tau | (tau << 16);
-    fill_spread_table<BITS>(spread_s, tid);
+    if constexpr (BITS != 8) fill_spread_table<BITS>(spread_s, tid);
   }
   uint32_t iso_lo = 0, iso_hi = 0;                // SPARSE: byte i = isolated channels of the lane's token i;
   uint32_t row_lo = 0, row_hi = 0;                // after the transposition byte j = isolated tokens of channel j
@@ -663,8 +689,11 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
 
   const int cnt = min(keep_cnt[b], cap);
   uint32_t words[8];                            // word j: channel 8 chunk + j, tokens 8 rs .. + 7
+  uint32_t words_hi[BITS == 8 ? 8 : 1];         // 8 bit: tokens 8 rs + 4 .. + 7 fill a second word
 #pragma unroll
   for (int j = 0; j < 8; ++j) words[j] = 0;
+#pragma unroll
+  for (int j = 0; j < (BITS == 8 ? 8 : 1); ++j) words_hi[j] = 0;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int owner = group_base + (i % LPG);
@@ -676,8 +705,14 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
       const uint32_t w4[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        words[2 * c] |= code_of<BITS>(lo_half(w4[c]), inv, zero) << (BITS * i);
-        words[2 * c + 1] |= code_of<BITS>(hi_half(w4[c]), inv, zero) << (BITS * i);
+        if constexpr (BITS == 8) {
+          uint32_t* dst = i < 4 ? words : words_hi;
+          dst[2 * c] |= code_of<8>(lo_half(w4[c]), inv, zero) << (8 * (i & 3));
+          dst[2 * c + 1] |= code_of<8>(hi_half(w4[c]), inv, zero) << (8 * (i & 3));
+        } else {
+          words[2 * c] |= code_of<BITS>(lo_half(w4[c]), inv, zero) << (BITS * i);
+          words[2 * c + 1] |= code_of<BITS>(hi_half(w4[c]), inv, zero) << (BITS * i);
+        }
       }
     } else {
       const int j = keep_slot(keep_idx + static_cast<size_t>(b) * cap, cnt, t0 + 8 * rs + i);
@@ -724,6 +759,14 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
       store_stream(out + qi, uint4{compose3(p, u), compose3(p + kPieceStride, u), compose3(p + 2 * kPieceStride, u),
                                    compose3(p + 3 * kPieceStride, u)});
     }
+    return;
+  }
+  if constexpr (BITS == 8) {                    // four tokens per word: word rows 2 rs and 2 rs + 1
+    uint4* out = reinterpret_cast<uint4*>(v_codes + (bh * tiles_per_head + static_cast<size_t>(tile)) * (W * 128) + 2 * rs * 128 + 8 * chunk);
+    store_stream(out, uint4{words[0], words[1], words[2], words[3]});
+    store_stream(out + 1, uint4{words[4], words[5], words[6], words[7]});
+    store_stream(out + 32, uint4{words_hi[0], words_hi[1], words_hi[2], words_hi[3]});
+    store_stream(out + 33, uint4{words_hi[4], words_hi[5], words_hi[6], words_hi[7]});
     return;
   }
   if (BITS == 2) {                              // 16 tokens per word: row slots (even, odd) share it
@@ -939,22 +982,24 @@ void launch_fast(const kvs_desc* d, const kvs::QuantSpan& sp, bool own_keep, con
     hipLaunchKernelGGL((quantize_k_token_fast_kernel<BITS, G>), dim3(bh * (sp.n_tokens / (2 * KVS_K_TILE))), dim3(kThreads), 0, s,
                        static_cast<const uint4*>(K), mask, sp, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
                        out->keep_cnt, cap, static_cast<uint4*>(out->keep_k), static_k);
-  else if (plan)      // isolated outliers: thresholds plan->tau[0 / 1], row counts behind the row pointers' first word
-    hipLaunchKernelGGL((quantize_k_fast_kernel<BITS, G, true>), dim3(bh * (sp.n_tokens / TB)), dim3(kThreads), 0, s,
-                       static_cast<const uint4*>(K), mask, sp, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
-                       out->keep_cnt, cap, static_cast<uint4*>(out->keep_k), static_k, plan->tau, out->k_rowptr + 1,
-                       plan->emit_k);
-  else
+  else if (plan) {    // isolated outliers: thresholds plan->tau[0 / 1], row counts behind the row pointers' first word
+    if constexpr (BITS != 8)                     // (never asked for at 8 bit: the descriptor check refuses it)
+      hipLaunchKernelGGL((quantize_k_fast_kernel<BITS, G, true>), dim3(bh * (sp.n_tokens / TB)), dim3(kThreads), 0, s,
+                         static_cast<const uint4*>(K), mask, sp, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
+                         out->keep_cnt, cap, static_cast<uint4*>(out->keep_k), static_k, plan->tau, out->k_rowptr + 1,
+                         plan->emit_k);
+  } else
     hipLaunchKernelGGL((quantize_k_fast_kernel<BITS, G, false>), dim3(bh * (sp.n_tokens / TB)), dim3(kThreads), 0, s,
                        static_cast<const uint4*>(K), mask, sp, d->Hkv, out->k_codes, out->k_params, out->keep_idx,
                        out->keep_cnt, cap, static_cast<uint4*>(out->keep_k), static_k, nullptr, nullptr,
                        kvs::SparseEmit{});
-  if (plan)
-    hipLaunchKernelGGL((quantize_v_fast_kernel<BITS, G, true>), dim3(bh * (sp.n_tokens / KVS_V_TILE)), dim3(kThreads), 0, s,
-                       static_cast<const uint4*>(V), mask, sp, d->Hkv, out->v_codes, out->v_params, out->keep_idx,
-                       out->keep_cnt, cap, static_cast<uint4*>(out->keep_v), static_v, plan->tau + 1, out->v_rowptr + 1,
-                       plan->emit_v);
-  else
+  if (plan) {
+    if constexpr (BITS != 8)
+      hipLaunchKernelGGL((quantize_v_fast_kernel<BITS, G, true>), dim3(bh * (sp.n_tokens / KVS_V_TILE)), dim3(kThreads), 0, s,
+                         static_cast<const uint4*>(V), mask, sp, d->Hkv, out->v_codes, out->v_params, out->keep_idx,
+                         out->keep_cnt, cap, static_cast<uint4*>(out->keep_v), static_v, plan->tau + 1, out->v_rowptr + 1,
+                         plan->emit_v);
+  } else
     hipLaunchKernelGGL((quantize_v_fast_kernel<BITS, G, false>), dim3(bh * (sp.n_tokens / KVS_V_TILE)), dim3(kThreads), 0, s,
                        static_cast<const uint4*>(V), mask, sp, d->Hkv, out->v_codes, out->v_params, out->keep_idx,
                        out->keep_cnt, cap, static_cast<uint4*>(out->keep_v), static_v, nullptr, nullptr,
@@ -981,7 +1026,8 @@ void launch_quantize_fast(const kvs_desc* d, const QuantSpan& sp, bool own_keep,
                           const SparsePlan* plan, hipStream_t s) {
   if (d->bits == 2) launch_fast_g<2>(d, sp, own_keep, K, V, mask, out, static_k, static_v, plan, s);
   else if (d->bits == 3) launch_fast_g<3>(d, sp, own_keep, K, V, mask, out, static_k, static_v, plan, s);
-  else launch_fast_g<4>(d, sp, own_keep, K, V, mask, out, static_k, static_v, plan, s);
+  else if (d->bits == 4) launch_fast_g<4>(d, sp, own_keep, K, V, mask, out, static_k, static_v, plan, s);
+  else launch_fast_g<8>(d, sp, own_keep, K, V, mask, out, static_k, static_v, plan, s);
 }
 
 void launch_calibrate_reset(const kvs_desc* d, uint32_t* calib, hipStream_t s) {
@@ -997,7 +1043,8 @@ void launch_static_params(const kvs_desc* d, const uint32_t* calib, uint32_t* st
                           hipStream_t s) {
   if (d->bits == 2) hipLaunchKernelGGL(static_params_kernel<2>, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv, d->group, d->key_per_token, static_k, static_v);
   else if (d->bits == 3) hipLaunchKernelGGL(static_params_kernel<3>, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv, d->group, d->key_per_token, static_k, static_v);
-  else hipLaunchKernelGGL(static_params_kernel<4>, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv, d->group, d->key_per_token, static_k, static_v);
+  else if (d->bits == 4) hipLaunchKernelGGL(static_params_kernel<4>, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv, d->group, d->key_per_token, static_k, static_v);
+  else hipLaunchKernelGGL(static_params_kernel<8>, dim3(d->Hkv), dim3(128), 0, s, calib, d->Hkv, d->group, d->key_per_token, static_k, static_v);
 }
 
 }  // namespace kvs

@@ -73,6 +73,7 @@ WORKLOADS = {
     "cfg3": Workload("cfg3", B=4, n=32768, Hq=32, Hkv=32, bits=2, group=32, k_sinks=8, first_n=16),
     "cfg1_per_token_keys": Workload("cfg1_per_token_keys", B=8, n=4096, Hq=32, Hkv=32, bits=4, group=128, k_sinks=5,
                                     key_per_token=True),
+    "cfg1_int8": Workload("cfg1_int8", B=8, n=4096, Hq=32, Hkv=32, bits=8, group=128, k_sinks=5),
     "cfg4": Workload("cfg4", B=32, n=4096, Hq=32, Hkv=32, bits=3, group=128, k_sinks=5,
                      sparse_frac=0.01, layers=32, student_t=True),
 }

@@ -51,6 +51,9 @@ def test_cache_bytes_for_the_headline_workload():
     assert kb.kvs_cache_bytes(d3)["k_codes"] == 16 * 8 * 8192 * 13 * 4   # 13 words per 128 codes
     d2 = kb.make_desc(B=4, n=32768, Hq=32, Hkv=32, bits=2, group=32, keep_cap=24)
     assert kb.kvs_cache_bytes(d2)["v_params"] == 4 * 32 * 32768 * 4 * 4
+    d8 = kb.make_desc(B=8, n=4096, Hq=32, Hkv=32, bits=8, group=128, keep_cap=5)
+    assert kb.kvs_cache_bytes(d8)["k_codes"] == kb.kvs_cache_bytes(d8)["v_codes"] == 8 * 32 * 4096 * 128   # a byte per element
+    assert kb.kvs_cache_bytes(d8)["k_params"] == s["k_params"]
     assert kb.kvs_workspace_bytes(d) >= 8 * 32 * kb.kvs_decode_splits(d) * 130 * 4
     assert 1 <= kb.kvs_decode_splits(d) <= 4096 // 128
 
@@ -87,6 +90,8 @@ def test_per_token_key_descriptors():
     sp = kb.make_desc(B=2, n=1024, Hq=32, Hkv=32, bits=4, group=128, keep_cap=2, sparse_frac=0.01, sparse_cap=100,
                       key_per_token=True)
     assert kb.lib().kvs_cache_bytes(C.byref(sp), sizes) == kb.KVS_ERR_UNSUPPORTED
+    sp8 = kb.make_desc(B=2, n=1024, Hq=32, Hkv=32, bits=8, group=128, keep_cap=2, sparse_frac=0.01, sparse_cap=100)
+    assert kb.lib().kvs_cache_bytes(C.byref(sp8), sizes) == kb.KVS_ERR_UNSUPPORTED     # nor with 8-bit codes
 
 
 def test_null_pointers_are_rejected_on_the_host():

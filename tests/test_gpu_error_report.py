@@ -25,7 +25,7 @@ def _close(got, ref):
 
 
 @pytest.mark.parametrize("bits,G,kpt", [(4, 128, False), (3, 64, False), (2, 32, False), (4, 64, True), (3, 32, True),
-                                        (2, 128, True)])
+                                        (2, 128, True), (8, 64, False), (8, 32, True)])
 def test_report_matches_the_oracle(bits, G, kpt):
     rng = np.random.default_rng(bits * 10 + G + kpt)
     B, H, n, cap = 2, 3, 640, 3

@@ -74,6 +74,7 @@ def check_decode(desc, cache, ws, q, gc, Hq):
     (4, 128, 1, 100),      # shorter than one block: residual rows only
     (2, 128, 4, 384),      # whole blocks only
     (4, 32, 1, 0),         # an empty prompt
+    (8, 64, 4, 300), (8, 128, 1, 257),
 ])
 def test_prefix_then_appends_match_the_oracle(bits, G, rep, n0):
     rng = np.random.default_rng(bits * 1000 + G + n0)

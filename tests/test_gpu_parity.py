@@ -482,6 +482,10 @@ def test_full_size_headline_shape_with_per_token_keys():
     _sampled_full_size("cfg1_per_token_keys")
 
 
+def test_full_size_headline_shape_with_8_bit_codes():
+    _sampled_full_size("cfg1_int8", n_pairs=2)
+
+
 def test_full_size_gqa_int3_workload():
     _sampled_full_size("cfg2", n_pairs=2)
 

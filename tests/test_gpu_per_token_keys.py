@@ -33,7 +33,7 @@ def _inputs(rng, B, H, n, Hq, v_kind="wide"):
     return K, V, mask, random_fp16(rng, (B, Hq, 128))
 
 
-@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("bits", [2, 3, 4, 8])
 @pytest.mark.parametrize("G,rep", SHAPES)
 def test_quantize_and_decode(bits, G, rep):
     rng = np.random.default_rng(1000 * bits + G + rep)
@@ -96,7 +96,7 @@ def test_degenerate_rows_and_everything_kept():
     assert row_rel_err(out[:1], ref64[:1]) <= OUT_TOL     # sequence 0 is an ordinary one
 
 
-@pytest.mark.parametrize("bits,G,rep", [(4, 128, 1), (3, 64, 4), (2, 32, 2), (4, 32, 4)])
+@pytest.mark.parametrize("bits,G,rep", [(4, 128, 1), (3, 64, 4), (2, 32, 2), (4, 32, 4), (8, 64, 2)])
 def test_static_parameters(bits, G, rep):
     rng = np.random.default_rng(50 + bits)
     B, H, n, cap = 2, 3, 1152, 6
@@ -125,7 +125,7 @@ def test_static_parameters(bits, G, rep):
     assert np.abs(lse - ref_lse).max() <= 2e-3 * max(1.0, np.abs(ref_lse).max())
 
 
-@pytest.mark.parametrize("bits,G,rep,n0", [(4, 128, 1, 300), (3, 64, 2, 257), (2, 32, 1, 100), (3, 64, 8, 200)])
+@pytest.mark.parametrize("bits,G,rep,n0", [(4, 128, 1, 300), (3, 64, 2, 257), (2, 32, 1, 100), (3, 64, 8, 200), (8, 32, 2, 300)])
 def test_growing_cache(bits, G, rep, n0):
     rng = np.random.default_rng(bits * 7 + n0)
     B, H, n_cap, cap, n1 = 2, 2, 640, 6, n0 + 140

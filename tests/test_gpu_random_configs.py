@@ -14,11 +14,11 @@ pytestmark = pytest.mark.gpu
 
 
 def _draw(rng):
-    bits = int(rng.choice([2, 3, 4]))
+    bits = int(rng.choice([2, 3, 4, 8]))
     G = int(rng.choice([32, 64, 128]))
     rep = int(rng.choice([1, 2, 4, 8]))
     kpt = bool(rng.integers(0, 2))
-    sparse = (not kpt) and rng.random() < 0.3
+    sparse = (not kpt) and bits != 8 and rng.random() < 0.3
     B = int(rng.integers(1, 4))
     H = int(rng.integers(1, 4))
     n = 128 * int(rng.integers(1, 13))

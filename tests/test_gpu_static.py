@@ -16,7 +16,8 @@ def dev(x):
     return torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
 
 
-@pytest.mark.parametrize("bits,G,rep", [(4, 128, 1), (3, 64, 4), (2, 32, 1), (4, 32, 2), (3, 128, 8)])
+@pytest.mark.parametrize("bits,G,rep", [(4, 128, 1), (3, 64, 4), (2, 32, 1), (4, 32, 2), (3, 128, 8), (8, 64, 1),
+                                          (8, 128, 4)])
 def test_calibrate_then_static_quantise(bits, G, rep):
     rng = np.random.default_rng(bits * 100 + G)
     B, H, n, cap = 2, 3, 1152, 4                                   # 9 tiles: a ragged calibration segment too

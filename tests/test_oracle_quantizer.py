@@ -9,7 +9,7 @@ import pytest
 from oracle import kvsink_oracle as O
 from tests.helpers import random_fp16
 
-BITS = [2, 3, 4]
+BITS = [2, 3, 4, 8]
 GROUPS = [32, 64, 128]
 
 
@@ -43,6 +43,7 @@ def test_scale_is_tight_upper_rounding_of_range_over_qmax(bits, kind):
         if mx[i] == mn[i]:
             continue
         exact = (Fraction(float(mx[i])) - Fraction(float(mn[i]))) / qmax
+        exact = max(exact, abs(Fraction(float(mn[i]))) / 32766)          # the int16 bound on the zero point
         s = Fraction(float(scale_h[i]))
         below = Fraction(float(np.nextafter(scale_h[i], np.float16(0))))
         assert s >= exact * (1 - Fraction(1, 2 ** 23))
@@ -230,6 +231,48 @@ def test_single_code_lands_in_the_documented_word_and_bits(bits):
         nz = np.argwhere(wv)
         assert nz.tolist() == [[t // 128, (t % 128) // cpw, c]]       # (tile, word = token chunk, channel)
         assert wv[tuple(nz[0])] == (2 ** bits - 1) << shift((t % 128) % cpw)
+
+
+def test_zero_point_bound_on_the_scale_cannot_bind_up_to_4_bits():
+    """Exhaustive over fp16: the narrowest non-constant group at a given minimum is {x, next fp16
+    above x}; even there (max - min) / 15 exceeds |min| / 32766 by a margin far above fp32 rounding,
+    so for 2, 3 and 4 bit the scale is the plain range / qmax whatever the data."""
+    bits16 = np.concatenate([np.arange(0x0000, 0x7BFF, dtype=np.uint16), np.arange(0x8001, 0xFC00, dtype=np.uint16)])
+    x = bits16.view(np.float16)
+    up = np.nextafter(x, np.float16(np.inf))
+    ok = np.isfinite(up) & (up > x)
+    mn, mx = x[ok].astype(np.float64), up[ok].astype(np.float64)
+    assert np.all((mx - mn) / 15 > 1.05 * np.abs(mn) / 32766)
+    for bits in (2, 3, 4):
+        pick = np.random.default_rng(bits).integers(0, mn.size, 4000)
+        scale_h, zero = O.group_params(mn[pick].astype(np.float32), mx[pick].astype(np.float32), np.full(4000, 2), bits)
+        plain = O.fp32_to_fp16_round_up(((mx[pick] - mn[pick]).astype(np.float32) / np.float32(2 ** bits - 1)).astype(np.float32))
+        assert np.array_equal(scale_h, plain)
+        assert np.abs(zero.astype(np.int64)).max() <= 2048 * (2 ** bits - 1)
+
+
+def test_8_bit_groups_far_from_zero_keep_an_int16_zero_point():
+    """Values within 1/128 of their distance from zero: range / 255 would put the zero point past
+    int16; the widened scale keeps it inside, every code stays in 0..255 and the round trip is
+    still finer than the fp16 spacing of the data."""
+    rng = np.random.default_rng(8)
+    for base in (1000.0, -1000.0, 12.5, -0.37, 30000.0):
+        x = (np.float16(base) + rng.integers(0, 4, (64, 32)) * np.spacing(np.float16(abs(base)))).astype(np.float16)
+        mn, mx = x.min(1).astype(np.float32), x.max(1).astype(np.float32)
+        assert np.all(np.abs(mn) / (mx - mn + 1e-30) > 128)               # the bound binds here
+        scale_h, zero = O.group_params(mn, mx, np.full(64, 32), 8)
+        assert np.abs(zero.astype(np.int64)).max() <= 32766
+        codes = O.quantize_entries(x.astype(np.float32), scale_h[:, None], zero[:, None], 8, np.zeros(x.shape, bool))
+        r = np.rint(x.astype(np.float64) / scale_h.astype(np.float64)[:, None]) + zero[:, None]
+        assert r.min() >= 0 and r.max() <= 255                            # nothing was clamped
+        back = O.dequantize_entries(codes, scale_h[:, None], zero[:, None]).astype(np.float64)
+        err = np.abs(back - x.astype(np.float64)).max()
+        assert err <= 0.51 * float(scale_h.max()) and err < 0.1 * float(np.spacing(np.float16(abs(base))))
+    # and where the range is wide the bound is idle: the scale is range / 255 rounded up
+    x = random_fp16(rng, (200, 32), "normal")
+    mn, mx = x.min(1).astype(np.float32), x.max(1).astype(np.float32)
+    scale_h, _ = O.group_params(mn, mx, np.full(200, 32), 8)
+    assert np.array_equal(scale_h, O.fp32_to_fp16_round_up(((mx - mn) / np.float32(255)).astype(np.float32)))
 
 
 def test_param_word_encoding():
