@@ -43,8 +43,18 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 #ifndef KVS_MFMA_WAVES_MHA
 #define KVS_MFMA_WAVES_MHA 8
 #endif
-// Waves per workgroup: with one query head per KV head a wave needs fewer registers.
-__host__ __device__ constexpr int waves_for(int R) { return R == 1 ? KVS_MFMA_WAVES_MHA : KVS_MFMA_WAVES; }
+// Waves per workgroup: 8, two per SIMD with up to 256 registers each, or 4 with up to 512.  At
+// 8 bit the stream registers of a wave double, and the variants that also carry several (head,
+// group) columns spill with 256 (1.3 - 2.3 times the run time); so do a few low-bit variants.
+// The table is by measurement: four waves where that was faster, eight elsewhere (a variant that
+// spills a few dozen bytes can still be faster with eight).
+__host__ __device__ constexpr int waves_for(int bits, int G, int R, bool kpt) {
+  if (bits == 8) return R * (128 / G) * (kpt ? 2 : 1) >= 4 ? 4 : 8;
+  if (!kpt) return (bits >= 3 && G == 32 && R == 4) ? 4 : (R == 1 ? KVS_MFMA_WAVES_MHA : KVS_MFMA_WAVES);
+  if (bits >= 3 && G == 128 && R == 8) return 4;
+  if (bits == 3 && ((G == 64 && R == 4) || (G == 32 && R == 2))) return 4;
+  return R == 1 ? KVS_MFMA_WAVES_MHA : KVS_MFMA_WAVES;
+}
 constexpr float kLog2eRsqrtD = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kWsRow = KVS_HEAD_DIM + 2;
@@ -205,9 +215,10 @@ struct MfmaArgs {
 //   score[t] = sum_g scale[t, g] (raw_g[t] - C_g - zero[t, g] Q_g),
 // C_g = what the product holds for the operand offsets, Q_g = the query's sum over the group.
 template <int BITS, int G, int R, bool SPARSE, bool KPT = false>
-__global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(MfmaArgs a) {
+__global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_mfma_kernel(MfmaArgs a) {
   static_assert(!(KPT && SPARSE), "per-token Keys are dense only");
-  constexpr int kWaves = waves_for(R);
+  constexpr int kWaves = waves_for(BITS, G, R, KPT);
+  constexpr int HPW = (R + kWaves - 1) / kWaves;   // heads whose states one wave merges at the end
   using S = Shape<BITS>;
   constexpr int W = S::W, KW = S::KW, RPW = S::RPW, NOPS = S::NOPS, TBL = S::TBL;
   constexpr int NGK = 128 / G;                     // Key token groups per chunk
@@ -250,13 +261,18 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
   const uint32_t* keep_rows_v = reinterpret_cast<const uint32_t*>(a.keep_v) + bh * a.cap * 64 + lane;
   uint32_t keep_first_k = 0, keep_first_v = 0;
   // The finishing wave of head r also requests the extra state now, if there is one.
-  float2 extra_o = {0.0f, 0.0f};
-  float extra_m = -INFINITY, extra_l = 0.0f;
-  if (a.extra && a.parts == 1 && !SPARSE && wave < R) {
-    const float* x = a.extra + (static_cast<size_t>(b) * (a.Hkv * R) + h * R + wave) * kWsRow;
-    extra_o = reinterpret_cast<const float2*>(x)[lane];
-    extra_m = x[128];
-    extra_l = x[129];
+  float2 extra_o[HPW];
+  float extra_m[HPW], extra_l[HPW];
+#pragma unroll
+  for (int k = 0; k < HPW; ++k) {
+    extra_o[k] = float2{0.0f, 0.0f};  extra_m[k] = -INFINITY;  extra_l[k] = 0.0f;
+    const int r = wave + k * kWaves;
+    if (a.extra && a.parts == 1 && !SPARSE && r < R) {
+      const float* x = a.extra + (static_cast<size_t>(b) * (a.Hkv * R) + h * R + r) * kWsRow;
+      extra_o[k] = reinterpret_cast<const float2*>(x)[lane];
+      extra_m[k] = x[128];
+      extra_l[k] = x[129];
+    }
   }
   if (a.parts == 1 && !SPARSE && wave < a.cap) {
     keep_first_k = keep_rows_k[wave * 64];
@@ -731,8 +747,10 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
   __syncthreads();
 
   // ---- merge the waves' states (and the kept rows' states) -----------------------------------
-  if (wave < R) {
-    const int r = wave;
+#pragma unroll
+  for (int k = 0; k < HPW; ++k) {
+    const int r = wave + k * kWaves;
+    if (r >= R) break;
     const size_t bq_row = static_cast<size_t>(b) * Hq + hq0 + r;
     float M = -INFINITY;
 #pragma unroll
@@ -740,14 +758,14 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
     if (fold_keep) {
 #pragma unroll
       for (int w = kWaves; w < 2 * kWaves; ++w) M = fmaxf(M, part_m[w][r]);
-      M = fmaxf(M, extra_m);
+      M = fmaxf(M, extra_m[k]);
     }
     float L = 0.0f, O0 = 0.0f, O1 = 0.0f;
-    if (fold_keep && extra_m != -INFINITY) {
-      const float f = __expf(extra_m - M);
-      L = extra_l * f;
-      O0 = extra_o.x * f;
-      O1 = extra_o.y * f;
+    if (fold_keep && extra_m[k] != -INFINITY) {
+      const float f = __expf(extra_m[k] - M);
+      L = extra_l[k] * f;
+      O0 = extra_o[k].x * f;
+      O1 = extra_o[k].y * f;
     }
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
@@ -762,7 +780,7 @@ __global__ __launch_bounds__(waves_for(R) * KVS_WAVE) void decode_mfma_kernel(Mf
       float* dst = a.ws + (bq_row * a.parts + part) * kWsRow;
       reinterpret_cast<float2*>(dst)[lane] = float2{O0, O1};
       if (lane == 0) { dst[128] = M; dst[129] = L; }
-      return;
+      continue;
     }
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
@@ -798,7 +816,7 @@ inline MfmaArgs make_args(const kvs_desc* d, const kvs::DecodeGeometry& geo, con
 
 template <int BITS, int G, int R>
 void launch_one_kpt(const kvs_desc* d, const kvs::DecodeGeometry& geo, const MfmaArgs& args, hipStream_t s) {
-  const dim3 grid(d->B * d->Hkv * geo.splits), block(waves_for(R) * KVS_WAVE);
+  const dim3 grid(d->B * d->Hkv * geo.splits), block(waves_for(BITS, G, R, true) * KVS_WAVE);
   hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, false, true>), grid, block, 0, s, args);
 }
 
@@ -825,7 +843,7 @@ void launch_bits_kpt(const kvs_desc* d, const kvs::DecodeGeometry& geo, const vo
 
 template <int BITS, int G, int R>
 void launch_one(const kvs_desc* d, const kvs::DecodeGeometry& geo, const MfmaArgs& args, hipStream_t s) {
-  const dim3 grid(d->B * d->Hkv * geo.splits), block(waves_for(R) * KVS_WAVE);
+  const dim3 grid(d->B * d->Hkv * geo.splits), block(waves_for(BITS, G, R, false) * KVS_WAVE);
   if constexpr (R == 1 && BITS != 8) {
     if (d->sparse_frac > 0.0f) {
       hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, true>), grid, block, 0, s, args);
