@@ -2,10 +2,6 @@
 // bit width) and the shapes they are instantiated for.
 #include "kvs_device.h"
 
-#ifndef KVS_MFMA_WAVES
-#define KVS_MFMA_WAVES 8
-#endif
-
 namespace kvs {
 
 void launch_decode_mfma_b2(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, float*, int, const float*, hipStream_t);
@@ -25,8 +21,6 @@ bool decode_mfma_supported(const kvs_desc* d) {
   if (rep == 1 || rep == 4) return true;
   return d->group == 128;                            // 2 or 8 query heads per KV head
 }
-
-int decode_mfma_waves() { return KVS_MFMA_WAVES; }
 
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
                         void* out, float* lse, float* ws, float* cs, int n_used, const float* extra, hipStream_t s) {

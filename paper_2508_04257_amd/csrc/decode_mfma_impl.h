@@ -14,13 +14,14 @@
 // the fp16 rounding of that operand does not reach the result, and - for group size 32 - the
 // second quantisation group that a 64-row tile spans.
 //
-// A workgroup of 8 waves owns one part of the token range of one (sequence, KV head); its
+// A workgroup of 8 waves (4 for the register-hungry variants, see waves_for) owns one part of the
+// token range of one (sequence, KV head); its
 // 128-token chunks are handed to the waves on demand (a counter in LDS), each wave keeping the
 // next chunk's codes in flight, and the waves meet once, at the end, to merge their running
 // softmax states in LDS.  (Which wave gets which chunk depends on timing, so the fp32 summation
 // order - not the result beyond rounding - can differ between two runs.)  When a single
 // workgroup covers the whole sequence the kept (sink) tokens' fp16 rows are folded in - wave w
-// takes rows w, w + 8, ... as one more softmax state - and the output row is written right
+// takes rows w, w + waves, ... as one more softmax state - and the output row is written right
 // there; otherwise the part's state goes to the workspace and the combine kernel of decode.hip
 // finishes.  Per 128-token chunk:
 //   scores  S^T[token, col] = sum_c code[token, c] * B[c, col]     tokens are the M rows
@@ -37,12 +38,6 @@ namespace kvs_mfma {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 
-#ifndef KVS_MFMA_WAVES
-#define KVS_MFMA_WAVES 8
-#endif
-#ifndef KVS_MFMA_WAVES_MHA
-#define KVS_MFMA_WAVES_MHA 8
-#endif
 // Waves per workgroup: 8, two per SIMD with up to 256 registers each, or 4 with up to 512.  At
 // 8 bit the stream registers of a wave double, and the variants that also carry several (head,
 // group) columns spill with 256 (1.3 - 2.3 times the run time); so do a few low-bit variants.
@@ -50,10 +45,10 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 // spills a few dozen bytes can still be faster with eight).
 __host__ __device__ constexpr int waves_for(int bits, int G, int R, bool kpt) {
   if (bits == 8) return R * (128 / G) * (kpt ? 2 : 1) >= 4 ? 4 : 8;
-  if (!kpt) return (bits >= 3 && G == 32 && R == 4) ? 4 : (R == 1 ? KVS_MFMA_WAVES_MHA : KVS_MFMA_WAVES);
+  if (!kpt) return (bits >= 3 && G == 32 && R == 4) ? 4 : 8;
   if (bits >= 3 && G == 128 && R == 8) return 4;
   if (bits == 3 && ((G == 64 && R == 4) || (G == 32 && R == 2))) return 4;
-  return R == 1 ? KVS_MFMA_WAVES_MHA : KVS_MFMA_WAVES;
+  return 8;
 }
 constexpr float kLog2eRsqrtD = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
 constexpr float kLn2 = 0.6931471805599453f;
@@ -158,12 +153,8 @@ struct Shape {
 // Streaming (read-once) 16-byte load: the code stream should not displace anything in the caches.
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 __device__ inline uint4 load_stream(const uint32_t* src) {
-#ifdef KVS_DECODE_PLAIN_LOADS
-  return *reinterpret_cast<const uint4*>(src);
-#else
   const uint4v v = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(src));
   return uint4{v.x, v.y, v.z, v.w};
-#endif
 }
 
 __device__ inline uint32_t word_of(const uint4& v, int r) { return r == 0 ? v.x : (r == 1 ? v.y : (r == 2 ? v.z : v.w)); }

@@ -28,9 +28,7 @@ kvs_status validate_desc(const kvs_desc* d) {
   return KVS_OK;
 }
 
-#ifndef KVS_MFMA_TARGET_GROUPS
-#define KVS_MFMA_TARGET_GROUPS 256   // one 8-wave workgroup per compute unit
-#endif
+constexpr int kMfmaTargetGroups = 256;   // one workgroup per compute unit
 
 // Splits are whole numbers of 128-token Value tiles.  Generic kernel: one workgroup (4 waves) per
 // split, enough workgroups to cover 256 compute units several times over.  Matrix-core kernel:
@@ -41,7 +39,7 @@ int decode_max_splits(const kvs_desc* d) {
   const int pairs = d->B * d->Hkv;
   int splits;
   if (decode_mfma_supported(d)) {
-    splits = pairs >= KVS_MFMA_TARGET_GROUPS ? 1 : (KVS_MFMA_TARGET_GROUPS + pairs / 2) / pairs;
+    splits = pairs >= kMfmaTargetGroups ? 1 : (kMfmaTargetGroups + pairs / 2) / pairs;
   } else {
     splits = (2048 + pairs - 1) / pairs;
   }
