@@ -99,7 +99,7 @@ struct SparseEmit {
 struct SparsePlan {
   size_t rows;      // B * Hkv * n, the row count of both CSR structures
   int nblk;         // scan workgroups
-  uint32_t* hist;   // [2][32768] magnitude histograms of K and V
+  uint32_t* hist;   // histograms of K and V: [2][32768] sample, [2][32768] full, [2][4096] bracket
   uint32_t* tau;    // [2] thresholds as fp16 magnitude patterns (0x8000 = isolate nothing)
   int* sums_k;      // [nblk + 1] scan scratch
   int* sums_v;

@@ -2,10 +2,11 @@
 // entries are isolated in 16 bit - 16-bit value + 16-bit index each, the cost the average-bits
 // column of Table 2 shows - and only the rest is quantised).
 //
-// Threshold: an exact histogram of the 15-bit fp16 magnitude pattern over all entries on
-// non-kept tokens (one workgroup per compute unit, the whole 32768-bin histogram in 128 KB of
-// LDS), then a suffix scan picks the magnitude tau at which the descending cumulative count
-// first reaches ceil(f * count).  Integer counting only, so the result is order-free.
+// Threshold: tau is the fp16 magnitude pattern at which the descending cumulative count over all
+// entries on non-kept tokens first reaches ceil(f * count).  A strided sample brackets it, one pass
+// over the tensor counts exactly what lies in and above the bracket, and a full 32768-bin
+// histogram (128 KB of LDS per workgroup) is the fallback when the bracket missed.  Integer
+// counting only, so the result is order-free and the same whichever way it was found.
 // CSR: the quantise kernels count the isolated entries per row and park them, block by block and
 // already in their final relative order, in a staging list; an in-place scan turns the counts
 // into row pointers and one small kernel moves every block's run to its place.  K and V are
@@ -39,165 +40,318 @@ FastDiv make_fastdiv(uint32_t d) {
 }
 __device__ inline uint32_t fastdiv(uint32_t x, const FastDiv& f) { return (__umulhi(f.m, x) + x) >> f.l; }
 
-// X: fp16 [B*Hkv*n, 128] viewed as uint4 (8 values); entries on kept tokens are skipped.
+// Threshold of one tensor, X: fp16 [B*Hkv*n, 128] viewed as 16-byte units (8 values); entries on
+// kept tokens are skipped everywhere.
 //
-// Only the top of the histogram decides tau, and one LDS atomic per element is what this pass
-// costs, so the bulk of the elements is not counted at all: a workgroup counts everything in its
-// first kSampleSteps grid-stride steps (a sample spread over the whole tensor), takes from that
-// sample the magnitude l0 above which about kSampleMargin * frac of the entries lie, and from
-// then on counts only magnitudes >= l0.  Bins >= the largest l0 of any workgroup are exact in
-// the merged histogram; the number of entries is counted separately.  If the threshold turns out
-// to lie below that (a sample that misjudged the tail), ctrl[kNeedFull] is raised and the full
-// histogram - the same kernel with full != 0 - is taken after all; it returns at once otherwise.
-constexpr int kSampleSteps = 8;
-constexpr float kSampleMargin = 3.0f;
-enum { kCtrlCount = 0, kCtrlL0 = 1, kNeedFull = 2, kCtrlWords = 4 };   // per tensor, in the control block
+// Only the top of the histogram decides tau, and an LDS atomic per element is what a full
+// histogram costs (besides 128 KB of LDS per workgroup, i.e. one workgroup per compute unit).  So:
+//   1. sample:   a full histogram of a strided sample (every stride-th 16 KB block, the block
+//                inside each stride picked by a hash so that no token position is favoured);
+//   2. bracket:  from the sample, the magnitudes lo / hi that about kMargin * f and f / kMargin
+//                of the entries reach; tau is expected in [lo, hi);
+//   3. count:    one pass over the whole tensor that counts the entries at or above hi (one
+//                number) and, per bin, those in [lo, hi): few entries take the slow path and the
+//                fine histogram is small; the kept tokens' entries are taken out again afterwards;
+//   4. threshold: the descending cumulative count from hi downwards; if it does not land inside
+//                [lo, hi) - a sample that misjudged the tail - ctrl[kNeedFull] is raised, and
+//   5. the full histogram of the whole tensor is taken after all (sparse_hist_kernel and pass 1
+//      of the threshold kernel; both return at once otherwise).
+// Every count is an integer and exact, so tau does not depend on which way it was found.
+constexpr float kMargin = 1.25f;
+constexpr int kFineBins = 4096;                   // most bins [lo, hi) may span
+constexpr int kSampleBlocks = 2048;               // 16 KB blocks a sample aims at (32 MB)
+constexpr int kCountThreads = 256;
+constexpr int kCountLoads = 4;                    // 16-byte loads per lane and step of the count pass
+enum { kCtrlCount = 0, kCtrlLo = 1, kNeedFull = 2, kCtrlHi = 3, kCtrlNHi = 4, kCtrlWords = 8 };   // per tensor
 
+struct TensorPair {
+  const uint4* x[2];                              // K, V
+};
+
+// Is the token of 16-byte unit u kept?  (row = (b * Hkv + h) * n + t, below 2^30)
+__device__ inline bool unit_kept(size_t u, const uint8_t* __restrict__ keep_mask, const FastDiv& by_n, const FastDiv& by_heads) {
+  const uint32_t row = static_cast<uint32_t>(u >> 4);
+  const uint32_t bh = fastdiv(row, by_n);
+  const uint32_t t = row - bh * by_n.d;
+  const uint32_t b = fastdiv(bh, by_heads);
+  return keep_mask[static_cast<size_t>(b) * by_n.d + t] != 0;
+}
+
+// Every element of the units a workgroup is given goes into its LDS histogram (32768 bins).
+// grid.y = tensor.  mode 0: the sample (blocks s * stride + hash(s) % stride); mode 1: the whole
+// tensor, only if ctrl[kNeedFull] was raised (it then also recounts nothing: the entry count of
+// the count pass stands).
 __global__ __launch_bounds__(kHistThreads) void sparse_hist_kernel(
-    const uint4* __restrict__ X, const uint8_t* __restrict__ keep_mask, size_t rows, FastDiv by_n, FastDiv by_heads,
-    float frac, int full, uint32_t* __restrict__ hist, uint32_t* __restrict__ ctrl) {
+    TensorPair X, const uint8_t* __restrict__ keep_mask, size_t rows, FastDiv by_n, FastDiv by_heads,
+    int full, uint32_t stride, uint32_t* __restrict__ hist_base, const uint32_t* __restrict__ ctrl_base) {
   __shared__ uint32_t h[kBins];
-  __shared__ unsigned long long part[kHistThreads];
-  __shared__ uint32_t l0_s, seen_s;
-  if (full && ctrl[kNeedFull] == 0) return;             // the bounded histogram was enough
-  for (int i = threadIdx.x; i < kBins; i += kHistThreads) h[i] = 0;
-  if (threadIdx.x == 0) { l0_s = 0; seen_s = 0; }
-  __syncthreads();
+  const int tensor = blockIdx.y;
+  if (full && ctrl_base[tensor * kCtrlWords + kNeedFull] == 0) return;   // the bracket was enough
+  const uint4* __restrict__ x = X.x[tensor];
+  uint32_t* hist = hist_base + static_cast<size_t>(tensor) * kBins;
   const int tid = threadIdx.x;
-  const size_t units = rows * 16;                       // 16-byte units
-  const size_t stride = static_cast<size_t>(gridDim.x) * kHistThreads;
-  uint32_t seen = 0;                                    // units of non-kept tokens this lane met
-  uint32_t l0 = 0;
-  constexpr int U = 4;                                  // 16-byte loads in flight per lane
-  const int steps = static_cast<int>((units + stride * U - 1) / (stride * U));   // the same for every lane
-  for (int step = 0; step < steps; ++step) {
-    if (!full && step == kSampleSteps / U) {
-      // ---- lower bound from the sample: suffix sums over 1024 runs of 32 bins -----------------
-      __syncthreads();
-      unsigned long long own = 0;
-      for (int j = 0; j < 32; ++j) own += h[32 * tid + j];
-      part[tid] = own;
-      __syncthreads();
-      for (int o = 1; o < kHistThreads; o <<= 1) {
-        const unsigned long long add = tid + o < kHistThreads ? part[tid + o] : 0ull;
-        __syncthreads();
-        part[tid] += add;
-        __syncthreads();
-      }
-      const unsigned long long total = part[0], above = part[tid] - own;
-      const unsigned long long want = static_cast<unsigned long long>(
-          fminf(kSampleMargin * frac, 1.0f) * static_cast<float>(total)) + 1;
-      if (want > total) { if (tid == 0) l0_s = 0; }
-      else if (above < want && above + own >= want) {
-        unsigned long long cum = above;
-        for (int j = 31; j >= 0; --j) {
-          cum += h[32 * tid + j];
-          if (cum >= want) { l0_s = static_cast<uint32_t>(32 * tid + j); break; }
-        }
-      }
-      __syncthreads();
-      l0 = l0_s;
-    }
+  for (int i = tid; i < kBins; i += kHistThreads) h[i] = 0;
+  __syncthreads();
+  const size_t units = rows * 16;
+  const size_t blocks = (units + kHistThreads - 1) / kHistThreads;        // 16 KB blocks of the tensor
+  const size_t picks = full ? blocks : (blocks + stride - 1) / stride;    // blocks this launch looks at
+  constexpr int U = 4;                                                     // 16-byte loads in flight per lane
+  for (size_t s0 = static_cast<size_t>(blockIdx.x) * U; s0 < picks; s0 += static_cast<size_t>(gridDim.x) * U) {
     uint4 v[U];
     bool use[U];
 #pragma unroll
     for (int k = 0; k < U; ++k) {
-      // step-major, then workgroup, then the U loads of a step: a workgroup's loads of one step are contiguous
-      const size_t u = ((static_cast<size_t>(step) * gridDim.x + blockIdx.x) * U + k) * kHistThreads + tid;
-      use[k] = u < units;
+      const size_t pick = s0 + k;
+      size_t blk = pick;
+      if (!full) blk = pick * stride + (static_cast<uint32_t>(pick) * 2654435761u >> 16) % stride;
+      const size_t u = blk * kHistThreads + tid;
+      use[k] = pick < picks && u < units;
       const size_t uc = use[k] ? u : 0;
-      const uint32_t row = static_cast<uint32_t>(uc >> 4);      // (b * Hkv + h) * n + t, below 2^30
-      const uint32_t bh = fastdiv(row, by_n);
-      const uint32_t t = row - bh * by_n.d;
-      const uint32_t b = fastdiv(bh, by_heads);
-      use[k] = use[k] && keep_mask[static_cast<size_t>(b) * by_n.d + t] == 0;
-      v[k] = X[uc];
+      use[k] = use[k] && !unit_kept(uc, keep_mask, by_n, by_heads);
+      v[k] = x[uc];
     }
-    const uint32_t l0_2 = l0 | (l0 << 16);
 #pragma unroll
     for (int k = 0; k < U; ++k) {
       if (!use[k]) continue;
-      ++seen;
       const uint32_t w[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
-      if (l0 == 0) {                                   // (uniform) everything is counted
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          atomicAdd(&h[w[j] & 0x7FFFu], 1u);
-          atomicAdd(&h[(w[j] >> 16) & 0x7FFFu], 1u);
-        }
-      } else {
-        // Few entries reach the bound: find them with packed arithmetic and walk only those.
-        uint32_t m[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) m[j] = kvs::below_mask(w[j], l0_2);
-        uint32_t bits = kvs::isolated8(m);
-        while (bits) {
-          const int j = __builtin_ctz(bits);
-          bits &= bits - 1;
-          const int q = j >> 1;
-          const uint32_t wq = q == 0 ? w[0] : (q == 1 ? w[1] : (q == 2 ? w[2] : w[3]));
-          atomicAdd(&h[((j & 1) ? wq >> 16 : wq) & 0x7FFFu], 1u);
-        }
+      for (int j = 0; j < 4; ++j) {
+        atomicAdd(&h[w[j] & 0x7FFFu], 1u);
+        atomicAdd(&h[(w[j] >> 16) & 0x7FFFu], 1u);
       }
     }
   }
-  atomicAdd(&seen_s, seen);
   __syncthreads();
-  // Only bins at or above this workgroup's own bound can matter (the threshold kernel never looks
-  // below the largest bound); the sample's counts in the bins below it are dropped, which spares
-  // most of the global atomics.
-  const int first_bin = full ? 0 : static_cast<int>(l0_s);
-  for (int i = first_bin + tid; i < kBins; i += kHistThreads)
+  for (int i = tid; i < kBins; i += kHistThreads)
     if (h[i]) atomicAdd(&hist[i], h[i]);
-  if (tid == 0) {
-    if (!full) {
-      atomicAdd(&ctrl[kCtrlCount], seen_s * 8u);
-      atomicMax(&ctrl[kCtrlL0], l0_s);
-    }
-  }
 }
 
-// One workgroup per tensor: tau = largest bin t with sum_{bin >= t} hist >= ceil(f * count), where
-// count is the number of entries on non-kept tokens.  pass 0 reads the bounded histogram, whose
-// bins below ctrl[kCtrlL0] are incomplete: if the walk would have to go below it, nothing is
-// written but ctrl[kNeedFull].  pass 1 does the same on the full histogram, if that was raised.
-__global__ __launch_bounds__(1024) void sparse_threshold_kernel(const uint32_t* __restrict__ hist_base,
-                                                                 uint32_t* __restrict__ ctrl_base, float frac, int pass,
-                                                                 uint32_t* __restrict__ tau_out) {
-  __shared__ unsigned long long part[1024];
-  const uint32_t* hist = hist_base + static_cast<size_t>(blockIdx.x) * kBins;
-  uint32_t* ctrl = ctrl_base + blockIdx.x * kCtrlWords;
-  if (pass == 1 && ctrl[kNeedFull] == 0) return;
-  const uint32_t l0 = pass == 0 ? ctrl[kCtrlL0] : 0u;
-  const int tid = threadIdx.x;
-  unsigned long long own = 0;
-  for (int j = 0; j < 32; ++j) own += hist[32 * tid + j];
-  part[tid] = own;
-  __syncthreads();
-  // suffix sums over threads (1024 values): simple log-step scan in LDS
+// Suffix sums over the 1024 threads of a workgroup (in place), log-step in LDS.
+__device__ inline void suffix_scan_1024(unsigned long long* part, int tid) {
   for (int o = 1; o < 1024; o <<= 1) {
     const unsigned long long add = tid + o < 1024 ? part[tid + o] : 0ull;
     __syncthreads();
     part[tid] += add;
     __syncthreads();
   }
-  const unsigned long long count = ctrl[kCtrlCount];
-  const unsigned long long above = part[tid] - own;     // entries in bins of higher threads
-  const double md = ceil(static_cast<double>(frac) * static_cast<double>(count));
-  const unsigned long long m = md <= 0.0 ? 0ull : static_cast<unsigned long long>(md);
-  if (tid == 0 && m == 0) tau_out[blockIdx.x] = 0x8000u;
-  if (m > 0 && above < m && above + own >= m) {         // exactly one thread
+}
+
+// One workgroup per tensor: lo / hi from the sample histogram.  lo = the largest bin that at least
+// min(1, kMargin f) of the sample reaches (0 if the sample is too small to say), hi = one above
+// the largest bin that at least f / kMargin of it reaches; at most kFineBins apart.
+__global__ __launch_bounds__(1024) void sparse_bracket_kernel(const uint32_t* __restrict__ hist_base, float frac,
+                                                               uint32_t* __restrict__ ctrl_base) {
+  __shared__ unsigned long long part[1024];
+  __shared__ uint32_t lo_s, hi_s;
+  const uint32_t* hist = hist_base + static_cast<size_t>(blockIdx.x) * kBins;
+  uint32_t* ctrl = ctrl_base + blockIdx.x * kCtrlWords;
+  const int tid = threadIdx.x;
+  if (tid == 0) { lo_s = 0; hi_s = kBins; }
+  unsigned long long own = 0;
+  for (int j = 0; j < 32; ++j) own += hist[32 * tid + j];
+  part[tid] = own;
+  __syncthreads();
+  suffix_scan_1024(part, tid);
+  const unsigned long long total = part[0], above = part[tid] - own;
+  const float share_lo = fminf(kMargin * frac, 1.0f), share_hi = frac / kMargin;
+  const unsigned long long want_lo = static_cast<unsigned long long>(share_lo * static_cast<float>(total)) + 1;
+  const unsigned long long want_hi = static_cast<unsigned long long>(share_hi * static_cast<float>(total)) + 1;
+  if (want_lo <= total && above < want_lo && above + own >= want_lo) {       // exactly one thread
     unsigned long long cum = above;
     for (int j = 31; j >= 0; --j) {
       cum += hist[32 * tid + j];
-      if (cum >= m) {
-        const uint32_t bin = static_cast<uint32_t>(32 * tid + j);
-        if (bin >= l0) tau_out[blockIdx.x] = bin; else ctrl[kNeedFull] = 1u;
-        break;
+      if (cum >= want_lo) { lo_s = static_cast<uint32_t>(32 * tid + j); break; }
+    }
+  }
+  if (want_hi <= total && above < want_hi && above + own >= want_hi) {       // exactly one thread
+    unsigned long long cum = above;
+    for (int j = 31; j >= 0; --j) {
+      cum += hist[32 * tid + j];
+      if (cum >= want_hi) { hi_s = static_cast<uint32_t>(32 * tid + j) + 1; break; }
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t lo = lo_s, hi = hi_s;
+    if (hi <= lo) hi = lo + 1;
+    if (hi - lo > kFineBins) lo = hi - kFineBins;
+    ctrl[kCtrlLo] = lo;
+    ctrl[kCtrlHi] = hi;
+  }
+}
+
+// The pass over the whole tensor.  grid.y = tensor.  A workgroup's loads of one step are
+// contiguous (4 x 4 KB) and the next step's loads are in flight while a step is counted (every
+// load is issued unconditionally, with a clamped address past the end: a load behind a branch
+// makes the compiler wait for all of them).  It does not look at the keep mask at all - two
+// divisions and a dependent load per 16 bytes - : kept tokens are counted like any other and
+// taken out again by sparse_uncount_kept_kernel; integer counts, so the difference is exact.
+// The pass then runs at the speed of the loads (5.1 - 5.4 TB/s on a 2 x 1 GB layer).
+__global__ __launch_bounds__(kCountThreads) void sparse_count_kernel(
+    TensorPair X, size_t rows, uint32_t* __restrict__ fine_base, uint32_t* __restrict__ ctrl_base) {
+  __shared__ uint32_t fine[kFineBins];
+  __shared__ uint32_t nhi_s;
+  const int tensor = blockIdx.y;
+  const uint4* __restrict__ x = X.x[tensor];
+  uint32_t* ctrl = ctrl_base + tensor * kCtrlWords;
+  const int tid = threadIdx.x;
+  const uint32_t lo = ctrl[kCtrlLo], hi = ctrl[kCtrlHi];
+  for (int i = tid; i < kFineBins; i += kCountThreads) fine[i] = 0;
+  if (tid == 0) nhi_s = 0;
+  __syncthreads();
+  const size_t units = rows * 16;
+  constexpr int U = kCountLoads;
+  const size_t per_step = static_cast<size_t>(gridDim.x) * U * kCountThreads;
+  const int steps = static_cast<int>((units + per_step - 1) / per_step);    // the same for every lane
+  // lo == 0 (a sample that could not say anything: tiny inputs) sends every entry down the slow path.
+  const uint32_t lo2 = lo | (lo << 16);
+  uint32_t nhi = 0;
+  uint4 cur[U], nxt[U];
+  auto fetch = [&](int step, uint4* v) {
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      const size_t u = ((static_cast<size_t>(step) * gridDim.x + blockIdx.x) * U + k) * kCountThreads + tid;
+      v[k] = x[u < units ? u : 0];                        // unconditional, so that the waits stay exact; past the end: the
+                                                          // first unit again, counted by nobody (see below)
+    }
+  };
+  if (steps > 0) fetch(0, cur);
+  for (int step = 0; step < steps; ++step) {
+    fetch(step + 1, nxt);                             // (past the last step: clamped addresses, nobody counts them)
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      const size_t u = ((static_cast<size_t>(step) * gridDim.x + blockIdx.x) * U + k) * kCountThreads + tid;
+      const uint32_t w[4] = {cur[k].x, cur[k].y, cur[k].z, cur[k].w};
+      uint32_t bits = 0xFFu;
+      if (lo != 0) {
+        uint32_t m[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) m[j] = kvs::below_mask(w[j], lo2);
+        bits = kvs::isolated8(m);
+      }
+      if (u >= units) bits = 0;
+      while (bits) {                                  // the few entries at or above lo
+        const int j = __builtin_ctz(bits);
+        bits &= bits - 1;
+        const int q = j >> 1;
+        const uint32_t wq = q == 0 ? w[0] : (q == 1 ? w[1] : (q == 2 ? w[2] : w[3]));
+        const uint32_t pat = ((j & 1) ? wq >> 16 : wq) & 0x7FFFu;
+        if (pat >= hi) ++nhi;
+        else if (pat >= lo) atomicAdd(&fine[pat - lo], 1u);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) cur[k] = nxt[k];
+  }
+  atomicAdd(&nhi_s, nhi);
+  __syncthreads();
+  uint32_t* out = fine_base + static_cast<size_t>(tensor) * kFineBins;
+  const int span = static_cast<int>(hi - lo);        // at most kFineBins
+  for (int i = tid; i < span; i += kCountThreads)
+    if (fine[i]) atomicAdd(&out[i], fine[i]);
+  if (tid == 0 && nhi_s) atomicAdd(&ctrl[kCtrlNHi], nhi_s);
+}
+
+// Takes the entries of kept tokens out of what sparse_count_kernel counted, and sets the number of
+// entries on non-kept tokens.  grid = (B, tensor, groups of four KV heads); a wave scans 256 mask
+// bytes at a time and, for every kept token it finds, reads the token's rows of the block's four
+// heads (16 lanes per row).  Runs after the count pass on the same stream, so no count goes
+// below zero.
+__global__ __launch_bounds__(256) void sparse_uncount_kept_kernel(
+    TensorPair X, const uint8_t* __restrict__ keep_mask, int n, int Hkv, uint32_t* __restrict__ fine_base,
+    uint32_t* __restrict__ ctrl_base) {
+  __shared__ uint32_t kept_s, nhi_s;
+  const int b = blockIdx.x, tensor = blockIdx.y;
+  const uint4* __restrict__ x = X.x[tensor];
+  uint32_t* ctrl = ctrl_base + tensor * kCtrlWords;
+  uint32_t* fine = fine_base + static_cast<size_t>(tensor) * kFineBins;
+  const uint32_t lo = ctrl[kCtrlLo], hi = ctrl[kCtrlHi];
+  const int tid = threadIdx.x, lane = tid & (KVS_WAVE - 1), wave = tid / KVS_WAVE;
+  const int h = 4 * blockIdx.z + (lane >> 4);
+  if (tid == 0) { kept_s = 0; nhi_s = 0; }
+  __syncthreads();
+  uint32_t kept = 0, nhi = 0;
+  const uint8_t* mrow = keep_mask + static_cast<size_t>(b) * n;
+  for (int t0 = wave * 256; t0 < n; t0 += 4 * 256) {
+    bool k[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int t = t0 + 64 * i + lane;
+      k[i] = mrow[t < n ? t : 0] != 0 && t < n;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      unsigned long long found = __ballot(k[i]);
+      kept += static_cast<uint32_t>(__popcll(found));             // (the same in every lane)
+      while (found) {                                             // wave-uniform
+        const int tk = t0 + 64 * i + __builtin_ctzll(found);
+        found &= found - 1;
+        if (h >= Hkv) continue;
+        const uint4 v = x[((static_cast<size_t>(b) * Hkv + h) * n + tk) * 16 + (lane & 15)];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const uint32_t pat = ((j & 1) ? w[j >> 1] >> 16 : w[j >> 1]) & 0x7FFFu;
+          if (pat >= hi) ++nhi;
+          else if (pat >= lo) atomicSub(&fine[pat - lo], 1u);
+        }
       }
     }
   }
-  if (m > 0 && tid == 0 && part[0] < m) ctrl[kNeedFull] = 1u;   // pass 0 only: the counted part is too small
+  if (lane == 0) atomicAdd(&kept_s, kept);
+  atomicAdd(&nhi_s, nhi);
+  __syncthreads();
+  if (tid == 0) {
+    if (blockIdx.z == 0)
+      atomicAdd(&ctrl[kCtrlCount], (static_cast<uint32_t>(n) - kept_s) * static_cast<uint32_t>(Hkv) * 128u);
+    if (nhi_s) atomicSub(&ctrl[kCtrlNHi], nhi_s);
+  }
+}
+
+// One workgroup per tensor: tau = largest bin t with sum_{bin >= t} counts >= m = ceil(f * count),
+// count = the number of entries on non-kept tokens.
+// pass 0: from the count pass - entries at or above hi, then the fine bins downwards.  If m is
+// already reached above hi, or not reached down to lo, only ctrl[kNeedFull] is written.
+// pass 1: the same walk over the full histogram, if that was raised.
+__global__ __launch_bounds__(1024) void sparse_threshold_kernel(const uint32_t* __restrict__ hist_base,
+                                                                 const uint32_t* __restrict__ fine_base,
+                                                                 uint32_t* __restrict__ ctrl_base, float frac, int pass,
+                                                                 uint32_t* __restrict__ tau_out) {
+  __shared__ unsigned long long part[1024];
+  uint32_t* ctrl = ctrl_base + blockIdx.x * kCtrlWords;
+  if (pass == 1 && ctrl[kNeedFull] == 0) return;
+  const int tid = threadIdx.x;
+  const unsigned long long count = ctrl[kCtrlCount];
+  const double md = ceil(static_cast<double>(frac) * static_cast<double>(count));
+  const unsigned long long m = md <= 0.0 ? 0ull : static_cast<unsigned long long>(md);
+  if (m == 0) {                                        // nothing to isolate
+    if (tid == 0) tau_out[blockIdx.x] = 0x8000u;
+    return;
+  }
+  // the bins this pass walks: per thread `per` consecutive ones, `first` = pattern of bin 0
+  const uint32_t* bins = pass == 0 ? fine_base + static_cast<size_t>(blockIdx.x) * kFineBins
+                                   : hist_base + static_cast<size_t>(blockIdx.x) * kBins;
+  const int per = pass == 0 ? kFineBins / 1024 : kBins / 1024;
+  const uint32_t first = pass == 0 ? ctrl[kCtrlLo] : 0u;
+  const unsigned long long top = pass == 0 ? ctrl[kCtrlNHi] : 0ull;     // entries above every walked bin
+  if (pass == 0 && top >= m) {                         // tau lies at or above hi
+    if (tid == 0) ctrl[kNeedFull] = 1u;
+    return;
+  }
+  unsigned long long own = 0;
+  for (int j = 0; j < per; ++j) own += bins[per * tid + j];
+  part[tid] = own;
+  __syncthreads();
+  suffix_scan_1024(part, tid);
+  const unsigned long long above = top + part[tid] - own;       // entries in higher bins
+  if (above < m && above + own >= m) {                 // exactly one thread
+    unsigned long long cum = above;
+    for (int j = per - 1; j >= 0; --j) {
+      cum += bins[per * tid + j];
+      if (cum >= m) { tau_out[blockIdx.x] = first + static_cast<uint32_t>(per * tid + j); break; }
+    }
+  }
+  if (tid == 0 && top + part[0] < m) ctrl[kNeedFull] = 1u;      // pass 0 only: tau lies below lo
 }
 
 // ---- in-place inclusive scan of int32 counts (three phases, 4096 items per workgroup) -------
@@ -303,15 +457,16 @@ namespace kvs {
 // Workspace layout in uint32 words: histograms and the control block - thresholds, per-tensor
 // control words, the staging counters of both tensors - (zeroed together), scan scratch, the
 // per-workgroup run starts, the two staging lists.
-constexpr int kCtrlBlock = 256;                  // words: 0-1 tau, 8-15 per-tensor control, 32.. / 128.. staging counters
+constexpr int kCtrlBlock = 256;                  // words: 0-1 tau, 8-23 per-tensor control, 32.. / 128.. staging counters
 static_assert(32 + kEmitCounters <= 128 && 128 + kEmitCounters <= kCtrlBlock, "control block layout");
+constexpr size_t kHistWords = 4 * kBins + 2 * kFineBins;
 static int key_block_rows(const kvs_desc* d) { return d->group > 64 ? d->group : 64; }
 
 size_t sparse_workspace_words(const kvs_desc* d) {
   const size_t rows = static_cast<size_t>(d->B) * d->Hkv * d->n;
   const size_t nblk = (rows + kScanBlock - 1) / kScanBlock;
   const size_t bases = rows / key_block_rows(d) + rows / KVS_V_TILE;
-  return 4 * kBins + kCtrlBlock + 2 * (nblk + 1) + bases + 2 * static_cast<size_t>(emit_list_words(d->sparse_cap));
+  return kHistWords + kCtrlBlock + 2 * (nblk + 1) + bases + 2 * static_cast<size_t>(emit_list_words(d->sparse_cap));
 }
 
 SparsePlan sparse_plan(const kvs_desc* d, void* workspace) {
@@ -320,8 +475,8 @@ SparsePlan sparse_plan(const kvs_desc* d, void* workspace) {
   const size_t rows = static_cast<size_t>(d->B) * d->Hkv * d->n;
   p.rows = rows;
   p.nblk = static_cast<int>((rows + kScanBlock - 1) / kScanBlock);
-  p.hist = w;                                              // [2][kBins] bounded, then [2][kBins] full
-  uint32_t* block = w + 4 * kBins;                         // the control block, zeroed with the histograms
+  p.hist = w;                                              // [2][kBins] sample, [2][kBins] full, [2][kFineBins] fine
+  uint32_t* block = w + kHistWords;                        // the control block, zeroed with the histograms
   p.tau = block;
   p.sums_k = reinterpret_cast<int*>(block + kCtrlBlock);
   p.sums_v = p.sums_k + p.nblk + 1;
@@ -336,23 +491,35 @@ SparsePlan sparse_plan(const kvs_desc* d, void* workspace) {
 
 void sparse_thresholds(const kvs_desc* d, const SparsePlan& p, const void* K, const void* V,
                        const uint8_t* mask, const kvs_cache* out, hipStream_t s) {
-  hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(1024), 0, s, p.hist, static_cast<size_t>(4 * kBins + kCtrlBlock), 0u);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(1024), 0, s, p.hist, static_cast<size_t>(kHistWords + kCtrlBlock), 0u);
   hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(out->k_rowptr), size_t{1}, 0u);
   hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(out->v_rowptr), size_t{1}, 0u);
-  // Two workgroups per compute unit in turn; fewer on small inputs, so that every workgroup still
-  // takes several times kSampleSteps grid-stride steps and the bounded count means something.
-  const size_t want_grid = p.rows * 16 / (static_cast<size_t>(kHistThreads) * 4 * kSampleSteps);   // >= 4 x the sample
-  const int grid = static_cast<int>(want_grid < 1 ? 1 : (want_grid > 512 ? 512 : want_grid));
+  uint32_t* sample = p.hist;                              // [2][kBins]
+  uint32_t* full = p.hist + 2 * kBins;                    // [2][kBins]
+  uint32_t* fine = p.hist + 4 * kBins;                    // [2][kFineBins]
   uint32_t* ctrl = p.tau + 8;                             // [2][kCtrlWords]
-  const void* X[2] = {K, V};
-  for (int full = 0; full < 2; ++full) {                  // the second round returns at once unless asked for
-    uint32_t* hist = p.hist + full * 2 * kBins;
-    for (int t = 0; t < 2; ++t)
-      hipLaunchKernelGGL(sparse_hist_kernel, dim3(grid), dim3(kHistThreads), 0, s, static_cast<const uint4*>(X[t]),
-                         mask, p.rows, make_fastdiv(static_cast<uint32_t>(d->n)), make_fastdiv(static_cast<uint32_t>(d->Hkv)),
-                         d->sparse_frac, full, hist + t * kBins, ctrl + t * kCtrlWords);
-    hipLaunchKernelGGL(sparse_threshold_kernel, dim3(2), dim3(1024), 0, s, hist, ctrl, d->sparse_frac, full, p.tau);
-  }
+  const TensorPair X{{static_cast<const uint4*>(K), static_cast<const uint4*>(V)}};
+  const FastDiv by_n = make_fastdiv(static_cast<uint32_t>(d->n)), by_heads = make_fastdiv(static_cast<uint32_t>(d->Hkv));
+  const size_t units = p.rows * 16;
+  const size_t blocks = (units + kHistThreads - 1) / kHistThreads;
+  const uint32_t stride = static_cast<uint32_t>(blocks / kSampleBlocks < 1 ? 1 : blocks / kSampleBlocks);
+  const size_t picks = (blocks + stride - 1) / stride;
+  const unsigned sample_grid = static_cast<unsigned>(picks < 4 ? 1 : (picks / 4 > 256 ? 256 : picks / 4));
+  hipLaunchKernelGGL(sparse_hist_kernel, dim3(sample_grid, 2), dim3(kHistThreads), 0, s, X, mask, p.rows, by_n, by_heads, 0,
+                     stride, sample, ctrl);
+  hipLaunchKernelGGL(sparse_bracket_kernel, dim3(2), dim3(1024), 0, s, sample, d->sparse_frac, ctrl);
+  // four workgroups per compute unit, each with several steps to pipeline; fewer on small inputs
+  const size_t per_wg = static_cast<size_t>(kCountThreads) * kCountLoads * 4;   // units of four steps
+  const size_t want = (units + per_wg - 1) / per_wg;
+  const unsigned count_grid = static_cast<unsigned>(want < 1 ? 1 : (want > 1024 ? 1024 : want));
+  hipLaunchKernelGGL(sparse_count_kernel, dim3(count_grid, 2), dim3(kCountThreads), 0, s, X, p.rows, fine, ctrl);
+  hipLaunchKernelGGL(sparse_uncount_kept_kernel, dim3(d->B, 2, (d->Hkv + 3) / 4), dim3(256), 0, s, X, mask, d->n, d->Hkv, fine, ctrl);
+  hipLaunchKernelGGL(sparse_threshold_kernel, dim3(2), dim3(1024), 0, s, full, fine, ctrl, d->sparse_frac, 0, p.tau);
+  // the full histogram: both launches return at once unless the bracket missed
+  const unsigned full_grid = static_cast<unsigned>(blocks < 4 ? 1 : (blocks / 4 > 256 ? 256 : blocks / 4));
+  hipLaunchKernelGGL(sparse_hist_kernel, dim3(full_grid, 2), dim3(kHistThreads), 0, s, X, mask, p.rows, by_n, by_heads, 1,
+                     1u, full, ctrl);
+  hipLaunchKernelGGL(sparse_threshold_kernel, dim3(2), dim3(1024), 0, s, full, fine, ctrl, d->sparse_frac, 1, p.tau);
 }
 
 void sparse_build_csr(const kvs_desc* d, const SparsePlan& p, const kvs_cache* out, hipStream_t s) {

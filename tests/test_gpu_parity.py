@@ -353,6 +353,54 @@ def test_dense_and_sparse_threshold_when_the_sample_misleads():
     assert row_rel_err(out, ref64) <= OUT_TOL
 
 
+# Scratch layout of the threshold search (csrc/sparse.hip): two sample, two full and two bracket
+# histograms, then the control block - thresholds at words 0-1, eight control words per tensor
+# from word 8, of which word 2 says that the full histogram was needed.
+_CTRL = 4 * 32768 + 2 * 4096
+
+
+def _threshold_state(ws):
+    words = ws.view(torch.int32)[_CTRL:_CTRL + 24].cpu().numpy()
+    return words[0:2], words[[8 + 2, 16 + 2]]               # (tau of K and V, full histogram needed?)
+
+
+@pytest.mark.parametrize("case", ["bracket", "below", "above"])
+def test_dense_and_sparse_threshold_paths(case):
+    """The three ways the threshold search can end, each with the oracle's tau, on a tensor large
+    enough that only every second 16 KB block is sampled: inside the bracket the sample predicts;
+    below it (large values only where the sample looks, so it overrates the tail); above it (large
+    values only where it does not look)."""
+    rng = np.random.default_rng(31)
+    bits, G, frac = 3, 128, 0.01
+    B, H, n = 1, 8, 32768                                # 4096 blocks of 64 rows
+    K = rng.standard_normal((B, H, n, 128)).astype(np.float16)
+    V = rng.standard_normal((B, H, n, 128)).astype(np.float16)
+    blocks = B * H * n // 64
+    stride = blocks // 2048
+    assert stride == 2
+    picks = np.arange((blocks + stride - 1) // stride, dtype=np.uint64)
+    sampled = (picks * stride + ((picks * 2654435761 % (1 << 32)) >> 16) % stride).astype(np.int64)
+    hidden = np.setdiff1d(np.arange(blocks), sampled)
+    if case != "bracket":                                # 0.8 % of all entries where the sample looks, or 1.5 % where it does not
+        where, share = (sampled, 0.008) if case == "below" else (hidden, 0.015)
+        for X in (K, V):
+            rows = X.reshape(blocks, 64 * 128)
+            cols = rng.choice(64 * 128, int(share * 64 * 128 * blocks / len(where)) + 1, replace=False)
+            rows[np.ix_(where, cols)] = np.float16(100.0)
+    mask = np.zeros((B, n), np.uint8)
+    mask[0, [0, 14, n - 1]] = 1
+    taus = (O.sparse_threshold(K, mask, frac), O.sparse_threshold(V, mask, frac))
+    not_kept = (mask[0] == 0)[None, None, :, None]
+    nnz = [int((((X.view(np.uint16) & 0x7FFF) >= t) & not_kept).sum()) for X, t in zip((K, V), taus)]
+    desc, cache, ws = hip_quantize(K, V, mask, bits, G, keep_cap=4, sparse_frac=frac, sparse_cap=max(nnz) + 16)
+    tau, needed_full = _threshold_state(ws)
+    assert tau.tolist() == [int(taus[0]), int(taus[1])]
+    assert needed_full.tolist() == ([0, 0] if case == "bracket" else [1, 1])
+    rows = B * H * n
+    assert int(cache.k_rowptr[rows].cpu()) == nnz[0] and int(cache.v_rowptr[rows].cpu()) == nnz[1]
+    assert int(cache.status.cpu()[0]) == 0
+
+
 def test_dense_and_sparse_long_sequence():
     """More than 4096 tokens: the finishing kernel stages the sequence in two segments, the second one
     ragged (5 tiles), and the stream is cut into several parts per head."""
