@@ -230,6 +230,48 @@ def per_token_key_leg(w, inputs, bufs, q, dec_bytes, qnt_bytes):
     }
 
 
+def eight_bit_leg(w, inputs, bufs, q):
+    """The same shapes with 8-bit codes (twice the cache bytes per call): quantise and decode over
+    rotating inputs and caches of their own, back to back.  None for dense-and-sparse workloads."""
+    import torch
+
+    from paper_2508_04257_amd import binding as kb
+    from paper_2508_04257_amd import pipeline
+
+    if w.bits == 8 or w.sparse_frac > 0:
+        return None
+    w8 = w.scaled(bits=8)
+    dev = q.device
+    desc = pipeline.desc_for(w8)
+    slots = len(inputs)
+    caches = [kb.alloc_cache(desc, dev) for _ in range(slots)]
+    ws = kb.alloc_workspace(desc, dev)
+    out = torch.empty((w.B, w.Hq, w.D), dtype=torch.float16, device=dev)
+    for i in range(slots):
+        kb.kvs_quantize_kv(desc, inputs[i][0], inputs[i][1], bufs[i].keep_mask, caches[i], ws)
+        kb.kvs_decode_attn(desc, q, caches[i], out, None, ws)
+    torch.cuda.synchronize()
+    reps = 12
+    e = [HipEvent() for _ in range(3)]
+    e[0].record()
+    for i in range(reps):
+        kb.kvs_quantize_kv(desc, inputs[i % slots][0], inputs[i % slots][1], bufs[i % slots].keep_mask, caches[i % slots], ws)
+    e[1].record()
+    for i in range(reps):
+        kb.kvs_decode_attn(desc, q, caches[i % slots], out, None, ws)
+    e[2].record()
+    torch.cuda.synchronize()
+    ms_q, ms_d = e[0].elapsed_time(e[1]) / reps, e[1].elapsed_time(e[2]) / reps
+    dec_bytes, qnt_bytes = decode_algorithmic_bytes(w8, w8.keep_cap), quantize_algorithmic_bytes(w8)
+    return {
+        "ms_quantize_kv": round(ms_q, 4), "quantize_gbps": round(qnt_bytes / (ms_q * 1e-3) / 1e9, 2),
+        "ms_decode_attn": round(ms_d, 4), "decode_gbps": round(dec_bytes / (ms_d * 1e-3) / 1e9, 2),
+        "decode_frac_of_hbm_peak": round(dec_bytes / (ms_d * 1e-3) / 8e12, 4),
+        "decode_algorithmic_bytes": dec_bytes,
+        "note": "INT8 codes on the same shapes; calls back to back over rotating cold caches",
+    }
+
+
 def graph_leg(w, hidden, inputs, q, bufs):
     """The same steps replayed from one HIP graph (all slots in sequence per replay): what the
     launch gaps of the eager loop cost."""
@@ -482,6 +524,9 @@ def main() -> int:
         kpt = per_token_key_leg(w, inputs, bufs, q, dec_bytes, qnt_bytes)
         if kpt is not None:
             result["per_token_keys"] = kpt
+        int8 = eight_bit_leg(w, inputs, bufs, q)
+        if int8 is not None:
+            result["int8"] = int8
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result))

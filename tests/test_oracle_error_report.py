@@ -39,7 +39,7 @@ def _loop_report(K, V, cache, sink_mask):
     return res
 
 
-@pytest.mark.parametrize("bits,G,kpt", [(4, 32, False), (3, 64, True), (2, 128, False)])
+@pytest.mark.parametrize("bits,G,kpt", [(4, 32, False), (3, 64, True), (2, 128, False), (8, 64, False)])
 def test_against_an_entry_by_entry_loop(bits, G, kpt):
     rng = np.random.default_rng(bits)
     B, H, n = 2, 1, 128

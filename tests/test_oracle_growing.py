@@ -35,7 +35,7 @@ def sdpa64(q, K, V):
     return torch.nn.functional.scaled_dot_product_attention(qt, Kt, Vt)[0, 0, 0].numpy()
 
 
-@pytest.mark.parametrize("bits,G", [(4, 128), (3, 64), (2, 32)])
+@pytest.mark.parametrize("bits,G", [(4, 128), (3, 64), (2, 32), (8, 64)])
 def test_blockwise_quantisation_is_the_whole_quantisation(bits, G):
     """Groups are positional and never straddle a 128-token block, so quantising block by block
     and concatenating is quantising the whole: what lets a cache grow one block at a time."""

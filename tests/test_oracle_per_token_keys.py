@@ -34,7 +34,7 @@ def _brute_force_row(x16, bits, G):
     return np.array(codes, np.uint8), np.array(scales, np.float16), np.array(zeros, np.int16)
 
 
-@pytest.mark.parametrize("bits,G", [(4, 128), (3, 64), (2, 32)])
+@pytest.mark.parametrize("bits,G", [(4, 128), (3, 64), (2, 32), (8, 32)])
 def test_rows_match_a_scalar_brute_force(bits, G):
     rng = np.random.default_rng(10 + bits)
     B, H, n = 1, 2, 128
@@ -80,7 +80,7 @@ def test_symmetric_tile_transposes_between_the_two_key_schemes():
     assert np.array_equal(K[0, 0], K[0, 0].T)
     V = random_fp16(rng, (1, 1, 128, 128))
     mask = np.zeros((1, 128), np.uint8)
-    for bits in (2, 3, 4):
+    for bits in (2, 3, 4, 8):
         pc = O.quantize_kv(K, V, mask, bits, 128, 0)
         pt = O.quantize_kv(K, V, mask, bits, 128, 0, key_per_token=True)
         assert np.array_equal(pc.k_codes_logical[0, 0], pt.k_codes_logical[0, 0].T)

@@ -165,7 +165,7 @@ def test_lossless_grid_with_isolated_outliers_equals_textbook_attention():
 def test_quantised_attention_error_shrinks_with_bit_width():
     K, V, mask, q = _small_case(seed=7)
     errs = {}
-    for bits in (2, 3, 4):
+    for bits in (2, 3, 4, 8):
         cache = O.quantize_kv(K, V, mask, bits, 64, keep_cap=3)
         _, _, out64 = O.decode_attn(q, cache, Hq=2)
         err = 0.0
@@ -174,7 +174,7 @@ def test_quantised_attention_error_shrinks_with_bit_width():
                 ref = _sdpa64(q[b, h], K[b, h], V[b, h])
                 err = max(err, np.abs(out64[b, h] - ref).max() / np.abs(ref).max())
         errs[bits] = err
-    assert errs[4] < errs[3] < errs[2] and errs[4] < 0.3
+    assert errs[8] < errs[4] < errs[3] < errs[2] and errs[4] < 0.3 and errs[8] < 0.02
 
 
 def test_gqa_mapping():

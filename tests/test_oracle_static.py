@@ -12,7 +12,7 @@ def _dequant_static(cache: O.Cache, b, h):
     return O.effective_kv(cache, b, h)
 
 
-@pytest.mark.parametrize("bits,G", [(4, 128), (3, 64), (2, 32)])
+@pytest.mark.parametrize("bits,G", [(4, 128), (3, 64), (2, 32), (8, 128)])
 def test_in_range_error_bound_and_clamping(bits, G):
     rng = np.random.default_rng(bits)
     B, H, n = 2, 2, 256
