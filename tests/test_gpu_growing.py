@@ -75,6 +75,8 @@ def check_decode(desc, cache, ws, q, gc, Hq):
     (2, 128, 4, 384),      # whole blocks only
     (4, 32, 1, 0),         # an empty prompt
     (8, 64, 4, 300), (8, 128, 1, 257),
+    (8, 128, 8, 300),      # four-wave workgroups: a wave merges two heads and takes two residual states
+    (3, 32, 4, 300),       # four-wave workgroups at 3 bit
 ])
 def test_prefix_then_appends_match_the_oracle(bits, G, rep, n0):
     rng = np.random.default_rng(bits * 1000 + G + n0)
