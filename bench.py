@@ -191,22 +191,20 @@ def static_leg(w, inputs, bufs, qnt_bytes):
     }
 
 
-def per_token_key_leg(w, inputs, bufs, q, dec_bytes, qnt_bytes):
-    """The per-token Key scheme on the same shapes: quantise and decode over rotating inputs and
-    caches of their own, back to back.  None where the scheme does not apply."""
+def _variant_leg(wv, inputs, bufs, q):
+    """Quantise and decode calls of a variant of the workload (same shapes, another scheme) over
+    rotating inputs and caches of its own, back to back.  Returns (ms quantise, ms decode)."""
     import torch
 
     from paper_2508_04257_amd import binding as kb
     from paper_2508_04257_amd import pipeline
 
-    if w.key_per_token or w.sparse_frac > 0:
-        return None
     dev = q.device
-    desc = pipeline.desc_for(w.scaled(key_per_token=True))
+    desc = pipeline.desc_for(wv)
     slots = len(inputs)
     caches = [kb.alloc_cache(desc, dev) for _ in range(slots)]
     ws = kb.alloc_workspace(desc, dev)
-    out = torch.empty((w.B, w.Hq, w.D), dtype=torch.float16, device=dev)
+    out = torch.empty((wv.B, wv.Hq, wv.D), dtype=torch.float16, device=dev)
     for i in range(slots):
         kb.kvs_quantize_kv(desc, inputs[i][0], inputs[i][1], bufs[i].keep_mask, caches[i], ws)
         kb.kvs_decode_attn(desc, q, caches[i], out, None, ws)
@@ -221,7 +219,14 @@ def per_token_key_leg(w, inputs, bufs, q, dec_bytes, qnt_bytes):
         kb.kvs_decode_attn(desc, q, caches[i % slots], out, None, ws)
     e[2].record()
     torch.cuda.synchronize()
-    ms_q, ms_d = e[0].elapsed_time(e[1]) / reps, e[1].elapsed_time(e[2]) / reps
+    return e[0].elapsed_time(e[1]) / reps, e[1].elapsed_time(e[2]) / reps
+
+
+def per_token_key_leg(w, inputs, bufs, q, dec_bytes, qnt_bytes):
+    """The per-token Key scheme on the same shapes.  None where the scheme does not apply."""
+    if w.key_per_token or w.sparse_frac > 0:
+        return None
+    ms_q, ms_d = _variant_leg(w.scaled(key_per_token=True), inputs, bufs, q)
     return {
         "ms_quantize_kv": round(ms_q, 4), "quantize_gbps": round(qnt_bytes / (ms_q * 1e-3) / 1e9, 2),
         "ms_decode_attn": round(ms_d, 4), "decode_gbps": round(dec_bytes / (ms_d * 1e-3) / 1e9, 2),
@@ -231,37 +236,12 @@ def per_token_key_leg(w, inputs, bufs, q, dec_bytes, qnt_bytes):
 
 
 def eight_bit_leg(w, inputs, bufs, q):
-    """The same shapes with 8-bit codes (twice the cache bytes per call): quantise and decode over
-    rotating inputs and caches of their own, back to back.  None for dense-and-sparse workloads."""
-    import torch
-
-    from paper_2508_04257_amd import binding as kb
-    from paper_2508_04257_amd import pipeline
-
+    """The same shapes with 8-bit codes (twice the cache bytes per call).  None for 8-bit and
+    dense-and-sparse workloads."""
     if w.bits == 8 or w.sparse_frac > 0:
         return None
     w8 = w.scaled(bits=8)
-    dev = q.device
-    desc = pipeline.desc_for(w8)
-    slots = len(inputs)
-    caches = [kb.alloc_cache(desc, dev) for _ in range(slots)]
-    ws = kb.alloc_workspace(desc, dev)
-    out = torch.empty((w.B, w.Hq, w.D), dtype=torch.float16, device=dev)
-    for i in range(slots):
-        kb.kvs_quantize_kv(desc, inputs[i][0], inputs[i][1], bufs[i].keep_mask, caches[i], ws)
-        kb.kvs_decode_attn(desc, q, caches[i], out, None, ws)
-    torch.cuda.synchronize()
-    reps = 12
-    e = [HipEvent() for _ in range(3)]
-    e[0].record()
-    for i in range(reps):
-        kb.kvs_quantize_kv(desc, inputs[i % slots][0], inputs[i % slots][1], bufs[i % slots].keep_mask, caches[i % slots], ws)
-    e[1].record()
-    for i in range(reps):
-        kb.kvs_decode_attn(desc, q, caches[i % slots], out, None, ws)
-    e[2].record()
-    torch.cuda.synchronize()
-    ms_q, ms_d = e[0].elapsed_time(e[1]) / reps, e[1].elapsed_time(e[2]) / reps
+    ms_q, ms_d = _variant_leg(w8, inputs, bufs, q)
     dec_bytes, qnt_bytes = decode_algorithmic_bytes(w8, w8.keep_cap), quantize_algorithmic_bytes(w8)
     return {
         "ms_quantize_kv": round(ms_q, 4), "quantize_gbps": round(qnt_bytes / (ms_q * 1e-3) / 1e9, 2),
