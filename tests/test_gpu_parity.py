@@ -353,6 +353,34 @@ def test_dense_and_sparse_threshold_when_the_sample_misleads():
     assert row_rel_err(out, ref64) <= OUT_TOL
 
 
+@pytest.mark.parametrize("case", ["all_kept", "one_entry", "constant"])
+def test_dense_and_sparse_degenerate(case):
+    """Nothing left to isolate (every token kept), a fraction that asks for a single entry, and a
+    tensor of one repeated magnitude (tau sits in a tie class that holds every entry)."""
+    rng = np.random.default_rng(5)
+    B, H, n, bits, G = 2, 2, 256, 4, 64
+    K, V = random_fp16(rng, (B, H, n, 128)), random_fp16(rng, (B, H, n, 128))
+    mask = np.zeros((B, n), np.uint8)
+    mask[0, [0, 14]] = 1
+    frac, cap = 0.01, 8
+    if case == "all_kept":
+        mask[:] = 1
+        cap = n
+    elif case == "one_entry":
+        frac = 1.0 / (B * H * n * 128)                     # ceil(f * count) = 1
+    else:
+        K[:] = np.float16(3.0)
+        V[:] = np.float16(-3.0)
+    ref = O.quantize_kv(K, V, mask, bits, G, keep_cap=cap, sparse_frac=frac)
+    scap = max(len(ref.k_col), len(ref.v_col)) + 16
+    desc, cache, ws = hip_quantize(K, V, mask, bits, G, keep_cap=cap, sparse_frac=frac, sparse_cap=scap)
+    assert_cache_equal(cache, ref)
+    assert_csr_equal(cache, ref)
+    q = random_fp16(rng, (B, H, 128))
+    out, _ = hip_decode(desc, cache, ws, q)
+    assert row_rel_err(out, O.decode_attn(q, ref, Hq=H)[2]) <= OUT_TOL
+
+
 # Scratch layout of the threshold search (csrc/sparse.hip): two sample, two full and two bracket
 # histograms, then the control block - thresholds at words 0-1, eight control words per tensor
 # from word 8, of which word 2 says that the full histogram was needed.
