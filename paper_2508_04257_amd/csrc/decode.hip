@@ -2,7 +2,11 @@
 // fp16 rows of the kept (sink) tokens (paper, Section 2 attention equation; the split of the
 // attention sum into sink and non-sink tokens is the equation of Section 4.2).
 //
-// Two kernels per call.
+// The entry points, the kernel that finishes a call whose stream was cut into parts, and the
+// vector-ALU stream kernel.  Dense caches, and caches with isolated outliers and one query head
+// per KV head, stream through the matrix-core kernel (decode_mfma_impl.h); the stream kernel here
+// serves caches with isolated outliers and several query heads per KV head, and states the
+// arithmetic (how scales and zero points are folded) in its plainest form.
 //   decode_partial_kernel  one workgroup per (sequence, KV head, token split).  Each wave walks
 //       128-token chunks: scores from the Key code tile (lane = token, the per-channel scale is
 //       folded into the query once per token group, the zero points into one bias per group),
@@ -38,11 +42,7 @@ struct SparseView {
   int cap;   // entries the col / val arrays hold; row pointers past it (reported overflow) are not followed
 };
 
-// KPT (per-token Keys, paper Section 5.1): the Key parameters belong to (token, channel group), so
-// nothing is folded into the query; a lane keeps one dot product per channel group and finishes
-// its token's score with the token's own parameters:
-//   score[t] = sum_g scale[t, g] (sum_{c in g} q_c code[t, c] - zero[t, g] sum_{c in g} q_c).
-template <int BITS, int G, int R, bool SPARSE, bool KPT = false>
+template <int BITS, int G, int R, bool SPARSE>
 __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
     const uint16_t* __restrict__ q, const uint32_t* __restrict__ k_codes,
     const uint32_t* __restrict__ v_codes, const uint32_t* __restrict__ k_params,
@@ -52,8 +52,6 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
   constexpr int NGK = 128 / G;   // Key token groups per 128-token chunk
   constexpr int NGC = 128 / G;   // Value channel groups per row
   constexpr int LOG2G = G == 32 ? 5 : (G == 64 ? 6 : 7);
-  static_assert(!(KPT && SPARSE), "per-token Keys are dense only");
-
   __shared__ float qf[R][128];                       // query / sqrt(D)
   __shared__ float qs[kWaves][NGK][R][128];          // query x Key scale, per wave and group
   __shared__ float wl[kWaves][R][NGC][128];          // softmax weight x Value scale, per token
@@ -81,19 +79,6 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
   }
   __syncthreads();
 
-  // KPT: the query's sum over each channel group (lane c and lane c + 64 hold one channel each).
-  float qsum[KPT ? NGC : 1][R];
-  if constexpr (KPT) {
-#pragma unroll
-    for (int g = 0; g < NGC; ++g)
-#pragma unroll
-      for (int r = 0; r < R; ++r) {
-        const float a = (lane >> LOG2G) == g ? qf[r][lane] : 0.0f;
-        const float c2 = ((lane + 64) >> LOG2G) == g ? qf[r][lane + 64] : 0.0f;
-        qsum[g][r] = kvs::wave_sum(a + c2);
-      }
-  }
-
   const int tok_begin = split * split_tokens;
   const int tok_end = min(n_used, tok_begin + split_tokens);   // n is the layout, n_used what is attended to
   const int chunks = (tok_end - tok_begin) / KVS_V_TILE;
@@ -115,7 +100,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
 
     // (1) query x Key scale for the chunk's token groups; bias = sum_c (q s)_c zero_c.
     float kbias[NGK][R];
-    if (active && !KPT) {
+    if (active) {
 #pragma unroll
       for (int gl = 0; gl < NGK; ++gl) {
         const uint32_t* kp = k_params + (bh * (n / G) + static_cast<size_t>(t0 / G + gl)) * 128;
@@ -150,13 +135,8 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
         const int gl = tl >> LOG2G;
         const uint32_t* tile = k_codes + (bh * (n / KVS_K_TILE) + static_cast<size_t>(t0 / KVS_K_TILE + kt)) * (W * KVS_K_TILE);
         float dot[R];
-        float gdot[KPT ? NGC : 1][R];                // KPT: one dot product per channel group
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-          dot[r] = 0.0f;
-#pragma unroll
-          for (int g = 0; g < (KPT ? NGC : 1); ++g) gdot[g][r] = 0.0f;
-        }
+        for (int r = 0; r < R; ++r) dot[r] = 0.0f;
 #pragma unroll
         for (int w = 0; w < W; ++w) {
           const uint32_t word = tile[w * KVS_K_TILE + lane];
@@ -166,20 +146,8 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
             if (c < 128) {
               const float f = code_at<BITS>(word, j);
 #pragma unroll
-              for (int r = 0; r < R; ++r) {
-                if constexpr (KPT) gdot[c >> LOG2G][r] += qf[r][c] * f;
-                else dot[r] += qs[wave][gl][r][c] * f;
-              }
+              for (int r = 0; r < R; ++r) dot[r] += qs[wave][gl][r][c] * f;
             }
-          }
-        }
-        if constexpr (KPT) {
-#pragma unroll
-          for (int g = 0; g < NGC; ++g) {
-            float sk; int zk;
-            kvs::unpack_param(k_params[(bh * n + static_cast<size_t>(t0 + tl)) * NGC + g], sk, zk);
-#pragma unroll
-            for (int r = 0; r < R; ++r) dot[r] += sk * (gdot[g][r] - static_cast<float>(zk) * qsum[g][r]);
           }
         }
         if constexpr (SPARSE) {
@@ -195,12 +163,9 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
         const bool kept = mask_b[t0 + tl] != 0;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-          float bias = 0.0f;
-          if constexpr (!KPT) {
-            bias = kbias[0][r];
+          float bias = kbias[0][r];
 #pragma unroll
-            for (int g = 1; g < NGK; ++g) bias = gl == g ? kbias[g][r] : bias;
-          }
+          for (int g = 1; g < NGK; ++g) bias = gl == g ? kbias[g][r] : bias;
           sc[kt][r] = kept ? -INFINITY : dot[r] - bias;
         }
       }
@@ -410,6 +375,8 @@ __global__ __launch_bounds__(KVS_WAVE) void decode_combine_kernel(
   if (lse && lane == 0) lse[bq] = L > 0.0f ? M + __logf(L) : -INFINITY;
 }
 
+// The stream kernel serves what the matrix-core kernel does not: caches with isolated outliers
+// and more than one query head per KV head (so only its SPARSE variant is launched).
 template <int BITS, int G, int R>
 void launch_partial(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c,
                     float* ws, int n_used, hipStream_t s) {
@@ -418,23 +385,7 @@ void launch_partial(const kvs_desc* d, const kvs::DecodeGeometry& geo, const voi
   SparseView sp{c->k_rowptr, c->k_col, static_cast<const uint16_t*>(c->k_val),
                 c->v_rowptr, c->v_col, static_cast<const uint16_t*>(c->v_val),
                 static_cast<int>(d->sparse_cap)};
-  if constexpr (R == 4 && G < 128) {                   // the per-token Key shapes the matrix-core kernel has no room for
-    if (d->key_per_token) {
-      hipLaunchKernelGGL((decode_partial_kernel<BITS, G, R, false, true>), dim3(grid), dim3(kThreads), 0, s,
-                         static_cast<const uint16_t*>(q), c->k_codes, c->v_codes, c->k_params, c->v_params,
-                         c->keep_mask, d->n, n_used, d->Hkv, rep, geo.splits, geo.split_tokens, ws, sp);
-      return;
-    }
-  }
-  if constexpr (BITS != 8) {                           // (no isolated outliers at 8 bit)
-    if (d->sparse_frac > 0.0f) {
-      hipLaunchKernelGGL((decode_partial_kernel<BITS, G, R, true>), dim3(grid), dim3(kThreads), 0, s,
-                         static_cast<const uint16_t*>(q), c->k_codes, c->v_codes, c->k_params, c->v_params,
-                         c->keep_mask, d->n, n_used, d->Hkv, rep, geo.splits, geo.split_tokens, ws, sp);
-      return;
-    }
-  }
-  hipLaunchKernelGGL((decode_partial_kernel<BITS, G, R, false>), dim3(grid), dim3(kThreads), 0, s,
+  hipLaunchKernelGGL((decode_partial_kernel<BITS, G, R, true>), dim3(grid), dim3(kThreads), 0, s,
                      static_cast<const uint16_t*>(q), c->k_codes, c->v_codes, c->k_params, c->v_params,
                      c->keep_mask, d->n, n_used, d->Hkv, rep, geo.splits, geo.split_tokens, ws, sp);
 }
@@ -556,8 +507,7 @@ static void decode_dense(const kvs_desc* desc, const void* q, const kvs_cache* c
       switch (desc->bits) {
         case 2: launch_partial_g<2>(desc, geo, q, cache, ws, n_used, s); break;
         case 3: launch_partial_g<3>(desc, geo, q, cache, ws, n_used, s); break;
-        case 4: launch_partial_g<4>(desc, geo, q, cache, ws, n_used, s); break;
-        default: launch_partial_g<8>(desc, geo, q, cache, ws, n_used, s); break;
+        default: launch_partial_g<4>(desc, geo, q, cache, ws, n_used, s); break;   // (8 bit has no isolated outliers)
       }
     }
   }

@@ -15,11 +15,8 @@ void launch_decode_mfma_kpt_b4(const kvs_desc*, const DecodeGeometry&, const voi
 void launch_decode_mfma_kpt_b8(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, int, const float*, hipStream_t);
 
 bool decode_mfma_supported(const kvs_desc* d) {
-  const int rep = d->Hq / d->Hkv;
-  if (d->key_per_token) return rep * (KVS_HEAD_DIM / d->group) <= 8;   // heads x channel groups x [hi | lo] <= 16 columns
-  if (d->sparse_frac != 0.0f) return rep == 1;       // isolated outliers: one query head per KV head
-  if (rep == 1 || rep == 4) return true;
-  return d->group == 128;                            // 2 or 8 query heads per KV head
+  // isolated outliers: one query head per KV head; every dense shape otherwise
+  return d->sparse_frac == 0.0f || d->Hq == d->Hkv;
 }
 
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,

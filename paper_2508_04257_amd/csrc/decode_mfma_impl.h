@@ -45,7 +45,7 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 // spills a few dozen bytes can still be faster with eight).
 __host__ __device__ constexpr int waves_for(int bits, int G, int R, bool kpt) {
   if (bits == 8) return R * (128 / G) * (kpt ? 2 : 1) >= 4 ? 4 : 8;
-  if (!kpt) return (bits >= 3 && G == 32 && R == 4) ? 4 : 8;
+  if (!kpt) return ((bits >= 3 && G == 32 && R == 4) || (G == 64 && R == 8)) ? 4 : 8;   // (64, 8): the tables of 8 waves exceed the LDS
   if (bits >= 3 && G == 128 && R == 8) return 4;
   if (bits == 3 && ((G == 64 && R == 4) || (G == 32 && R == 2))) return 4;
   return 8;
@@ -190,6 +190,8 @@ struct MfmaArgs {
   const float* extra;   // one more softmax state per (b, hq) to merge (a growing cache's residual rows), or null
   int parts;         // workgroups per (b, h)
   int part_tokens;   // tokens per workgroup
+  int rep;           // query heads per KV head (Hq / Hkv)
+  int head_off;      // first of them that this launch takes; it takes R
 };
 
 // SPARSE (caches with isolated fp16 outliers): an isolated slot holds code 0.  A kernel that ran
@@ -243,8 +245,8 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
   const size_t bh = blockIdx.x / a.parts;
   const int part = blockIdx.x % a.parts;
   const int b = static_cast<int>(bh / a.Hkv), h = static_cast<int>(bh % a.Hkv);
-  const int Hq = a.Hkv * R;
-  const int hq0 = h * R;
+  const int Hq = a.Hkv * a.rep;
+  const int hq0 = h * a.rep + a.head_off;        // the launch's R heads of KV head h
   const int keep_cnt_b = a.keep_cnt[b];            // uniform: a scalar load, issued first
   // The wave's first kept row (rows past the count are zero padding), requested before the
   // stream starts so that it has long arrived when it is needed.
@@ -259,7 +261,7 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
     extra_o[k] = float2{0.0f, 0.0f};  extra_m[k] = -INFINITY;  extra_l[k] = 0.0f;
     const int r = wave + k * kWaves;
     if (a.extra && a.parts == 1 && !SPARSE && r < R) {
-      const float* x = a.extra + (static_cast<size_t>(b) * (a.Hkv * R) + h * R + r) * kWsRow;
+      const float* x = a.extra + (static_cast<size_t>(b) * Hq + hq0 + r) * kWsRow;
       extra_o[k] = reinterpret_cast<const float2*>(x)[lane];
       extra_m[k] = x[128];
       extra_l[k] = x[129];
@@ -802,67 +804,72 @@ inline MfmaArgs make_args(const kvs_desc* d, const kvs::DecodeGeometry& geo, con
   a.n = d->n; a.Hkv = d->Hkv; a.cap = d->keep_cap;
   a.n_used = n_used; a.extra = extra;
   a.parts = geo.splits; a.part_tokens = geo.split_tokens;
+  a.rep = d->Hq / d->Hkv; a.head_off = 0;
   return a;
 }
 
-template <int BITS, int G, int R>
-void launch_one_kpt(const kvs_desc* d, const kvs::DecodeGeometry& geo, const MfmaArgs& args, hipStream_t s) {
-  const dim3 grid(d->B * d->Hkv * geo.splits), block(waves_for(BITS, G, R, true) * KVS_WAVE);
-  hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, false, true>), grid, block, 0, s, args);
+// One launch takes R query heads of every KV head, starting at head_off; a shape whose heads do
+// not fit the 16 tile columns is served by several launches of a narrower variant, each of which
+// streams the codes again.
+template <int BITS, int G, int R, bool KPT>
+void launch_heads(const kvs_desc* d, const kvs::DecodeGeometry& geo, MfmaArgs args, hipStream_t s) {
+  const dim3 grid(d->B * d->Hkv * geo.splits), block(waves_for(BITS, G, R, KPT) * KVS_WAVE);
+  const bool sparse = d->sparse_frac > 0.0f;
+  for (args.head_off = 0; args.head_off < args.rep; args.head_off += R) {
+    if constexpr (R == 1 && BITS != 8 && !KPT) {
+      if (sparse) {
+        hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, true, false>), grid, block, 0, s, args);
+        continue;
+      }
+    }
+    hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, false, KPT>), grid, block, 0, s, args);
+  }
 }
 
-// Per-token Keys: every shape with heads x channel groups <= 8 (the 16 tile columns).
+// Per-token Keys: heads x channel groups x [hi | lo] must fit the 16 tile columns, i.e.
+// R (128 / G) <= 8 per launch.
 template <int BITS>
 void launch_bits_kpt(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c, void* out,
                      float* lse, float* ws, int n_used, const float* extra, hipStream_t s) {
   const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws, nullptr, n_used, extra);
-  const int rep = d->Hq / d->Hkv;
+  const int rep = a.rep;
   if (d->group == 128) {
-    if (rep == 1) launch_one_kpt<BITS, 128, 1>(d, geo, a, s);
-    else if (rep == 2) launch_one_kpt<BITS, 128, 2>(d, geo, a, s);
-    else if (rep == 4) launch_one_kpt<BITS, 128, 4>(d, geo, a, s);
-    else launch_one_kpt<BITS, 128, 8>(d, geo, a, s);
+    if (rep == 1) launch_heads<BITS, 128, 1, true>(d, geo, a, s);
+    else if (rep == 2) launch_heads<BITS, 128, 2, true>(d, geo, a, s);
+    else if (rep == 4) launch_heads<BITS, 128, 4, true>(d, geo, a, s);
+    else launch_heads<BITS, 128, 8, true>(d, geo, a, s);
   } else if (d->group == 64) {
-    if (rep == 1) launch_one_kpt<BITS, 64, 1>(d, geo, a, s);
-    else if (rep == 2) launch_one_kpt<BITS, 64, 2>(d, geo, a, s);
-    else launch_one_kpt<BITS, 64, 4>(d, geo, a, s);
+    if (rep == 1) launch_heads<BITS, 64, 1, true>(d, geo, a, s);
+    else if (rep == 2) launch_heads<BITS, 64, 2, true>(d, geo, a, s);
+    else launch_heads<BITS, 64, 4, true>(d, geo, a, s);             // 8 heads: two launches
   } else {
-    if (rep == 1) launch_one_kpt<BITS, 32, 1>(d, geo, a, s);
-    else launch_one_kpt<BITS, 32, 2>(d, geo, a, s);
+    if (rep == 1) launch_heads<BITS, 32, 1, true>(d, geo, a, s);
+    else launch_heads<BITS, 32, 2, true>(d, geo, a, s);             // 4, 8 heads: two, four launches
   }
 }
 
-template <int BITS, int G, int R>
-void launch_one(const kvs_desc* d, const kvs::DecodeGeometry& geo, const MfmaArgs& args, hipStream_t s) {
-  const dim3 grid(d->B * d->Hkv * geo.splits), block(waves_for(BITS, G, R, false) * KVS_WAVE);
-  if constexpr (R == 1 && BITS != 8) {
-    if (d->sparse_frac > 0.0f) {
-      hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, true>), grid, block, 0, s, args);
-      return;
-    }
-  }
-  hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, false>), grid, block, 0, s, args);
-}
-
-// Instantiated shapes: every group size with 1 or 4 query heads per KV head; 2 and 8 heads for
-// group size 128 (8 heads x 2 groups x hi/lo would need 32 tile columns at group size 32).
-// The dense-and-sparse variant exists for one query head per KV head.
+// Per-channel Keys: 2 R (token groups per tile) columns for the scores, 2 R or (G = 32) 4 R for the
+// output: everything fits but 8 heads at G = 32, which takes two launches of 4.  The
+// dense-and-sparse variant exists for one query head per KV head.
 template <int BITS>
 void launch_bits(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c, void* out,
                  float* lse, float* ws, float* cs, int n_used, const float* extra, hipStream_t s) {
   const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws, cs, n_used, extra);
-  const int rep = d->Hq / d->Hkv;
+  const int rep = a.rep;
   if (d->group == 128) {
-    if (rep == 1) launch_one<BITS, 128, 1>(d, geo, a, s);
-    else if (rep == 2) launch_one<BITS, 128, 2>(d, geo, a, s);
-    else if (rep == 4) launch_one<BITS, 128, 4>(d, geo, a, s);
-    else launch_one<BITS, 128, 8>(d, geo, a, s);
+    if (rep == 1) launch_heads<BITS, 128, 1, false>(d, geo, a, s);
+    else if (rep == 2) launch_heads<BITS, 128, 2, false>(d, geo, a, s);
+    else if (rep == 4) launch_heads<BITS, 128, 4, false>(d, geo, a, s);
+    else launch_heads<BITS, 128, 8, false>(d, geo, a, s);
   } else if (d->group == 64) {
-    if (rep == 1) launch_one<BITS, 64, 1>(d, geo, a, s);
-    else launch_one<BITS, 64, 4>(d, geo, a, s);
+    if (rep == 1) launch_heads<BITS, 64, 1, false>(d, geo, a, s);
+    else if (rep == 2) launch_heads<BITS, 64, 2, false>(d, geo, a, s);
+    else if (rep == 4) launch_heads<BITS, 64, 4, false>(d, geo, a, s);
+    else launch_heads<BITS, 64, 8, false>(d, geo, a, s);
   } else {
-    if (rep == 1) launch_one<BITS, 32, 1>(d, geo, a, s);
-    else launch_one<BITS, 32, 4>(d, geo, a, s);
+    if (rep == 1) launch_heads<BITS, 32, 1, false>(d, geo, a, s);
+    else if (rep == 2) launch_heads<BITS, 32, 2, false>(d, geo, a, s);
+    else launch_heads<BITS, 32, 4, false>(d, geo, a, s);             // 8 heads: two launches
   }
 }
 

@@ -36,7 +36,7 @@ constexpr int kMfmaTargetGroups = 256;   // one workgroup per compute unit
 // whenever there are enough (b, h) pairs - then no second kernel is needed.
 // Most splits any token count up to d->n can get (what the workspace is sized for).
 int decode_max_splits(const kvs_desc* d) {
-  const int pairs = d->B * d->Hkv;
+  const int pairs = d->B * d->Hkv;                     // (per launch, when the heads take several launches)
   int splits;
   if (decode_mfma_supported(d)) {
     splits = pairs >= kMfmaTargetGroups ? 1 : (kMfmaTargetGroups + pairs / 2) / pairs;
