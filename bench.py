@@ -466,7 +466,8 @@ def main() -> int:
                                                                             ",per-token Keys" if w.key_per_token else "")
                        + ("" if kb.kvs_decode_splits(bufs[0].desc) == 1 else " + decode_combine_kernel"))
                       if w.sparse_frac == 0 else
-                      "kvs_decode_attn = decode_partial_kernel + decode_combine_kernel",
+                      ("kvs_decode_attn = sparse_key_corr_kernel + decode_mfma_kernel<%d,%d,%d,isolated outliers> + "
+                       "decode_finish_sparse_kernel" % (w.bits, w.group, w.Hq // w.Hkv)),
             "bound": "hbm",
             "achieved": round(dec_gbps, 2),
             "peak": HBM_PEAK_GBPS,

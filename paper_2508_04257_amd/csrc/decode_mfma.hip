@@ -14,11 +14,6 @@ void launch_decode_mfma_kpt_b3(const kvs_desc*, const DecodeGeometry&, const voi
 void launch_decode_mfma_kpt_b4(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, int, const float*, hipStream_t);
 void launch_decode_mfma_kpt_b8(const kvs_desc*, const DecodeGeometry&, const void*, const kvs_cache*, void*, float*, float*, int, const float*, hipStream_t);
 
-bool decode_mfma_supported(const kvs_desc* d) {
-  // isolated outliers: one query head per KV head; every dense shape otherwise
-  return d->sparse_frac == 0.0f || d->Hq == d->Hkv;
-}
-
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
                         void* out, float* lse, float* ws, float* cs, int n_used, const float* extra, hipStream_t s) {
   if (d->key_per_token) {

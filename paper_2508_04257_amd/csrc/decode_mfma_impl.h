@@ -1,11 +1,20 @@
 // Matrix-core decode-attention kernel over the packed low-bit KV cache, all bit widths and group
 // sizes (paper, Section 2 attention equation over the quantised cache; the sink / non-sink split
-// of Section 4.2).  Same result as the generic kernel in decode.hip, which documents the folding
-// of scales and zero points.  Included by decode_mfma_b{2,3,4}.hip, one bit width each.
+// of Section 4.2).  Included by decode_mfma_b{2,3,4,8}.hip and decode_mfma_kpt_b{2,3,4,8}.hip,
+// one bit width each.
+//
+// Dequantised values are never formed.  With x' = scale (code - zero) (Appendix C):
+//   score[t]  = sum_c q_c scale_c (code[t, c] - zero_c)        per-channel Keys, one (scale, zero)
+//             = sum_c (q scale)_c code[t, c] - sum_c (q scale)_c zero_c     per channel and token group:
+//     the scale goes into the query once per token group, the zero points into one bias per group;
+//   out[c]    = sum_t p_t scale_t (code[t, c] - zero_t)        per-token Values, one (scale, zero)
+//             = sum_t (p scale)_t code[t, c] - sum_t (p scale)_t zero_t     per token and channel group:
+//     the scale goes into the softmax weight, the zero points into one running scalar per channel
+//     group.  Kept tokens get weight zero here (their fp16 rows are merged separately).
 //
 // Why matrix cores even for a one-row query: at ~0.5 byte per cached element the HBM stream
 // delivers ~1e13 codes/s, and unpack + convert + multiply-add on the vector ALU costs 3+
-// instructions per code, which is what bounds the generic kernel.  Here a code becomes an fp16
+// instructions per code, which is what bounded a vector-ALU version of this kernel.  Here a code becomes an fp16
 // operand with ~0.6 instruction: a b-bit field sitting in mantissa bits [p, p+b) of a half whose
 // exponent field is set to 25 - p reads as 2^(10-p) + code, so (w & mask) | magic yields two
 // operands at once and most fields need no shift.  The additive offsets leave with the zero
@@ -816,7 +825,7 @@ void launch_heads(const kvs_desc* d, const kvs::DecodeGeometry& geo, MfmaArgs ar
   const dim3 grid(d->B * d->Hkv * geo.splits), block(waves_for(BITS, G, R, KPT) * KVS_WAVE);
   const bool sparse = d->sparse_frac > 0.0f;
   for (args.head_off = 0; args.head_off < args.rep; args.head_off += R) {
-    if constexpr (R == 1 && BITS != 8 && !KPT) {
+    if constexpr (BITS != 8 && !KPT) {
       if (sparse) {
         hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, true, false>), grid, block, 0, s, args);
         continue;

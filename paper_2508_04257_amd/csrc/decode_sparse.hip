@@ -8,7 +8,7 @@
 //   2. decode_mfma_kernel<SPARSE>  adds them to the scores, leaves every corrected score behind
 //   3. decode_finish_sparse_kernel Value corrections with the final softmax weights, merge of the
 //                                  parts, kept rows, output.
-// One query head per KV head only; other shapes use the generic kernel of decode.hip.
+// Any number of query heads per KV head: the corrections are per (sequence, query head, token).
 #include "kvs_device.h"
 
 namespace {
@@ -24,14 +24,15 @@ constexpr int kKeyIlp = 4;
 __global__ __launch_bounds__(128) void sparse_key_corr_kernel(
     const uint16_t* __restrict__ q, const uint32_t* __restrict__ k_params, const int32_t* __restrict__ k_rowptr,
     const uint16_t* __restrict__ k_col, const uint16_t* __restrict__ k_val, int cap, int n, int group,
-    float* __restrict__ cs) {
+    int Hq, int Hkv, float* __restrict__ cs) {
   __shared__ float qf[128];
   __shared__ uint32_t prm_s[(128 * kKeyIlp / 32) * 128];     // parameter rows of the block's token groups
   const int blocks = (n + 128 * kKeyIlp - 1) / (128 * kKeyIlp);
-  const size_t bh = blockIdx.x / blocks;              // = b * Hq + hq: one query head per KV head
+  const size_t bq = blockIdx.x / blocks;              // b * Hq + hq
+  const size_t bh = (bq / Hq) * Hkv + (bq % Hq) / (Hq / Hkv);  // b * Hkv + h: the rows the head reads
   const int tb = (blockIdx.x % blocks) * (128 * kKeyIlp);     // first token of the block
   const int t0 = tb + threadIdx.x;
-  qf[threadIdx.x] = kvs::half_bits_to_float(q[bh * 128 + threadIdx.x]) * kLog2eRsqrtD;
+  qf[threadIdx.x] = kvs::half_bits_to_float(q[bq * 128 + threadIdx.x]) * kLog2eRsqrtD;
   const int groups = (min(n - tb, 128 * kKeyIlp) + group - 1) / group;
   for (int i = threadIdx.x; i < groups * 128; i += 128)
     prm_s[i] = k_params[(bh * (n / group) + static_cast<size_t>(tb / group)) * 128 + i];
@@ -72,7 +73,7 @@ __global__ __launch_bounds__(128) void sparse_key_corr_kernel(
   }
 #pragma unroll
   for (int u = 0; u < kKeyIlp; ++u)
-    if (t0 + 128 * u < n) cs[bh * n + t0 + 128 * u] = acc[u];
+    if (t0 + 128 * u < n) cs[bq * n + t0 + 128 * u] = acc[u];
 }
 
 // One workgroup per (b, hq).  A thread owns one channel and every eighth 128-token tile, i.e. a
@@ -231,9 +232,9 @@ size_t decode_sparse_score_floats(const kvs_desc* d) {
 }
 
 void launch_sparse_key_corr(const kvs_desc* d, const void* q, const kvs_cache* c, float* cs, hipStream_t s) {
-  hipLaunchKernelGGL(sparse_key_corr_kernel, dim3(d->B * d->Hkv * ((d->n + 128 * kKeyIlp - 1) / (128 * kKeyIlp))), dim3(128), 0, s,
+  hipLaunchKernelGGL(sparse_key_corr_kernel, dim3(d->B * d->Hq * ((d->n + 128 * kKeyIlp - 1) / (128 * kKeyIlp))), dim3(128), 0, s,
                      static_cast<const uint16_t*>(q), c->k_params, c->k_rowptr, c->k_col,
-                     static_cast<const uint16_t*>(c->k_val), static_cast<int>(d->sparse_cap), d->n, d->group, cs);
+                     static_cast<const uint16_t*>(c->k_val), static_cast<int>(d->sparse_cap), d->n, d->group, d->Hq, d->Hkv, cs);
 }
 
 void launch_decode_finish_sparse(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,

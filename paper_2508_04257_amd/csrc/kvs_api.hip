@@ -30,19 +30,14 @@ kvs_status validate_desc(const kvs_desc* d) {
 
 constexpr int kMfmaTargetGroups = 256;   // one workgroup per compute unit
 
-// Splits are whole numbers of 128-token Value tiles.  Generic kernel: one workgroup (4 waves) per
-// split, enough workgroups to cover 256 compute units several times over.  Matrix-core kernel:
-// one 8-wave workgroup per split, about one per compute unit, and a single split per (b, h)
-// whenever there are enough (b, h) pairs - then no second kernel is needed.
+// Splits are whole numbers of 128-token Value tiles: one workgroup per split and (sequence, KV
+// head), about one workgroup per compute unit in all, and a single split per (sequence, KV head)
+// whenever there are enough of those - then no second kernel is needed.  (Per launch, where the
+// query heads of a KV head take several launches.)
 // Most splits any token count up to d->n can get (what the workspace is sized for).
 int decode_max_splits(const kvs_desc* d) {
-  const int pairs = d->B * d->Hkv;                     // (per launch, when the heads take several launches)
-  int splits;
-  if (decode_mfma_supported(d)) {
-    splits = pairs >= kMfmaTargetGroups ? 1 : (kMfmaTargetGroups + pairs / 2) / pairs;
-  } else {
-    splits = (2048 + pairs - 1) / pairs;
-  }
+  const int pairs = d->B * d->Hkv;
+  const int splits = pairs >= kMfmaTargetGroups ? 1 : (kMfmaTargetGroups + pairs / 2) / pairs;
   const int tiles = d->n / KVS_V_TILE;
   return splits > tiles ? tiles : (splits < 1 ? 1 : splits);
 }
@@ -53,7 +48,6 @@ DecodeGeometry decode_geometry(const kvs_desc* d) { return decode_geometry(d, d-
 DecodeGeometry decode_geometry(const kvs_desc* d, int n_used) {
   const int tiles = n_used / KVS_V_TILE;
   DecodeGeometry g;
-  g.mfma = decode_mfma_supported(d);
   int splits = decode_max_splits(d);
   if (splits > tiles) splits = tiles;
   if (splits < 1) splits = 1;
@@ -131,7 +125,7 @@ extern "C" size_t kvs_workspace_bytes(const kvs_desc* d) {
   // decode: per (b, hq, split) the unnormalised fp32 output row plus running max and sum (sized
   // for the most splits any token count of a growing cache can get)
   size_t decode = static_cast<size_t>(d->B) * d->Hq * kvs::decode_max_splits(d) * (KVS_HEAD_DIM + 2) * 4;
-  if (g.mfma && d->sparse_frac > 0.0f)               // plus one score per (b, hq, token)
+  if (d->sparse_frac > 0.0f)                         // plus one score per (b, hq, token)
     decode = (kvs::decode_parts_floats(d, g) + kvs::decode_sparse_score_floats(d)) * 4;
   // quantise (dense-and-sparse only): two 32768-bin histograms, thresholds, scan scratch
   const size_t quant = d->sparse_frac > 0.0f ? kvs::sparse_workspace_words(d) * 4 : 0;

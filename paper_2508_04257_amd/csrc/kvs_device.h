@@ -40,13 +40,11 @@ kvs_status validate_desc(const kvs_desc* d);
 struct DecodeGeometry {
   int splits;        // workgroups (token ranges) per (sequence, KV head)
   int split_tokens;  // tokens per split, a multiple of 128
-  bool mfma;         // matrix-core kernel instead of the generic one
 };
 DecodeGeometry decode_geometry(const kvs_desc* d);
 DecodeGeometry decode_geometry(const kvs_desc* d, int n_used);
 int decode_max_splits(const kvs_desc* d);
 // Matrix-core decode kernel (decode_mfma.hip).
-bool decode_mfma_supported(const kvs_desc* d);
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
                         void* out, float* lse, float* ws, float* cs, int n_used, const float* extra, hipStream_t s);
 // Dense-and-sparse companions of the matrix-core kernel (decode_sparse.hip).  The workspace then
