@@ -56,7 +56,6 @@ __host__ __device__ constexpr int waves_for(int bits, int G, int R, bool kpt) {
   if (bits == 8) return R * (128 / G) * (kpt ? 2 : 1) >= 4 ? 4 : 8;
   if (!kpt) return ((bits >= 3 && G == 32 && R == 4) || (G == 64 && R == 8)) ? 4 : 8;   // (64, 8): the tables of 8 waves exceed the LDS
   if (bits >= 3 && G == 128 && R == 8) return 4;
-  if (bits == 3 && ((G == 64 && R == 4) || (G == 32 && R == 2))) return 4;
   return 8;
 }
 constexpr float kLog2eRsqrtD = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
