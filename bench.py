@@ -33,8 +33,8 @@ HBM_PEAK_GBPS = 8000.0
 DECODE_TRAFFIC = {
     "workload": "cfg1",
     "sources": ["decode_mfma_impl.h", "decode_mfma_b4.hip", "decode_mfma.hip", "kvs_device.h", "kvs_api.hip"],
-    "sha256_16": "937b5038bc1026ef",
-    "fetch_bytes": 144047319,
+    "sha256_16": "0bfde1e14df2e448",
+    "fetch_bytes": 144054281,
     "write_bytes": 73728,
 }
 
