@@ -5,8 +5,7 @@ state, kvs_decode_attn of one query per sequence and head over a cache, kvs_quan
 layer's K and V into a cache.  The step quantises into cache slot i and decodes from slot i + 1
 (quantised several steps earlier), and the K/V inputs rotate over distinct copies, so every
 stream comes from HBM rather than from the 256 MB last-level cache.  Decode runs between
-predict and quantise: it has no data dependence on this step's quantise, and placed right
-after it it would share HBM with the write-back of the 143 MB that call has just written.
+predict and quantise: it has no data dependence on this step's quantise.
 
 Prints ONE JSON line.  value = effective HBM GB/s of kvs_decode_attn (algorithmic bytes of the
 call / its mean duration, both kernels), the headline metric; quantize tokens/s is reported next
@@ -23,6 +22,8 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+
+from paper_2508_04257_amd.traffic import decode_algorithmic_bytes, quantize_algorithmic_bytes  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0
 
@@ -53,27 +54,6 @@ def measured_decode_traffic(workload_name: str):
     if h.hexdigest()[:16] != DECODE_TRAFFIC["sha256_16"]:
         return None
     return DECODE_TRAFFIC["fetch_bytes"] + DECODE_TRAFFIC["write_bytes"]
-
-
-def decode_algorithmic_bytes(w, keep_rows_per_seq: int) -> int:
-    """Bytes one kvs_decode_attn call must move: packed codes, 4-byte parameter words, the keep
-    mask, the fp16 keep rows, q and out.  (Not the fp16 cache it avoids reading.)"""
-    W = {2: 8, 3: 13, 4: 16, 8: 32}[w.bits]
-    bh = w.B * w.Hkv
-    codes = 2 * bh * w.n * W * 4
-    params = bh * (w.n // w.group) * w.D * 4 + bh * w.n * (w.D // w.group) * 4
-    keep = 2 * bh * keep_rows_per_seq * w.D * 2 + w.B * w.n
-    qo = 2 * w.B * w.Hq * w.D * 2
-    return codes + params + keep + qo
-
-
-def quantize_algorithmic_bytes(w) -> int:
-    """fp16 K and V read once, codes and parameters written once."""
-    W = {2: 8, 3: 13, 4: 16, 8: 32}[w.bits]
-    bh = w.B * w.Hkv
-    read = 2 * bh * w.n * w.D * 2 + w.B * w.n
-    write = 2 * bh * w.n * W * 4 + bh * (w.n // w.group) * w.D * 4 + bh * w.n * (w.D // w.group) * 4
-    return read + write
 
 
 class HipEvent:
