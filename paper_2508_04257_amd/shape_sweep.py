@@ -60,9 +60,18 @@ def main():
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
     ap.add_argument("--pairs", type=int, default=256, help="(sequence, KV head) pairs; a multiple of 32")
     ap.add_argument("--n", type=int, default=4096, help="tokens per sequence; a multiple of 128")
+    ap.add_argument("--shape", default=None, metavar="BITS,G,HEADS,PER_TOKEN",
+                    help="time one shape only, e.g. 4,128,8,0")
     args = ap.parse_args()
     if not torch.cuda.is_available():
         raise SystemExit("the sweep needs a GPU")
+    if args.shape:
+        bits, group, rep, kpt = (int(x) for x in args.shape.split(","))
+        t_dec, t_qnt, b_dec, b_qnt, splits = measure(bits, group, rep, bool(kpt), args.pairs, args.n)
+        print(f"bits {bits} G {group} heads per KV head {rep} per-token Keys {kpt}: decode {t_dec * 1e6:.1f} us "
+              f"({100 * b_dec / t_dec / HBM_PEAK:.1f} % of 8 TB/s, {splits} part(s)), quantise {t_qnt * 1e6:.1f} us "
+              f"({100 * b_qnt / t_qnt / HBM_PEAK:.1f} %)")
+        return
     for kpt in (False, True):
         print(("Per-token Keys" if kpt else "Per-channel Keys") +
               f", {args.pairs} (sequence, KV head) pairs x {args.n} tokens; decode: time, % of 8 TB/s\n")
