@@ -1,6 +1,8 @@
 """Seeded sweep over descriptor combinations the other parity tests do not enumerate one by one:
 bit width x group size x heads per KV head x Key scheme x isolated outliers x shapes x keep
 patterns.  Same bars as everywhere: cache bit-exact, attention outputs within 2e-3."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -25,7 +27,7 @@ def _draw(rng):
     return bits, G, rep, kpt, sparse, B, H, n
 
 
-@pytest.mark.parametrize("case", range(64))
+@pytest.mark.parametrize("case", range(int(os.environ.get("KVS_RANDOM_CASES", "64"))))   # more seeds on request
 def test_random_configuration(case):
     rng = np.random.default_rng(9000 + case)
     bits, G, rep, kpt, sparse, B, H, n = _draw(rng)
