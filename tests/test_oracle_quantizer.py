@@ -197,7 +197,11 @@ def test_hand_computed_words():
     c = np.zeros(128, np.uint8)
     c[:16] = [1, 2, 3, 0, 1, 2, 3, 0, 3, 3, 0, 0, 1, 1, 2, 2]
     assert O._pack_last_axis(c, 2)[0] == int("".join(f"{v:02b}" for v in reversed(c[:16].tolist())), 2)
-    assert O.words_per_128(2) == 8 and O.words_per_128(3) == 13 and O.words_per_128(4) == 16
+    c = np.zeros(128, np.uint8)
+    c[:8] = [0x11, 0x22, 0x33, 0xFF, 0x01, 0x80, 0x7F, 0xA5]
+    words = O._pack_last_axis(c, 8)
+    assert words[0] == 0xFF332211 and words[1] == 0xA57F8001 and not words[2:].any()
+    assert O.words_per_128(2) == 8 and O.words_per_128(3) == 13 and O.words_per_128(4) == 16 and O.words_per_128(8) == 32
 
 
 @pytest.mark.parametrize("bits", BITS)
