@@ -23,6 +23,10 @@ def _snapshot(buf):
     ("dense", dict(B=2, n=1024, Hq=8, Hkv=8, bits=4, group=128, k_sinks=2)),
     ("gqa_int3", dict(B=2, n=1152, Hq=8, Hkv=2, bits=3, group=64, k_sinks=3, first_n=2)),
     ("sparse", dict(B=2, n=1024, Hq=4, Hkv=4, bits=3, group=128, k_sinks=2, sparse_frac=0.01, student_t=True)),
+    ("sparse_gqa", dict(B=2, n=1024, Hq=8, Hkv=2, bits=4, group=64, k_sinks=2, sparse_frac=0.01, student_t=True)),
+    # heads that take several decode launches: 8 heads at G 32 (8 bit), per-token Keys at G 32
+    ("int8_gqa8", dict(B=1, n=1152, Hq=16, Hkv=2, bits=8, group=32, k_sinks=2)),
+    ("per_token_g32", dict(B=2, n=1024, Hq=8, Hkv=2, bits=4, group=32, k_sinks=2, key_per_token=True)),
 ])
 def test_captured_steps_replay_like_eager_calls(name, kw):
     w = synth.Workload(name, **kw)
