@@ -147,6 +147,87 @@ def test_shifted_grid_gives_nonzero_zero_point_with_the_right_sign():
     assert np.array_equal(codes, (X + 6).astype(np.uint8))
 
 
+# Hand-computed pins for the rounding rule of Appendix C's "round" (reading R1: ties go to the even
+# integer).  Every group below has scale exactly 1, so x * (1 / scale) is x itself and each listed
+# value sits exactly halfway between two codes; rounding halves away from zero (or up) would give
+# the neighbouring code.
+_TIE_VALUES = [0.5, 1.5, 2.5, 3.5, 4.5, 5.5, 6.5]
+_TIE_CODES_EVEN = [0, 2, 2, 4, 4, 6, 6]          # what half-away would make 1, 2, 3, 4, 5, 6, 7
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("which", ["k", "v"])
+def test_exact_halves_round_to_the_even_code(bits, which):
+    qmax = 2 ** bits - 1
+    ties = [(v, c) for v, c in zip(_TIE_VALUES, _TIE_CODES_EVEN) if v < qmax]
+    group = np.zeros(128, np.float16)
+    group[0], group[1] = 0, qmax                                   # range qmax -> scale 1, zero 0
+    for i, (v, _) in enumerate(ties):
+        group[2 + i] = v
+    other = np.linspace(-3, 3, 128).astype(np.float16)             # the other groups: anything
+    if which == "k":                                               # Key group = tokens 0..127 of channel 5
+        X = np.tile(other[:, None], (1, 128))
+        X[:, 5] = group
+        codes, s, z = O.quantize_k_head(X, np.zeros_like(X, bool), bits, 128)
+        assert s[0, 5] == np.float16(1) and z[0, 5] == 0
+        got = codes[2:2 + len(ties), 5]
+    else:                                                          # Value group = channels 0..127 of token 9
+        X = np.tile(other[None, :], (128, 1))
+        X[9, :] = group
+        codes, s, z = O.quantize_v_head(X, np.zeros_like(X, bool), bits, 128)
+        assert s[9, 0] == np.float16(1) and z[9, 0] == 0
+        got = codes[9, 2:2 + len(ties)]
+    assert got.tolist() == [c for _, c in ties]
+
+
+@pytest.mark.parametrize("which", ["k", "v"])
+def test_negative_halves_round_to_the_even_code(which):
+    # 4 bit, values in [-8, 7]: scale 1, zero 8.  -0.5 -> -0 -> code 8 (half-away: 7);
+    # -1.5 -> -2 -> 6;  -2.5 -> -2 -> 6 (half-away: 5);  -3.5 -> -4 -> 4;  2.5 -> 2 -> 10 (half-away: 11).
+    group = np.zeros(32, np.float16)
+    group[:7] = [-8, 7, -0.5, -1.5, -2.5, -3.5, 2.5]
+    want = [0, 15, 8, 6, 6, 4, 10]
+    if which == "k":
+        X = np.zeros((64, 128), np.float16)
+        X[32:64, 17] = group                                       # token group 1 of channel 17
+        codes, s, z = O.quantize_k_head(X, np.zeros_like(X, bool), 4, 32)
+        assert s[1, 17] == np.float16(1) and z[1, 17] == 8
+        assert codes[32:39, 17].tolist() == want
+    else:
+        X = np.zeros((64, 128), np.float16)
+        X[3, 96:128] = group                                       # channel group 3 of token 3
+        codes, s, z = O.quantize_v_head(X, np.zeros_like(X, bool), 4, 32)
+        assert s[3, 3] == np.float16(1) and z[3, 3] == 8
+        assert codes[3, 96:103].tolist() == want
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_zero_point_of_a_minimum_at_an_exact_half_is_the_even_integer(bits):
+    # range exactly qmax -> scale 1; min / scale = -2.5 must give zero = 2 and -3.5 must give 4
+    # (half-away: 3 and 4; half-up: 2 and 3 - only ties-to-even gives 2 and 4).  Positive minima:
+    # +2.5 -> zero = -2, +3.5 -> -4.
+    qmax = 2 ** bits - 1
+    mins = np.array([-2.5, -3.5, 2.5, 3.5, -0.5, -1.5], np.float32)
+    want = [2, 4, -2, -4, 0, 2]
+    scale_h, zero = O.group_params(mins, mins + np.float32(qmax), np.full(len(mins), 8), bits)
+    assert np.all(scale_h == np.float16(1))
+    assert zero.tolist() == want
+    # ... and through a whole head on both axes: the group's minimum itself is a tie
+    # (-2.5 -> -2, plus zero 2 -> code 0) and so is its maximum (qmax - 2.5 rounds to the even
+    # neighbour; 4 bit: 12.5 -> 12 -> code 14).
+    top = qmax - 2.5
+    top_code = {2: 0 + 2, 3: 4 + 2, 4: 12 + 2, 8: 252 + 2}[bits]     # 0.5 -> 0, 4.5 -> 4, 12.5 -> 12, 252.5 -> 252
+    X = np.full((128, 128), -1.0, np.float16)
+    X[0, :], X[1, :] = -2.5, top                                   # Key groups: tokens of each channel
+    codes, s, z = O.quantize_k_head(X, np.zeros_like(X, bool), bits, 64)
+    assert np.all(s[0] == np.float16(1)) and np.all(z[0] == 2)
+    assert np.all(codes[0] == 0) and np.all(codes[1] == top_code) and np.all(codes[2:64] == 1)
+    Xv = np.ascontiguousarray(X.T)                                 # Value groups: channels of each token
+    codes, s, z = O.quantize_v_head(Xv, np.zeros_like(Xv, bool), bits, 128)
+    assert np.all(s[:, 0] == np.float16(1)) and np.all(z[:, 0] == 2)
+    assert np.all(codes[:, 0] == 0) and np.all(codes[:, 1] == top_code)
+
+
 @pytest.mark.parametrize("bits", BITS)
 def test_chosen_code_minimises_reconstruction_error_brute_force(bits):
     rng = np.random.default_rng(6 + bits)
