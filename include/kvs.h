@@ -67,13 +67,15 @@ extern "C" {
 #define KVS_CACHE_FIELDS 18
 #define KVS_MAX_TOPK 1024
 #define KVS_MAX_PREDICT_TOKENS 65536
+#define KVS_NOALLOC_SCRATCH_BYTES (4u << 20) /* scratch kvs_decode_attn_noalloc holds per GPU */
 
 typedef enum {
   KVS_OK = 0,
   KVS_ERR_INVALID = 1,     /* null pointer, non-positive size, shape rule broken           */
   KVS_ERR_UNSUPPORTED = 2, /* valid request outside what this version implements           */
   KVS_ERR_CAPACITY = 3,    /* only ever written to cache->status, see above                */
-  KVS_ERR_DEVICE = 4       /* a HIP launch failed                                          */
+  KVS_ERR_DEVICE = 4,      /* a HIP launch failed                                          */
+  KVS_ERR_SCRATCH = 5      /* kvs_decode_attn_noalloc: desc needs more than the fixed scratch */
 } kvs_status;
 
 /* Shape and quantiser setting of one layer's cache.  Plain data, filled by the caller. */
@@ -188,6 +190,23 @@ kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const void* V,
  */
 kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const kvs_cache* cache,
                            void* out, float* lse, void* workspace, void* stream);
+
+/*
+ * kvs_decode_attn for callers that cannot allocate device memory and hold no workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments
+ * minus `workspace`, same kernels, same result; the scratch is an array of
+ * KVS_NOALLOC_SCRATCH_BYTES that the library itself holds on every GPU it runs on (from the first
+ * call on that GPU until the process ends).  The call allocates and frees nothing.
+ *   - A descriptor with kvs_workspace_bytes(desc) > KVS_NOALLOC_SCRATCH_BYTES is rejected with
+ *     KVS_ERR_SCRATCH before anything is launched (the four dense workloads of the benchmark need
+ *     less than 1 MiB; a dense-and-sparse cache needs 4 bytes per (sequence, query head, token)).
+ *   - The GPU is the one current on the calling thread (hipGetDevice); `stream` must belong to it.
+ *   - Every call on a GPU shares that GPU's one array: calls that overlap on one GPU (different
+ *     streams, or different threads) race on it.  Order them on one stream, or use
+ *     kvs_decode_attn with a workspace per stream.
+ */
+kvs_status kvs_decode_attn_noalloc(const kvs_desc* desc, const void* q, const kvs_cache* cache,
+                                   void* out, float* lse, void* stream);
 
 /*
  * Growing caches (Section 2, "KV cache": in the decoding phase every new token's K and V are

@@ -15,7 +15,8 @@ import torch
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvs.so")
 _lib = None
 
-KVS_OK, KVS_ERR_INVALID, KVS_ERR_UNSUPPORTED, KVS_ERR_CAPACITY, KVS_ERR_DEVICE = range(5)
+KVS_OK, KVS_ERR_INVALID, KVS_ERR_UNSUPPORTED, KVS_ERR_CAPACITY, KVS_ERR_DEVICE, KVS_ERR_SCRATCH = range(6)
+KVS_NOALLOC_SCRATCH_BYTES = 4 << 20
 KVS_CACHE_FIELDS = 18
 CACHE_FIELD_NAMES = (
     "k_codes", "v_codes", "k_params", "v_params", "keep_k", "keep_v", "keep_idx", "keep_cnt",
@@ -99,6 +100,9 @@ def lib() -> C.CDLL:
         L.kvs_decode_attn.restype = C.c_int
         L.kvs_decode_attn.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.POINTER(KvsCache), C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p]
+        L.kvs_decode_attn_noalloc.restype = C.c_int
+        L.kvs_decode_attn_noalloc.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.POINTER(KvsCache), C.c_void_p,
+                                              C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -237,6 +241,20 @@ def kvs_decode_attn(desc: KvsDesc, q: torch.Tensor, cache: CacheBuffers, out: to
                                _ptr(lse), workspace.data_ptr(), _stream_handle())
     if st != KVS_OK:
         raise KvsError("kvs_decode_attn", st)
+
+
+def kvs_decode_attn_noalloc(desc: KvsDesc, q: torch.Tensor, cache: CacheBuffers, out: torch.Tensor,
+                            lse: Optional[torch.Tensor]) -> None:
+    """kvs_decode_attn on the library's own scratch (no workspace, no allocation in the call)."""
+    _check_tensor("q", q, (desc.B, desc.Hq, desc.D), torch.float16)
+    _check_tensor("out", out, (desc.B, desc.Hq, desc.D), torch.float16)
+    if lse is not None:
+        _check_tensor("lse", lse, (desc.B, desc.Hq), torch.float32)
+    _check_cache(desc, cache)
+    st = lib().kvs_decode_attn_noalloc(C.byref(desc), q.data_ptr(), C.byref(cache.struct), out.data_ptr(),
+                                       _ptr(lse), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_decode_attn_noalloc", st)
 
 
 # ---- growing caches: desc.n is the capacity, n_tokens what the cache holds ---------------------

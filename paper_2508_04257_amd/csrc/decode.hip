@@ -10,9 +10,33 @@
 //   residual_part_kernel   the fp16 residual rows of a growing cache as one more part.
 // Caches with isolated outliers take the two kernels of decode_sparse.hip around the stream
 // kernel instead of the combine kernel.
+#include <atomic>
+
 #include "kvs_device.h"
 
 namespace {
+
+// Scratch of kvs_decode_attn_noalloc: what the other decode calls take as `workspace`, held by the
+// library so that the call needs no allocation.  Every GPU the library runs on holds its own copy
+// (at its own address) until the process ends.  In host code the array's name is only a handle
+// for hipGetSymbolAddress; the address that kernels, copies and fills take is looked up once per
+// device (scratch_of_current_device) and kept.
+constexpr size_t kScratchBytes = size_t{KVS_NOALLOC_SCRATCH_BYTES};
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> scratch_addr[kMaxDevices];      // device address of `scratch` on each device, null until asked
+
+kvs_status scratch_of_current_device(void** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return KVS_ERR_DEVICE;
+  void* p = scratch_addr[dev].load(std::memory_order_acquire);
+  if (!p) {                                          // two threads may both ask: they get the same answer
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return KVS_ERR_DEVICE;
+    scratch_addr[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  return KVS_OK;
+}
 
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * KVS_WAVE;
@@ -181,11 +205,10 @@ __global__ __launch_bounds__(kThreads) void residual_part_kernel(
   }
 }
 
-static kvs_status check_decode_args(const kvs_desc* desc, const void* q, const kvs_cache* cache, const void* out,
-                                    const void* workspace) {
+static kvs_status check_decode_args(const kvs_desc* desc, const void* q, const kvs_cache* cache, const void* out) {
   const kvs_status st = kvs::validate_desc(desc);
   if (st != KVS_OK) return st;
-  if (!q || !cache || !out || !workspace) return KVS_ERR_INVALID;
+  if (!q || !cache || !out) return KVS_ERR_INVALID;
   if (!cache->k_codes || !cache->v_codes || !cache->k_params || !cache->v_params ||
       !cache->keep_cnt || !cache->keep_mask)
     return KVS_ERR_INVALID;
@@ -216,8 +239,9 @@ static void decode_dense(const kvs_desc* desc, const void* q, const kvs_cache* c
 
 extern "C" kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const kvs_cache* cache,
                                        void* out, float* lse, void* workspace, void* stream) {
-  const kvs_status st = check_decode_args(desc, q, cache, out, workspace);
+  const kvs_status st = check_decode_args(desc, q, cache, out);
   if (st != KVS_OK) return st;
+  if (!workspace) return KVS_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(stream);
   float* ws = static_cast<float*>(workspace);
   const kvs::DecodeGeometry geo = kvs::decode_geometry(desc);
@@ -232,10 +256,24 @@ extern "C" kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const
   return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
 }
 
+// kvs_decode_attn for callers that cannot allocate: the same kernels, with the library's own
+// scratch array in place of the caller's workspace.
+extern "C" kvs_status kvs_decode_attn_noalloc(const kvs_desc* desc, const void* q, const kvs_cache* cache,
+                                               void* out, float* lse, void* stream) {
+  const kvs_status st = check_decode_args(desc, q, cache, out);
+  if (st != KVS_OK) return st;
+  if (kvs_workspace_bytes(desc) > kScratchBytes) return KVS_ERR_SCRATCH;
+  void* ws = nullptr;
+  const kvs_status sp = scratch_of_current_device(&ws);
+  if (sp != KVS_OK) return sp;
+  return kvs_decode_attn(desc, q, cache, out, lse, ws, stream);
+}
+
 extern "C" kvs_status kvs_decode_attn_n(const kvs_desc* desc, const void* q, const kvs_cache* cache, int32_t n_tokens,
                                          void* out, float* lse, void* workspace, void* stream) {
-  const kvs_status st = check_decode_args(desc, q, cache, out, workspace);
+  const kvs_status st = check_decode_args(desc, q, cache, out);
   if (st != KVS_OK) return st;
+  if (!workspace) return KVS_ERR_INVALID;
   if (desc->sparse_frac > 0.0f) return KVS_ERR_UNSUPPORTED;
   if (n_tokens < 1 || n_tokens > desc->n) return KVS_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(stream);

@@ -72,6 +72,7 @@ extern "C" const char* kvs_status_string(kvs_status s) {
     case KVS_ERR_UNSUPPORTED: return "unsupported configuration";
     case KVS_ERR_CAPACITY: return "capacity exceeded";
     case KVS_ERR_DEVICE: return "device launch failed";
+    case KVS_ERR_SCRATCH: return "descriptor needs more scratch than the library holds";
   }
   return "unknown status";
 }
