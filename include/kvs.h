@@ -130,9 +130,17 @@ const char* kvs_status_string(kvs_status s);
 kvs_status kvs_cache_bytes(const kvs_desc* desc, size_t* sizes);
 
 /* Bytes of scratch `workspace` that kvs_quantize_kv and kvs_decode_attn need for `desc`
- * (the larger of the two; 0 for an invalid descriptor).  Contents need not be preserved
- * between calls; calls that share a workspace must be ordered on one stream. */
+ * (the larger of the two; 0 for an invalid descriptor).  Calls that share a workspace must be
+ * ordered on one stream.
+ * The first kvs_workspace_zero_bytes(desc) bytes are arrival counters of the decode kernels (when
+ * several workgroups share a (sequence, KV head), the one that finishes last merges their
+ * results): the caller ZEROES THEM ONCE after allocating the workspace, every call that runs to
+ * completion leaves them zero, and nothing else in the workspace needs to be preserved or
+ * initialised.  Like cache->status this is a contract, not checked: with stale counters a decode
+ * call still stays inside its buffers and terminates, but output rows may not be written.  After
+ * an aborted launch (device reset, failed call) zero them again. */
 size_t kvs_workspace_bytes(const kvs_desc* desc);
+size_t kvs_workspace_zero_bytes(const kvs_desc* desc);
 
 /* Number of token splits kvs_decode_attn uses for `desc` (each split is one workgroup per
  * (sequence, KV head); informational, 0 for an invalid descriptor). */
@@ -186,7 +194,7 @@ kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const void* V,
  *   out = sum_t p_t V'[t]  (fp32 accumulation, stored fp16);  lse = log sum_t exp(s_t).
  * Query head hq reads KV head hq / (Hq / Hkv).
  *   q fp16 [B, Hq, 128];  out fp16 [B, Hq, 128];  lse float [B, Hq] or NULL.
- *   workspace: kvs_workspace_bytes(desc) bytes.
+ *   workspace: kvs_workspace_bytes(desc) bytes, its head zeroed once (kvs_workspace_zero_bytes).
  */
 kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const kvs_cache* cache,
                            void* out, float* lse, void* workspace, void* stream);
@@ -194,7 +202,8 @@ kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const kvs_cache*
 /*
  * kvs_decode_attn for callers that cannot allocate device memory and hold no workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments
- * minus `workspace`, same kernels, same result; the scratch is an array of
+ * minus `workspace`, same kernels (after one small kernel that clears the arrival counters at the
+ * scratch's head), same result; the scratch is an array of
  * KVS_NOALLOC_SCRATCH_BYTES that the library itself holds on every GPU it runs on (from the first
  * call on that GPU until the process ends).  The call allocates and frees nothing.
  *   - A descriptor with kvs_workspace_bytes(desc) > KVS_NOALLOC_SCRATCH_BYTES is rejected with

@@ -63,6 +63,8 @@ def lib() -> C.CDLL:
         L.kvs_cache_bytes.argtypes = [C.POINTER(KvsDesc), C.POINTER(C.c_size_t)]
         L.kvs_workspace_bytes.restype = C.c_size_t
         L.kvs_workspace_bytes.argtypes = [C.POINTER(KvsDesc)]
+        L.kvs_workspace_zero_bytes.restype = C.c_size_t
+        L.kvs_workspace_zero_bytes.argtypes = [C.POINTER(KvsDesc)]
         L.kvs_decode_splits.restype = C.c_int32
         L.kvs_decode_splits.argtypes = [C.POINTER(KvsDesc)]
         L.kvs_predict_sinks.restype = C.c_int
@@ -171,8 +173,15 @@ def alloc_cache(desc: KvsDesc, device="cuda") -> CacheBuffers:
     return CacheBuffers(desc, tensors, struct)
 
 
+def kvs_workspace_zero_bytes(desc: KvsDesc) -> int:
+    return int(lib().kvs_workspace_zero_bytes(C.byref(desc)))
+
+
 def alloc_workspace(desc: KvsDesc, device="cuda") -> torch.Tensor:
-    return torch.empty(max(16, kvs_workspace_bytes(desc)), dtype=torch.uint8, device=device)
+    """Allocates the workspace and zeroes the counter block at its head (once; calls keep it zero)."""
+    ws = torch.empty(max(16, kvs_workspace_bytes(desc)), dtype=torch.uint8, device=device)
+    ws[:kvs_workspace_zero_bytes(desc)].zero_()
+    return ws
 
 
 def _check_tensor(name: str, t: torch.Tensor, shape, dtype) -> None:

@@ -12,6 +12,7 @@
 // kernel instead of the combine kernel.
 #include <atomic>
 
+#include "decode_finish.h"
 #include "kvs_device.h"
 
 namespace {
@@ -38,13 +39,20 @@ kvs_status scratch_of_current_device(void** ptr) {
   return KVS_OK;
 }
 
+__global__ void clear_words_kernel(uint32_t* __restrict__ p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * KVS_WAVE;
 constexpr float kRsqrtD = 0.08838834764831845f;   // 1 / sqrt(128)
 constexpr int kWsRow = KVS_HEAD_DIM + 2;          // output row, running max, running sum
 
-// One wave per (b, hq), lane = channels 2 lane and 2 lane + 1: log-sum-exp merge of the splits,
-// then the kept tokens' fp16 rows join the same running softmax.
+// One wave per (b, hq): the parts a stream kernel left in the workspace, the extra part and the
+// kept rows into one output row (finish_row).  Only needed when no stream kernel ran at all (a
+// growing cache that still holds fewer than 128 tokens: splits == 0); a stream cut into parts is
+// finished by its own last-arriving workgroup.
 __global__ __launch_bounds__(KVS_WAVE) void decode_combine_kernel(
     const uint16_t* __restrict__ q, const float* __restrict__ ws, const float* __restrict__ extra, int splits, int Hq, int Hkv,
     int cap, const uint16_t* __restrict__ keep_k, const uint16_t* __restrict__ keep_v,
@@ -53,90 +61,12 @@ __global__ __launch_bounds__(KVS_WAVE) void decode_combine_kernel(
   const size_t bq = blockIdx.x;                       // b * Hq + hq
   const int b = static_cast<int>(bq / Hq), hq = static_cast<int>(bq % Hq);
   const int h = hq / (Hq / Hkv);
-  const float* row = ws + bq * splits * kWsRow;
   const int cnt = min(keep_cnt[b], cap);
   const uint32_t q2 = reinterpret_cast<const uint32_t*>(q + bq * 128)[lane];
-  const float q0 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 & 0xFFFFu));
-  const float q1 = kvs::half_bits_to_float(static_cast<uint16_t>(q2 >> 16));
-
-  // The first kept rows are requested before anything else is read.
-  constexpr int kKeepBatch = 8;
   const uint32_t* kk = reinterpret_cast<const uint32_t*>(keep_k) + (static_cast<size_t>(b) * Hkv + h) * cap * 64 + lane;
   const uint32_t* kv = reinterpret_cast<const uint32_t*>(keep_v) + (static_cast<size_t>(b) * Hkv + h) * cap * 64 + lane;
-  uint32_t kw_next[kKeepBatch], vw_next[kKeepBatch];
-#pragma unroll
-  for (int u = 0; u < kKeepBatch; ++u) {
-    kw_next[u] = 0;  vw_next[u] = 0;
-    if (cnt > 0) {
-      const int j = min(u, cnt - 1);
-      kw_next[u] = kk[j * 64];
-      vw_next[u] = kv[j * 64];
-    }
-  }
-
-  // One more part, if given: the fp16 rows of a growing cache's residual window (the same triple
-  // of unnormalised row, maximum and sum, one per (b, hq)).
-  const float* xrow = extra ? extra + bq * kWsRow : nullptr;
-  float M = -INFINITY;
-  for (int s = lane; s < splits; s += KVS_WAVE) M = fmaxf(M, row[s * kWsRow + 128]);
-  M = kvs::wave_max(M);
-  if (xrow) M = fmaxf(M, xrow[128]);
-  float L = 0.0f, O0 = 0.0f, O1 = 0.0f;
-  if (xrow) {
-    const float ms = xrow[128];
-    const float f = ms == -INFINITY ? 0.0f : __expf(ms - M);
-    const float2 o = reinterpret_cast<const float2*>(xrow)[lane];
-    L = xrow[129] * f;
-    O0 = o.x * f;
-    O1 = o.y * f;
-  }
-#pragma unroll 4
-  for (int s = 0; s < splits; ++s) {
-    const float ms = row[s * kWsRow + 128];
-    const float f = ms == -INFINITY ? 0.0f : __expf(ms - M);
-    const float2 o = reinterpret_cast<const float2*>(row + s * kWsRow)[lane];
-    L += row[s * kWsRow + 129] * f;
-    O0 += o.x * f;
-    O1 += o.y * f;
-  }
-
-  // Kept tokens: exact fp16 rows, eight per step; the step after next is requested before this
-  // one is folded in (the first one was requested at the top of the kernel).
-  for (int j0 = 0; j0 < cnt; j0 += kKeepBatch) {
-    uint32_t kw[kKeepBatch], vw[kKeepBatch];
-#pragma unroll
-    for (int u = 0; u < kKeepBatch; ++u) { kw[u] = kw_next[u]; vw[u] = vw_next[u]; }
-    if (j0 + kKeepBatch < cnt) {
-#pragma unroll
-      for (int u = 0; u < kKeepBatch; ++u) {
-        const int j = min(j0 + kKeepBatch + u, cnt - 1);
-        kw_next[u] = kk[j * 64];
-        vw_next[u] = kv[j * 64];
-      }
-    }
-    float sc[kKeepBatch];
-#pragma unroll
-    for (int u = 0; u < kKeepBatch; ++u)               // the reductions of one step are independent of each other
-      sc[u] = kvs::wave_sum(q0 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] & 0xFFFFu)) +
-                            q1 * kvs::half_bits_to_float(static_cast<uint16_t>(kw[u] >> 16))) * kRsqrtD;
-#pragma unroll
-    for (int u = 0; u < kKeepBatch; ++u) {
-      if (j0 + u < cnt) {
-        const float m_new = fmaxf(M, sc[u]);
-        const float alpha = M == -INFINITY ? 0.0f : __expf(M - m_new);
-        const float p = __expf(sc[u] - m_new);
-        L = L * alpha + p;
-        O0 = O0 * alpha + p * kvs::half_bits_to_float(static_cast<uint16_t>(vw[u] & 0xFFFFu));
-        O1 = O1 * alpha + p * kvs::half_bits_to_float(static_cast<uint16_t>(vw[u] >> 16));
-        M = m_new;
-      }
-    }
-  }
-  const float inv = L > 0.0f ? 1.0f / L : 0.0f;
-  const uint32_t packed = static_cast<uint32_t>(kvs::float_to_half_bits_rn(O0 * inv)) |
-                          (static_cast<uint32_t>(kvs::float_to_half_bits_rn(O1 * inv)) << 16);
-  reinterpret_cast<uint32_t*>(out + bq * 128)[lane] = packed;
-  if (lse && lane == 0) lse[bq] = L > 0.0f ? M + __logf(L) : -INFINITY;
+  kvs::finish_row<false>(q2, ws + bq * splits * kWsRow, splits, extra ? extra + bq * kWsRow : nullptr, kk, kv, cnt,
+                  reinterpret_cast<uint32_t*>(out + bq * 128), lse ? lse + bq : nullptr, lane);
 }
 
 }  // namespace
@@ -219,20 +149,18 @@ static kvs_status check_decode_args(const kvs_desc* desc, const void* q, const k
   return KVS_OK;
 }
 
-// Dense caches: the first n_used tokens (whole blocks) through the stream kernel, then - unless
-// one workgroup per head has already finished the rows - the combine kernel, which also takes
-// the residual rows' part when there is one.
+// Dense caches: the first n_used tokens (whole blocks) through the stream kernel, which also
+// finishes the rows (kept rows, the residual rows' part when there is one) whether one workgroup
+// or several cover a head.  Only a cache without a single whole block takes the combine kernel.
 static void decode_dense(const kvs_desc* desc, const void* q, const kvs_cache* cache, int n_used, const float* extra,
-                         void* out, float* lse, float* ws, hipStream_t s) {
-  int splits = 0;
+                         void* out, float* lse, float* ws, int* arrive, hipStream_t s) {
   if (n_used > 0) {
     const kvs::DecodeGeometry geo = kvs::decode_geometry(desc, n_used);
-    splits = geo.splits;
-    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, nullptr, n_used, extra, s);
-    if (geo.splits == 1) return;                         // finished in one kernel, the extra part included
+    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, arrive, nullptr, n_used, extra, s);
+    return;
   }
   hipLaunchKernelGGL(decode_combine_kernel, dim3(desc->B * desc->Hq), dim3(KVS_WAVE), 0, s,
-                     static_cast<const uint16_t*>(q), ws, extra, splits, desc->Hq, desc->Hkv, desc->keep_cap,
+                     static_cast<const uint16_t*>(q), ws, extra, 0, desc->Hq, desc->Hkv, desc->keep_cap,
                      static_cast<const uint16_t*>(cache->keep_k), static_cast<const uint16_t*>(cache->keep_v),
                      cache->keep_cnt, static_cast<uint16_t*>(out), lse);
 }
@@ -243,15 +171,16 @@ extern "C" kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const
   if (st != KVS_OK) return st;
   if (!workspace) return KVS_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  float* ws = static_cast<float*>(workspace);
+  int* arrive = static_cast<int*>(workspace);
+  float* ws = static_cast<float*>(workspace) + kvs::workspace_counter_words(desc);
   const kvs::DecodeGeometry geo = kvs::decode_geometry(desc);
   if (desc->sparse_frac > 0.0f) {                    // Key corrections, stream kernel, finish
     float* cs = ws + kvs::decode_parts_floats(desc, geo);
     kvs::launch_sparse_key_corr(desc, q, cache, cs, s);
-    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, cs, desc->n, nullptr, s);
+    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, arrive, cs, desc->n, nullptr, s);
     kvs::launch_decode_finish_sparse(desc, geo, q, cache, ws, cs, out, lse, s);
   } else {
-    decode_dense(desc, q, cache, desc->n, nullptr, out, lse, ws, s);
+    decode_dense(desc, q, cache, desc->n, nullptr, out, lse, ws, arrive, s);
   }
   return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
 }
@@ -266,6 +195,12 @@ extern "C" kvs_status kvs_decode_attn_noalloc(const kvs_desc* desc, const void* 
   void* ws = nullptr;
   const kvs_status sp = scratch_of_current_device(&ws);
   if (sp != KVS_OK) return sp;
+  // The array keeps what the last call on this GPU left.  A finished call leaves the arrival
+  // counters at its head zero; an interrupted one may not have, so they are cleared first - by a
+  // kernel, which a graph capture records like any other launch.
+  const int words = static_cast<int>(kvs::workspace_counter_words(desc));
+  hipLaunchKernelGGL(clear_words_kernel, dim3((words + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<uint32_t*>(ws), words);
   return kvs_decode_attn(desc, q, cache, out, lse, ws, stream);
 }
 
@@ -277,7 +212,8 @@ extern "C" kvs_status kvs_decode_attn_n(const kvs_desc* desc, const void* q, con
   if (desc->sparse_frac > 0.0f) return KVS_ERR_UNSUPPORTED;
   if (n_tokens < 1 || n_tokens > desc->n) return KVS_ERR_INVALID;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  float* ws = static_cast<float*>(workspace);
+  int* arrive = static_cast<int*>(workspace);
+  float* ws = static_cast<float*>(workspace) + kvs::workspace_counter_words(desc);
   const int n_used = (n_tokens / KVS_V_TILE) * KVS_V_TILE;
   const int rows = n_tokens - n_used;
   float* extra = nullptr;
@@ -289,6 +225,6 @@ extern "C" kvs_status kvs_decode_attn_n(const kvs_desc* desc, const void* q, con
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(cache->res_k),
                        static_cast<const uint16_t*>(cache->res_v), rows, desc->Hq, desc->Hkv, extra);
   }
-  decode_dense(desc, q, cache, n_used, extra, out, lse, ws, s);
+  decode_dense(desc, q, cache, n_used, extra, out, lse, ws, arrive, s);
   return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
 }

@@ -31,8 +31,10 @@
 // order - not the result beyond rounding - can differ between two runs.)  When a single
 // workgroup covers the whole sequence the kept (sink) tokens' fp16 rows are folded in - wave w
 // takes rows w, w + waves, ... as one more softmax state - and the output row is written right
-// there; otherwise the part's state goes to the workspace and the combine kernel of decode.hip
-// finishes.  Per 128-token chunk:
+// there; otherwise the part's state goes to the workspace, the workgroup counts itself in on the
+// (sequence, KV head)'s arrival counter, and the workgroup that arrives last merges all parts,
+// folds the kept rows in and writes the output rows (the counter block heads the workspace; it
+// is zero before the call and the last arriver leaves it zero).  Per 128-token chunk:
 //   scores  S^T[token, col] = sum_c code[token, c] * B[c, col]     tokens are the M rows
 //   softmax with lane = token (scores pass through LDS once)
 //   output  O^T[chan, col] = sum_t code[t, chan] * W[t, col]       channels are the M rows
@@ -40,6 +42,7 @@
 // indices of chunk (l / 16); the result holds rows 4 (l / 16) + i of column (l % 16).
 #pragma once
 
+#include "decode_finish.h"
 #include "kvs_device.h"
 
 namespace kvs_mfma {
@@ -192,6 +195,7 @@ struct MfmaArgs {
   const uint8_t* keep_mask;
   const uint16_t* keep_k; const uint16_t* keep_v; const int32_t* keep_cnt;
   uint16_t* out; float* lse; float* ws;
+  int* arrive;       // one arrival counter per (b, kv head): zero on entry, zero again on exit
   float* cs;         // dense-and-sparse only: per (b, hq, token) score correction in, final score out
   int n, Hkv, cap;   // n: tokens per (b, h) the buffers are laid out for
   int n_used;        // tokens to attend to (the first n_used; a multiple of 128)
@@ -243,6 +247,7 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
   auto part_o = [&](int w, int r) -> float* { return reinterpret_cast<float*>(&wh[w][0][0][0]) + r * 128; };
   __shared__ float part_m[2 * kWaves][R], part_l[2 * kWaves][R];         // [kWaves + w]: wave w's kept rows
   __shared__ int next_chunk;                                             // chunk hand-out counter
+  __shared__ int arrived_last;                                           // this workgroup completes its (b, h)
 
   const int lane = threadIdx.x & (KVS_WAVE - 1), wave = threadIdx.x / KVS_WAVE;
   const int col = lane & 15, grp = lane >> 4;
@@ -777,10 +782,16 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
       O0 += o.x * f;
       O1 += o.y * f;
     }
-    if (a.parts > 1 || SPARSE) {                       // another kernel finishes
+    if (SPARSE) {                                      // another kernel finishes
       float* dst = a.ws + (bq_row * a.parts + part) * kWsRow;
       reinterpret_cast<float2*>(dst)[lane] = float2{O0, O1};
       if (lane == 0) { dst[128] = M; dst[129] = L; }
+      continue;
+    }
+    if (a.parts > 1) {                                 // the last workgroup to arrive finishes (below)
+      float* dst = a.ws + (bq_row * a.parts + part) * kWsRow;
+      kvs::store_coherent(reinterpret_cast<float2*>(dst) + lane, float2{O0, O1});
+      if (lane == 0) { kvs::store_coherent(dst + 128, M); kvs::store_coherent(dst + 129, L); }
       continue;
     }
 #pragma unroll
@@ -798,17 +809,47 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
     reinterpret_cast<uint32_t*>(a.out + bq_row * 128)[lane] = packed;
     if (a.lse && lane == 0) a.lse[bq_row] = L > 0.0f ? M + __logf(L) : -INFINITY;
   }
+
+  // ---- several workgroups per (b, h): the one that arrives last finishes the rows ---------------
+  // Every part is in memory before its workgroup counts itself in: the parts are written with
+  // device-coherent stores, every wave waits until its stores have been acknowledged, then the
+  // barrier, then one atomic per workgroup.  The workgroup whose count completes the (b, h) reads
+  // all parts with device-coherent loads.  (A device-scope fence pair would do the same by writing
+  // back and invalidating the whole L2 of the die, once per workgroup: that more than doubled the
+  // kernel's time.)  The last arriver also puts the counter back to zero: nobody else touches it
+  // any more in this launch.
+  if (a.parts > 1 && !SPARSE) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0)
+      arrived_last = __hip_atomic_fetch_add(a.arrive + bh, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.parts - 1 ? 1 : 0;
+    __syncthreads();
+    if (arrived_last) {
+      const int cnt = min(keep_cnt_b, a.cap);
+#pragma unroll
+      for (int k = 0; k < HPW; ++k) {
+        const int r = wave + k * kWaves;
+        if (r >= R) break;
+        const size_t bq_row = static_cast<size_t>(b) * Hq + hq0 + r;
+        const uint32_t q2 = reinterpret_cast<const uint32_t*>(a.q + bq_row * 128)[lane];
+        kvs::finish_row<true>(q2, a.ws + bq_row * a.parts * kWsRow, a.parts, a.extra ? a.extra + bq_row * kWsRow : nullptr,
+                        keep_rows_k, keep_rows_v, cnt, reinterpret_cast<uint32_t*>(a.out + bq_row * 128),
+                        a.lse ? a.lse + bq_row : nullptr, lane);
+      }
+      if (threadIdx.x == 0) __hip_atomic_store(a.arrive + bh, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
 }
 
 inline MfmaArgs make_args(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                          void* out, float* lse, float* ws, float* cs, int n_used, const float* extra) {
+                          void* out, float* lse, float* ws, int* arrive, float* cs, int n_used, const float* extra) {
   MfmaArgs a;
   a.q = static_cast<const uint16_t*>(q);
   a.k_codes = c->k_codes; a.v_codes = c->v_codes; a.k_params = c->k_params; a.v_params = c->v_params;
   a.keep_mask = c->keep_mask;
   a.keep_k = static_cast<const uint16_t*>(c->keep_k); a.keep_v = static_cast<const uint16_t*>(c->keep_v);
   a.keep_cnt = c->keep_cnt;
-  a.out = static_cast<uint16_t*>(out); a.lse = lse; a.ws = ws; a.cs = cs;
+  a.out = static_cast<uint16_t*>(out); a.lse = lse; a.ws = ws; a.arrive = arrive; a.cs = cs;
   a.n = d->n; a.Hkv = d->Hkv; a.cap = d->keep_cap;
   a.n_used = n_used; a.extra = extra;
   a.parts = geo.splits; a.part_tokens = geo.split_tokens;
@@ -838,8 +879,8 @@ void launch_heads(const kvs_desc* d, const kvs::DecodeGeometry& geo, MfmaArgs ar
 // R (128 / G) <= 8 per launch.
 template <int BITS>
 void launch_bits_kpt(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c, void* out,
-                     float* lse, float* ws, int n_used, const float* extra, hipStream_t s) {
-  const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws, nullptr, n_used, extra);
+                     float* lse, float* ws, int* arrive, int n_used, const float* extra, hipStream_t s) {
+  const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws, arrive, nullptr, n_used, extra);
   const int rep = a.rep;
   if (d->group == 128) {
     if (rep == 1) launch_heads<BITS, 128, 1, true>(d, geo, a, s);
@@ -861,8 +902,8 @@ void launch_bits_kpt(const kvs_desc* d, const kvs::DecodeGeometry& geo, const vo
 // dense-and-sparse variant exists for one query head per KV head.
 template <int BITS>
 void launch_bits(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c, void* out,
-                 float* lse, float* ws, float* cs, int n_used, const float* extra, hipStream_t s) {
-  const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws, cs, n_used, extra);
+                 float* lse, float* ws, int* arrive, float* cs, int n_used, const float* extra, hipStream_t s) {
+  const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws, arrive, cs, n_used, extra);
   const int rep = a.rep;
   if (d->group == 128) {
     if (rep == 1) launch_heads<BITS, 128, 1, false>(d, geo, a, s);

@@ -132,5 +132,10 @@ extern "C" size_t kvs_workspace_bytes(const kvs_desc* d) {
   const size_t quant = d->sparse_frac > 0.0f ? kvs::sparse_workspace_words(d) * 4 : 0;
   // growing caches: one more part per (b, hq) for the residual rows
   decode += static_cast<size_t>(d->B) * d->Hq * (KVS_HEAD_DIM + 2) * 4;
-  return round16(decode > quant ? decode : quant);
+  return round16(kvs::workspace_counter_words(d) * 4 + (decode > quant ? decode : quant));
+}
+
+extern "C" size_t kvs_workspace_zero_bytes(const kvs_desc* d) {
+  if (kvs::validate_desc(d) != KVS_OK) return 0;
+  return kvs::workspace_counter_words(d) * 4;
 }

@@ -46,7 +46,13 @@ DecodeGeometry decode_geometry(const kvs_desc* d, int n_used);
 int decode_max_splits(const kvs_desc* d);
 // Matrix-core decode kernel (decode_mfma.hip).
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                        void* out, float* lse, float* ws, float* cs, int n_used, const float* extra, hipStream_t s);
+                        void* out, float* lse, float* ws, int* arrive, float* cs, int n_used, const float* extra, hipStream_t s);
+// The workspace starts with the stream kernel's arrival counters, one 32-bit word per (sequence,
+// KV head), rounded up to 256 bytes: zero before a call, put back to zero by the call.  What the
+// calls keep in the workspace otherwise follows them.
+inline size_t workspace_counter_words(const kvs_desc* d) {
+  return (static_cast<size_t>(d->B) * d->Hkv + 63) & ~static_cast<size_t>(63);
+}
 // Dense-and-sparse companions of the matrix-core kernel (decode_sparse.hip).  The workspace then
 // holds the parts (B * Hq * splits rows of 130 floats, rounded up to 64 floats) followed by one
 // float per (b, hq, token).

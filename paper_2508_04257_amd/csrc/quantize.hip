@@ -88,7 +88,7 @@ static void quantize_span(const kvs_desc* desc, const kvs::QuantSpan& sp, bool w
   kvs::SparsePlan plan{};
   const bool sparse = desc->sparse_frac > 0.0f;
   if (sparse) {                                        // thresholds of K and V first (plan.tau)
-    plan = kvs::sparse_plan(desc, workspace);
+    plan = kvs::sparse_plan(desc, static_cast<uint32_t*>(workspace) + kvs::workspace_counter_words(desc));   // behind decode's counters
     kvs::sparse_thresholds(desc, plan, K, V, mask, out, s);
   }
   kvs::launch_quantize_fast(desc, sp, whole, K, V, mask, out, static_k, static_v, sparse ? &plan : nullptr, s);

@@ -55,6 +55,10 @@ def test_cache_bytes_for_the_headline_workload():
     assert kb.kvs_cache_bytes(d8)["k_codes"] == kb.kvs_cache_bytes(d8)["v_codes"] == 8 * 32 * 4096 * 128   # a byte per element
     assert kb.kvs_cache_bytes(d8)["k_params"] == s["k_params"]
     assert kb.kvs_workspace_bytes(d) >= 8 * 32 * kb.kvs_decode_splits(d) * 130 * 4
+    # the counter block at its head: one word per (sequence, KV head), whole 256-byte lines
+    assert kb.kvs_workspace_zero_bytes(d) == 8 * 32 * 4
+    small = kb.make_desc(B=1, n=1024, Hq=8, Hkv=2, bits=4, group=128, keep_cap=2)
+    assert kb.kvs_workspace_zero_bytes(small) == 256 and kb.kvs_workspace_bytes(small) > 256
     assert 1 <= kb.kvs_decode_splits(d) <= 4096 // 128
 
 

@@ -3,8 +3,9 @@ the library's own scratch array) against kvs_decode_attn on the same cache, thro
 
 Two calls in a row on one GPU, the second on a smaller input, so that the second runs on scratch
 that still holds the first call's contents.  Shapes are chosen so that the scratch is really used:
-several workgroups per (sequence, KV head) leave their parts there for the combine kernel, and the
-dense-and-sparse cache also parks one score per (query head, token) there.
+several workgroups per (sequence, KV head) leave their parts there and count themselves in on the
+arrival counters at its head, and the dense-and-sparse cache also parks one score per (query head,
+token) there.
 """
 import ctypes as C
 
