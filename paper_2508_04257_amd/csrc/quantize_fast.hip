@@ -313,7 +313,8 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
     }
     inv_s[g][2 * cp] = p0.inv;  inv_s[g][2 * cp + 1] = p1.inv;
     zero_s[g][2 * cp] = p0.zero;  zero_s[g][2 * cp + 1] = p1.zero;
-    reinterpret_cast<uint2*>(k_params + (bh * (n / G) + static_cast<size_t>(tc0 / G + g)) * 128)[cp] = uint2{p0.word, p1.word};
+    __builtin_nontemporal_store(__builtin_bit_cast(unsigned long long, uint2{p0.word, p1.word}),
+                                reinterpret_cast<unsigned long long*>(k_params + (bh * (n / G) + static_cast<size_t>(tc0 / G + g)) * 128) + cp);
   }
   if (SPARSE && tid >= kThreads - KVS_WAVE) {
     // Meanwhile the last wave: row counts (CSR row = token), their exclusive scan over the block,
@@ -492,7 +493,7 @@ __global__ __launch_bounds__(kThreads) void quantize_k_token_fast_kernel(
                                : make_param<BITS>(lo_half(s), -hi_half(s), !kp);
     inv_mine[k] = prm.inv;
     zero_mine[k] = prm.zero;
-    if (row < ROWS) k_params[(bh * n + static_cast<size_t>(tc0 + rslot + 16 * row)) * NGC + chunk / LPG] = prm.word;
+    if (row < ROWS) __builtin_nontemporal_store(prm.word, &k_params[(bh * n + static_cast<size_t>(tc0 + rslot + 16 * row)) * NGC + chunk / LPG]);
   }
 
   const int cnt = min(keep_cnt[b], cap);
@@ -684,7 +685,7 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
                                : make_param<BITS>(lo_half(s), -hi_half(s), any);
     inv_mine[k] = prm.inv;
     zero_mine[k] = prm.zero;
-    if (row < 8) v_params[(bh * n + static_cast<size_t>(t0 + 8 * rs + row)) * NGC + chunk / LPG] = prm.word;
+    if (row < 8) __builtin_nontemporal_store(prm.word, &v_params[(bh * n + static_cast<size_t>(t0 + 8 * rs + row)) * NGC + chunk / LPG]);
   }
 
   const int cnt = min(keep_cnt[b], cap);
