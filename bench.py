@@ -7,9 +7,11 @@ layer's K and V into a cache.  The step quantises into cache slot i and decodes 
 stream comes from HBM rather than from the 256 MB last-level cache.  Decode runs between
 predict and quantise: it has no data dependence on this step's quantise.
 
-Prints ONE JSON line.  value = effective HBM GB/s of kvs_decode_attn (algorithmic bytes of the
-call / its mean duration, both kernels), the headline metric; quantize tokens/s is reported next
-to it.  Inputs are resident in HBM before the timed region.
+Prints ONE JSON line.  value = effective HBM GB/s of kvs_decode_attn on the headline workload
+(algorithmic bytes of the call / its mean duration inside the step); quantize tokens/s is reported
+next to it, the other workloads are timed the same way under "configs", and the 32-layer
+dense-and-sparse workload under "configs.cfg4.layers32".  Inputs are resident in HBM before the
+timed region.  The CPU oracle is timed first, before the GPU is touched.
 """
 from __future__ import annotations
 
@@ -26,23 +28,24 @@ if ROOT not in sys.path:
 from paper_2508_04257_amd.traffic import decode_algorithmic_bytes, quantize_algorithmic_bytes  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0
+OTHER_CONFIGS = ("cfg0_kvsink", "cfg2", "cfg3", "cfg4")
 
 # HBM bytes per kvs_decode_attn launch on the cfg1 workload, from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE; profiles/pmc_cfg1_hbm_traffic.md), each scaled by what the same counter
-# reads for a plain copy of known size.  Valid for the kernel sources whose hash is given: once any
-# of them changes the benchmark reports "traffic": null until the counters are taken again.
+# reads for a plain copy of known size.  Valid for the decode kernel's sources whose hash is given:
+# once any of them changes the benchmark reports "traffic": null until the counters are taken again.
 DECODE_TRAFFIC = {
     "workload": "cfg1",
-    "sources": ["decode_mfma_impl.h", "decode_mfma_b4.hip", "decode_mfma.hip", "kvs_device.h", "kvs_api.hip"],
-    "sha256_16": "0bfde1e14df2e448",
-    "fetch_bytes": 144054281,
-    "write_bytes": 73728,
+    "sources": ["decode_mfma_impl.h", "decode_mfma_b4.hip", "decode_finish.h"],
+    "sha256_16": "",
+    "fetch_bytes": 0,
+    "write_bytes": 0,
 }
 
 
 def measured_decode_traffic(workload_name: str):
     import hashlib
-    if workload_name != DECODE_TRAFFIC["workload"]:
+    if workload_name != DECODE_TRAFFIC["workload"] or not DECODE_TRAFFIC["sha256_16"]:
         return None
     h = hashlib.sha256()
     try:
@@ -87,6 +90,156 @@ class HipEvent:
         return float(ms.value)
 
 
+# ------------------------------------------------------------------------------------------------
+# one workload: rotating inputs and caches, the timed steps
+# ------------------------------------------------------------------------------------------------
+class Rig:
+    """Inputs, caches and buffers of one workload on the GPU, `slots` rotating copies of each."""
+
+    def __init__(self, w, slots, dev):
+        import torch
+
+        from paper_2508_04257_amd import pipeline, synth
+
+        self.w, self.slots, self.dev = w, slots, dev
+        self.hidden = synth.make_hidden(w, dev)
+        self.q = synth.make_query(w, dev)
+        self.inputs = [synth.make_kv(w, dev, layer=s) for s in range(slots)]
+        self.bufs = [pipeline.alloc_step(w, dev) for _ in range(slots)]
+        # Fill every cache slot once so that the first timed decode reads real data.
+        for s in range(slots):
+            pipeline.run_step(w, self.hidden, self.inputs[s][0], self.inputs[s][1], self.q, self.bufs[s])
+        torch.cuda.synchronize()
+        self.nnz = None
+        if w.sparse_frac > 0:                                   # entries the caches really hold
+            rows = w.B * w.Hkv * w.n
+            c = self.bufs[0].cache
+            self.nnz = (int(c.k_rowptr[rows].cpu()), int(c.v_rowptr[rows].cpu()))
+        self.dec_bytes = decode_algorithmic_bytes(w, w.keep_cap, self.nnz)
+        self.qnt_bytes = quantize_algorithmic_bytes(w, self.nnz)
+
+    def step(self, i, ev=None, mid_after_decode=False):
+        """predict -> decode -> quantise.  ev = (start, middle, end) events; the middle one sits
+        after predict or after decode (see the timing note in timed_steps)."""
+        from paper_2508_04257_amd import pipeline
+
+        cur, old = self.bufs[i % self.slots], self.bufs[(i + 1) % self.slots]
+        K, V = self.inputs[i % self.slots]
+        if ev:
+            ev[0].record()
+        pipeline.predict(self.w, self.hidden, cur)
+        if ev and not mid_after_decode:
+            ev[1].record()
+        pipeline.decode(self.q, old)
+        if ev and mid_after_decode:
+            ev[1].record()
+        pipeline.quantize(K, V, cur)
+        if ev:
+            ev[2].record()
+
+    def timed_steps(self, steps, warmup):
+        """Timing note.  A pair of HIP events around ONE launch measures the launch plus what the
+        event packets themselves cost (an empty pair reads ~4 us on this machine), so a kernel is
+        never bracketed on its own here.  Every step carries three events; the middle one alternates
+        between "after predict" and "after decode", and a call's duration is a difference of
+        brackets that hold real work only:
+          decode   = mean[start -> after decode](odd steps) - mean[start -> after predict](even steps)
+                   and mean[after predict -> end](even steps) - mean[after decode -> end](odd steps),
+                   averaged (rocprofv3's kernel trace of the same run lies between the two)
+          quantise = mean[after decode -> end](odd steps)
+          predict  = mean[start -> after predict](even steps)"""
+        import torch
+
+        for i in range(warmup):
+            self.step(i)
+        torch.cuda.synchronize()
+        events = [[HipEvent() for _ in range(3)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(warmup + i, events[i], mid_after_decode=(i % 2 == 1))
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        tagged = [(i % 2 == 1, events[i]) for i in range(steps)]
+        while min(sum(k for k, _ in tagged), sum(not k for k, _ in tagged)) < 3:
+            # too few timed steps for both kinds of bracket: untimed extra steps supply them
+            kind = sum(k for k, _ in tagged) <= sum(not k for k, _ in tagged)
+            ev = [HipEvent() for _ in range(3)]
+            self.step(warmup + len(tagged), ev, mid_after_decode=kind)
+            tagged.append((kind, ev))
+        torch.cuda.synchronize()
+        even = [e for is_odd, e in tagged if not is_odd]
+        odd = [e for is_odd, e in tagged if is_odd]
+        mean = lambda xs: sum(xs) / len(xs)
+        ms_predict = mean([e[0].elapsed_time(e[1]) for e in even])
+        ms_predict_decode = mean([e[0].elapsed_time(e[1]) for e in odd])
+        ms_quant = mean([e[1].elapsed_time(e[2]) for e in odd])
+        ms_decode_quant = mean([e[1].elapsed_time(e[2]) for e in even])
+        front = ms_predict_decode - ms_predict     # the event's own cost falls on the bracket it closes,
+        back = ms_decode_quant - ms_quant          # so the two differences err in opposite directions
+        for b in self.bufs:
+            assert int(b.cache.status.cpu()[0]) == 0, "capacity overflow reported by the library"
+        return {"ms_step": 1e3 * (t1 - t0) / max(steps, 1), "ms_predict": ms_predict, "ms_quant": ms_quant,
+                "ms_decode": 0.5 * (front + back), "ms_decode_estimates": [front, back]}
+
+    def back_to_back(self, reps):
+        """The same decode call back to back over the rotating (cold) caches, one event pair around
+        the whole run: no event sits between kernels."""
+        import torch
+
+        from paper_2508_04257_amd import pipeline
+
+        b0, b1 = HipEvent(), HipEvent()
+        b0.record()
+        for i in range(reps):
+            pipeline.decode(self.q, self.bufs[i % self.slots])
+        b1.record()
+        torch.cuda.synchronize()
+        return b0.elapsed_time(b1) / reps
+
+    def stream_ceiling(self, reps=40):
+        """A pure streaming read of as many bytes as one decode call moves, in the decode kernel's
+        launch shape, over rotating cold buffers: what the memory system alone takes."""
+        import torch
+
+        from paper_2508_04257_amd import binding as kb
+
+        n = (self.dec_bytes + 15) // 16 * 16
+        src = [torch.ones(n, dtype=torch.uint8, device=self.dev) for _ in range(max(self.slots, 4))]
+        sink = torch.zeros(4, dtype=torch.int32, device=self.dev)
+        for s in src:
+            kb.kvs_probe_stream_read(s, sink)
+        torch.cuda.synchronize()
+        e0, e1 = HipEvent(), HipEvent()
+        e0.record()
+        for i in range(reps):
+            kb.kvs_probe_stream_read(src[i % len(src)], sink)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        return {"ms": round(ms, 4), "achieved": round(n / (ms * 1e-3) / 1e9, 2),
+                "frac": round(n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                "note": "kvs_probe_stream_read: the same bytes read once with no arithmetic, 256 workgroups x 8 waves, "
+                        "back to back over rotating cold buffers"}
+
+
+def decode_kernel_name(w, splits):
+    if w.sparse_frac == 0:
+        return ("kvs_decode_attn = decode_mfma_kernel<%d,%d,%d%s>" % (w.bits, w.group, w.Hq // w.Hkv,
+                                                                     ",per-token Keys" if w.key_per_token else "")
+                + ("" if splits == 1 else " (%d workgroups per (sequence, KV head), the last arriver merges)" % splits))
+    return ("kvs_decode_attn = sparse_key_corr_kernel + decode_mfma_kernel<%d,%d,%d,isolated outliers> + "
+            "decode_finish_sparse_kernel" % (w.bits, w.group, w.Hq // w.Hkv))
+
+
+def workload_label(w):
+    return (f"{w.name}: B={w.B} n={w.n} Hq={w.Hq} Hkv={w.Hkv} D={w.D} INT{w.bits} G={w.group} "
+            f"keep=first{w.first_n}+top{w.k_sinks} sparse={w.sparse_frac}")
+
+
+# ------------------------------------------------------------------------------------------------
+# legs beside the headline numbers
+# ------------------------------------------------------------------------------------------------
 def growing_cache_leg(w, kv, q, dec_bytes):
     """The decoding-phase calls on the same shapes: a cache of capacity n holding n - 64 tokens
     (64 of them in the fp16 residual window), decode over it, then 128 appends (one of which
@@ -232,14 +385,14 @@ def eight_bit_leg(w, inputs, bufs, q):
     }
 
 
-def graph_leg(w, hidden, inputs, q, bufs):
+def graph_leg(rig):
     """The same steps replayed from one HIP graph (all slots in sequence per replay): what the
     launch gaps of the eager loop cost."""
     import torch
 
     from paper_2508_04257_amd import pipeline
 
-    graph = pipeline.capture_steps(w, hidden, inputs, q, bufs)
+    graph = pipeline.capture_steps(rig.w, rig.hidden, rig.inputs, rig.q, rig.bufs)
     for _ in range(2):
         graph.replay()
     torch.cuda.synchronize()
@@ -250,13 +403,134 @@ def graph_leg(w, hidden, inputs, q, bufs):
         graph.replay()
     e1.record()
     torch.cuda.synchronize()
-    return {"ms_per_step": round(e0.elapsed_time(e1) / (reps * len(bufs)), 4), "steps_per_replay": len(bufs)}
+    return {"ms_per_step": round(e0.elapsed_time(e1) / (reps * len(rig.bufs)), 4), "steps_per_replay": len(rig.bufs)}
 
 
-def cpu_baseline(w, budget_s: float = 12.0):
+def layers_leg(rig, layers):
+    """The multi-layer form of a workload (Algorithm 1: the sink set is fixed once, at the
+    emergence layer, and every later layer is quantised under it): one kvs_predict_sinks, then
+    `layers` kvs_quantize_kv calls into `layers` distinct caches under that one mask, then one
+    kvs_decode_attn per layer.  The K/V inputs rotate over the rig's slots (layer l reads input
+    l mod slots); every layer has a cache of its own, so the decode stream of all layers together
+    comes from HBM."""
+    import torch
+
+    from paper_2508_04257_amd import binding as kb
+    from paper_2508_04257_amd import pipeline
+
+    w, dev = rig.w, rig.dev
+    desc = rig.bufs[0].desc
+    caches = [kb.alloc_cache(desc, dev) for _ in range(layers)]
+    ws = rig.bufs[0].workspace
+    buf = rig.bufs[0]
+    out = torch.empty((layers, w.B, w.Hq, w.D), dtype=torch.float16, device=dev)
+
+    def run(ev=None):
+        if ev:
+            ev[0].record()
+        pipeline.predict(w, rig.hidden, buf)                       # once: the mask every layer reuses
+        if ev:
+            ev[1].record()
+        for l in range(layers):
+            K, V = rig.inputs[l % rig.slots]
+            kb.kvs_quantize_kv(desc, K, V, buf.keep_mask, caches[l], ws)
+        if ev:
+            ev[2].record()
+        for l in range(layers):
+            kb.kvs_decode_attn(desc, rig.q, caches[l], out[l], None, ws)
+        if ev:
+            ev[3].record()
+
+    run()
+    torch.cuda.synchronize()
+    ev = [HipEvent() for _ in range(4)]
+    run(ev)
+    torch.cuda.synchronize()
+    for c in caches:
+        assert int(c.status.cpu()[0]) == 0, "capacity overflow reported by the library"
+    ms_p, ms_q, ms_d = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]), ev[2].elapsed_time(ev[3])
+    cache_bytes = sum(t.numel() * t.element_size() for c in caches for t in c.tensors.values() if t is not None)
+    return {
+        "layers": layers, "caches_resident_gb": round(cache_bytes / 1e9, 2),
+        "ms_predict_once": round(ms_p, 4),
+        "ms_quantize_total": round(ms_q, 3), "ms_quantize_per_layer": round(ms_q / layers, 4),
+        "quantize_tokens_per_s_per_layer": round(w.B * w.n / (ms_q / layers * 1e-3), 1),
+        "ms_decode_total": round(ms_d, 3), "ms_decode_per_layer": round(ms_d / layers, 4),
+        "decode_gbps": round(rig.dec_bytes / (ms_d / layers * 1e-3) / 1e9, 2),
+        "decode_frac": round(rig.dec_bytes / (ms_d / layers * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "note": "one prediction, its mask reused by every layer's quantise call; a cache per layer, K/V inputs "
+                f"rotating over {rig.slots} copies; one event pair around each phase",
+    }
+
+
+def config_leg(name, steps, warmup, slots, dev):
+    """One of the other workloads, timed like the headline one (same step, same event brackets)."""
+    import gc
+
+    import torch
+
+    from paper_2508_04257_amd import binding as kb
+    from paper_2508_04257_amd import synth
+
+    w = synth.WORKLOADS[name]
+    rig = Rig(w, slots, dev)
+    t = rig.timed_steps(steps, warmup)
+    b2b = rig.back_to_back(max(steps, 20))
+    gbps = rig.dec_bytes / (t["ms_decode"] * 1e-3) / 1e9
+    out = {
+        "workload": workload_label(w),
+        "kernel": decode_kernel_name(w, kb.kvs_decode_splits(rig.bufs[0].desc)),
+        "steps": steps,
+        "ms_decode": round(t["ms_decode"], 4), "decode_gbps": round(gbps, 2), "frac": round(gbps / HBM_PEAK_GBPS, 4),
+        "ms_decode_back_to_back": round(b2b, 4),
+        "frac_back_to_back": round(rig.dec_bytes / (b2b * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "algorithmic_bytes": rig.dec_bytes,
+        "ms_quantize": round(t["ms_quant"], 4),
+        "quantize_tokens_per_s": round(w.B * w.n / (t["ms_quant"] * 1e-3), 1),
+        "quantize_gbps": round(rig.qnt_bytes / (t["ms_quant"] * 1e-3) / 1e9, 2),
+        "ms_predict": round(t["ms_predict"], 4),
+    }
+    if rig.nnz is not None:
+        out["csr_entries"] = {"k": rig.nnz[0], "v": rig.nnz[1]}
+    if w.layers > 1:
+        out["layers%d" % w.layers] = layers_leg(rig, w.layers)
+    del rig
+    gc.collect()
+    torch.cuda.empty_cache()
+    return out
+
+
+# ------------------------------------------------------------------------------------------------
+# the CPU oracle, timed before the GPU is touched
+# ------------------------------------------------------------------------------------------------
+def _cpu_slice(args):
+    """One (sequence, KV head) slice of the workload at full length through the oracle, one
+    thread.  Returns (seconds quantise, seconds decode)."""
+    from threadpoolctl import threadpool_limits
+
+    from oracle import kvsink_oracle as O
+    from paper_2508_04257_amd import synth
+
+    small, idx, q, mask = args
+    with threadpool_limits(limits=1):
+        K, V = synth.make_kv(small.scaled(seed=small.seed + idx))
+        K, V = K.numpy(), V.numpy()
+        t0 = time.perf_counter()
+        cache = O.quantize_kv(K, V, mask, small.bits, small.group, max(small.keep_cap, 1),
+                              key_per_token=small.key_per_token)
+        t1 = time.perf_counter()
+        O.decode_attn(q, cache, Hq=small.Hq)
+        t2 = time.perf_counter()
+    return t1 - t0, t2 - t1
+
+
+def cpu_baseline(w, budget_s: float = 10.0):
     """The oracle as it stands, timed on this host on a bounded sample of the same workload:
-    whole (sequence 0, head h) slices, one at a time, until the budget is used."""
-    import numpy as np
+    whole (sequence, head) slices at full length, first one at a time on one thread, then over
+    all the host cores this process may use (one single-threaded worker process per core)."""
+    import multiprocessing as mp
+
+    import torch
     from threadpoolctl import threadpool_limits
 
     from oracle import kvsink_oracle as O
@@ -265,34 +539,54 @@ def cpu_baseline(w, budget_s: float = 12.0):
     small = w.scaled(B=1, Hq=w.Hq // w.Hkv, Hkv=1)            # one (b, h) slice at the full n
     H = synth.make_hidden(small).numpy()
     q = synth.make_query(small).numpy()
-    done, t_quant, t_dec = 0, 0.0, 0.0
     with threadpool_limits(limits=1):
         _, mask = O.predict_sinks(H, small.channels, small.k_sinks, small.first_n)
-        t_start = time.perf_counter()
-        while time.perf_counter() - t_start < budget_s and done < w.B * w.Hkv:
-            K, V = synth.make_kv(small.scaled(seed=small.seed + done))
-            K, V = K.numpy(), V.numpy()
-            t0 = time.perf_counter()
-            cache = O.quantize_kv(K, V, mask, small.bits, small.group, max(small.keep_cap, 1),
-                                  key_per_token=small.key_per_token)
-            t1 = time.perf_counter()
-            O.decode_attn(q, cache, Hq=small.Hq)
-            t2 = time.perf_counter()
-            t_quant += t1 - t0
-            t_dec += t2 - t1
-            done += 1
+    total = w.B * w.Hkv
+    done, t_quant, t_dec = 0, 0.0, 0.0
+    t_start = time.perf_counter()
+    torch.set_num_threads(1)
+    while time.perf_counter() - t_start < budget_s and done < total:
+        tq, td = _cpu_slice((small, done, q, mask))
+        t_quant += tq
+        t_dec += td
+        done += 1
     slice_bytes = decode_algorithmic_bytes(small, small.keep_cap)
-    return {
+    out = {
         "value": round(done * slice_bytes / t_dec / 1e9, 6),
         "unit": "GB/s",
         "cores": 1,
         "kind": "oracle",
         "sample": f"{done} (sequence, KV head) slices of {w.name} at full length n={w.n} "
-                  f"(of {w.B * w.Hkv}); numpy oracle, single thread",
+                  f"(of {total}); numpy oracle, single thread",
         "quantize_tokens_per_s": round(done * w.n / (w.Hkv * t_quant), 3),   # whole-layer equivalent
         "decode_ms_per_slice": round(1e3 * t_dec / done, 3),
         "quantize_ms_per_slice": round(1e3 * t_quant / done, 3),
     }
+    # All cores: the same slices handed to one worker process per core (forked before this process
+    # has touched the GPU); decode rate = bytes of all slices / (wall time x the decode share of
+    # the workers' busy time).
+    try:
+        cores = min(len(os.sched_getaffinity(0)), 16)
+    except AttributeError:
+        cores = min(os.cpu_count() or 1, 16)
+    if cores > 1:
+        per_slice = (t_quant + t_dec) / done
+        count = int(min(total, max(cores, budget_s * cores / max(per_slice, 1e-3))))
+        with mp.get_context("fork").Pool(cores) as pool:
+            pool.map(_cpu_slice, [(small, 10_000 + i, q, mask) for i in range(cores)])     # start-up, imports
+            t0 = time.perf_counter()
+            times = pool.map(_cpu_slice, [(small, i, q, mask) for i in range(count)], chunksize=1)
+            wall = time.perf_counter() - t0
+        busy_q, busy_d = sum(t[0] for t in times), sum(t[1] for t in times)
+        out["all_cores"] = {
+            "value": round(count * slice_bytes / (wall * busy_d / (busy_q + busy_d)) / 1e9, 6),
+            "unit": "GB/s",
+            "cores": cores,
+            "quantize_tokens_per_s": round(count * w.n / (w.Hkv * wall * busy_q / (busy_q + busy_d)), 3),
+            "sample": f"{count} slices over {cores} single-threaded worker processes, {wall:.1f} s wall "
+                      "(input generation included in the wall time, excluded from the shares)",
+        }
+    return out
 
 
 def main() -> int:
@@ -303,6 +597,8 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg1")
     ap.add_argument("--slots", type=int, default=4, help="rotating copies of inputs and caches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true", help="skip the other workloads (\"configs\" in the JSON line)")
+    ap.add_argument("--config-steps", type=int, default=20, help="timed steps of each other workload")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain copy of known size (256 MiB read + 256 MiB written) a few times "
                          "before the steps: the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE")
@@ -311,12 +607,17 @@ def main() -> int:
         print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         return 2
 
+    from paper_2508_04257_amd import synth
+
+    w = synth.WORKLOADS[args.workload]
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w)                        # before anything touches the GPU (it forks workers)
+
     import torch
 
     from paper_2508_04257_amd import binding as kb
-    from paper_2508_04257_amd import pipeline, synth
 
-    w = synth.WORKLOADS[args.workload]
     dev = "cuda:0"
     torch.cuda.set_device(0)
     slots = max(2, args.slots)
@@ -329,93 +630,14 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    hidden = synth.make_hidden(w, dev)
-    q = synth.make_query(w, dev)
-    inputs = [synth.make_kv(w, dev, layer=s) for s in range(slots)]
-    bufs = [pipeline.alloc_step(w, dev) for _ in range(slots)]
-    # Fill every cache slot once so that the first timed decode reads real data.
-    for s in range(slots):
-        pipeline.run_step(w, hidden, inputs[s][0], inputs[s][1], q, bufs[s])
-    torch.cuda.synchronize()
-
-    def step(i, ev=None, mid_after_decode=False):
-        """predict -> decode -> quantise.  ev = (start, middle, end) events; the middle one sits
-        after predict or after decode (see the timing note below)."""
-        cur, old = bufs[i % slots], bufs[(i + 1) % slots]
-        K, V = inputs[i % slots]
-        if ev:
-            ev[0].record()
-        pipeline.predict(w, hidden, cur)
-        if ev and not mid_after_decode:
-            ev[1].record()
-        pipeline.decode(q, old)
-        if ev and mid_after_decode:
-            ev[1].record()
-        pipeline.quantize(K, V, cur)
-        if ev:
-            ev[2].record()
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-
-    # Timing note.  A pair of HIP events around ONE launch measures the launch plus what the
-    # event packets themselves cost (an empty pair reads ~4 us on this machine), so a kernel is
-    # never bracketed on its own here.  Every step carries three events; the middle one alternates
-    # between "after predict" and "after decode", and a call's duration is a difference of
-    # brackets that hold real work only:
-    #   decode   = mean[start -> after decode](odd steps) - mean[start -> after predict](even steps)
-    #            and mean[after predict -> end](even steps) - mean[after decode -> end](odd steps),
-    #            averaged (rocprofv3's kernel trace of the same run lies between the two)
-    #   quantise = mean[after decode -> end](odd steps)
-    #   predict  = mean[start -> after predict](even steps)
-    steps = args.steps
-    events = [[HipEvent() for _ in range(3)] for _ in range(steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        step(args.warmup + i, events[i], mid_after_decode=(i % 2 == 1))
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    tagged = [(i % 2 == 1, events[i]) for i in range(steps)]
-    while min(sum(k for k, _ in tagged), sum(not k for k, _ in tagged)) < 3:
-        # too few timed steps for both kinds of bracket: untimed extra steps supply them
-        kind = sum(k for k, _ in tagged) <= sum(not k for k, _ in tagged)
-        ev = [HipEvent() for _ in range(3)]
-        step(args.warmup + len(tagged), ev, mid_after_decode=kind)
-        tagged.append((kind, ev))
-    torch.cuda.synchronize()
-
-    even = [e for is_odd, e in tagged if not is_odd]
-    odd = [e for is_odd, e in tagged if is_odd]
-    mean = lambda xs: sum(xs) / len(xs)
-    ms_step = 1e3 * (t1 - t0) / max(steps, 1)
-    ms_predict = mean([e[0].elapsed_time(e[1]) for e in even])
-    ms_predict_decode = mean([e[0].elapsed_time(e[1]) for e in odd])
-    ms_quant = mean([e[1].elapsed_time(e[2]) for e in odd])
-    ms_decode_quant = mean([e[1].elapsed_time(e[2]) for e in even])
-    ms_decode_front = ms_predict_decode - ms_predict  # the event's own cost falls on the bracket it closes,
-    ms_decode_back = ms_decode_quant - ms_quant       # so the two differences err in opposite directions
-    ms_decode = 0.5 * (ms_decode_front + ms_decode_back)
-
-    # The same decode call back to back over the rotating (cold) caches, one event pair around
-    # the whole run: no event sits between kernels, so this is the kernel's own rate.
-    reps = max(args.steps, 20)
-    b0, b1 = HipEvent(), HipEvent()
-    b0.record()
-    for i in range(reps):
-        pipeline.decode(q, bufs[i % slots])
-    b1.record()
-    torch.cuda.synchronize()
-    ms_decode_b2b = b0.elapsed_time(b1) / reps
-
-    for b in bufs:
-        assert int(b.cache.status.cpu()[0]) == 0, "capacity overflow reported by the library"
-
-    dec_bytes = decode_algorithmic_bytes(w, w.keep_cap)
-    qnt_bytes = quantize_algorithmic_bytes(w)
+    rig = Rig(w, slots, dev)
+    t = rig.timed_steps(args.steps, args.warmup)
+    ms_decode, ms_quant = t["ms_decode"], t["ms_quant"]
+    ms_decode_b2b = rig.back_to_back(max(args.steps, 20))
+    dec_bytes, qnt_bytes = rig.dec_bytes, rig.qnt_bytes
     dec_gbps = dec_bytes / (ms_decode * 1e-3) / 1e9
     qnt_gbps = qnt_bytes / (ms_quant * 1e-3) / 1e9
+    splits = kb.kvs_decode_splits(rig.bufs[0].desc)
 
     result = {
         "metric": "decode-attn effective HBM GB/s",
@@ -424,30 +646,21 @@ def main() -> int:
         "pct_of_hbm_peak": round(100 * dec_gbps / HBM_PEAK_GBPS, 2),
         "quantize_tokens_per_s": round(w.B * w.n / (ms_quant * 1e-3), 1),
         "n_gpus": 1,
-        "steps": steps,
+        "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_step, 4),
-        "ms_predict": round(ms_predict, 4),
+        "ms_per_step": round(t["ms_step"], 4),
+        "ms_predict": round(t["ms_predict"], 4),
         "ms_quantize": round(ms_quant, 4),
         "ms_decode": round(ms_decode, 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f16",
+        "dtype_note": "decode: 2-8 bit codes as fp16 matrix-core operands, fp32 accumulation; quantise: fp32",
         "data": "synthetic",
-        "config": {
-            "workload": f"{w.name}: B={w.B} n={w.n} Hq={w.Hq} Hkv={w.Hkv} D={w.D} INT{w.bits} G={w.group} "
-                        f"keep=first{w.first_n}+top{w.k_sinks} sparse={w.sparse_frac}",
-            "cache_slots": slots,
-            "decode_splits": kb.kvs_decode_splits(bufs[0].desc),
-        },
+        "config": {"workload": workload_label(w), "cache_slots": slots, "decode_splits": splits},
         "roofline": {
-            "kernel": ("kvs_decode_attn = decode_mfma_kernel<%d,%d,%d%s>" % (w.bits, w.group, w.Hq // w.Hkv,
-                                                                            ",per-token Keys" if w.key_per_token else "")
-                       + ("" if kb.kvs_decode_splits(bufs[0].desc) == 1 else " + decode_combine_kernel"))
-                      if w.sparse_frac == 0 else
-                      ("kvs_decode_attn = sparse_key_corr_kernel + decode_mfma_kernel<%d,%d,%d,isolated outliers> + "
-                       "decode_finish_sparse_kernel" % (w.bits, w.group, w.Hq // w.Hkv)),
+            "kernel": decode_kernel_name(w, splits),
             "bound": "hbm",
             "achieved": round(dec_gbps, 2),
             "peak": HBM_PEAK_GBPS,
@@ -456,13 +669,14 @@ def main() -> int:
             "traffic": measured_decode_traffic(w.name),
             "algorithmic_bytes": dec_bytes,
             "ms_kernel": round(ms_decode, 4),
-            "ms_kernel_estimates": [round(ms_decode_front, 4), round(ms_decode_back, 4)],
+            "ms_kernel_estimates": [round(x, 4) for x in t["ms_decode_estimates"]],
             "timing": "HIP events on the launch stream, never around the kernel alone: mean of "
                       "([predict+decode] - [predict]) and ([decode+quantise] - [quantise]), brackets of alternate steps",
             "back_to_back": {"ms": round(ms_decode_b2b, 4),
                              "achieved": round(dec_bytes / (ms_decode_b2b * 1e-3) / 1e9, 2),
                              "frac": round(dec_bytes / (ms_decode_b2b * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                              "note": "same call repeated over the rotating cold caches, no events between launches"},
+            "stream_ceiling": rig.stream_ceiling(),
         },
         "roofline_quantize": {
             "kernel": ("kvs_quantize_kv = keep_index_fast_kernel + quantize_k%s_fast_kernel + quantize_v_fast_kernel"
@@ -478,18 +692,27 @@ def main() -> int:
             "algorithmic_bytes": qnt_bytes,
         },
     }
-    result["graph_replay"] = graph_leg(w, hidden, inputs, q, bufs)
+    result["graph_replay"] = graph_leg(rig)
     if w.sparse_frac == 0:
-        result["growing_cache"] = growing_cache_leg(w, inputs[0], q, dec_bytes)
-        result["static_quantisation"] = static_leg(w, inputs, bufs, qnt_bytes)
-        kpt = per_token_key_leg(w, inputs, bufs, q, dec_bytes, qnt_bytes)
+        result["growing_cache"] = growing_cache_leg(w, rig.inputs[0], rig.q, dec_bytes)
+        result["static_quantisation"] = static_leg(w, rig.inputs, rig.bufs, qnt_bytes)
+        kpt = per_token_key_leg(w, rig.inputs, rig.bufs, rig.q, dec_bytes, qnt_bytes)
         if kpt is not None:
             result["per_token_keys"] = kpt
-        int8 = eight_bit_leg(w, inputs, bufs, q)
+        int8 = eight_bit_leg(w, rig.inputs, rig.bufs, rig.q)
         if int8 is not None:
             result["int8"] = int8
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w)
+    elif w.layers > 1:
+        result["layers%d" % w.layers] = layers_leg(rig, w.layers)
+    if not args.no_configs:
+        import gc
+        del rig
+        gc.collect()
+        torch.cuda.empty_cache()
+        result["configs"] = {name: config_leg(name, args.config_steps, 3, slots, dev)
+                             for name in OTHER_CONFIGS if name != w.name}
+    if cpu is not None:
+        result["cpu_baseline"] = cpu
     print(json.dumps(result))
     return 0
 

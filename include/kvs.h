@@ -294,6 +294,15 @@ kvs_status kvs_quantize_kv_static(const kvs_desc* desc, const void* K, const voi
 kvs_status kvs_quant_error(const kvs_desc* desc, const void* K, const void* V, const kvs_cache* cache,
                            const uint8_t* sink_mask, void* report, void* stream);
 
+/*
+ * Diagnostic, not part of the method: reads `bytes` (a multiple of 16 is read; src 16-byte aligned)
+ * of device memory once, in the launch shape of the decode kernels (256 workgroups of 8 waves,
+ * 16 KB of read-once loads in flight per wave) and with no arithmetic.  Its duration is what the
+ * memory system alone needs for that many bytes - the ceiling the benchmark prints beside the
+ * decode kernel's time.  sink: one device word (written practically never).
+ */
+kvs_status kvs_probe_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

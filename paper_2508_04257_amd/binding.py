@@ -102,6 +102,8 @@ def lib() -> C.CDLL:
         L.kvs_decode_attn.restype = C.c_int
         L.kvs_decode_attn.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.POINTER(KvsCache), C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p]
+        L.kvs_probe_stream_read.restype = C.c_int
+        L.kvs_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.kvs_decode_attn_noalloc.restype = C.c_int
         L.kvs_decode_attn_noalloc.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.POINTER(KvsCache), C.c_void_p,
                                               C.c_void_p, C.c_void_p]
@@ -304,6 +306,15 @@ def kvs_decode_attn_n(desc: KvsDesc, q: torch.Tensor, cache: CacheBuffers, n_tok
                                  _ptr(lse), workspace.data_ptr(), _stream_handle())
     if st != KVS_OK:
         raise KvsError("kvs_decode_attn_n", st)
+
+
+def kvs_probe_stream_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    """Diagnostic pure streaming read of `src` (see kvs.h)."""
+    if not (src.is_cuda and src.is_contiguous() and sink.is_cuda and sink.numel() * sink.element_size() >= 4):
+        raise ValueError("kvs_probe_stream_read: device tensors expected")
+    st = lib().kvs_probe_stream_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_probe_stream_read", st)
 
 
 # ---- static quantisation -------------------------------------------------------------------------

@@ -25,6 +25,7 @@ SOURCES = {
     "sparse.hip": [],
     "decode.hip": [],
     "error_report.hip": ["-ffp-contract=off"],
+    "probe.hip": [],
     "decode_sparse.hip": [],
     "decode_mfma.hip": [],
     "decode_mfma_b2.hip": [],
