@@ -544,7 +544,7 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
     wave_lds_sync();
   };
 
-  auto value_chunk = [&](ValueRegs& s, int refill, int cur) {
+  auto value_chunk = [&](ValueRegs& s, int refill, int cur, bool settle) {
     // ---- (3) online softmax, lane = tokens (lane, lane + 64); weights x Value scale to LDS -----
     float alpha[R];
     {
@@ -659,6 +659,35 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
       load_value_half(s, refill, hf);
       __builtin_amdgcn_sched_barrier(0);
     }
+    // ---- (5) every few chunks: take what the accumulators hold for offsets and zero points out ----
+    // The accumulators carry sum_t w_t (offset + code) and z_run carries sum_t w_t (offset + zero):
+    // two sums up to 2^10 times larger than their difference, the output.  Left to grow over a whole
+    // token range their fp32 roundings reach a few 1e-5 of the Value scale, which a long sequence
+    // with flat attention (small outputs) sees; subtracting the running zero-point sums every
+    // fourth chunk keeps both sums short.
+    if (settle) {
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        float sub = 0.0f;                              // for this lane's column and channel group
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+          for (int g = 0; g < NGC; ++g) {
+            if (hf == 0) z_run[r][g] = uniform(kvs::wave_sum(z_run[r][g]));   // the lanes' partial sums, once
+            bool mine;
+            if (G == 128) mine = col == r && g == 0;
+            else if (G == 64) mine = col == r && g == hf;
+            else mine = grp < 2 ? (col == r && g == 2 * hf) : (col == 2 * R + r && g == 2 * hf + 1);
+            sub = mine ? z_run[r][g] : sub;
+          }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[hf][r] -= sub;
+      }
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int g = 0; g < NGC; ++g) z_run[r][g] = 0.0f;
+    }
     wave_lds_sync();                                   // tables are rewritten by the next chunk
   };
 
@@ -666,9 +695,10 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
   if (wave < nchunks) {
     int nxt = take_chunk();
     int cur = wave;
+    int done = 0;
     while (true) {                                     // the registers hold chunk cur and are filled
       score_chunk(keys, nxt);                          // again, piece by piece, for chunk nxt
-      value_chunk(vals, nxt, cur);
+      value_chunk(vals, nxt, cur, (++done & 3) == 0);
       if (nxt >= nchunks) break;
       cur = nxt;
       nxt = take_chunk();
