@@ -188,6 +188,31 @@ kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const void* V,
                            void* stream);
 
 /*
+ * The prefill loop of Algorithm 1 without the model: L layers' K and V quantised in the order the
+ * algorithm runs them, with the sink set filled once, after the emergence layer l_E (Section 4.3,
+ * item (2)).  The set is empty while layers 1 .. l_E run, so those layers are quantised under the
+ * first-N mask alone; layers l_E + 1 .. L under first-N united with the top-k tokens of
+ * |hidden[b, i, c]| - exactly kvs_quantize_kv(K[l], V[l], mask of the layer's phase, caches[l])
+ * for every layer, and kvs_predict_sinks for the masks, enqueued as one sequence on `stream`.
+ *   n_layers L >= 1;  emergence_layer l_E in [0, L] (0: the set is known before layer 1; L: no
+ *   cache sees it);  k + first_n <= desc->keep_cap.
+ *   K, V        HOST arrays of L device pointers, fp16 [B, Hkv, n, 128] each (layer 1 first)
+ *   hidden      fp16 [B, n, d], the hidden state after layer l_E;  channels HOST, as in kvs_predict_sinks
+ *   sink_idx    int32 [B, k] (may be NULL when k == 0);  early_mask, keep_mask uint8 [B, n]: the
+ *               masks of the two phases, both written (early_mask only when l_E > 0)
+ *   caches      HOST array of L kvs_cache structs (device buffers sized by kvs_cache_bytes(desc))
+ *   workspace   as for kvs_quantize_kv, shared by the layers;  predict_workspace as for
+ *               kvs_predict_sinks (may be NULL)
+ * Every argument of every layer is checked before anything is launched.
+ */
+kvs_status kvs_prefill_layers(const kvs_desc* desc, int32_t n_layers, int32_t emergence_layer,
+                              const void* const* K, const void* const* V, const void* hidden, int32_t d,
+                              const int32_t* channels, int32_t n_channels, int32_t k, int32_t first_n,
+                              int32_t* sink_idx, uint8_t* early_mask, uint8_t* keep_mask,
+                              const kvs_cache* caches, void* workspace, void* predict_workspace,
+                              void* stream);
+
+/*
  * Decode attention of one query per (sequence, query head) over the whole cache:
  *   K'[t], V'[t] = the fp16 keep row if token t is kept, else the dequantised row with isolated
  *   outliers replaced by their fp16 value;  s_t = q . K'[t] / sqrt(128);  p = softmax(s);

@@ -51,6 +51,8 @@ Readings taken where the paper is silent (every one is restated in the design no
   R16 error report (the structure of Table 1): squared error of every cache entry of a non-kept
       token, summed separately over quantisation groups that contain a flagged (sink) token and
       groups that do not (see ``quant_error``).
+  R18 Algorithm 1's loop order (``prefill_layers``): layers up to and including the emergence
+      layer are quantised before the sink set is filled, i.e. without predicted sinks.
   R17 bit widths 2, 3, 4 and 8 (8: four codes per word, 32 words per 128 codes).  So that the
       zero point always fits its int16, the scale is never taken smaller than |min| / 32766.
       For fp16 data and b <= 4 that bound cannot bind (max - min is at least |min| / 2048);
@@ -711,6 +713,50 @@ def quant_error(K: np.ndarray, V: np.ndarray, cache: Cache, sink_mask: np.ndarra
                     cnt[c] += int(rows.sum()) * D
         out[name] = (sse[0], cnt[0], sse[1], cnt[1])
     return out
+
+
+# ----------------------------------------------------------------------------------------
+# The prefill loop of Algorithm 1, the part that needs no model: the order in which the layers'
+# K, V are quantised and the sink set is filled.
+#   S_sink starts empty; layer l = 1 .. L quantises K^l, V^l leaving out the tokens in S_sink as it
+#   stands when the layer runs; after layer l_E the set becomes the top-k tokens of |H^{l_E}[:, c]|.
+# So layers 1 .. l_E are quantised without any predicted sink (only the first-N tokens of the
+# PFN policy, when N > 0, are kept there), layers l_E + 1 .. L with the predicted set.
+# ----------------------------------------------------------------------------------------
+def prefill_layers(Ks, Vs, hidden_at_emergence: np.ndarray, emergence_layer: int, channels, k: int,
+                   first_n: int, bits: int, group: int, keep_cap: int, sparse_frac: float = 0.0,
+                   sparse_cap: Optional[int] = None, key_per_token: bool = False):
+    """Ks, Vs: lists of L tensors fp16 [B, Hkv, n, D] (layer 1 first); hidden_at_emergence fp16
+    [B, n, d] = H^{l_E}; emergence_layer = l_E in [0, L] (0: the set is known before layer 1).
+    Returns (caches [L], sink_idx int32 [B, k], early_mask uint8 [B, n], keep_mask uint8 [B, n])."""
+    L = len(Ks)
+    assert len(Vs) == L and 0 <= emergence_layer <= L
+    B, _, n, _ = np.asarray(Ks[0]).shape
+    sink = np.zeros((B, n), bool)                      # S_sink = {} (per sequence)
+    first = np.zeros((B, n), bool)
+    first[:, :first_n] = True
+    sink_idx = None
+    early_mask = first.astype(np.uint8)
+    keep_mask = None
+
+    def fill():                                        # the "if l = l_E" branch
+        idx, _ = predict_sinks(hidden_at_emergence, channels, k, 0)
+        s = np.zeros((B, n), bool)
+        for b in range(B):
+            s[b, idx[b]] = True
+        return idx, s
+
+    if emergence_layer == 0:
+        sink_idx, sink = fill()
+    caches = []
+    for l in range(1, L + 1):
+        mask = (sink | first).astype(np.uint8)         # token not in S_sink (nor among the first N) -> quantised
+        caches.append(quantize_kv(Ks[l - 1], Vs[l - 1], mask, bits, group, keep_cap, sparse_frac=sparse_frac,
+                                  sparse_cap=sparse_cap, key_per_token=key_per_token))
+        if l == emergence_layer:
+            sink_idx, sink = fill()
+    keep_mask = (sink | first).astype(np.uint8)
+    return caches, sink_idx, early_mask, keep_mask
 
 
 # ----------------------------------------------------------------------------------------

@@ -102,6 +102,11 @@ def lib() -> C.CDLL:
         L.kvs_decode_attn.restype = C.c_int
         L.kvs_decode_attn.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.POINTER(KvsCache), C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p]
+        L.kvs_prefill_layers.restype = C.c_int
+        L.kvs_prefill_layers.argtypes = [C.POINTER(KvsDesc), C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
+                                         C.POINTER(C.c_void_p), C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32,
+                                         C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(KvsCache),
+                                         C.c_void_p, C.c_void_p, C.c_void_p]
         L.kvs_probe_stream_read.restype = C.c_int
         L.kvs_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.kvs_decode_attn_noalloc.restype = C.c_int
@@ -237,6 +242,42 @@ def kvs_quantize_kv(desc: KvsDesc, K: torch.Tensor, V: torch.Tensor, keep_mask: 
                                C.byref(cache.struct), _ptr(workspace), _stream_handle())
     if st != KVS_OK:
         raise KvsError("kvs_quantize_kv", st)
+
+
+def kvs_prefill_layers(desc: KvsDesc, emergence_layer: int, Ks: Sequence[torch.Tensor], Vs: Sequence[torch.Tensor],
+                       hidden: torch.Tensor, channels: Sequence[int], k: int, first_n: int,
+                       sink_idx: Optional[torch.Tensor], early_mask: torch.Tensor, keep_mask: torch.Tensor,
+                       caches: Sequence[CacheBuffers], workspace: Optional[torch.Tensor],
+                       predict_workspace: Optional[torch.Tensor] = None) -> None:
+    """Algorithm 1's loop order over len(Ks) layers in one submission (see kvs.h)."""
+    L = len(Ks)
+    if len(Vs) != L or len(caches) != L:
+        raise ValueError("one K, one V and one cache per layer")
+    shape = (desc.B, desc.Hkv, desc.n, desc.D)
+    for l in range(L):
+        _check_tensor(f"K[{l}]", Ks[l], shape, torch.float16)
+        _check_tensor(f"V[{l}]", Vs[l], shape, torch.float16)
+        _check_cache(desc, caches[l])
+    B, n, d = hidden.shape
+    _check_tensor("hidden", hidden, (desc.B, desc.n, d), torch.float16)
+    _check_tensor("early_mask", early_mask, (desc.B, desc.n), torch.uint8)
+    _check_tensor("keep_mask", keep_mask, (desc.B, desc.n), torch.uint8)
+    if k > 0:
+        _check_tensor("sink_idx", sink_idx, (desc.B, k), torch.int32)
+    if desc.sparse_frac > 0 and (workspace is None or workspace.numel() * workspace.element_size() < kvs_workspace_bytes(desc)):
+        raise ValueError("workspace too small")
+    if predict_workspace is not None and (predict_workspace.numel() * predict_workspace.element_size()
+                                          < kvs_predict_workspace_bytes(desc.B, desc.n, k)):
+        raise ValueError("predict workspace too small")
+    kp = (C.c_void_p * L)(*[t.data_ptr() for t in Ks])
+    vp = (C.c_void_p * L)(*[t.data_ptr() for t in Vs])
+    structs = (KvsCache * L)(*[c.struct for c in caches])
+    ch = (C.c_int32 * len(channels))(*channels)
+    st = lib().kvs_prefill_layers(C.byref(desc), L, emergence_layer, kp, vp, hidden.data_ptr(), d, ch, len(channels), k,
+                                  first_n, _ptr(sink_idx), early_mask.data_ptr(), keep_mask.data_ptr(), structs,
+                                  _ptr(workspace), _ptr(predict_workspace), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_prefill_layers", st)
 
 
 def kvs_decode_attn(desc: KvsDesc, q: torch.Tensor, cache: CacheBuffers, out: torch.Tensor,

@@ -17,6 +17,8 @@ LIB = os.path.join(PKG, "libkvs.so")
 
 # translation unit -> extra flags.  The quantiser's arithmetic must match a fixed fp32 operation
 # sequence bit for bit: no fused multiply-add, IEEE division.
+DECODE_FLAGS = []
+
 SOURCES = {
     "kvs_api.hip": [],
     "predict.hip": [],
@@ -26,16 +28,17 @@ SOURCES = {
     "decode.hip": [],
     "error_report.hip": ["-ffp-contract=off"],
     "probe.hip": [],
+    "prefill.hip": [],
     "decode_sparse.hip": [],
     "decode_mfma.hip": [],
-    "decode_mfma_b2.hip": [],
-    "decode_mfma_b3.hip": [],
-    "decode_mfma_b4.hip": [],
-    "decode_mfma_b8.hip": [],
-    "decode_mfma_kpt_b2.hip": [],
-    "decode_mfma_kpt_b3.hip": [],
-    "decode_mfma_kpt_b4.hip": [],
-    "decode_mfma_kpt_b8.hip": [],
+    "decode_mfma_b2.hip": DECODE_FLAGS,
+    "decode_mfma_b3.hip": DECODE_FLAGS,
+    "decode_mfma_b4.hip": DECODE_FLAGS,
+    "decode_mfma_b8.hip": DECODE_FLAGS,
+    "decode_mfma_kpt_b2.hip": DECODE_FLAGS,
+    "decode_mfma_kpt_b3.hip": DECODE_FLAGS,
+    "decode_mfma_kpt_b4.hip": DECODE_FLAGS,
+    "decode_mfma_kpt_b8.hip": DECODE_FLAGS,
 }
 
 COMMON = [

@@ -44,6 +44,12 @@ struct DecodeGeometry {
 DecodeGeometry decode_geometry(const kvs_desc* d);
 DecodeGeometry decode_geometry(const kvs_desc* d, int n_used);
 int decode_max_splits(const kvs_desc* d);
+// Host-side argument checks of the two prefill calls (what they refuse before launching anything).
+kvs_status check_predict_call(const void* hidden, int32_t B, int32_t n, int32_t d, const int32_t* channels,
+                              int32_t n_channels, int32_t k, int32_t first_n, const int32_t* sink_idx,
+                              const uint8_t* keep_mask);
+kvs_status check_quantize_call(const kvs_desc* desc, const void* K, const void* V, const uint8_t* keep_mask,
+                               const kvs_cache* out, const void* workspace);
 // Matrix-core decode kernel (decode_mfma.hip).
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
                         void* out, float* lse, float* ws, int* arrive, float* cs, int n_used, const float* extra, hipStream_t s);

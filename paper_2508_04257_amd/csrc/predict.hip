@@ -179,10 +179,10 @@ extern "C" size_t kvs_predict_workspace_bytes(int32_t B, int32_t n, int32_t k) {
   return ((static_cast<size_t>(B) * slices * k * sizeof(uint32_t)) + 15) & ~static_cast<size_t>(15);
 }
 
-extern "C" kvs_status kvs_predict_sinks(const void* hidden, int32_t B, int32_t n, int32_t d,
-                                         const int32_t* channels, int32_t n_channels, int32_t k,
-                                         int32_t first_n, int32_t* sink_idx, uint8_t* keep_mask,
-                                         void* workspace, void* stream) {
+// Everything kvs_predict_sinks can refuse on the host, without launching anything.
+kvs_status kvs::check_predict_call(const void* hidden, int32_t B, int32_t n, int32_t d, const int32_t* channels,
+                                   int32_t n_channels, int32_t k, int32_t first_n, const int32_t* sink_idx,
+                                   const uint8_t* keep_mask) {
   if (!hidden || !channels || !keep_mask) return KVS_ERR_INVALID;
   if (B < 1 || n < 1 || d < 1 || n_channels < 1 || k < 0 || first_n < 0) return KVS_ERR_INVALID;
   if (k > n || first_n > n) return KVS_ERR_INVALID;
@@ -191,6 +191,15 @@ extern "C" kvs_status kvs_predict_sinks(const void* hidden, int32_t B, int32_t n
     if (channels[j] < 0 || channels[j] >= d) return KVS_ERR_INVALID;
   if (n_channels > kMaxChannels || k > KVS_MAX_TOPK || n > KVS_MAX_PREDICT_TOKENS)
     return KVS_ERR_UNSUPPORTED;
+  return KVS_OK;
+}
+
+extern "C" kvs_status kvs_predict_sinks(const void* hidden, int32_t B, int32_t n, int32_t d,
+                                         const int32_t* channels, int32_t n_channels, int32_t k,
+                                         int32_t first_n, int32_t* sink_idx, uint8_t* keep_mask,
+                                         void* workspace, void* stream) {
+  const kvs_status st = kvs::check_predict_call(hidden, B, n, d, channels, n_channels, k, first_n, sink_idx, keep_mask);
+  if (st != KVS_OK) return st;
 
   ChannelList list{};
   list.count = n_channels;

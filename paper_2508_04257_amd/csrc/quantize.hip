@@ -115,9 +115,9 @@ static kvs_status check_quantize_args(const kvs_desc* desc, const kvs_cache* out
   return KVS_OK;
 }
 
-extern "C" kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const void* V,
-                                       const uint8_t* keep_mask, const kvs_cache* out,
-                                       void* workspace, void* stream) {
+// Everything kvs_quantize_kv can refuse on the host, without launching anything.
+kvs_status kvs::check_quantize_call(const kvs_desc* desc, const void* K, const void* V, const uint8_t* keep_mask,
+                                    const kvs_cache* out, const void* workspace) {
   const kvs_status st = check_quantize_args(desc, out);
   if (st != KVS_OK) return st;
   if (!K || !V || !keep_mask) return KVS_ERR_INVALID;
@@ -125,6 +125,14 @@ extern "C" kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const
   if (sparse && (!workspace || !out->k_rowptr || !out->k_col || !out->k_val || !out->v_rowptr ||
                  !out->v_col || !out->v_val))
     return KVS_ERR_INVALID;
+  return KVS_OK;
+}
+
+extern "C" kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const void* V,
+                                       const uint8_t* keep_mask, const kvs_cache* out,
+                                       void* workspace, void* stream) {
+  const kvs_status st = kvs::check_quantize_call(desc, K, V, keep_mask, out, workspace);
+  if (st != KVS_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(stream);
   quantize_span(desc, kvs::whole_span(desc), true, K, V, keep_mask, keep_mask, desc->n, out, workspace, s);
   return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;

@@ -151,6 +151,30 @@ def test_static_quantisation_calls_check_their_arguments_on_the_host():
     assert kb.kvs_calibration_bytes(bad) == 0
 
 
+def test_prefill_layers_checks_every_argument_before_launching():
+    d = kb.make_desc(B=2, n=1024, Hq=32, Hkv=32, bits=4, group=128, keep_cap=4)
+    L = kb.lib()
+    full = kb.KvsCache(**{name: 16 for name in kb.CACHE_FIELD_NAMES})
+    caches = (kb.KvsCache * 3)(full, full, full)
+    ptrs = (C.c_void_p * 3)(16, 16, 16)
+    ch = (C.c_int32 * 1)(7)
+
+    def call(n_layers=3, l_e=1, K=ptrs, V=ptrs, hidden=16, dd=64, k=3, first_n=1, idx=16, early=16, keep=16, cs=caches):
+        return L.kvs_prefill_layers(C.byref(d), n_layers, l_e, K, V, hidden, dd, ch, 1, k, first_n, idx, early, keep, cs,
+                                    None, None, None)
+
+    assert call(n_layers=0) == kb.KVS_ERR_INVALID
+    assert call(l_e=4) == kb.KVS_ERR_INVALID and call(l_e=-1) == kb.KVS_ERR_INVALID
+    assert call(k=4, first_n=1) == kb.KVS_ERR_INVALID                 # 5 kept rows do not fit keep_cap = 4
+    assert call(hidden=None) == kb.KVS_ERR_INVALID and call(keep=None) == kb.KVS_ERR_INVALID
+    assert call(early=None) == kb.KVS_ERR_INVALID and call(idx=None) == kb.KVS_ERR_INVALID
+    assert call(dd=5) == kb.KVS_ERR_INVALID                             # channel 7 outside the hidden size
+    holes = (C.c_void_p * 3)(16, None, 16)
+    assert call(K=holes) == kb.KVS_ERR_INVALID and call(V=holes) == kb.KVS_ERR_INVALID
+    broken = (kb.KvsCache * 3)(full, full, kb.KvsCache())               # the third layer's cache has no buffers
+    assert call(cs=broken) == kb.KVS_ERR_INVALID
+
+
 def test_header_is_plain_c(tmp_path):
     """The boundary is a C ABI: the header must compile as C99 with a C compiler, and a C program
     must link against the library's host-side calls."""
