@@ -501,6 +501,70 @@ def config_leg(name, steps, warmup, slots, dev):
 
 
 # ------------------------------------------------------------------------------------------------
+# --sweep: every supported shape
+# ------------------------------------------------------------------------------------------------
+def sweep_shape(bits, group, rep, key_per_token, pairs, n, dev="cuda:0", slots=3):
+    """(decode seconds, quantise seconds, decode bytes, quantise bytes, workgroups per (sequence,
+    KV head)) of one shape: calls back to back over rotating caches."""
+    import gc
+
+    import torch
+
+    from paper_2508_04257_amd import binding as kb
+    from paper_2508_04257_amd import pipeline, synth
+
+    Hkv = 32 // rep
+    w = synth.Workload("sweep", B=pairs // Hkv, n=n, Hq=32, Hkv=Hkv, bits=bits, group=group, k_sinks=5,
+                       key_per_token=key_per_token)
+    rig = Rig(w, slots, dev)
+
+    def timed(fn, iters):
+        for i in range(6):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = HipEvent(), HipEvent()
+        e0.record()
+        for i in range(iters):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e-3
+
+    t_dec = timed(lambda i: pipeline.decode(rig.q, rig.bufs[i % slots]), 60)
+    t_qnt = timed(lambda i: pipeline.quantize(rig.inputs[i % slots][0], rig.inputs[i % slots][1], rig.bufs[i % slots]), 30)
+    out = (t_dec, t_qnt, rig.dec_bytes, rig.qnt_bytes, kb.kvs_decode_splits(rig.bufs[0].desc))
+    del rig
+    gc.collect()
+    torch.cuda.empty_cache()
+    return out
+
+
+def sweep(pairs, n):
+    """Two markdown tables (per-channel and per-token Keys): bit width x group size x query heads
+    per KV head, for a cache of `pairs` (sequence, KV head) pairs of `n` tokens, i.e. the same cache
+    bytes in every row of one bit width.  The percentage is algorithmic bytes / time against
+    8 TB/s, so a shape whose heads take several launches - each streams the codes again - shows a
+    low figure by construction."""
+    peak = HBM_PEAK_GBPS * 1e9
+    for kpt in (False, True):
+        print(("Per-token Keys" if kpt else "Per-channel Keys") +
+              f", {pairs} (sequence, KV head) pairs x {n} tokens; decode: time, % of 8 TB/s\n")
+        print("| bits | G | Hq/Hkv = 1 | 2 | 4 | 8 | quantise |")
+        print("|---|---|---|---|---|---|---|")
+        for bits in (2, 3, 4, 8):
+            for group in (32, 64, 128):
+                cells, qs = [], []
+                for rep in (1, 2, 4, 8):
+                    t_dec, t_qnt, b_dec, b_qnt, _ = sweep_shape(bits, group, rep, kpt, pairs, n)
+                    cells.append(f"{t_dec * 1e6:.0f} us, {100 * b_dec / t_dec / peak:.0f} %")
+                    qs.append((t_qnt * 1e6, 100 * b_qnt / t_qnt / peak))
+                print(f"| {bits} | {group} | " + " | ".join(cells) +
+                      f" | {min(t for t, _ in qs):.0f}-{max(t for t, _ in qs):.0f} us, "
+                      f"{min(p for _, p in qs):.0f}-{max(p for _, p in qs):.0f} % |", flush=True)
+        print()
+
+
+# ------------------------------------------------------------------------------------------------
 # the CPU oracle, timed before the GPU is touched
 # ------------------------------------------------------------------------------------------------
 def _cpu_slice(args):
@@ -599,6 +663,11 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the other workloads (\"configs\" in the JSON line)")
     ap.add_argument("--config-steps", type=int, default=20, help="timed steps of each other workload")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the JSON line: decode and quantise timings over the grid of supported shapes "
+                         "(bits x group x heads per KV head x Key scheme) as two markdown tables")
+    ap.add_argument("--sweep-pairs", type=int, default=256, help="--sweep: (sequence, KV head) pairs; a multiple of 32")
+    ap.add_argument("--sweep-n", type=int, default=4096, help="--sweep: tokens per sequence; a multiple of 128")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain copy of known size (256 MiB read + 256 MiB written) a few times "
                          "before the steps: the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE")
@@ -608,6 +677,12 @@ def main() -> int:
         return 2
 
     from paper_2508_04257_amd import synth
+
+    if args.sweep:
+        import torch
+        torch.cuda.set_device(0)
+        sweep(args.sweep_pairs, args.sweep_n)
+        return 0
 
     w = synth.WORKLOADS[args.workload]
     cpu = None

@@ -261,6 +261,14 @@ kvs_status kvs_decode_attn_noalloc(const kvs_desc* desc, const void* q, const kv
  * kvs_decode_attn_n: kvs_decode_attn over the first n_tokens in [1, desc->n] tokens: quantised
  *   blocks, kept rows and residual rows in one softmax.
  * workspace: kvs_workspace_bytes(desc) bytes in all three.
+ * State the calls rely on (not checked; a caller that breaks it gets wrong results, never an
+ * access outside the buffers):
+ *   - kvs_quantize_prefix initialises a cache: it zeroes keep_mask out to the capacity and writes
+ *     keep_idx / keep_cnt.  A cache must have had one kvs_quantize_prefix call (n_tokens = 0 is
+ *     allowed, K and V may then be any non-NULL pointers) before its first kvs_append_kv.
+ *   - n_tokens in kvs_append_kv is the number of tokens the cache holds, i.e. the n_tokens of the
+ *     prefix call plus the appends since; n_tokens in kvs_decode_attn_n is that number after the
+ *     last append.  A smaller value still attends to every kept row the cache has recorded.
  */
 kvs_status kvs_quantize_prefix(const kvs_desc* desc, const void* K, const void* V,
                                const uint8_t* keep_mask, int32_t n_tokens, const kvs_cache* out,

@@ -18,9 +18,13 @@ kvs_status validate_desc(const kvs_desc* d) {
   const int rep = d->Hq / d->Hkv;
   if (rep != 1 && rep != 2 && rep != 4 && rep != 8) return KVS_ERR_UNSUPPORTED;
   if (d->key_per_token && d->sparse_frac > 0.0f) return KVS_ERR_UNSUPPORTED;   // per-token Keys: dense caches only
-  // CSR rows and word offsets are 32-bit quantities in places; keep a wide margin.
-  const int64_t rows = static_cast<int64_t>(d->B) * d->Hkv * d->n;
+  // CSR rows and word offsets are 32-bit quantities in places; keep a wide margin.  (Two factors
+  // first: the product of three 31-bit numbers does not fit 64 bits.)
+  const int64_t pairs = static_cast<int64_t>(d->B) * d->Hkv;
+  if (pairs >= (int64_t{1} << 30)) return KVS_ERR_UNSUPPORTED;
+  const int64_t rows = pairs * d->n;
   if (rows >= (int64_t{1} << 30)) return KVS_ERR_UNSUPPORTED;
+  if (static_cast<int64_t>(d->B) * d->Hq >= (int64_t{1} << 30)) return KVS_ERR_UNSUPPORTED;   // query rows likewise
   if (d->sparse_frac > 0.0f) {
     // CSR positions are int32: the whole tensor must be countable even if every entry ties.
     if (d->sparse_cap > (int64_t{1} << 31) - 1 || rows * KVS_HEAD_DIM >= (int64_t{1} << 31)) return KVS_ERR_UNSUPPORTED;

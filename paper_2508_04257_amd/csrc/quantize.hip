@@ -15,10 +15,11 @@ using kvs::Fmt;
 // ---------------------------------------------------------------------------------------------
 constexpr int kIndexThreads = 1024;
 
-// n tokens are indexed; both masks have `stride` bytes per sequence (they may be the same array).
+// n tokens are indexed; both masks have `stride` bytes per sequence.  They may be the same array
+// (a growing cache normalises its own mask in place), hence no __restrict__ on the two.
 __global__ __launch_bounds__(kIndexThreads) void keep_index_kernel(
-    const uint8_t* __restrict__ keep_mask, int n, int stride, int cap, int32_t* __restrict__ keep_idx,
-    int32_t* __restrict__ keep_cnt, uint8_t* __restrict__ mask_copy, int32_t* __restrict__ status) {
+    const uint8_t* keep_mask, int n, int stride, int cap, int32_t* __restrict__ keep_idx,
+    int32_t* __restrict__ keep_cnt, uint8_t* mask_copy, int32_t* __restrict__ status) {
   __shared__ int wave_count[kIndexThreads / KVS_WAVE];
   __shared__ int base_s;
   const int b = blockIdx.x, tid = threadIdx.x;
