@@ -32,11 +32,8 @@ __global__ __launch_bounds__(128) void sparse_key_corr_kernel(
   const size_t bh = (bq / Hq) * Hkv + (bq % Hq) / (Hq / Hkv);  // b * Hkv + h: the rows the head reads
   const int tb = (blockIdx.x % blocks) * (128 * kKeyIlp);     // first token of the block
   const int t0 = tb + threadIdx.x;
-  qf[threadIdx.x] = kvs::half_bits_to_float(q[bq * 128 + threadIdx.x]) * kLog2eRsqrtD;
-  const int groups = (min(n - tb, 128 * kKeyIlp) + group - 1) / group;
-  for (int i = threadIdx.x; i < groups * 128; i += 128)
-    prm_s[i] = k_params[(bh * (n / group) + static_cast<size_t>(tb / group)) * 128 + i];
-  __syncthreads();
+  // The row pointers head the chain of dependent loads: they are requested first, together with
+  // the query and the parameter rows (before the barrier, which would otherwise hold them back).
   int e0[kKeyIlp], e1[kKeyIlp];
 #pragma unroll
   for (int u = 0; u < kKeyIlp; ++u) {
@@ -45,6 +42,20 @@ __global__ __launch_bounds__(128) void sparse_key_corr_kernel(
     e0[u] = max(0, min(k_rowptr[bh * n + t], cap));
     e1[u] = max(0, min(k_rowptr[bh * n + t + 1], cap));
   }
+  // the first entry of every row likewise (most rows hold one or two)
+  int c_first[kKeyIlp];
+  float v_first[kKeyIlp];
+#pragma unroll
+  for (int u = 0; u < kKeyIlp; ++u) {
+    const int e = min(e0[u], max(e1[u], 1) - 1);
+    c_first[u] = k_col[e] & 127;
+    v_first[u] = kvs::half_bits_to_float(k_val[e]);
+  }
+  qf[threadIdx.x] = kvs::half_bits_to_float(q[bq * 128 + threadIdx.x]) * kLog2eRsqrtD;
+  const int groups = (min(n - tb, 128 * kKeyIlp) + group - 1) / group;
+  for (int i = threadIdx.x; i < groups * 128; i += 128)
+    prm_s[i] = k_params[(bh * (n / group) + static_cast<size_t>(tb / group)) * 128 + i];
+  __syncthreads();
   float acc[kKeyIlp];
   int len = 0;
 #pragma unroll
@@ -55,6 +66,7 @@ __global__ __launch_bounds__(128) void sparse_key_corr_kernel(
     uint32_t prm[kKeyIlp];
 #pragma unroll
     for (int u = 0; u < kKeyIlp; ++u) {
+      if (i == 0) { c[u] = c_first[u]; v[u] = v_first[u]; continue; }
       const int e = min(e0[u] + i, max(e1[u], 1) - 1);      // clamped; unused when the row is shorter
       c[u] = k_col[e] & 127;
       v[u] = kvs::half_bits_to_float(k_val[e]);
@@ -141,6 +153,15 @@ __global__ __launch_bounds__(kFinishThreads) void decode_finish_sparse_kernel(
       e0[u] = max(0, min(v_rowptr[row], sparse_cap));
       e1[u] = seg_tile + tg + kStride * u < tiles ? max(0, min(v_rowptr[row + 1], sparse_cap)) : e0[u];
     }
+    // the first entry of every row is requested before the segment is staged (most rows hold one or two)
+    int col_first[kValIlp];
+    float val_first[kValIlp];
+#pragma unroll
+    for (int u = 0; u < kValIlp; ++u) {
+      const int e = min(e0[u], max(e1[u], 1) - 1);
+      col_first[u] = v_col[e] & 127;
+      val_first[u] = kvs::half_bits_to_float(v_val[e]);
+    }
     __syncthreads();
     for (int i = tid; i < seg_tokens; i += kFinishThreads) sc_s[i] = cs[bq * n + seg_tile * 128 + i];
     for (int i = tid; i < seg_tokens * ngc; i += kFinishThreads)
@@ -153,6 +174,7 @@ __global__ __launch_bounds__(kFinishThreads) void decode_finish_sparse_kernel(
       float val[kValIlp];
 #pragma unroll
       for (int u = 0; u < kValIlp; ++u) {
+        if (i == 0) { tok[u] = (tg + kStride * u) * 128 + col_first[u]; val[u] = val_first[u]; continue; }
         const int e = min(e0[u] + i, max(e1[u], 1) - 1);    // clamped; unused when the row is shorter
         tok[u] = (tg + kStride * u) * 128 + (v_col[e] & 127);   // token inside the segment
         val[u] = kvs::half_bits_to_float(v_val[e]);
