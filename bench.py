@@ -228,8 +228,8 @@ def decode_kernel_name(w, splits):
         return ("kvs_decode_attn = decode_mfma_kernel<%d,%d,%d%s>" % (w.bits, w.group, w.Hq // w.Hkv,
                                                                      ",per-token Keys" if w.key_per_token else "")
                 + ("" if splits == 1 else " (%d workgroups per (sequence, KV head), the last arriver merges)" % splits))
-    return ("kvs_decode_attn = sparse_key_corr_kernel + decode_mfma_kernel<%d,%d,%d,isolated outliers> + "
-            "decode_finish_sparse_kernel" % (w.bits, w.group, w.Hq // w.Hkv))
+    return ("kvs_decode_attn = decode_mfma_kernel<%d,%d,%d,isolated outliers>" % (w.bits, w.group, w.Hq // w.Hkv)
+            + ("" if splits == 1 else " (%d workgroups per (sequence, KV head), the last arriver merges)" % splits))
 
 
 def workload_label(w):

@@ -45,7 +45,9 @@
  *            zero padded;  keep_idx int32 [B, keep_cap] (-1 padded);  keep_cnt int32 [B];
  *            keep_mask uint8 [B, n] (copy of the mask the cache was built with).
  *   CSR of isolated outliers (only when sparse_frac > 0), B*Hkv*n rows per tensor:
- *            rowptr int32 [B*Hkv*n + 1], col uint16 [sparse_cap] ascending per row, val fp16.
+ *            rowptr int32 [B*Hkv*n + 1], col uint16 [sparse_cap + 4] ascending per row, val fp16
+ *            [sparse_cap + 4] (the four entries behind the capacity are padding that decode may
+ *            read and never uses; kvs_cache_bytes() counts them).
  *            Keys: row = (b, h, token), col = channel.  Values: row = (b, h, 128-token tile,
  *            channel), col = token inside the tile (the transposition of the Value code tiles).
  *   Residual window (growing caches only): res_k / res_v fp16 [B, Hkv, 128, 128], row r = token
@@ -91,6 +93,7 @@ typedef struct kvs_desc {
                             /* k_params is then [B, Hkv, n, 128/G].  Not with sparse_frac > 0     */
                             /* (KVS_ERR_UNSUPPORTED).                                             */
   int64_t sparse_cap;       /* CSR capacity in entries per tensor when sparse_frac > 0        */
+                            /* (1 .. 2^31 - 257, beyond: KVS_ERR_UNSUPPORTED)                 */
 } kvs_desc;
 
 /* The quantised cache of one layer: device pointers to caller-owned buffers whose byte sizes
@@ -231,9 +234,10 @@ kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const kvs_cache*
  * scratch's head), same result; the scratch is an array of
  * KVS_NOALLOC_SCRATCH_BYTES that the library itself holds on every GPU it runs on (from the first
  * call on that GPU until the process ends).  The call allocates and frees nothing.
- *   - A descriptor with kvs_workspace_bytes(desc) > KVS_NOALLOC_SCRATCH_BYTES is rejected with
- *     KVS_ERR_SCRATCH before anything is launched (the four dense workloads of the benchmark need
- *     less than 1 MiB; a dense-and-sparse cache needs 4 bytes per (sequence, query head, token)).
+ *   - A descriptor whose decode calls need more than KVS_NOALLOC_SCRATCH_BYTES of workspace
+ *     (520 bytes per (sequence, query head) and part of the token range, plus the counters; the
+ *     benchmark's workloads need less than 1 MiB) is rejected with KVS_ERR_SCRATCH before anything
+ *     is launched.
  *   - The GPU is the one current on the calling thread (hipGetDevice); `stream` must belong to it.
  *   - Every call on a GPU shares that GPU's one array: calls that overlap on one GPU (different
  *     streams, or different threads) race on it.  Order them on one stream, or use

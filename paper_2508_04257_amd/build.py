@@ -29,7 +29,6 @@ SOURCES = {
     "error_report.hip": ["-ffp-contract=off"],
     "probe.hip": [],
     "prefill.hip": [],
-    "decode_sparse.hip": [],
     "decode_mfma.hip": [],
     "decode_mfma_b2.hip": DECODE_FLAGS,
     "decode_mfma_b3.hip": DECODE_FLAGS,

@@ -8,8 +8,7 @@
 //       into, then the kept tokens' fp16 rows are folded into the same online softmax,
 //       normalise, store fp16.  Not needed when one workgroup covered the whole sequence.
 //   residual_part_kernel   the fp16 residual rows of a growing cache as one more part.
-// Caches with isolated outliers take the two kernels of decode_sparse.hip around the stream
-// kernel instead of the combine kernel.
+// Caches with isolated outliers go the same way: their corrections are part of the stream kernel.
 #include <atomic>
 
 #include "decode_finish.h"
@@ -156,7 +155,7 @@ static void decode_dense(const kvs_desc* desc, const void* q, const kvs_cache* c
                          void* out, float* lse, float* ws, int* arrive, hipStream_t s) {
   if (n_used > 0) {
     const kvs::DecodeGeometry geo = kvs::decode_geometry(desc, n_used);
-    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, arrive, nullptr, n_used, extra, s);
+    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, arrive, n_used, extra, s);
     return;
   }
   hipLaunchKernelGGL(decode_combine_kernel, dim3(desc->B * desc->Hq), dim3(KVS_WAVE), 0, s,
@@ -173,15 +172,7 @@ extern "C" kvs_status kvs_decode_attn(const kvs_desc* desc, const void* q, const
   hipStream_t s = static_cast<hipStream_t>(stream);
   int* arrive = static_cast<int*>(workspace);
   float* ws = static_cast<float*>(workspace) + kvs::workspace_counter_words(desc);
-  const kvs::DecodeGeometry geo = kvs::decode_geometry(desc);
-  if (desc->sparse_frac > 0.0f) {                    // Key corrections, stream kernel, finish
-    float* cs = ws + kvs::decode_parts_floats(desc, geo);
-    kvs::launch_sparse_key_corr(desc, q, cache, cs, s);
-    kvs::launch_decode_mfma(desc, geo, q, cache, out, lse, ws, arrive, cs, desc->n, nullptr, s);
-    kvs::launch_decode_finish_sparse(desc, geo, q, cache, ws, cs, out, lse, s);
-  } else {
-    decode_dense(desc, q, cache, desc->n, nullptr, out, lse, ws, arrive, s);
-  }
+  decode_dense(desc, q, cache, desc->n, nullptr, out, lse, ws, arrive, s);
   return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
 }
 
@@ -191,7 +182,7 @@ extern "C" kvs_status kvs_decode_attn_noalloc(const kvs_desc* desc, const void* 
                                                void* out, float* lse, void* stream) {
   const kvs_status st = check_decode_args(desc, q, cache, out);
   if (st != KVS_OK) return st;
-  if (kvs_workspace_bytes(desc) > kScratchBytes) return KVS_ERR_SCRATCH;
+  if (kvs::decode_workspace_bytes(desc) > kScratchBytes) return KVS_ERR_SCRATCH;
   void* ws = nullptr;
   const kvs_status sp = scratch_of_current_device(&ws);
   if (sp != KVS_OK) return sp;

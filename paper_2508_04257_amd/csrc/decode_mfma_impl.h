@@ -55,7 +55,8 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 // group) columns spill with 256 (1.3 - 2.3 times the run time); so do a few low-bit variants.
 // The table is by measurement: four waves where that was faster, eight elsewhere (a variant that
 // spills a few dozen bytes can still be faster with eight).
-__host__ __device__ constexpr int waves_for(int bits, int G, int R, bool kpt) {
+__host__ __device__ constexpr int waves_for(int bits, int G, int R, bool kpt, bool sparse = false) {
+  if (sparse && G == 32 && R == 4) return 4;       // the outlier tables of eight waves would not fit the LDS
   if (bits == 8) return R * (128 / G) * (kpt ? 2 : 1) >= 4 ? 4 : 8;
   if (!kpt) return ((bits >= 3 && G == 32 && R == 4) || (G == 64 && R == 8)) ? 4 : 8;   // (64, 8): the tables of 8 waves exceed the LDS
   if (bits >= 3 && G == 128 && R == 8) return 4;
@@ -196,7 +197,11 @@ struct MfmaArgs {
   const uint16_t* keep_k; const uint16_t* keep_v; const int32_t* keep_cnt;
   uint16_t* out; float* lse; float* ws;
   int* arrive;       // one arrival counter per (b, kv head): zero on entry, zero again on exit
-  float* cs;         // dense-and-sparse only: per (b, hq, token) score correction in, final score out
+  // dense-and-sparse only: the CSR arrays of the isolated outliers (rows (b, h, token) for Keys,
+  // (b, h, tile, channel) for Values - the same row numbering) and their capacity in entries
+  const int32_t* k_rowptr; const uint16_t* k_col; const uint16_t* k_val;
+  const int32_t* v_rowptr; const uint16_t* v_col; const uint16_t* v_val;
+  int sparse_cap;
   int n, Hkv, cap;   // n: tokens per (b, h) the buffers are laid out for
   int n_used;        // tokens to attend to (the first n_used; a multiple of 128)
   const float* extra;   // one more softmax state per (b, hq) to merge (a growing cache's residual rows), or null
@@ -206,11 +211,18 @@ struct MfmaArgs {
   int head_off;      // first of them that this launch takes; it takes R
 };
 
-// SPARSE (caches with isolated fp16 outliers): an isolated slot holds code 0.  A kernel that ran
-// before this one left, per token, what replacing those Key slots by their fp16 values adds to the
-// score (a.cs, log2 units); it is added before the softmax, the corrected score is written back in
-// its place, and the workgroup's state always goes to the workspace: the finishing kernel applies
-// the Value-side corrections, which need the final softmax weights.
+// SPARSE (caches with isolated fp16 outliers, Section 5.1): an isolated slot holds code 0, i.e.
+// it dequantises to -scale * zero; replacing it by its fp16 value v adds
+//     q_c (v + scale zero)   to the score of its token         (Keys,   CSR row = token,   column = channel)
+//     w_t (v + scale zero)   to the output channel it sits in  (Values, CSR row = channel of the tile, column = token)
+// Both are done here, per chunk, by the lane that owns the row (lane = tokens lane, lane + 64 in
+// the softmax stage; lane = channels lane, lane + 64 after the Value product): the row pointers
+// travel with the Value parameters, the first four entries of a row are requested at the start
+// of the stage before the one that uses them, longer rows (a few per thousand) are walked on
+// demand.  Key corrections use the chunk's q and scale * zero tables in LDS; Value corrections use
+// the chunk's softmax weights, which replace the scores in LDS once those have been read, and
+// accumulate in two registers per head that follow the accumulators' rescaling.  Every index read
+// from the cache is clamped, so a cache with garbage in its CSR arrays yields garbage, not a fault.
 //
 // KPT (per-token Keys, the other Key scheme of the paper's Section 5.1): a Key row carries one
 // parameter pair per group of G channels, like a Value row.  The scale then depends on the token
@@ -220,9 +232,9 @@ struct MfmaArgs {
 //   score[t] = sum_g scale[t, g] (raw_g[t] - C_g - zero[t, g] Q_g),
 // C_g = what the product holds for the operand offsets, Q_g = the query's sum over the group.
 template <int BITS, int G, int R, bool SPARSE, bool KPT = false>
-__global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_mfma_kernel(MfmaArgs a) {
+__global__ __launch_bounds__(waves_for(BITS, G, R, KPT, SPARSE) * KVS_WAVE) void decode_mfma_kernel(MfmaArgs a) {
   static_assert(!(KPT && SPARSE), "per-token Keys are dense only");
-  constexpr int kWaves = waves_for(BITS, G, R, KPT);
+  constexpr int kWaves = waves_for(BITS, G, R, KPT, SPARSE);
   constexpr int HPW = (R + kWaves - 1) / kWaves;   // heads whose states one wave merges at the end
   using S = Shape<BITS>;
   constexpr int W = S::W, KW = S::KW, RPW = S::RPW, NOPS = S::NOPS, TBL = S::TBL;
@@ -247,6 +259,11 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
   auto part_o = [&](int w, int r) -> float* { return reinterpret_cast<float*>(&wh[w][0][0][0]) + r * 128; };
   __shared__ float part_m[2 * kWaves][R], part_l[2 * kWaves][R];         // [kWaves + w]: wave w's kept rows
   __shared__ int next_chunk;                                             // chunk hand-out counter
+  // SPARSE: the query (log2 units) by channel; scale x zero of the chunk's Key groups by channel
+  // and of its Value groups by token
+  __shared__ __align__(16) float qtab[SPARSE ? R : 1][SPARSE ? 128 : 1];
+  __shared__ __align__(16) float sz_k[SPARSE ? kWaves : 1][SPARSE ? NGK : 1][SPARSE ? 128 : 1];
+  __shared__ __align__(16) float sz_v[SPARSE ? kWaves : 1][SPARSE ? NGC : 1][SPARSE ? 128 : 1];
   __shared__ int arrived_last;                                           // this workgroup completes its (b, h)
 
   const int lane = threadIdx.x & (KVS_WAVE - 1), wave = threadIdx.x / KVS_WAVE;
@@ -273,14 +290,14 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
   for (int k = 0; k < HPW; ++k) {
     extra_o[k] = float2{0.0f, 0.0f};  extra_m[k] = -INFINITY;  extra_l[k] = 0.0f;
     const int r = wave + k * kWaves;
-    if (a.extra && a.parts == 1 && !SPARSE && r < R) {
+    if (a.extra && a.parts == 1 && r < R) {
       const float* x = a.extra + (static_cast<size_t>(b) * Hq + hq0 + r) * kWsRow;
       extra_o[k] = reinterpret_cast<const float2*>(x)[lane];
       extra_m[k] = x[128];
       extra_l[k] = x[129];
     }
   }
-  if (a.parts == 1 && !SPARSE && wave < a.cap) {
+  if (a.parts == 1 && wave < a.cap) {
     keep_first_k = keep_rows_k[wave * 64];
     keep_first_v = keep_rows_v[wave * 64];
   }
@@ -307,6 +324,21 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
 #pragma unroll
     for (int r = 0; r < 4; ++r) acc[hf][r] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
 
+  // Four consecutive CSR entries (16-bit each, any 2-byte alignment) of one array.
+  struct __attribute__((packed, aligned(2))) Four { uint16_t v[4]; };
+  auto load_four = [&](const uint16_t* arr, int first) -> Four {
+    Four f;
+    __builtin_memcpy(&f, arr + first, sizeof f);
+    return f;
+  };
+  // A row's range as the cache gives it, made safe: 0 <= begin <= capacity, at most 128 entries
+  // (a row has 128 columns).  The arrays hold four entries more than the capacity, so four entries
+  // from any begin can be read.
+  struct RowRange { int begin, len; };
+  auto row_range = [&](int lo, int hi) -> RowRange {
+    const int b0 = max(0, min(lo, a.sparse_cap));
+    return RowRange{b0, min(max(min(hi, a.sparse_cap), b0) - b0, 128)};
+  };
   // The stream of one chunk lives in registers, and every piece of it (a 64-token Key tile, the
   // parameters, a 64-channel half of the Value tile) is requested again - for the wave's next
   // chunk - as soon as its last use is over, so that about one chunk per wave is always in
@@ -323,11 +355,18 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
     uint4 vx[KW][2];       // [token word row 4 k + grp][channel half], channels 4 col .. + 3
     uint32_t vp0[NGC], vp1[NGC];   // parameters of tokens lane, lane + 64
     uint32_t kq0[KPT ? NGC : 1], kq1[KPT ? NGC : 1];   // KPT: Key parameters of the same tokens
-    float c0[SPARSE ? R : 1], c1[SPARSE ? R : 1];   // score corrections of the same tokens
+    int krp[SPARSE ? 4 : 1], vrp[SPARSE ? 4 : 1];   // CSR row pointers of rows lane, lane + 64: [begin, end, begin, end]
     uint8_t mask0, mask1;  // keep-mask bytes of the same tokens
   };
   KeyRegs keys;
   ValueRegs vals;
+  // SPARSE: the current chunk's rows (lane, lane + 64) of both CSR structures, their first four
+  // entries, and the Value corrections accumulated so far (same scale as the accumulators).
+  RowRange krow[2] = {{0, 0}, {0, 0}}, vrow[2] = {{0, 0}, {0, 0}};
+  Four kcol0[2] = {}, kval0[2] = {}, vcol0[2] = {}, vval0[2] = {};
+  float vcorr[R][2];
+#pragma unroll
+  for (int r = 0; r < R; ++r) { vcorr[r][0] = 0.0f; vcorr[r][1] = 0.0f; }
   auto take_chunk = [&]() -> int {
     int c = 0;
     if (lane == 0) c = atomicAdd(&next_chunk, 1);
@@ -373,13 +412,12 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
     }
     s.mask0 = mask_b[t0 + lane_tok];
     s.mask1 = mask_b[t0 + 64 + lane_tok];
-    if (SPARSE) {
-#pragma unroll
-      for (int r = 0; r < R; ++r) {
-        const float* row = a.cs + (static_cast<size_t>(b) * Hq + hq0 + r) * n + t0 + lane_tok;
-        s.c0[r] = row[0];
-        s.c1[r] = row[64];
-      }
+    if (SPARSE) {                                  // Key rows are tokens, Value rows the channels of the tile:
+      const size_t row = bh * n + t0 + lane_tok;   // the same numbers
+      s.krp[0] = a.k_rowptr[row];       s.krp[1] = a.k_rowptr[row + 1];
+      s.krp[2] = a.k_rowptr[row + 64];  s.krp[3] = a.k_rowptr[row + 65];
+      s.vrp[0] = a.v_rowptr[row];       s.vrp[1] = a.v_rowptr[row + 1];
+      s.vrp[2] = a.v_rowptr[row + 64];  s.vrp[3] = a.v_rowptr[row + 65];
     }
   };
   auto load_value_half = [&](ValueRegs& s, int ci, int hf) {    // 128 tokens x 64 channels
@@ -425,6 +463,10 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
     qf[r][0] = kvs::half_bits_to_float(static_cast<uint16_t>(two & 0xFFFFu)) * kLog2eRsqrtD;
     qf[r][1] = kvs::half_bits_to_float(static_cast<uint16_t>(two >> 16)) * kLog2eRsqrtD;
   }
+  if (SPARSE && wave == 0) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) reinterpret_cast<float2*>(&qtab[r][0])[lane] = float2{qf[r][0], qf[r][1]};
+  }
   const int cpos0 = S::table_pos(2 * lane), cpos1 = S::table_pos(2 * lane + 1);
   const float coff0 = S::elem_offset(2 * lane), coff1 = S::elem_offset(2 * lane + 1);
   const int tpos0 = S::table_pos(lane), tpos1 = S::table_pos(lane + 64);
@@ -465,6 +507,14 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
   float bias[NGK][R];                              // what the score product holds for offsets and zero points
 
   auto score_chunk = [&](KeyRegs& s, int refill) {
+    if (SPARSE) {                                      // the chunk's Key outliers: needed at the softmax stage
+#pragma unroll
+      for (int row = 0; row < 2; ++row) {
+        krow[row] = row_range(vals.krp[2 * row], vals.krp[2 * row + 1]);
+        kcol0[row] = load_four(a.k_col, krow[row].begin);
+        kval0[row] = load_four(a.k_val, krow[row].begin);
+      }
+    }
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
       // ---- (1) B operand of the score product: q x scale as hi + lo halves, per token group ----
@@ -476,6 +526,8 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
           kvs::unpack_param(s.kp[gi].x, s0, z0);
           kvs::unpack_param(s.kp[gi].y, s1, z1);
           const float zf0 = static_cast<float>(z0) + coff0, zf1 = static_cast<float>(z1) + coff1;
+          if (SPARSE)
+            reinterpret_cast<float2*>(&sz_k[wave][gi][0])[lane] = float2{s0 * static_cast<float>(z0), s1 * static_cast<float>(z1)};
 #pragma unroll
           for (int r = 0; r < R; ++r) {
             const float a0 = qf[r][0] * s0, a1 = qf[r][1] * s1;
@@ -547,6 +599,42 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
   auto value_chunk = [&](ValueRegs& s, int refill, int cur, bool settle) {
     // ---- (3) online softmax, lane = tokens (lane, lane + 64); weights x Value scale to LDS -----
     float alpha[R];
+    float kcorr[R][2];                                 // SPARSE: what the isolated Key entries add to the scores
+#pragma unroll
+    for (int r = 0; r < R; ++r) { kcorr[r][0] = 0.0f; kcorr[r][1] = 0.0f; }
+    if (SPARSE) {
+      // the chunk's Value outliers are requested now (used after the Value product) ...
+#pragma unroll
+      for (int row = 0; row < 2; ++row) {
+        vrow[row] = row_range(s.vrp[2 * row], s.vrp[2 * row + 1]);
+        vcol0[row] = load_four(a.v_col, vrow[row].begin);
+        vval0[row] = load_four(a.v_val, vrow[row].begin);
+      }
+      // ... and the Key outliers of tokens lane, lane + 64 are folded into their scores' corrections
+      auto add_k = [&](int row, const Four& cols, const Four& vals4, int first) {
+        const int gi = G == 128 ? 0 : (lane + 64 * row) / G;          // the token's Key group in the chunk
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (first + j < krow[row].len) {
+            const int c = cols.v[j] & 127;
+            const float base = kvs::half_bits_to_float(vals4.v[j]) + sz_k[wave][gi][c];
+#pragma unroll
+            for (int r = 0; r < R; ++r) kcorr[r][row] += qtab[r][c] * base;
+          }
+        }
+      };
+      add_k(0, kcol0[0], kval0[0], 0);
+      add_k(1, kcol0[1], kval0[1], 0);
+      const int longest = static_cast<int>(kvs::wave_max_u32(static_cast<uint32_t>(max(krow[0].len, krow[1].len))));
+      for (int first = 4; first < longest; first += 4) {               // wave-uniform; rare
+#pragma unroll
+        for (int row = 0; row < 2; ++row) {
+          const int at = min(krow[row].begin + first, a.sparse_cap);
+          const Four cols = load_four(a.k_col, at), vals4 = load_four(a.k_val, at);
+          add_k(row, cols, vals4, first);
+        }
+      }
+    }
     {
       float sv0[NGC], sv1[NGC], zf0[NGC], zf1[NGC];
       float sk0[KPT ? NGC : 1], sk1[KPT ? NGC : 1], zk0[KPT ? NGC : 1], zk1[KPT ? NGC : 1];
@@ -557,6 +645,7 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
         kvs::unpack_param(s.vp1[g], sv1[g], z1);
         zf0[g] = static_cast<float>(z0) + toff0;
         zf1[g] = static_cast<float>(z1) + toff1;
+        if (SPARSE) { sz_v[wave][g][lane] = sv0[g] * static_cast<float>(z0); sz_v[wave][g][64 + lane] = sv1[g] * static_cast<float>(z1); }
         // Convert here and now: the parameter registers are about to be loaded again, and a
         // conversion postponed past that load would keep them alive in a second set.
         asm volatile("" : "+v"(sv0[g]), "+v"(sv1[g]), "+v"(zf0[g]), "+v"(zf1[g]));
@@ -588,11 +677,7 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
           s0 = s.mask0 ? -INFINITY : sc[wave][r][lane] - b0;
           s1 = s.mask1 ? -INFINITY : sc[wave][r][64 + lane] - b1;
         }
-        if (SPARSE) {
-          s0 += s.c0[r];  s1 += s.c1[r];
-          float* row = a.cs + (static_cast<size_t>(b) * Hq + hq0 + r) * n + part_begin + cur * 128 + lane;
-          row[0] = s0;  row[64] = s1;
-        }
+        if (SPARSE) { s0 += kcorr[r][0];  s1 += kcorr[r][1]; }
         const float mx = uniform(kvs::wave_max(fmaxf(s0, s1)));
         const float m_new = fmaxf(m_run[r], mx);
         const float m_use = m_new == -INFINITY ? 0.0f : m_new;
@@ -600,6 +685,7 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
         const float e0 = __builtin_amdgcn_exp2f(s0 - m_use), e1 = __builtin_amdgcn_exp2f(s1 - m_use);
         m_run[r] = m_new;
         l_run[r] = l_run[r] * alpha[r] + (e0 + e1);
+        if (SPARSE) { sc[wave][r][lane] = e0;  sc[wave][r][64 + lane] = e1; }   // the weights take the scores' place
 #pragma unroll
         for (int g = 0; g < NGC; ++g) {
           const float w0 = e0 * sv0[g], w1 = e1 * sv1[g];
@@ -659,6 +745,35 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
       load_value_half(s, refill, hf);
       __builtin_amdgcn_sched_barrier(0);
     }
+    if (SPARSE) {
+      // ---- the chunk's isolated Value entries: lane = channels lane, lane + 64 of the tile -------
+      // out[c] += sum over the row's entries (token t, value v) of  weight[t] (v + scale[t] zero[t])
+      auto add_v = [&](int row, const Four& cols, const Four& vals4, int first) {
+        const int gc = G == 128 ? 0 : (lane + 64 * row) / G;          // the channel's Value group
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (first + j < vrow[row].len) {
+            const int t = cols.v[j] & 127;
+            const float base = kvs::half_bits_to_float(vals4.v[j]) + sz_v[wave][gc][t];
+#pragma unroll
+            for (int r = 0; r < R; ++r) vcorr[r][row] += sc[wave][r][t] * base;
+          }
+        }
+      };
+#pragma unroll
+      for (int r = 0; r < R; ++r) { vcorr[r][0] *= alpha[r];  vcorr[r][1] *= alpha[r]; }
+      add_v(0, vcol0[0], vval0[0], 0);
+      add_v(1, vcol0[1], vval0[1], 0);
+      const int longest = static_cast<int>(kvs::wave_max_u32(static_cast<uint32_t>(max(vrow[0].len, vrow[1].len))));
+      for (int first = 4; first < longest; first += 4) {               // wave-uniform; rare
+#pragma unroll
+        for (int row = 0; row < 2; ++row) {
+          const int at = min(vrow[row].begin + first, a.sparse_cap);
+          const Four cols = load_four(a.v_col, at), vals4 = load_four(a.v_val, at);
+          add_v(row, cols, vals4, first);
+        }
+      }
+    }
     // ---- (5) every few chunks: take what the accumulators hold for offsets and zero points out ----
     // The accumulators carry sum_t w_t (offset + code) and z_run carries sum_t w_t (offset + zero):
     // two sums up to 2^10 times larger than their difference, the output.  Left to grow over a whole
@@ -709,7 +824,7 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
   // (only when this workgroup covers the whole sequence; otherwise the combine kernel does it).
   // Lane = channels 2 lane, 2 lane + 1; the wave's score exchange area is free by now and takes
   // the unnormalised row.  The first row was requested at kernel start.
-  const bool fold_keep = a.parts == 1 && !SPARSE;
+  const bool fold_keep = a.parts == 1;
   if (fold_keep) {
     const int cnt = min(keep_cnt_b, a.cap);
     float ms[R], ls[R], o0[R], o1[R];
@@ -780,6 +895,14 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
     }
     if (col < R && grp == 0) { part_m[wave][head] = mmine * kLn2; part_l[wave][head] = lmine; }
   }
+  if (SPARSE) {                                        // the Value corrections join the wave's rows
+    wave_lds_sync();
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      part_o(wave, r)[lane] += vcorr[r][0];
+      part_o(wave, r)[64 + lane] += vcorr[r][1];
+    }
+  }
   __syncthreads();
 
   // ---- merge the waves' states (and the kept rows' states) -----------------------------------
@@ -812,12 +935,6 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
       O0 += o.x * f;
       O1 += o.y * f;
     }
-    if (SPARSE) {                                      // another kernel finishes
-      float* dst = a.ws + (bq_row * a.parts + part) * kWsRow;
-      reinterpret_cast<float2*>(dst)[lane] = float2{O0, O1};
-      if (lane == 0) { dst[128] = M; dst[129] = L; }
-      continue;
-    }
     if (a.parts > 1) {                                 // the last workgroup to arrive finishes (below)
       float* dst = a.ws + (bq_row * a.parts + part) * kWsRow;
       kvs::store_coherent(reinterpret_cast<float2*>(dst) + lane, float2{O0, O1});
@@ -848,7 +965,7 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
   // back and invalidating the whole L2 of the die, once per workgroup: that more than doubled the
   // kernel's time.)  The last arriver also puts the counter back to zero: nobody else touches it
   // any more in this launch.
-  if (a.parts > 1 && !SPARSE) {
+  if (a.parts > 1) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0)
@@ -872,14 +989,17 @@ __global__ __launch_bounds__(waves_for(BITS, G, R, KPT) * KVS_WAVE) void decode_
 }
 
 inline MfmaArgs make_args(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                          void* out, float* lse, float* ws, int* arrive, float* cs, int n_used, const float* extra) {
+                          void* out, float* lse, float* ws, int* arrive, int n_used, const float* extra) {
   MfmaArgs a;
   a.q = static_cast<const uint16_t*>(q);
   a.k_codes = c->k_codes; a.v_codes = c->v_codes; a.k_params = c->k_params; a.v_params = c->v_params;
   a.keep_mask = c->keep_mask;
   a.keep_k = static_cast<const uint16_t*>(c->keep_k); a.keep_v = static_cast<const uint16_t*>(c->keep_v);
   a.keep_cnt = c->keep_cnt;
-  a.out = static_cast<uint16_t*>(out); a.lse = lse; a.ws = ws; a.arrive = arrive; a.cs = cs;
+  a.out = static_cast<uint16_t*>(out); a.lse = lse; a.ws = ws; a.arrive = arrive;
+  a.k_rowptr = c->k_rowptr; a.k_col = c->k_col; a.k_val = static_cast<const uint16_t*>(c->k_val);
+  a.v_rowptr = c->v_rowptr; a.v_col = c->v_col; a.v_val = static_cast<const uint16_t*>(c->v_val);
+  a.sparse_cap = static_cast<int>(d->sparse_cap);
   a.n = d->n; a.Hkv = d->Hkv; a.cap = d->keep_cap;
   a.n_used = n_used; a.extra = extra;
   a.parts = geo.splits; a.part_tokens = geo.split_tokens;
@@ -892,16 +1012,17 @@ inline MfmaArgs make_args(const kvs_desc* d, const kvs::DecodeGeometry& geo, con
 // streams the codes again.
 template <int BITS, int G, int R, bool KPT>
 void launch_heads(const kvs_desc* d, const kvs::DecodeGeometry& geo, MfmaArgs args, hipStream_t s) {
-  const dim3 grid(d->B * d->Hkv * geo.splits), block(waves_for(BITS, G, R, KPT) * KVS_WAVE);
+  const dim3 grid(d->B * d->Hkv * geo.splits);
   const bool sparse = d->sparse_frac > 0.0f;
   for (args.head_off = 0; args.head_off < args.rep; args.head_off += R) {
     if constexpr (BITS != 8 && !KPT) {
       if (sparse) {
-        hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, true, false>), grid, block, 0, s, args);
+        hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, true, false>), grid, dim3(waves_for(BITS, G, R, false, true) * KVS_WAVE),
+                           0, s, args);
         continue;
       }
     }
-    hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, false, KPT>), grid, block, 0, s, args);
+    hipLaunchKernelGGL((decode_mfma_kernel<BITS, G, R, false, KPT>), grid, dim3(waves_for(BITS, G, R, KPT) * KVS_WAVE), 0, s, args);
   }
 }
 
@@ -910,7 +1031,7 @@ void launch_heads(const kvs_desc* d, const kvs::DecodeGeometry& geo, MfmaArgs ar
 template <int BITS>
 void launch_bits_kpt(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c, void* out,
                      float* lse, float* ws, int* arrive, int n_used, const float* extra, hipStream_t s) {
-  const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws, arrive, nullptr, n_used, extra);
+  const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws, arrive, n_used, extra);
   const int rep = a.rep;
   if (d->group == 128) {
     if (rep == 1) launch_heads<BITS, 128, 1, true>(d, geo, a, s);
@@ -932,8 +1053,8 @@ void launch_bits_kpt(const kvs_desc* d, const kvs::DecodeGeometry& geo, const vo
 // dense-and-sparse variant exists for one query head per KV head.
 template <int BITS>
 void launch_bits(const kvs_desc* d, const kvs::DecodeGeometry& geo, const void* q, const kvs_cache* c, void* out,
-                 float* lse, float* ws, int* arrive, float* cs, int n_used, const float* extra, hipStream_t s) {
-  const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws, arrive, cs, n_used, extra);
+                 float* lse, float* ws, int* arrive, int n_used, const float* extra, hipStream_t s) {
+  const MfmaArgs a = make_args(d, geo, q, c, out, lse, ws, arrive, n_used, extra);
   const int rep = a.rep;
   if (d->group == 128) {
     if (rep == 1) launch_heads<BITS, 128, 1, false>(d, geo, a, s);

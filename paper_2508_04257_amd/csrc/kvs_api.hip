@@ -26,8 +26,9 @@ kvs_status validate_desc(const kvs_desc* d) {
   if (rows >= (int64_t{1} << 30)) return KVS_ERR_UNSUPPORTED;
   if (static_cast<int64_t>(d->B) * d->Hq >= (int64_t{1} << 30)) return KVS_ERR_UNSUPPORTED;   // query rows likewise
   if (d->sparse_frac > 0.0f) {
-    // CSR positions are int32: the whole tensor must be countable even if every entry ties.
-    if (d->sparse_cap > (int64_t{1} << 31) - 1 || rows * KVS_HEAD_DIM >= (int64_t{1} << 31)) return KVS_ERR_UNSUPPORTED;
+    // CSR positions are int32 (with room for a row's 128 entries past any position): the whole
+    // tensor must be countable even if every entry ties.
+    if (d->sparse_cap > (int64_t{1} << 31) - 1 - 256 || rows * KVS_HEAD_DIM >= (int64_t{1} << 31)) return KVS_ERR_UNSUPPORTED;
   }
   return KVS_OK;
 }
@@ -91,7 +92,7 @@ extern "C" kvs_status kvs_cache_bytes(const kvs_desc* d, size_t* sizes) {
   const size_t code_bytes = bh * n * W * 4;                 // W words per 128 codes, K and V alike
   const size_t keep_rows = bh * d->keep_cap * KVS_HEAD_DIM * 2;
   const bool sparse = d->sparse_frac > 0.0f;
-  const size_t cap = sparse ? static_cast<size_t>(d->sparse_cap) : 0;
+  const size_t cap = sparse ? static_cast<size_t>(d->sparse_cap) + kvs::kCsrPadEntries : 0;   // see kCsrPadEntries
   const size_t v[KVS_CACHE_FIELDS] = {
       code_bytes,                                   // k_codes
       code_bytes,                                   // v_codes
@@ -124,19 +125,21 @@ extern "C" int32_t kvs_decode_splits(const kvs_desc* d) {
   return kvs::decode_geometry(d).splits;
 }
 
+// What the decode calls keep in the workspace: the arrival counters, per (b, hq, split) the
+// unnormalised fp32 output row plus running max and sum (sized for the most splits any token count
+// of a growing cache can get), and one more part per (b, hq) for a growing cache's residual rows.
+size_t kvs::decode_workspace_bytes(const kvs_desc* d) {
+  const size_t rows = static_cast<size_t>(d->B) * d->Hq * (kvs::decode_max_splits(d) + 1);
+  return round16(kvs::workspace_counter_words(d) * 4 + rows * (KVS_HEAD_DIM + 2) * 4);
+}
+
 extern "C" size_t kvs_workspace_bytes(const kvs_desc* d) {
   if (kvs::validate_desc(d) != KVS_OK) return 0;
-  const kvs::DecodeGeometry g = kvs::decode_geometry(d);
-  // decode: per (b, hq, split) the unnormalised fp32 output row plus running max and sum (sized
-  // for the most splits any token count of a growing cache can get)
-  size_t decode = static_cast<size_t>(d->B) * d->Hq * kvs::decode_max_splits(d) * (KVS_HEAD_DIM + 2) * 4;
-  if (d->sparse_frac > 0.0f)                         // plus one score per (b, hq, token)
-    decode = (kvs::decode_parts_floats(d, g) + kvs::decode_sparse_score_floats(d)) * 4;
-  // quantise (dense-and-sparse only): two 32768-bin histograms, thresholds, scan scratch
-  const size_t quant = d->sparse_frac > 0.0f ? kvs::sparse_workspace_words(d) * 4 : 0;
-  // growing caches: one more part per (b, hq) for the residual rows
-  decode += static_cast<size_t>(d->B) * d->Hq * (KVS_HEAD_DIM + 2) * 4;
-  return round16(kvs::workspace_counter_words(d) * 4 + (decode > quant ? decode : quant));
+  // quantise (dense-and-sparse only): histograms, thresholds, scan scratch, staging lists - behind
+  // the counters, which quantise calls leave alone
+  const size_t quant = d->sparse_frac > 0.0f ? kvs::workspace_counter_words(d) * 4 + kvs::sparse_workspace_words(d) * 4 : 0;
+  const size_t decode = kvs::decode_workspace_bytes(d);
+  return round16(decode > quant ? decode : quant);
 }
 
 extern "C" size_t kvs_workspace_zero_bytes(const kvs_desc* d) {

@@ -44,32 +44,26 @@ struct DecodeGeometry {
 DecodeGeometry decode_geometry(const kvs_desc* d);
 DecodeGeometry decode_geometry(const kvs_desc* d, int n_used);
 int decode_max_splits(const kvs_desc* d);
+size_t decode_workspace_bytes(const kvs_desc* d);   // the part of kvs_workspace_bytes the decode calls use
 // Host-side argument checks of the two prefill calls (what they refuse before launching anything).
 kvs_status check_predict_call(const void* hidden, int32_t B, int32_t n, int32_t d, const int32_t* channels,
                               int32_t n_channels, int32_t k, int32_t first_n, const int32_t* sink_idx,
                               const uint8_t* keep_mask);
 kvs_status check_quantize_call(const kvs_desc* desc, const void* K, const void* V, const uint8_t* keep_mask,
                                const kvs_cache* out, const void* workspace);
-// Matrix-core decode kernel (decode_mfma.hip).
+// Matrix-core decode kernel (decode_mfma.hip); dense-and-sparse caches included (the isolated
+// outliers' corrections are applied inside it).
 void launch_decode_mfma(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                        void* out, float* lse, float* ws, int* arrive, float* cs, int n_used, const float* extra, hipStream_t s);
+                        void* out, float* lse, float* ws, int* arrive, int n_used, const float* extra, hipStream_t s);
 // The workspace starts with the stream kernel's arrival counters, one 32-bit word per (sequence,
 // KV head), rounded up to 256 bytes: zero before a call, put back to zero by the call.  What the
 // calls keep in the workspace otherwise follows them.
 inline size_t workspace_counter_words(const kvs_desc* d) {
   return (static_cast<size_t>(d->B) * d->Hkv + 63) & ~static_cast<size_t>(63);
 }
-// Dense-and-sparse companions of the matrix-core kernel (decode_sparse.hip).  The workspace then
-// holds the parts (B * Hq * splits rows of 130 floats, rounded up to 64 floats) followed by one
-// float per (b, hq, token).
-size_t decode_sparse_score_floats(const kvs_desc* d);
-inline size_t decode_parts_floats(const kvs_desc* d, const DecodeGeometry& g) {
-  const size_t f = static_cast<size_t>(d->B) * d->Hq * g.splits * (KVS_HEAD_DIM + 2);
-  return (f + 63) & ~static_cast<size_t>(63);
-}
-void launch_sparse_key_corr(const kvs_desc* d, const void* q, const kvs_cache* c, float* cs, hipStream_t s);
-void launch_decode_finish_sparse(const kvs_desc* d, const DecodeGeometry& geo, const void* q, const kvs_cache* c,
-                                 const float* ws, const float* cs, void* out, float* lse, hipStream_t s);
+// The CSR column / value arrays are four entries longer than the capacity: the decode kernel
+// reads an entry together with the three that follow it.
+constexpr int kCsrPadEntries = 4;
 
 // Which tokens a quantise launch reads and where they go.  A plain call quantises the whole
 // tensor in place (every field = desc->n, offsets 0); a growing cache quantises the whole blocks of

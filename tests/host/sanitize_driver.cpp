@@ -48,11 +48,15 @@ int main() {
             EXPECT(kvs_calibration_bytes(&d) == size_t{4} * 8 * 128 * 4);
           }
   // dense-and-sparse sizing, small and at the largest capacities the descriptor admits
-  for (int64_t cap : {int64_t{1}, int64_t{1} << 20, (int64_t{1} << 31) - 1}) {
+  for (int64_t cap : {int64_t{1}, int64_t{1} << 20, (int64_t{1} << 31) - 257}) {
     const kvs_desc d = desc(32, 4096, 32, 32, 3, 128, 8, 0.01f, cap);
     EXPECT(kvs_cache_bytes(&d, sizes) == KVS_OK);
-    EXPECT(sizes[10] >= static_cast<size_t>(cap) * 2);
-    EXPECT(kvs_workspace_bytes(&d) > static_cast<size_t>(32) * 32 * 4096 * 4);
+    EXPECT(sizes[10] >= static_cast<size_t>(cap + 4) * 2);      // four entries of padding behind the capacity
+    EXPECT(kvs_workspace_bytes(&d) > kvs_workspace_zero_bytes(&d));
+  }
+  {
+    const kvs_desc d = desc(32, 4096, 32, 32, 3, 128, 8, 0.01f, (int64_t{1} << 31) - 256);
+    EXPECT(kvs_cache_bytes(&d, sizes) == KVS_ERR_UNSUPPORTED);
   }
   // the largest row count that passes validation, and the first that does not
   {
@@ -100,8 +104,7 @@ int main() {
     EXPECT(kvs_decode_attn(&d, p, &none, p, nullptr, p, nullptr) == KVS_ERR_INVALID);
     EXPECT(kvs_decode_attn_noalloc(&d, nullptr, &full, p, nullptr, nullptr) == KVS_ERR_INVALID);
     {
-      const kvs_desc big = desc(32, 4096, 32, 32, 3, 128, 8, 0.01f, 1 << 20);
-      EXPECT(kvs_workspace_bytes(&big) > KVS_NOALLOC_SCRATCH_BYTES);
+      const kvs_desc big = desc(128, 1024, 64, 64, 4, 128, 8);           // 8192 output rows, two parts each
       EXPECT(kvs_decode_attn_noalloc(&big, p, &full, p, nullptr, nullptr) == KVS_ERR_SCRATCH);
     }
     EXPECT(kvs_predict_sinks(p, 1, 128, 4096, ch_bad, 1, 2, 0, static_cast<int32_t*>(p), static_cast<uint8_t*>(p), nullptr, nullptr) == KVS_ERR_INVALID);

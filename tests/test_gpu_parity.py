@@ -470,8 +470,8 @@ def test_dense_and_sparse_threshold_paths(case):
 
 
 def test_dense_and_sparse_long_sequence():
-    """More than 4096 tokens: the finishing kernel stages the sequence in two segments, the second one
-    ragged (5 tiles), and the stream is cut into several parts per head."""
+    """More than 4096 tokens with a ragged number of tiles: the stream is cut into many parts per
+    head, each adds its own outlier corrections, and the last workgroup to arrive merges them."""
     rng = np.random.default_rng(77)
     B, H, n, bits, G, frac = 1, 2, 4096 + 640, 4, 128, 0.01
     K = np.clip(rng.standard_t(4, (B, H, n, 128)), -60000, 60000).astype(np.float16)

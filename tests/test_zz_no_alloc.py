@@ -4,8 +4,8 @@ the library's own scratch array) against kvs_decode_attn on the same cache, thro
 Two calls in a row on one GPU, the second on a smaller input, so that the second runs on scratch
 that still holds the first call's contents.  Shapes are chosen so that the scratch is really used:
 several workgroups per (sequence, KV head) leave their parts there and count themselves in on the
-arrival counters at its head, and the dense-and-sparse cache also parks one score per (query head,
-token) there.
+arrival counters at its head (the dense-and-sparse cache takes the same path with its outlier
+corrections inside the stream kernel).
 """
 import ctypes as C
 
@@ -67,7 +67,6 @@ def test_noalloc_decode_matches_the_workspace_call_on_two_calls_in_a_row(sparse)
     for seed, B, H, Hq, n, bits, G in shapes:
         desc, cache, ws, q, ref_out = _make(seed, B, H, Hq, n, bits, G, sparse)
         assert kb.kvs_decode_splits(desc) > 1 or sparse            # the scratch is in use
-        assert kb.kvs_workspace_bytes(desc) <= kb.KVS_NOALLOC_SCRATCH_BYTES
         out_ws, lse_ws, out_na, lse_na = _both(desc, cache, ws, q)
         # same kernels on another buffer: equal up to the order in which a workgroup's waves
         # happened to take their chunks (fp32 sums), far inside the bar against the oracle
@@ -78,10 +77,9 @@ def test_noalloc_decode_matches_the_workspace_call_on_two_calls_in_a_row(sparse)
 
 
 def test_noalloc_decode_rejects_a_descriptor_beyond_its_scratch():
-    # 32 x 32 heads x 4096 tokens with isolated outliers: 16 MiB of scores alone
-    d = kb.make_desc(B=32, n=4096, Hq=32, Hkv=32, bits=3, group=128, keep_cap=8, sparse_frac=0.01,
-                     sparse_cap=1 << 20)
-    assert kb.kvs_workspace_bytes(d) > kb.KVS_NOALLOC_SCRATCH_BYTES
+    # 128 sequences x 64 heads: 8192 output rows of 520 bytes, one part each plus the residual part
+    d = kb.make_desc(B=128, n=1024, Hq=64, Hkv=64, bits=4, group=128, keep_cap=8)
+    assert 2 * 128 * 64 * 520 > kb.KVS_NOALLOC_SCRATCH_BYTES
     full = kb.KvsCache(**{name: 16 for name in kb.CACHE_FIELD_NAMES})
     st = kb.lib().kvs_decode_attn_noalloc(C.byref(d), 16, C.byref(full), 16, None, None)
     assert st == kb.KVS_ERR_SCRATCH
