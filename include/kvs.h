@@ -28,6 +28,8 @@
  *     returns KVS_OK.  The caller zeroes *status before the first call and reads it after
  *     synchronising.
  *   - fp16 is IEEE binary16; inputs must be finite.  All tensors are dense, row-major.
+ *   - Every buffer starts at a multiple of 16 bytes (the decode calls return KVS_ERR_INVALID for a
+ *     cache whose code, parameter, kept-row or CSR arrays do not).
  *
  * Packed cache layout (D = 128 only)
  *   cpw = codes per 32-bit word: 16 (2 bit), 10 (3 bit), 8 (4 bit), 4 (8 bit);
@@ -45,11 +47,12 @@
  *            zero padded;  keep_idx int32 [B, keep_cap] (-1 padded);  keep_cnt int32 [B];
  *            keep_mask uint8 [B, n] (copy of the mask the cache was built with).
  *   CSR of isolated outliers (only when sparse_frac > 0), B*Hkv*n rows per tensor:
- *            rowptr int32 [B*Hkv*n + 1], col uint16 [sparse_cap + 4] ascending per row, val fp16
- *            [sparse_cap + 4] (the four entries behind the capacity are padding that decode may
- *            read and never uses; kvs_cache_bytes() counts them).
+ *            rowptr int32 [B*Hkv*n + 1], col uint16 [sparse_cap + 4], val fp16 [sparse_cap + 4]
+ *            (the four entries behind the capacity are padding that decode may read and never
+ *            uses; kvs_cache_bytes() counts them).
  *            Keys: row = (b, h, token), col = channel.  Values: row = (b, h, 128-token tile,
  *            channel), col = token inside the tile (the transposition of the Value code tiles).
+ *            Columns ascend inside a row.
  *   Residual window (growing caches only): res_k / res_v fp16 [B, Hkv, 128, 128], row r = token
  *            128 * (n_tokens / 128) + r of the sequence, still in 16 bit.
  */

@@ -145,6 +145,14 @@ static kvs_status check_decode_args(const kvs_desc* desc, const void* q, const k
   if (desc->sparse_frac > 0.0f && (!cache->k_rowptr || !cache->k_col || !cache->k_val ||
                                    !cache->v_rowptr || !cache->v_col || !cache->v_val))
     return KVS_ERR_INVALID;
+  // The stream is read 16 bytes a lane, CSR entries four (8 bytes) at a time.
+  const auto misaligned = [](const void* p, uintptr_t to) { return (reinterpret_cast<uintptr_t>(p) & (to - 1)) != 0; };
+  if (misaligned(cache->k_codes, 16) || misaligned(cache->v_codes, 16) || misaligned(cache->keep_k, 16) ||
+      misaligned(cache->keep_v, 16) || misaligned(cache->k_params, 8) || misaligned(cache->v_params, 4))
+    return KVS_ERR_INVALID;
+  if (desc->sparse_frac > 0.0f && (misaligned(cache->k_col, 8) || misaligned(cache->k_val, 8) ||
+                                   misaligned(cache->v_col, 8) || misaligned(cache->v_val, 8)))
+    return KVS_ERR_INVALID;
   return KVS_OK;
 }
 

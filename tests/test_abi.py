@@ -106,6 +106,14 @@ def test_null_pointers_are_rejected_on_the_host():
     assert L.kvs_quantize_kv(C.byref(d), 16, 16, 16, C.byref(cache), None, None) == kb.KVS_ERR_INVALID
     assert L.kvs_decode_attn(C.byref(d), 16, C.byref(cache), 16, None, 16, None) == kb.KVS_ERR_INVALID
     assert L.kvs_quantize_kv(None, 16, 16, 16, C.byref(cache), None, None) == kb.KVS_ERR_INVALID
+    # decode reads the stream 16 bytes a lane and CSR entries 8 bytes at a time: misplaced arrays are refused
+    for field, at in (("k_codes", 24), ("v_codes", 20), ("keep_k", 18)):
+        odd = kb.KvsCache(**{name: (at if name == field else 16) for name in kb.CACHE_FIELD_NAMES})
+        assert L.kvs_decode_attn(C.byref(d), 16, C.byref(odd), 16, None, 16, None) == kb.KVS_ERR_INVALID, field
+    ds = kb.make_desc(B=8, n=4096, Hq=32, Hkv=32, bits=3, group=128, keep_cap=5, sparse_frac=0.01, sparse_cap=1 << 20)
+    for field in ("k_col", "k_val", "v_col", "v_val"):
+        odd = kb.KvsCache(**{name: (18 if name == field else 16) for name in kb.CACHE_FIELD_NAMES})
+        assert L.kvs_decode_attn(C.byref(ds), 16, C.byref(odd), 16, None, 16, None) == kb.KVS_ERR_INVALID, field
     ch = (C.c_int32 * 1)(5000)
     assert L.kvs_predict_sinks(16, 1, 128, 4096, ch, 1, 2, 0, 16, 16, None, None) == kb.KVS_ERR_INVALID   # channel >= d
     ch = (C.c_int32 * 1)(7)
