@@ -425,7 +425,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(int* __restric
   int run = sums[blockIdx.x] + block_exclusive_scan(v, &total);
   for (int j = 0; j < kScanItems; ++j) {
     run += item[j];
-    if (base + j < count) x[base + j] = run;
+    if (base + j < count) __builtin_nontemporal_store(run, &x[base + j]);   // read next by another kernel: not left dirty in the cache
   }
 }
 
@@ -444,8 +444,8 @@ __global__ __launch_bounds__(KVS_WAVE) void csr_move_kernel(
   for (int e = threadIdx.x; e < cnt; e += KVS_WAVE) {
     if (dst0 + e < cap) {
       const uint32_t w = src0 + e < list_words ? list[src0 + e] : 0u;
-      col[dst0 + e] = static_cast<uint16_t>(w & 0xFFFFu);
-      val[dst0 + e] = static_cast<uint16_t>(w >> 16);
+      __builtin_nontemporal_store(static_cast<uint16_t>(w & 0xFFFFu), &col[dst0 + e]);
+      __builtin_nontemporal_store(static_cast<uint16_t>(w >> 16), &val[dst0 + e]);
     }
   }
 }
