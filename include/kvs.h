@@ -50,9 +50,12 @@
  *            rowptr int32 [B*Hkv*n + 1], col uint16 [sparse_cap + 4], val fp16 [sparse_cap + 4]
  *            (the four entries behind the capacity are padding that decode may read and never
  *            uses; kvs_cache_bytes() counts them).
- *            Keys: row = (b, h, token), col = channel.  Values: row = (b, h, 128-token tile,
- *            channel), col = token inside the tile (the transposition of the Value code tiles).
- *            Columns ascend inside a row.
+ *            Keys: row = (b, h, token), column = channel.  Values: row = (b, h, 128-token tile,
+ *            channel), column = token inside the tile (the transposition of the Value code tiles).
+ *            A col word holds the column in bits 0-6 and, in bits 7-13, the row's place inside its
+ *            128-row tile (token % 128 for Keys, the channel for Values): decode reads the entries
+ *            of a tile as one contiguous run, rowptr[tile start] .. rowptr[tile end], and an entry
+ *            then says which quantisation group its row belongs to.  Columns ascend inside a row.
  *   Residual window (growing caches only): res_k / res_v fp16 [B, Hkv, 128, 128], row r = token
  *            128 * (n_tokens / 128) + r of the sequence, still in 16 bit.
  */
@@ -96,7 +99,7 @@ typedef struct kvs_desc {
                             /* k_params is then [B, Hkv, n, 128/G].  Not with sparse_frac > 0     */
                             /* (KVS_ERR_UNSUPPORTED).                                             */
   int64_t sparse_cap;       /* CSR capacity in entries per tensor when sparse_frac > 0        */
-                            /* (1 .. 2^31 - 257, beyond: KVS_ERR_UNSUPPORTED)                 */
+                            /* (1 .. 2^31 - 32769, beyond: KVS_ERR_UNSUPPORTED)               */
 } kvs_desc;
 
 /* The quantised cache of one layer: device pointers to caller-owned buffers whose byte sizes

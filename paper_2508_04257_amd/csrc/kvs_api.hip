@@ -26,9 +26,9 @@ kvs_status validate_desc(const kvs_desc* d) {
   if (rows >= (int64_t{1} << 30)) return KVS_ERR_UNSUPPORTED;
   if (static_cast<int64_t>(d->B) * d->Hq >= (int64_t{1} << 30)) return KVS_ERR_UNSUPPORTED;   // query rows likewise
   if (d->sparse_frac > 0.0f) {
-    // CSR positions are int32 (with room for a row's 128 entries past any position): the whole
-    // tensor must be countable even if every entry ties.
-    if (d->sparse_cap > (int64_t{1} << 31) - 1 - 256 || rows * KVS_HEAD_DIM >= (int64_t{1} << 31)) return KVS_ERR_UNSUPPORTED;
+    // CSR positions are int32 (with room for a tile's 16384 entries and a round of loads past any
+    // position): the whole tensor must be countable even if every entry ties.
+    if (d->sparse_cap > (int64_t{1} << 31) - 1 - 32768 || rows * KVS_HEAD_DIM >= (int64_t{1} << 31)) return KVS_ERR_UNSUPPORTED;
   }
   return KVS_OK;
 }

@@ -396,7 +396,8 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
       while (bits) {
         const int j = __builtin_ctz(bits);
         bits &= bits - 1;
-        if (pos < list_words) emit.list[pos] = static_cast<uint32_t>(8 * chunk + j) | (half_of(raw[i], j) << 16);
+        if (pos < list_words)                      // channel | token inside its 128-token tile << 7 | fp16 value << 16
+          emit.list[pos] = static_cast<uint32_t>(8 * chunk + j) | (static_cast<uint32_t>((tc0 + r) & 127) << 7) | (half_of(raw[i], j) << 16);
         ++pos;
       }
     }
@@ -744,7 +745,8 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
         const uint32_t tokens = (j < 4 ? iso_lo >> (8 * j) : iso_hi >> (8 * (j - 4))) & 0xFFu;   // the lane's tokens of channel c
         const long long pos = static_cast<long long>(run_base) + chan_off_s[c] + bits_below_byte(&iso_s[c][0], rs) +
                               __popc(tokens & ((1u << i) - 1u));
-        if (pos < list_words) emit.list[pos] = static_cast<uint32_t>(8 * rs + i) | (half_of(raw[i], j) << 16);
+        if (pos < list_words)                      // token inside the tile | channel << 7 | fp16 value << 16
+          emit.list[pos] = static_cast<uint32_t>(8 * rs + i) | (static_cast<uint32_t>(c) << 7) | (half_of(raw[i], j) << 16);
       }
     }
   }

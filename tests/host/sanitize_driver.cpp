@@ -48,14 +48,14 @@ int main() {
             EXPECT(kvs_calibration_bytes(&d) == size_t{4} * 8 * 128 * 4);
           }
   // dense-and-sparse sizing, small and at the largest capacities the descriptor admits
-  for (int64_t cap : {int64_t{1}, int64_t{1} << 20, (int64_t{1} << 31) - 257}) {
+  for (int64_t cap : {int64_t{1}, int64_t{1} << 20, (int64_t{1} << 31) - 32769}) {
     const kvs_desc d = desc(32, 4096, 32, 32, 3, 128, 8, 0.01f, cap);
     EXPECT(kvs_cache_bytes(&d, sizes) == KVS_OK);
     EXPECT(sizes[10] >= static_cast<size_t>(cap + 4) * 2);      // four entries of padding behind the capacity
     EXPECT(kvs_workspace_bytes(&d) > kvs_workspace_zero_bytes(&d));
   }
   {
-    const kvs_desc d = desc(32, 4096, 32, 32, 3, 128, 8, 0.01f, (int64_t{1} << 31) - 256);
+    const kvs_desc d = desc(32, 4096, 32, 32, 3, 128, 8, 0.01f, (int64_t{1} << 31) - 32768);
     EXPECT(kvs_cache_bytes(&d, sizes) == KVS_ERR_UNSUPPORTED);
   }
   // the largest row count that passes validation, and the first that does not

@@ -63,6 +63,15 @@ def assert_cache_equal(cache, ref: O.Cache, check_status=True):
         assert np.array_equal(kv, ref.keep_v.view(np.uint16))
 
 
+def assert_col_words(words, ref_col, ref_rowptr):
+    """A col word of the cache: the column in bits 0-6 (what the oracle's CSR holds), the row's place
+    inside its 128-row tile in bits 7-13 (token % 128 for Keys, the channel for Values: in both
+    structures the row number modulo 128), nothing above."""
+    row_of_entry = np.repeat(np.arange(len(ref_rowptr) - 1), np.diff(ref_rowptr))
+    assert np.array_equal(words & 127, ref_col)
+    assert np.array_equal(words >> 7, row_of_entry & 127)
+
+
 def assert_csr_equal(cache, ref: O.Cache):
     rows = ref.B * ref.Hkv * ref.n
     for name in ("k", "v"):
@@ -70,7 +79,7 @@ def assert_csr_equal(cache, ref: O.Cache):
         ref_rp = getattr(ref, name + "_rowptr")
         assert np.array_equal(rp, ref_rp)
         nnz = int(ref_rp[-1])
-        assert np.array_equal(getattr(cache, name + "_col").cpu().numpy().view(np.uint16)[:nnz], getattr(ref, name + "_col"))
+        assert_col_words(getattr(cache, name + "_col").cpu().numpy().view(np.uint16)[:nnz], getattr(ref, name + "_col"), ref_rp)
         assert np.array_equal(getattr(cache, name + "_val").cpu().numpy().view(np.uint16)[:nnz],
                               getattr(ref, name + "_val").view(np.uint16))
 
@@ -570,7 +579,7 @@ def _full_size(name, every=1):
                     csr_host, (ref.k_rowptr, ref.v_rowptr), (ref.k_col, ref.v_col), (ref.k_val, ref.v_val)):
                 lo, hi = int(rp[base]), int(rp[base + w.n])
                 assert np.array_equal(rp[base:base + w.n + 1] - lo, rref)
-                assert np.array_equal(col[lo:hi], cref)
+                assert_col_words(col[lo:hi], cref, rref)
                 assert np.array_equal(val[lo:hi], vref.view(np.uint16))
         assert np.array_equal(kc[b, h], ref.k_codes[0, 0])
         assert np.array_equal(vc[b, h], ref.v_codes[0, 0])
