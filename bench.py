@@ -37,8 +37,8 @@ OTHER_CONFIGS = ("cfg0_kvsink", "cfg2", "cfg3", "cfg4")
 DECODE_TRAFFIC = {
     "workload": "cfg1",
     "sources": ["decode_mfma_impl.h", "decode_mfma_b4.hip", "decode_finish.h"],
-    "sha256_16": "85d478d18673c7f4",
-    "fetch_bytes": 144050860,
+    "sha256_16": "a9fa369b22b50917",
+    "fetch_bytes": 144057580,
     "write_bytes": 73728,
 }
 
