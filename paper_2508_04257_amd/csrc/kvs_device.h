@@ -62,7 +62,7 @@ inline size_t workspace_counter_words(const kvs_desc* d) {
   return (static_cast<size_t>(d->B) * d->Hkv + 63) & ~static_cast<size_t>(63);
 }
 // The CSR column / value arrays are four entries longer than the capacity: the decode kernel
-// reads an entry together with the three that follow it.
+// reads aligned groups of four entries, and the last group may start just below the capacity.
 constexpr int kCsrPadEntries = 4;
 
 // Which tokens a quantise launch reads and where they go.  A plain call quantises the whole
