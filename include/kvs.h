@@ -197,6 +197,30 @@ kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const void* V,
                            void* stream);
 
 /*
+ * Outlier thresholds apart from the quantise call.  The dense-and-sparse setting of Section 5.1 is
+ * KVQuant's, which fixes its outlier thresholds on calibration data before inference (the
+ * counterpart, for the isolated entries, of the static quantisation of Appendix C); the search
+ * inside kvs_quantize_kv is the dynamic form.  Only with sparse_frac > 0 (KVS_ERR_INVALID else).
+ * kvs_outlier_thresholds: the search of kvs_quantize_kv alone.  tau: DEVICE uint32 [2], written:
+ *   tau[0] for Keys, tau[1] for Values, each the fp16 magnitude pattern (bits 0-14 of the half;
+ *   0x8000 = nothing is isolated) at which the descending cumulative count over the non-kept
+ *   entries first reaches ceil(sparse_frac * count).
+ * kvs_quantize_kv_thresholds: kvs_quantize_kv with the thresholds given (device words as the
+ *   search writes them, of this or of other data; larger values count as 0x8000): every non-kept
+ *   entry with magnitude pattern >= tau is isolated, whatever fraction of the tensor that is;
+ *   desc->sparse_frac only has to be > 0.  More entries than sparse_cap are reported through
+ *   cache->status as in kvs_quantize_kv.  With the thresholds kvs_outlier_thresholds finds on the
+ *   same K, V and mask the result is that of kvs_quantize_kv, bit for bit.
+ *   workspace: kvs_workspace_bytes(desc) bytes in both.
+ */
+kvs_status kvs_outlier_thresholds(const kvs_desc* desc, const void* K, const void* V,
+                                  const uint8_t* keep_mask, uint32_t* tau, void* workspace,
+                                  void* stream);
+kvs_status kvs_quantize_kv_thresholds(const kvs_desc* desc, const void* K, const void* V,
+                                      const uint8_t* keep_mask, const uint32_t* tau,
+                                      const kvs_cache* out, void* workspace, void* stream);
+
+/*
  * The prefill loop of Algorithm 1 without the model: L layers' K and V quantised in the order the
  * algorithm runs them, with the sink set filled once, after the emergence layer l_E (Section 4.3,
  * item (2)).  The set is empty while layers 1 .. l_E run, so those layers are quantised under the

@@ -53,6 +53,9 @@ Readings taken where the paper is silent (every one is restated in the design no
       groups that do not (see ``quant_error``).
   R18 Algorithm 1's loop order (``prefill_layers``): layers up to and including the emergence
       layer are quantised before the sink set is filled, i.e. without predicted sinks.
+  R19 outlier thresholds fixed beforehand (``quantize_kv(..., taus=...)``): every non-kept entry
+      whose magnitude pattern reaches the given threshold is isolated, whatever fraction of the
+      tensor that turns out to be (the calibrated form of R8, as static quantisation is of R1).
   R17 bit widths 2, 3, 4 and 8 (8: four codes per word, 32 words per 128 codes).  So that the
       zero point always fits its int16, the scale is never taken smaller than |min| / 32766.
       For fp16 data and b <= 4 that bound cannot bind (max - min is at least |min| / 2048);
@@ -352,8 +355,9 @@ def quantize_kv(K: np.ndarray, V: np.ndarray, keep_mask: np.ndarray, bits: int, 
                 taus: Optional[tuple] = None, key_per_token: bool = False) -> Cache:
     """Algorithm 1's two quantise steps for one layer: K and V rows of tokens outside the
     keep set are quantised, rows inside it are copied unchanged into the fp16 side buffer.
-    ``taus`` = (k_tau, v_tau) supplies thresholds that ``sparse_threshold`` found on a larger
-    tensor of which K, V are a slice (the threshold is a property of the whole layer).
+    ``taus`` = (k_tau, v_tau) supplies the thresholds instead of searching them: those that
+    ``sparse_threshold`` found on a larger tensor of which K, V are a slice (the threshold is a
+    property of the whole layer), or thresholds fixed on other data beforehand (R19).
     ``key_per_token`` selects the per-token Key scheme (Section 5.1; reading R15)."""
     K = np.asarray(K)
     V = np.asarray(V)

@@ -76,6 +76,12 @@ def lib() -> C.CDLL:
         L.kvs_quantize_kv.restype = C.c_int
         L.kvs_quantize_kv.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.POINTER(KvsCache), C.c_void_p, C.c_void_p]
+        L.kvs_outlier_thresholds.restype = C.c_int
+        L.kvs_outlier_thresholds.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.c_void_p]
+        L.kvs_quantize_kv_thresholds.restype = C.c_int
+        L.kvs_quantize_kv_thresholds.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                 C.POINTER(KvsCache), C.c_void_p, C.c_void_p]
         L.kvs_quantize_prefix.restype = C.c_int
         L.kvs_quantize_prefix.argtypes = [C.POINTER(KvsDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                           C.POINTER(KvsCache), C.c_void_p, C.c_void_p]
@@ -242,6 +248,37 @@ def kvs_quantize_kv(desc: KvsDesc, K: torch.Tensor, V: torch.Tensor, keep_mask: 
                                C.byref(cache.struct), _ptr(workspace), _stream_handle())
     if st != KVS_OK:
         raise KvsError("kvs_quantize_kv", st)
+
+
+def _check_sparse_call(desc: KvsDesc, K, V, keep_mask, tau, workspace) -> None:
+    shape = (desc.B, desc.Hkv, desc.n, desc.D)
+    _check_tensor("K", K, shape, torch.float16)
+    _check_tensor("V", V, shape, torch.float16)
+    _check_tensor("keep_mask", keep_mask, (desc.B, desc.n), torch.uint8)
+    _check_tensor("tau", tau, (2,), torch.int32)
+    if workspace is None or workspace.numel() * workspace.element_size() < kvs_workspace_bytes(desc):
+        raise ValueError("workspace too small")
+
+
+def kvs_outlier_thresholds(desc: KvsDesc, K: torch.Tensor, V: torch.Tensor, keep_mask: torch.Tensor,
+                           tau: torch.Tensor, workspace: torch.Tensor) -> None:
+    """The threshold search of kvs_quantize_kv alone; tau int32 [2] on the device, written."""
+    _check_sparse_call(desc, K, V, keep_mask, tau, workspace)
+    st = lib().kvs_outlier_thresholds(C.byref(desc), K.data_ptr(), V.data_ptr(), keep_mask.data_ptr(), tau.data_ptr(),
+                                      _ptr(workspace), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_outlier_thresholds", st)
+
+
+def kvs_quantize_kv_thresholds(desc: KvsDesc, K: torch.Tensor, V: torch.Tensor, keep_mask: torch.Tensor,
+                               tau: torch.Tensor, cache: CacheBuffers, workspace: torch.Tensor) -> None:
+    """kvs_quantize_kv with the outlier thresholds given (tau int32 [2] on the device)."""
+    _check_sparse_call(desc, K, V, keep_mask, tau, workspace)
+    _check_cache(desc, cache)
+    st = lib().kvs_quantize_kv_thresholds(C.byref(desc), K.data_ptr(), V.data_ptr(), keep_mask.data_ptr(),
+                                          tau.data_ptr(), C.byref(cache.struct), _ptr(workspace), _stream_handle())
+    if st != KVS_OK:
+        raise KvsError("kvs_quantize_kv_thresholds", st)
 
 
 def kvs_prefill_layers(desc: KvsDesc, emergence_layer: int, Ks: Sequence[torch.Tensor], Vs: Sequence[torch.Tensor],

@@ -114,6 +114,8 @@ size_t sparse_workspace_words(const kvs_desc* d);
 SparsePlan sparse_plan(const kvs_desc* d, void* workspace);
 void sparse_thresholds(const kvs_desc* d, const SparsePlan& p, const void* K, const void* V,
                        const uint8_t* mask, const kvs_cache* out, hipStream_t s);
+void sparse_given_thresholds(const SparsePlan& p, const uint32_t* given, const kvs_cache* out, hipStream_t s);
+void sparse_export_thresholds(const SparsePlan& p, uint32_t* tau_out, hipStream_t s);
 void sparse_build_csr(const kvs_desc* d, const SparsePlan& p, const kvs_cache* out, hipStream_t s);
 
 __host__ __device__ inline int words_per_128(int bits) { return bits == 2 ? 8 : (bits == 3 ? 13 : (bits == 4 ? 16 : 32)); }

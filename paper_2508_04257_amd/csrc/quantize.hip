@@ -85,12 +85,13 @@ __global__ __launch_bounds__(KVS_WAVE) void keep_gather_kernel(
 static void quantize_span(const kvs_desc* desc, const kvs::QuantSpan& sp, bool whole, const void* K, const void* V,
                           const uint8_t* mask, const uint8_t* index_mask, int n_index, const kvs_cache* out,
                           void* workspace, hipStream_t s, const uint32_t* static_k = nullptr,
-                          const uint32_t* static_v = nullptr) {
+                          const uint32_t* static_v = nullptr, const uint32_t* given_tau = nullptr) {
   kvs::SparsePlan plan{};
   const bool sparse = desc->sparse_frac > 0.0f;
-  if (sparse) {                                        // thresholds of K and V first (plan.tau)
+  if (sparse) {                                        // thresholds of K and V first (plan.tau): searched, or the caller's
     plan = kvs::sparse_plan(desc, static_cast<uint32_t*>(workspace) + kvs::workspace_counter_words(desc));   // behind decode's counters
-    kvs::sparse_thresholds(desc, plan, K, V, mask, out, s);
+    if (given_tau) kvs::sparse_given_thresholds(plan, given_tau, out, s);
+    else kvs::sparse_thresholds(desc, plan, K, V, mask, out, s);
   }
   kvs::launch_quantize_fast(desc, sp, whole, K, V, mask, out, static_k, static_v, sparse ? &plan : nullptr, s);
   if (sparse) kvs::sparse_build_csr(desc, plan, out, s);
@@ -136,6 +137,36 @@ extern "C" kvs_status kvs_quantize_kv(const kvs_desc* desc, const void* K, const
   if (st != KVS_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(stream);
   quantize_span(desc, kvs::whole_span(desc), true, K, V, keep_mask, keep_mask, desc->n, out, workspace, s);
+  return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
+}
+
+// Outlier thresholds apart from the quantise call (the dense-and-sparse setting of the paper's
+// Section 5.1 is KVQuant's, whose outlier thresholds are fixed on calibration data before
+// inference): the search alone, and the quantise call with the thresholds given.
+extern "C" kvs_status kvs_outlier_thresholds(const kvs_desc* desc, const void* K, const void* V,
+                                              const uint8_t* keep_mask, uint32_t* tau, void* workspace,
+                                              void* stream) {
+  const kvs_status st = kvs::validate_desc(desc);
+  if (st != KVS_OK) return st;
+  if (!(desc->sparse_frac > 0.0f)) return KVS_ERR_INVALID;
+  if (!K || !V || !keep_mask || !tau || !workspace) return KVS_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const kvs::SparsePlan plan =
+      kvs::sparse_plan(desc, static_cast<uint32_t*>(workspace) + kvs::workspace_counter_words(desc));
+  kvs::sparse_thresholds(desc, plan, K, V, keep_mask, nullptr, s);
+  kvs::sparse_export_thresholds(plan, tau, s);
+  return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
+}
+
+extern "C" kvs_status kvs_quantize_kv_thresholds(const kvs_desc* desc, const void* K, const void* V,
+                                                  const uint8_t* keep_mask, const uint32_t* tau,
+                                                  const kvs_cache* out, void* workspace, void* stream) {
+  const kvs_status st = kvs::check_quantize_call(desc, K, V, keep_mask, out, workspace);
+  if (st != KVS_OK) return st;
+  if (!(desc->sparse_frac > 0.0f) || !tau) return KVS_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  quantize_span(desc, kvs::whole_span(desc), true, K, V, keep_mask, keep_mask, desc->n, out, workspace, s, nullptr,
+                nullptr, tau);
   return hipGetLastError() == hipSuccess ? KVS_OK : KVS_ERR_DEVICE;
 }
 

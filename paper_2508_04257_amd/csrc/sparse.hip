@@ -489,11 +489,36 @@ SparsePlan sparse_plan(const kvs_desc* d, void* workspace) {
   return p;
 }
 
+// Thresholds given by the caller (device words, e.g. what an earlier search left): the control
+// block starts from zero as after a search, the two words are taken over, anything above 0x8000
+// (the pattern no magnitude reaches) counts as 0x8000.
+__global__ void take_thresholds_kernel(const uint32_t* __restrict__ given, uint32_t* __restrict__ tau) {
+  if (threadIdx.x < 2) tau[threadIdx.x] = given[threadIdx.x] < 0x8000u ? given[threadIdx.x] : 0x8000u;
+}
+__global__ void copy_thresholds_kernel(const uint32_t* __restrict__ tau, uint32_t* __restrict__ out) {
+  if (threadIdx.x < 2) out[threadIdx.x] = tau[threadIdx.x];
+}
+
+static void start_row_pointers(const kvs_cache* out, hipStream_t s) {
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(out->k_rowptr), size_t{1}, 0u);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(out->v_rowptr), size_t{1}, 0u);
+}
+
+void sparse_given_thresholds(const SparsePlan& p, const uint32_t* given, const kvs_cache* out, hipStream_t s) {
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(kCtrlBlock), 0, s, p.tau, static_cast<size_t>(kCtrlBlock), 0u);
+  start_row_pointers(out, s);
+  hipLaunchKernelGGL(take_thresholds_kernel, dim3(1), dim3(64), 0, s, given, p.tau);
+}
+
+void sparse_export_thresholds(const SparsePlan& p, uint32_t* tau_out, hipStream_t s) {
+  hipLaunchKernelGGL(copy_thresholds_kernel, dim3(1), dim3(64), 0, s, p.tau, tau_out);
+}
+
+// out == nullptr: the search alone (no CSR is going to be built).
 void sparse_thresholds(const kvs_desc* d, const SparsePlan& p, const void* K, const void* V,
                        const uint8_t* mask, const kvs_cache* out, hipStream_t s) {
   hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(1024), 0, s, p.hist, static_cast<size_t>(kHistWords + kCtrlBlock), 0u);
-  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(out->k_rowptr), size_t{1}, 0u);
-  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(out->v_rowptr), size_t{1}, 0u);
+  if (out) start_row_pointers(out, s);
   uint32_t* sample = p.hist;                              // [2][kBins]
   uint32_t* full = p.hist + 2 * kBins;                    // [2][kBins]
   uint32_t* fine = p.hist + 4 * kBins;                    // [2][kFineBins]

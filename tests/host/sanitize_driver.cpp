@@ -100,6 +100,17 @@ int main() {
     EXPECT(kvs_quantize_kv(&d, nullptr, p, pm, &full, nullptr, nullptr) == KVS_ERR_INVALID);
     EXPECT(kvs_quantize_kv(&d, p, p, pm, &none, nullptr, nullptr) == KVS_ERR_INVALID);
     EXPECT(kvs_quantize_kv(nullptr, p, p, pm, &full, nullptr, nullptr) == KVS_ERR_INVALID);
+    {
+      const kvs_desc sp = desc(2, 1024, 32, 32, 3, 128, 2, 0.01f, 4096);
+      uint32_t* tau = reinterpret_cast<uint32_t*>(p);
+      EXPECT(kvs_outlier_thresholds(&d, p, p, pm, tau, p, nullptr) == KVS_ERR_INVALID);          // a dense descriptor
+      EXPECT(kvs_outlier_thresholds(&sp, p, p, pm, nullptr, p, nullptr) == KVS_ERR_INVALID);
+      EXPECT(kvs_outlier_thresholds(&sp, p, p, pm, tau, nullptr, nullptr) == KVS_ERR_INVALID);
+      EXPECT(kvs_quantize_kv_thresholds(&d, p, p, pm, tau, &full, p, nullptr) == KVS_ERR_INVALID);
+      EXPECT(kvs_quantize_kv_thresholds(&sp, p, p, pm, nullptr, &full, p, nullptr) == KVS_ERR_INVALID);
+      EXPECT(kvs_quantize_kv_thresholds(&sp, p, p, pm, tau, &none, p, nullptr) == KVS_ERR_INVALID);
+      EXPECT(kvs_quantize_kv_thresholds(&sp, p, p, pm, tau, &full, nullptr, nullptr) == KVS_ERR_INVALID);
+    }
     EXPECT(kvs_decode_attn(&d, p, &full, p, nullptr, nullptr, nullptr) == KVS_ERR_INVALID);     // no workspace
     EXPECT(kvs_decode_attn(&d, p, &none, p, nullptr, p, nullptr) == KVS_ERR_INVALID);
     EXPECT(kvs_decode_attn_noalloc(&d, nullptr, &full, p, nullptr, nullptr) == KVS_ERR_INVALID);

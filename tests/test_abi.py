@@ -123,6 +123,26 @@ def test_null_pointers_are_rejected_on_the_host():
     assert kb.kvs_predict_workspace_bytes(4, 32768, 8) == 4 * 8 * 8 * 4 and kb.kvs_predict_workspace_bytes(8, 4096, 5) == 0
 
 
+def test_threshold_calls_check_their_arguments_on_the_host():
+    L = kb.lib()
+    dense = kb.make_desc(B=2, n=1024, Hq=32, Hkv=32, bits=3, group=128, keep_cap=2)
+    sparse = kb.make_desc(B=2, n=1024, Hq=32, Hkv=32, bits=3, group=128, keep_cap=2, sparse_frac=0.01, sparse_cap=4096)
+    full = kb.KvsCache(**{name: 16 for name in kb.CACHE_FIELD_NAMES})
+    # only for dense-and-sparse descriptors
+    assert L.kvs_outlier_thresholds(C.byref(dense), 16, 16, 16, 16, 16, None) == kb.KVS_ERR_INVALID
+    assert L.kvs_quantize_kv_thresholds(C.byref(dense), 16, 16, 16, 16, C.byref(full), 16, None) == kb.KVS_ERR_INVALID
+    # every pointer is needed
+    for hole in range(5):
+        args = [16, 16, 16, 16, 16]
+        args[hole] = None
+        assert L.kvs_outlier_thresholds(C.byref(sparse), *args, None) == kb.KVS_ERR_INVALID, hole
+    for hole in (0, 1, 2, 3, 5):
+        args = [16, 16, 16, 16, C.byref(full), 16]
+        args[hole] = None
+        assert L.kvs_quantize_kv_thresholds(C.byref(sparse), *args, None) == kb.KVS_ERR_INVALID, hole
+    assert L.kvs_quantize_kv_thresholds(C.byref(sparse), 16, 16, 16, 16, None, 16, None) == kb.KVS_ERR_INVALID
+
+
 def test_growing_cache_calls_check_their_arguments_on_the_host():
     d = kb.make_desc(B=2, n=1024, Hq=32, Hkv=32, bits=4, group=128, keep_cap=2)
     L = kb.lib()
