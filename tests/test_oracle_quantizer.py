@@ -452,3 +452,38 @@ def test_sparse_csr_structure_and_reduction_to_dense():
     assert len(tiny.k_col) <= 2 * 1 + 64                             # ceil(tiny * count) = 1 entry (+ ties)
     none = O.quantize_kv(K, V, mask, 3, 128, keep_cap=2, sparse_frac=0.0)
     assert np.array_equal(none.k_codes, dense_cache.k_codes) and none.k_rowptr is None
+
+
+def test_given_thresholds_isolate_exactly_what_reaches_them():
+    """R19: with `taus` the oracle isolates every non-kept entry whose magnitude reaches the given
+    threshold - counted here by brute force - and nothing else; the thresholds the search finds on
+    the same data give the dynamic result; 32768 isolates nothing and gives the dense codes; the
+    isolated entries leave the group statistics (a group's parameters are those of what is left)."""
+    rng = np.random.default_rng(19)
+    B, H, n, D = 1, 2, 128, 128
+    K, V = random_fp16(rng, (B, H, n, D), "wide"), random_fp16(rng, (B, H, n, D))
+    mask = np.zeros((B, n), np.uint8)
+    mask[0, [0, 3]] = 1
+    live = mask[0] == 0
+    dyn = O.quantize_kv(K, V, mask, 3, 128, keep_cap=2, sparse_frac=0.01)
+    same = O.quantize_kv(K, V, mask, 3, 128, keep_cap=2, sparse_frac=0.01, taus=(dyn.k_tau, dyn.v_tau))
+    for name in ("k_codes", "v_codes", "k_params", "v_params", "k_rowptr", "k_col", "k_val", "v_rowptr", "v_col", "v_val"):
+        assert np.array_equal(getattr(same, name), getattr(dyn, name)), name
+    tk, tv = np.float16(1.5), np.float16(0.75)                       # thresholds of some other data
+    taus = (int(tk.view(np.uint16)), int(tv.view(np.uint16)))
+    given = O.quantize_kv(K, V, mask, 3, 128, keep_cap=2, sparse_frac=0.01, taus=taus)
+    want_k = int((np.abs(K[:, :, live].astype(np.float32)) >= 1.5).sum())
+    want_v = int((np.abs(V[:, :, live].astype(np.float32)) >= 0.75).sum())
+    assert len(given.k_col) == want_k == int(given.k_rowptr[-1]) and want_k > 0.02 * K[:, :, live].size
+    assert len(given.v_col) == want_v == int(given.v_rowptr[-1])
+    assert np.all(np.abs(given.k_val.astype(np.float32)) >= 1.5) and np.all(np.abs(given.v_val.astype(np.float32)) >= 0.75)
+    # what is left of a Key group (one channel, the 126 live tokens) sets its parameters
+    c = 17
+    col = K[0, 0, :, c].astype(np.float32)
+    rest = col[live & (np.abs(col) < 1.5)]
+    scale = float(np.uint16(int(given.k_params[0, 0, 0, c]) & 0xFFFF).view(np.float16))
+    assert (rest.max() - rest.min()) / 7 <= scale <= (rest.max() - rest.min()) / 7 * (1 + 2.0 ** -9)
+    none = O.quantize_kv(K, V, mask, 3, 128, keep_cap=2, sparse_frac=0.01, taus=(32768, 32768))
+    dense = O.quantize_kv(K, V, mask, 3, 128, keep_cap=2)
+    assert len(none.k_col) == 0 and len(none.v_col) == 0
+    assert np.array_equal(none.k_codes, dense.k_codes) and np.array_equal(none.v_params, dense.v_params)
