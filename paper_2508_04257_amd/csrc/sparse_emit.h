@@ -42,7 +42,12 @@ typedef short short2v __attribute__((ext_vector_type(2)));
 // tau <= 0x8000), 0 in the others.
 __device__ inline uint32_t below_mask(uint32_t w, uint32_t tau2) {
   const ushort2v d = __builtin_bit_cast(ushort2v, w & 0x7FFF7FFFu) - __builtin_bit_cast(ushort2v, tau2);
-  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2v, d) >> 15);
+  uint32_t m = __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2v, d) >> 15);
+  // The empty statement hides where the mask comes from: knowing that it is a sign, the compiler
+  // turns every (a & m) | (b & ~m) that follows into two 16-bit compares, selects and a byte
+  // permute - eight instructions where one bit-field insert does it.
+  asm volatile("" : "+v"(m));
+  return m;
 }
 // Bit j = element j of the uint4 (eight halves) is at or above tau.  Each mask contributes the
 // two bits of its pair: the low half's at bit 2 k, the high half's at bit 16 + 2 k + 1.
