@@ -385,19 +385,31 @@ __global__ __launch_bounds__(kThreads) void quantize_k_fast_kernel(
     // Isolated entries to the block's run of the staging list, in final order (rows ascending,
     // channels ascending inside a row): the lane that holds an entry writes it from its
     // registers; its place is the row's start plus the entries of the row to its left.
-    const int run_base = run_base_s;
-    const long long list_words = kvs::emit_list_words(emit.cap);
+    // The run's start is the same for the whole workgroup: the list is addressed from there with
+    // 32-bit positions, and `room` is what is left of the list behind it.
+    const int run_base = __builtin_amdgcn_readfirstlane(run_base_s);
+    const long long left = kvs::emit_list_words(emit.cap) - run_base;
+    const int room = left < 0 ? 0 : (left > 0x7FFFFFFF ? 0x7FFFFFFF : static_cast<int>(left));
+    uint32_t* run = emit.list + run_base;
 #pragma unroll
     for (int i = 0; i < ROWS; ++i) {
+      // Entries of the row to the lane's left: the sixteen lanes of a row are one 16-lane row of the
+      // wave, so a shift-and-add scan of the lanes' counts gives it without a look at the row's mask.
+      const int own = __popc(iso8[i]);
+      int upto = own;
+      upto += __builtin_amdgcn_update_dpp(0, upto, 0x111, 0xF, 0xF, true);
+      upto += __builtin_amdgcn_update_dpp(0, upto, 0x112, 0xF, 0xF, true);
+      upto += __builtin_amdgcn_update_dpp(0, upto, 0x114, 0xF, 0xF, true);
+      upto += __builtin_amdgcn_update_dpp(0, upto, 0x118, 0xF, 0xF, true);
       uint32_t bits = iso8[i];
       if (bits == 0) continue;
       const int r = rslot + 16 * i;
-      long long pos = static_cast<long long>(run_base) + row_off_s[r] + bits_below_byte(&iso_s[r][0], chunk);
+      int pos = row_off_s[r] + upto - own;
       while (bits) {
         const int j = __builtin_ctz(bits);
         bits &= bits - 1;
-        if (pos < list_words)                      // channel | token inside its 128-token tile << 7 | fp16 value << 16
-          emit.list[pos] = static_cast<uint32_t>(8 * chunk + j) | (static_cast<uint32_t>((tc0 + r) & 127) << 7) | (half_of(raw[i], j) << 16);
+        if (pos < room)                            // channel | token inside its 128-token tile << 7 | fp16 value << 16
+          run[pos] = static_cast<uint32_t>(8 * chunk + j) | (static_cast<uint32_t>((tc0 + r) & 127) << 7) | (half_of(raw[i], j) << 16);
         ++pos;
       }
     }
@@ -733,8 +745,12 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
       run_base_s = run_claim;
     }
     __syncthreads();
-    const int run_base = run_base_s;
-    const long long list_words = kvs::emit_list_words(emit.cap);
+    // (the list is addressed from the run's start, the same for the whole workgroup, with 32-bit
+    // positions; `room` is what is left of the list behind it)
+    const int run_base = __builtin_amdgcn_readfirstlane(run_base_s);
+    const long long left = kvs::emit_list_words(emit.cap) - run_base;
+    const int room = left < 0 ? 0 : (left > 0x7FFFFFFF ? 0x7FFFFFFF : static_cast<int>(left));
+    uint32_t* run = emit.list + run_base;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       uint32_t bits = (i < 4 ? row_lo >> (8 * i) : row_hi >> (8 * (i - 4))) & 0xFFu;   // channels of token 8 rs + i
@@ -743,10 +759,9 @@ __global__ __launch_bounds__(kThreads) void quantize_v_fast_kernel(
         bits &= bits - 1;
         const int c = 8 * chunk + j;
         const uint32_t tokens = (j < 4 ? iso_lo >> (8 * j) : iso_hi >> (8 * (j - 4))) & 0xFFu;   // the lane's tokens of channel c
-        const long long pos = static_cast<long long>(run_base) + chan_off_s[c] + bits_below_byte(&iso_s[c][0], rs) +
-                              __popc(tokens & ((1u << i) - 1u));
-        if (pos < list_words)                      // token inside the tile | channel << 7 | fp16 value << 16
-          emit.list[pos] = static_cast<uint32_t>(8 * rs + i) | (static_cast<uint32_t>(c) << 7) | (half_of(raw[i], j) << 16);
+        const int pos = chan_off_s[c] + bits_below_byte(&iso_s[c][0], rs) + __popc(tokens & ((1u << i) - 1u));
+        if (pos < room)                            // token inside the tile | channel << 7 | fp16 value << 16
+          run[pos] = static_cast<uint32_t>(8 * rs + i) | (static_cast<uint32_t>(c) << 7) | (half_of(raw[i], j) << 16);
       }
     }
   }
