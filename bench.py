@@ -490,6 +490,14 @@ def layers_leg(rig, layers):
     }
 
 
+def guarded(leg, *args):
+    """The leg's result, or a record of why it has none."""
+    try:
+        return leg(*args)
+    except Exception as e:                                # noqa: BLE001 - anything a side leg can raise
+        return {"error": f"{type(e).__name__}: {e}"[:300]}
+
+
 def config_leg(name, steps, warmup, slots, dev):
     """One of the other workloads, timed like the headline one (same step, same event brackets)."""
     import gc
@@ -520,7 +528,7 @@ def config_leg(name, steps, warmup, slots, dev):
     if rig.nnz is not None:
         out["csr_entries"] = {"k": rig.nnz[0], "v": rig.nnz[1]}
     if w.layers > 1:
-        out["layers%d" % w.layers] = layers_leg(rig, w.layers)
+        out["layers%d" % w.layers] = guarded(layers_leg, rig, w.layers)
     del rig
     gc.collect()
     torch.cuda.empty_cache()
@@ -794,24 +802,26 @@ def main() -> int:
             "algorithmic_bytes": qnt_bytes,
         },
     }
-    result["graph_replay"] = graph_leg(rig)
+    # The figures above are the line's contract; what follows are legs reported beside them.  A leg
+    # that fails is reported as such and does not take the line with it.
+    result["graph_replay"] = guarded(graph_leg, rig)
     if w.sparse_frac == 0:
-        result["growing_cache"] = growing_cache_leg(w, rig.inputs[0], rig.q, dec_bytes)
-        result["static_quantisation"] = static_leg(w, rig.inputs, rig.bufs, qnt_bytes)
-        kpt = per_token_key_leg(w, rig.inputs, rig.bufs, rig.q, dec_bytes, qnt_bytes)
+        result["growing_cache"] = guarded(growing_cache_leg, w, rig.inputs[0], rig.q, dec_bytes)
+        result["static_quantisation"] = guarded(static_leg, w, rig.inputs, rig.bufs, qnt_bytes)
+        kpt = guarded(per_token_key_leg, w, rig.inputs, rig.bufs, rig.q, dec_bytes, qnt_bytes)
         if kpt is not None:
             result["per_token_keys"] = kpt
-        int8 = eight_bit_leg(w, rig.inputs, rig.bufs, rig.q)
+        int8 = guarded(eight_bit_leg, w, rig.inputs, rig.bufs, rig.q)
         if int8 is not None:
             result["int8"] = int8
     elif w.layers > 1:
-        result["layers%d" % w.layers] = layers_leg(rig, w.layers)
+        result["layers%d" % w.layers] = guarded(layers_leg, rig, w.layers)
     if not args.no_configs:
         import gc
         del rig
         gc.collect()
-        torch.cuda.empty_cache()
-        result["configs"] = {name: config_leg(name, args.config_steps, 3, slots, dev)
+        guarded(torch.cuda.empty_cache)
+        result["configs"] = {name: guarded(config_leg, name, args.config_steps, 3, slots, dev)
                              for name in OTHER_CONFIGS if name != w.name}
     if cpu is not None:
         result["cpu_baseline"] = cpu
