@@ -26,7 +26,10 @@
  *     keep_cap, more sparse entries than sparse_cap) cannot be known on the host: it is written
  *     to cache->status on the device (0 = fine, KVS_ERR_CAPACITY otherwise) and the call still
  *     returns KVS_OK.  The caller zeroes *status before the first call and reads it after
- *     synchronising.
+ *     synchronising.  With more flagged tokens than keep_cap, keep_cnt[b] still holds the number
+ *     flagged, the rows hold the keep_cap lowest token indices, and every flagged token is left
+ *     out of the quantisation (code 0): such a cache reports the condition, it is not one to
+ *     decode from.
  *   - fp16 is IEEE binary16; inputs must be finite.  All tensors are dense, row-major.
  *   - Every buffer starts at a multiple of 16 bytes (the decode calls return KVS_ERR_INVALID for a
  *     cache whose code, parameter, kept-row or CSR arrays do not).

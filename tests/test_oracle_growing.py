@@ -75,6 +75,28 @@ def test_appending_reaches_the_state_of_a_prefill(n0, n1):
     assert_same_growing(gc, O.prefill_cache(K, V, mask, bits, G, cap))
 
 
+def test_a_token_appended_with_its_keep_flag_is_kept_when_its_block_is_quantised():
+    rng = np.random.default_rng(21)
+    bits, G, cap, n0, n1 = 4, 128, 4, 100, 256
+    K, V = random_fp16(rng, (2, 1, n1, 128)), random_fp16(rng, (2, 1, n1, 128))
+    mask = np.zeros((2, n1), np.uint8)
+    mask[0, 3], mask[0, 110], mask[1, 200] = 1, 1, 1              # 110 and 200 arrive by append
+    K[0, 0, 110] *= 50                                             # a kept row this wild would wreck its groups' ranges
+    gc = O.prefill_cache(K[:, :, :n0], V[:, :, :n0], mask[:, :n0], bits, G, cap)
+    for t in range(n0, n1):
+        gc = O.append_token(gc, K[:, :, t], V[:, :, t], keep_new=mask[:, t])
+    want = O.prefill_cache(K, V, mask, bits, G, cap)
+    assert_same_growing(gc, want)
+    assert gc.quant.keep_idx[0].tolist() == [3, 110, -1, -1] and gc.quant.keep_idx[1].tolist() == [200, -1, -1, -1]
+    assert np.array_equal(gc.quant.keep_k[0, 0, 1].view(np.uint16), K[0, 0, 110].view(np.uint16))
+    # without the flag the wild row is quantised and stretches the range of every channel's group
+    plain = O.prefill_cache(K[:, :, :n0], V[:, :, :n0], mask[:, :n0], bits, G, cap)
+    for t in range(n0, n1):
+        plain = O.append_token(plain, K[:, :, t], V[:, :, t])
+    assert plain.quant.keep_cnt.tolist() == [1, 0]
+    assert not np.array_equal(plain.quant.k_params[0, 0, 0], gc.quant.k_params[0, 0, 0])
+
+
 def test_residual_rows_are_exact_and_short_caches_are_plain_attention():
     rng = np.random.default_rng(3)
     K, V = random_fp16(rng, (1, 2, 100, 128)), random_fp16(rng, (1, 2, 100, 128))

@@ -52,7 +52,9 @@ def test_topk_against_python_sort_with_ties_and_permutation():
     # several channels: the score of a token is its largest listed magnitude
     Hm = np.zeros((1, 8, 4), np.float16)
     Hm[0, 2, 0], Hm[0, 6, 1], Hm[0, 4, 2] = 5, -9, 100                 # channel 2 is not listed
+    Hm[0, 3, 0], Hm[0, 3, 1] = 4, -4                                   # largest, not summed: 4 < 5 although 4 + 4 > 5
     assert O.predict_sinks(Hm, [0, 1], 2, 0)[0].tolist() == [[2, 6]]
+    assert O.predict_sinks(Hm, [0, 1], 3, 0)[0].tolist() == [[2, 3, 6]]
 
 
 def test_model_constant_table_matches_the_paper():

@@ -228,6 +228,85 @@ def test_zero_point_of_a_minimum_at_an_exact_half_is_the_even_integer(bits):
     assert np.all(codes[:, 0] == 0) and np.all(codes[:, 1] == top_code)
 
 
+# Hand-computed pins for the order of operations (reading R1: x / scale is evaluated as the fp32
+# product x * fl32(1 / scale)).  Exact arithmetic, fp32 spacing 2^-23 in [1, 2), 2^-22 in [2, 4),
+# 2^-21 in [4, 8):
+#   scale 7/8:  1 / scale = 8/7 = 9586980.57.. * 2^-23 -> fl32 = 9586981 * 2^-23 (a little above 8/7);
+#     x = 5.6875 = 91/16:  x * fl32(1 / scale) = 13631488.609.. * 2^-21 -> fl32 = 13631489 * 2^-21
+#     = 6.5000005 -> 7, where the exact quotient 6.5 (and a true division) would round to the even 6.
+#   scale 65/128:  1 / scale = 128/65 = 16519104.98.. * 2^-23 -> fl32 = 16519105 * 2^-23;
+#     x = 325/256 = 1.26953125:  the product is 10485760.0098 * 2^-22 -> fl32 = 10485760 * 2^-22 = 2.5
+#     exactly -> 2; left in double precision the product 2.5000000023 would round to 3.
+def test_codes_come_from_an_fp32_product_with_the_fp32_reciprocal():
+    a = np.zeros(32, np.float16)
+    a[:3] = [0, 13.125, 5.6875]                         # range 15 * 7/8: scale 7/8, zero 0
+    b = np.zeros(32, np.float16)
+    b[:3] = [0, 7.6171875, 1.26953125]                  # range 15 * 65/128: scale 65/128, zero 0
+    X = np.zeros((64, 128), np.float16)
+    X[0:32, 9], X[32:64, 9] = a, b                      # Key groups 0 and 1 of channel 9
+    codes, s, z = O.quantize_k_head(X, np.zeros_like(X, bool), 4, 32)
+    assert (float(s[0, 9]), float(s[1, 9]), int(z[0, 9]), int(z[1, 9])) == (0.875, 0.5078125, 0, 0)
+    assert codes[0:3, 9].tolist() == [0, 15, 7] and codes[32:35, 9].tolist() == [0, 15, 2]
+    Xv = np.zeros((64, 128), np.float16)
+    Xv[5, 32:64], Xv[6, 96:128] = a, b                  # Value groups (token 5, group 1), (token 6, group 3)
+    codes, s, z = O.quantize_v_head(Xv, np.zeros_like(Xv, bool), 4, 32)
+    assert (float(s[5, 1]), float(s[6, 3]), int(z[5, 1]), int(z[6, 3])) == (0.875, 0.5078125, 0, 0)
+    assert codes[5, 32:35].tolist() == [0, 15, 7] and codes[6, 96:99].tolist() == [0, 15, 2]
+
+
+def test_zero_point_comes_from_the_same_product():
+    # min -5.6875, max 7.4375: range 13.125 = 15 * 7/8 -> scale 7/8; min * fl32(8/7) = -6.5000005
+    # -> zero = 7 (the exact quotient -6.5 would give the even 6).  Codes: min -> 0, max -> 15.
+    scale_h, zero = O.group_params(np.float32([-5.6875]), np.float32([7.4375]), np.array([32]), 4)
+    assert float(scale_h[0]) == 0.875 and int(zero[0]) == 7
+    g = np.zeros(32, np.float16)
+    g[:2] = [-5.6875, 7.4375]
+    X = np.zeros((32, 128), np.float16)
+    X[:, 0] = g
+    codes, s, z = O.quantize_k_head(X, np.zeros_like(X, bool), 4, 32)
+    assert int(z[0, 0]) == 7 and codes[:3, 0].tolist() == [0, 15, 7]      # 0 -> rne(0) + 7
+
+
+@pytest.mark.parametrize("which", ["k", "v"])
+def test_masked_entries_stay_out_of_both_ends_of_the_range(which):
+    # group = 0 .. 15 plus two masked entries far below and far above: scale 1, zero 0 - either
+    # entry taken into the minimum or the maximum would change both
+    g = np.zeros(32, np.float16)
+    g[:16] = np.arange(16)
+    g[20], g[21] = -100, 300
+    m = np.zeros(32, bool)
+    m[20] = m[21] = True
+    if which == "k":
+        X, M = np.zeros((32, 128), np.float16), np.zeros((32, 128), bool)
+        X[:, 40], M[:, 40] = g, m
+        codes, s, z = O.quantize_k_head(X, M, 4, 32)
+        assert float(s[0, 40]) == 1.0 and int(z[0, 40]) == 0
+        assert codes[:, 40].tolist() == list(range(16)) + [0] * 16
+    else:
+        X, M = np.zeros((4, 128), np.float16), np.zeros((4, 128), bool)
+        X[2, 64:96], M[2, 64:96] = g, m
+        codes, s, z = O.quantize_v_head(X, M, 4, 32)
+        assert float(s[2, 2]) == 1.0 and int(z[2, 2]) == 0
+        assert codes[2, 64:96].tolist() == list(range(16)) + [0] * 16
+
+
+def test_more_kept_tokens_than_rows_keeps_the_first_and_reports_the_count():
+    rng = np.random.default_rng(12)
+    K, V = random_fp16(rng, (1, 2, 128, 128)), random_fp16(rng, (1, 2, 128, 128))
+    mask = np.zeros((1, 128), np.uint8)
+    flagged = [2, 9, 40, 77, 100]
+    mask[0, flagged] = 1
+    c = O.quantize_kv(K, V, mask, 4, 128, keep_cap=3)
+    assert c.status == O.STATUS_CAPACITY
+    assert c.keep_cnt.tolist() == [5]                               # the number flagged, not the number stored
+    assert c.keep_idx[0].tolist() == [2, 9, 40]                     # lowest token indices first
+    for j, t in enumerate(flagged[:3]):
+        assert np.array_equal(c.keep_k[0, :, j].view(np.uint16), K[0, :, t].view(np.uint16))
+        assert np.array_equal(c.keep_v[0, :, j].view(np.uint16), V[0, :, t].view(np.uint16))
+    # every flagged token, stored or not, is left out of the quantisation (code 0 everywhere)
+    assert not c.k_codes_logical[0, :, flagged].any() and not c.v_codes_logical[0, :, flagged].any()
+
+
 @pytest.mark.parametrize("bits", BITS)
 def test_chosen_code_minimises_reconstruction_error_brute_force(bits):
     rng = np.random.default_rng(6 + bits)
