@@ -56,6 +56,35 @@ def test_blockwise_quantisation_is_the_whole_quantisation(bits, G):
                               y.view(np.uint16) if y.dtype == np.float16 else y), name
 
 
+def test_kept_rows_beyond_the_capacity_are_reported_however_the_blocks_split_them():
+    rng = np.random.default_rng(17)
+    K, V = random_fp16(rng, (1, 1, 256, 128)), random_fp16(rng, (1, 1, 256, 128))
+    blocks = lambda mask: [O.quantize_kv(K[:, :, t:t + 128], V[:, :, t:t + 128], mask[:, t:t + 128], 4, 128, keep_cap=3)
+                           for t in (0, 128)]
+    # two kept tokens in each block: neither block overflows on its own, together they do
+    mask = np.zeros((1, 256), np.uint8)
+    mask[0, [4, 9, 130, 200]] = 1
+    a, b = blocks(mask)
+    assert a.status == b.status == O.STATUS_OK
+    both = O._concat_caches(a, b)
+    assert both.status == O.STATUS_CAPACITY and both.keep_cnt.tolist() == [4]
+    assert both.keep_idx[0].tolist() == [4, 9, 130]
+    whole = O.quantize_kv(K, V, mask, 4, 128, keep_cap=3)
+    assert whole.status == O.STATUS_CAPACITY and np.array_equal(whole.keep_idx, both.keep_idx)
+    assert np.array_equal(whole.keep_k.view(np.uint16), both.keep_k.view(np.uint16))
+    # the second block overflows by itself, the first holds none
+    mask = np.zeros((1, 256), np.uint8)
+    mask[0, [130, 140, 150, 160, 170]] = 1
+    a, b = blocks(mask)
+    assert (a.status, b.status) == (O.STATUS_OK, O.STATUS_CAPACITY)
+    assert O._concat_caches(a, b).status == O.STATUS_CAPACITY
+    # decoding such a cache still works on the rows it has (the count is clamped to the capacity)
+    q = random_fp16(rng, (1, 1, 128))
+    Kd, _ = O.effective_kv(both, 0, 0)
+    assert np.array_equal(Kd[[4, 9, 130]], K[0, 0, [4, 9, 130]].astype(np.float64))
+    assert np.all(np.isfinite(O.decode_attn(q, both, Hq=1)[2]))
+
+
 @pytest.mark.parametrize("n0,n1", [(0, 130), (44, 300), (128, 257), (300, 300), (255, 256)])
 def test_appending_reaches_the_state_of_a_prefill(n0, n1):
     rng = np.random.default_rng(n0 + n1)

@@ -147,21 +147,43 @@ def test_lossless_grid_cache_equals_textbook_attention(G):
 
 def test_lossless_grid_with_isolated_outliers_equals_textbook_attention():
     rng = np.random.default_rng(3)
-    B, H, n = 1, 1, 256
+    B, H, n = 2, 2, 256
     K = rng.integers(0, 8, (B, H, n, 128)).astype(np.float16)
     V = rng.integers(0, 8, (B, H, n, 128)).astype(np.float16)
     K[:, :, 0::128], K[:, :, 1::128] = 0, 7
     V[..., 0], V[..., 1] = 0, 7
-    for X in (K, V):                                                  # ~1% huge entries, not on rows 0/1 or channels 0/1
-        t, c = rng.integers(2, 128, 300), rng.integers(2, 128, 300)
-        X[0, 0, t + 128 * rng.integers(0, 2, 300), c] = 500.0
+    for X in (K, V):                                                  # ~1% huge entries, not on rows 0/1 or channels 0/1,
+        for b in range(B):                                            # elsewhere in every (sequence, head)
+            for h in range(H):
+                t, c = rng.integers(2, 128, 300), rng.integers(2, 128, 300)
+                X[b, h, t + 128 * rng.integers(0, 2, 300), c] = 500.0
     mask = np.zeros((B, n), np.uint8)
+    mask[1, 77] = 1
+    K[1, :, 77], V[1, :, 77] = 0.37, -1000.0                          # a kept row is off the grid and never isolated
     q = (random_fp16(rng, (B, H, 128)) * np.float16(0.01)).astype(np.float16)
-    frac = float((K == 500).mean())
-    cache = O.quantize_kv(K, V, mask, 3, 128, keep_cap=0, sparse_frac=frac)
-    assert cache.k_tau == int(np.float16(500).view(np.uint16))
+    live = np.ones((B, 1, n, 1), bool)
+    live[1, 0, 77] = False
+    frac = min(int(((X == 500) & live).sum()) for X in (K, V)) / float(live.sum() * H * 128)
+    cache = O.quantize_kv(K, V, mask, 3, 128, keep_cap=1, sparse_frac=frac)
+    assert cache.k_tau == cache.v_tau == int(np.float16(500).view(np.uint16))
+    assert len(cache.k_col) == int((K == 500).sum()) and len(cache.v_col) == int((V == 500).sum())
     _, _, out64 = O.decode_attn(q, cache, Hq=H)
-    assert np.allclose(out64[0, 0], _sdpa64(q[0, 0], K[0, 0], V[0, 0]), atol=1e-12)
+    for b in range(B):
+        for h in range(H):
+            assert np.allclose(out64[b, h], _sdpa64(q[b, h], K[b, h], V[b, h]), atol=1e-12), (b, h)
+
+
+def test_sparse_capacity_is_the_larger_of_the_two_counts_and_may_be_met_exactly():
+    rng = np.random.default_rng(5)
+    K, V = random_fp16(rng, (1, 1, 128, 128)), random_fp16(rng, (1, 1, 128, 128))
+    K[0, 0, 3, :4] = 900.0                                            # 4 isolated Key entries ...
+    V[0, 0, 5, :9] = 900.0                                            # ... and 9 isolated Value entries
+    mask = np.zeros((1, 128), np.uint8)
+    tau = int(np.float16(900).view(np.uint16))
+    for cap, want in ((9, O.STATUS_OK), (8, O.STATUS_CAPACITY), (4, O.STATUS_CAPACITY), (100, O.STATUS_OK)):
+        c = O.quantize_kv(K, V, mask, 4, 128, keep_cap=0, sparse_frac=0.01, sparse_cap=cap, taus=(tau, tau))
+        assert (len(c.k_col), len(c.v_col)) == (4, 9)
+        assert c.status == want, cap
 
 
 def test_quantised_attention_error_shrinks_with_bit_width():
